@@ -1,0 +1,112 @@
+/*
+ * CPU oracle for low-rank binary indexing (arXiv 1905.05686).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+ * GPU library must compute.  It shares no code with the HIP path, is never
+ * called from it, and must stay free of blocking, packing or fusion so that it
+ * can be checked against the paper by eye.
+ *
+ * Conventions (one byte per bit, row-major everywhere):
+ *   W     m x n      weights (already rounded to the storage dtype, widened to double)
+ *   Ip01  [T][r][k]  left binary factor of every tile,  T = (m/r)*(n/c)
+ *   Iz01  [T][k][c]  right binary factor of every tile
+ *   tile t = ti*(n/c) + tj covers rows ti*r .. ti*r+r-1, columns tj*c .. tj*c+c-1
+ *   M     m x n      decoded mask, 1 = weight kept, 0 = weight pruned (Sec. 2, Eq. 2)
+ *   X     n x N,  Y  m x N
+ *
+ * Pins (tests/test_oracle_*.py): the printed 5x5 example (Eq. 5 -> Eq. 6),
+ * brute force against the set definition on tiny tiles, the integer-product
+ * formulation, closed forms of Table 1 / Table 3, the density law of Eq. 7.
+ * The LSTM recurrence and the CSR size formula (oracle/lstm.py, csr_bits) are
+ * the builder's own definitions: parity unpinned.
+ */
+#include <stddef.h>
+#include <stdint.h>
+
+/* Eq. 3, applied independently to every tile (Sec. 3.1):
+ * (I_a)_{i,j} = OR_{l=1..k} (I_p)_{i,l} AND (I_z)_{l,j}. */
+int lrbi_oracle_decode(int64_t m, int64_t n, int64_t r, int64_t c, int64_t k,
+                       const uint8_t *Ip01, const uint8_t *Iz01, uint8_t *M)
+{
+    if (m <= 0 || n <= 0 || r <= 0 || c <= 0 || k <= 0) return -1;
+    if (m % r != 0 || n % c != 0) return -2;
+    const int64_t tile_rows = m / r, tile_cols = n / c;
+    for (int64_t ti = 0; ti < tile_rows; ++ti) {
+        for (int64_t tj = 0; tj < tile_cols; ++tj) {
+            const int64_t t = ti * tile_cols + tj;
+            const uint8_t *Ip = Ip01 + t * r * k;   /* r x k */
+            const uint8_t *Iz = Iz01 + t * k * c;   /* k x c */
+            for (int64_t i = 0; i < r; ++i) {
+                for (int64_t j = 0; j < c; ++j) {
+                    uint8_t bit = 0;
+                    for (int64_t l = 0; l < k; ++l) {
+                        const uint8_t a = Ip[i * k + l] != 0;
+                        const uint8_t b = Iz[l * c + j] != 0;
+                        bit = bit | (a & b);
+                    }
+                    M[(ti * r + i) * n + (tj * c + j)] = bit;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* Masked layer product (Sec. 2: the mask is a "binary masking layer" on W):
+ * Y[i,q] = sum over j with M[i,j] = 1 of W[i,j] * X[j,q], in double.
+ * A pruned weight is skipped, so whatever value sits under a 0 bit (even NaN
+ * or Inf) never reaches Y.  Rows are independent; `threads` > 1 only spreads
+ * rows over OpenMP threads and does not change any sum's order (ascending j). */
+int lrbi_oracle_masked_gemm(int64_t m, int64_t n, int64_t N,
+                            const double *W, const uint8_t *M, const double *X,
+                            double *Y, int threads)
+{
+    if (m <= 0 || n <= 0 || N <= 0) return -1;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t i = 0; i < m; ++i) {
+        double *y = Y + i * N;
+        for (int64_t q = 0; q < N; ++q) y[q] = 0.0;
+        for (int64_t j = 0; j < n; ++j) {
+            if (M[i * n + j] == 0) continue;
+            const double w = W[i * n + j];
+            const double *x = X + j * N;
+            for (int64_t q = 0; q < N; ++q) y[q] += w * x[q];
+        }
+    }
+    return 0;
+}
+
+/* Index size of the factor pair: k(m+n) bits for one matrix (Sec. 2.2, the
+ * compression ratio mn/(k(m+n))); with tiling every tile stores its own
+ * r x k and k x c factors (Sec. 3.1), so tiles * k * (r + c) bits. */
+uint64_t lrbi_oracle_index_bits(int64_t m, int64_t n, int64_t r, int64_t c, int64_t k)
+{
+    if (m <= 0 || n <= 0 || r <= 0 || c <= 0 || k <= 0) return 0;
+    if (m % r != 0 || n % c != 0) return 0;
+    const uint64_t tiles = (uint64_t)(m / r) * (uint64_t)(n / c);
+    return tiles * (uint64_t)k * (uint64_t)(r + c);
+}
+
+/* The "binary" format of Fig. 1 / Table 1: one bit per weight. */
+uint64_t lrbi_oracle_dense_bits(int64_t m, int64_t n)
+{
+    if (m <= 0 || n <= 0) return 0;
+    return (uint64_t)m * (uint64_t)n;
+}
+
+/* Number of kept weights in a decoded mask. */
+uint64_t lrbi_oracle_popcount(int64_t m, int64_t n, const uint8_t *M)
+{
+    uint64_t cnt = 0;
+    for (int64_t e = 0; e < m * n; ++e) cnt += (M[e] != 0);
+    return cnt;
+}
+
+/* CSR index size under the builder's own accounting (the paper prints CSR
+ * sizes in Tables 1 and 3 but not the formula; parity unpinned):
+ * one column index per kept weight plus m+1 row pointers. */
+uint64_t lrbi_oracle_csr_bits(uint64_t nnz, int64_t m, int idx_bits, int ptr_bits)
+{
+    return nnz * (uint64_t)idx_bits + (uint64_t)(m + 1) * (uint64_t)ptr_bits;
+}
