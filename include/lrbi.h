@@ -1,0 +1,177 @@
+/*
+ * lrbi.h - low-rank binary index (LRBI) inference path for AMD MI355X (gfx950).
+ *
+ * C ABI of the library built from paper_1905_05686_amd/csrc.  It implements the
+ * inference side of "Network Pruning for Low-Rank Binary Indexing"
+ * (arXiv 1905.05686): the pruning mask of a weight matrix is stored, tile by
+ * tile, as two small binary factors and rebuilt on the fly as their Boolean
+ * product; the mask is applied to the weights and the layer product is taken.
+ *
+ * Notation follows the paper: W is m x n, a tile is r x c, the rank is k,
+ * I_p is r x k and I_z is k x c per tile, the decoded mask is I_a (1 = weight
+ * kept, 0 = weight pruned; Sec. 2, Eq. 2).
+ *
+ * General rules for every entry point
+ *   - Returns LRBI_OK (0) or a negative lrbi_status.  Nothing throws or aborts.
+ *     Arguments are validated before any GPU work is queued.
+ *   - The library allocates nothing, frees nothing, keeps no global state and
+ *     never synchronises.  Every buffer belongs to the caller.
+ *   - Pointers named d* are DEVICE pointers valid on the device of `stream`;
+ *     pointers named h* are HOST pointers.  `stream` is a hipStream_t passed as
+ *     void* (NULL = the default stream).  GPU work is queued on it and has not
+ *     finished when the call returns; inputs and outputs must stay alive and
+ *     unmodified until it has.
+ *   - An out-of-bounds buffer is outside the contract: sizes are stated below
+ *     and the library trusts them.
+ *
+ * Logical layout
+ *   Tiles are numbered row-major: t = ti * (n / c) + tj, T = (m / r) * (n / c).
+ *   Mask bit (i, j) of W belongs to tile (i / r, j / c) at (i mod r, j mod c).
+ *   Every tile has the same rank k (Sec. 3.1).  r must divide m and c must
+ *   divide n.
+ *
+ * Packed layouts (defined as byte images, little-endian bit order: bit b of a
+ * row sits in byte b >> 3 at position b & 7)
+ *   I_p packed: T * r rows of ip_row_bytes = 4 * ceil(k / 32) bytes; row
+ *               (t, i) holds bits l = 0 .. k-1 of (I_p,t)[i, :].  Pad bits zero.
+ *   I_z packed: T * k rows of iz_row_bytes = 8 * ceil(c / 64) bytes; row
+ *               (t, l) holds bits j = 0 .. c-1 of (I_z,t)[l, :].  Pad bits zero.
+ *   Mask      : m rows of mask_pitch_bytes; row i holds bits j = 0 .. n-1.
+ *   lrbi_index_bits reports the two packed sizes.
+ */
+#ifndef LRBI_H
+#define LRBI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LRBI_MAX_RANK 256
+
+typedef struct lrbi_desc {
+    int64_t m, n;   /* rows and columns of W                                   */
+    int32_t r, c;   /* tile rows and columns; r | m and c | n                  */
+    int32_t k;      /* rank of every tile, 1 <= k <= LRBI_MAX_RANK             */
+    uint32_t flags; /* 0, or LRBI_FLAG_* bits (kernel choice overrides)        */
+} lrbi_desc;
+
+/* desc.flags: force a kernel family in lrbi_masked_gemm (default: by N, dtype). */
+#define LRBI_FLAG_PATH_MASK   0x0000000Fu
+#define LRBI_FLAG_PATH_AUTO   0x00000000u
+#define LRBI_FLAG_PATH_VALU   0x00000001u /* bandwidth-bound vector-ALU kernel    */
+#define LRBI_FLAG_PATH_MFMA   0x00000002u /* matrix-core kernel (f16 / bf16 only) */
+/* desc.flags bits 8..15: split of the n (reduction) range over workgroups for the
+ * MFMA path, 0 = chosen by the library.  Values > 1 need a workspace. */
+#define LRBI_FLAG_SPLITK_SHIFT 8
+#define LRBI_FLAG_SPLITK_MASK  0x0000FF00u
+/* desc.flags bits 16..19: MFMA tile variant, 0 = chosen by the library. */
+#define LRBI_FLAG_TILE_SHIFT 16
+#define LRBI_FLAG_TILE_MASK  0x000F0000u
+/* desc.flags: force the generic decode kernel in lrbi_decode_mask. */
+#define LRBI_FLAG_DECODE_GENERIC 0x00100000u
+
+typedef enum lrbi_dtype { LRBI_F32 = 0, LRBI_F16 = 1, LRBI_BF16 = 2 } lrbi_dtype;
+
+typedef enum lrbi_status {
+    LRBI_OK = 0,
+    LRBI_ERR_NULL = -1,      /* a required pointer is NULL                       */
+    LRBI_ERR_SHAPE = -2,     /* non-positive size, r does not divide m, c not n  */
+    LRBI_ERR_RANK = -3,      /* k outside 1 .. LRBI_MAX_RANK                     */
+    LRBI_ERR_DTYPE = -4,     /* unknown dtype, or dtype not served by forced path */
+    LRBI_ERR_PITCH = -5,     /* pitch / leading dimension too small or misaligned */
+    LRBI_ERR_ALIGN = -6,     /* a pointer is not aligned as stated               */
+    LRBI_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch                 */
+    LRBI_ERR_WORKSPACE = -8, /* forced split needs a larger workspace            */
+    LRBI_ERR_FLAGS = -9      /* unknown bits in desc.flags                       */
+} lrbi_status;
+
+/* Text for a status code; never NULL, static storage. */
+const char *lrbi_strerror(int status);
+
+/*
+ * Index size accounting (Sec. 2.2: compression ratio mn / (k(m+n)); Sec. 3.1:
+ * every tile is factorised on its own with the same rank; Tables 1 and 3).
+ * Host only.  Any out pointer may be NULL.
+ *   lrbi_bits   = T * k * (r + c)      bits of the factor pair of all tiles
+ *   dense_bits  = m * n                bits of the plain binary mask
+ *   packed_ip_bytes / packed_iz_bytes  sizes of the packed factor buffers above
+ */
+int lrbi_index_bits(const lrbi_desc *desc, uint64_t *lrbi_bits, uint64_t *dense_bits,
+                    uint64_t *packed_ip_bytes, uint64_t *packed_iz_bytes);
+
+/*
+ * CSR index size under this library's stated accounting (the paper compares
+ * against CSR in Tables 1 and 3 without giving a formula):
+ *   bits = nnz * idx_bits + (m + 1) * ptr_bits.        Host only.
+ */
+int lrbi_csr_bits(uint64_t nnz, int64_t m, int32_t idx_bits, int32_t ptr_bits, uint64_t *bits);
+
+/*
+ * Pack factors given one byte per bit into the packed layouts (host only).
+ *   hIp01 [T][r][k], hIz01 [T][k][c]: any non-zero byte is a set bit.
+ *   hIp_packed: packed_ip_bytes, 4-byte aligned.  hIz_packed: packed_iz_bytes,
+ *   8-byte aligned.  Both are fully overwritten (pad bits zero).
+ */
+int lrbi_pack_factors(const lrbi_desc *desc, const uint8_t *hIp01, const uint8_t *hIz01,
+                      void *hIp_packed, void *hIz_packed);
+
+/*
+ * Unpack a packed mask (host only): hM01 [m][n] receives 0 / 1 bytes.
+ * mask_pitch_bytes >= ceil(n / 8).
+ */
+int lrbi_unpack_mask(const lrbi_desc *desc, const void *hMask, int64_t mask_pitch_bytes,
+                     uint8_t *hM01);
+
+/*
+ * Decode the mask of every tile: I_a,t = I_p,t (x) I_z,t with the Boolean
+ * product of Eq. 3, (I_a)_{i,j} = OR_l (I_p)_{i,l} AND (I_z)_{l,j}, each tile
+ * independently (Sec. 3.1), written as the one-bit-per-weight binary index form
+ * (Fig. 1).
+ *   dIp_packed, dIz_packed: packed factors (4- and 8-byte aligned).
+ *   dMask: m * mask_pitch_bytes bytes, 16-byte aligned; mask_pitch_bytes is a
+ *   multiple of 16 and >= ceil(n / 8).  In every row the first
+ *   16 * ceil(n / 128) bytes are written (bits >= n as zero); bytes beyond that
+ *   up to the pitch are left untouched.
+ * One kernel launch on `stream`.
+ */
+int lrbi_decode_mask(const lrbi_desc *desc, const void *dIp_packed, const void *dIz_packed,
+                     void *dMask, int64_t mask_pitch_bytes, void *stream);
+
+/*
+ * Workspace the masked product may use for (desc, dtype, N): partial sums when
+ * the reduction over n is split across workgroups.  Host only.  *bytes may be 0.
+ */
+int lrbi_masked_gemm_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t N,
+                                     uint64_t *bytes);
+
+/*
+ * Fused masked layer product Y = (W o I_a) X: the mask of Eq. 3 is rebuilt from
+ * the factors inside the kernel (it never goes through HBM), applied to W as a
+ * masking layer (Sec. 2, Sec. 2.2: a pruned weight contributes nothing, whatever
+ * value is stored under it, NaN and Inf included), and multiplied with X.
+ *   dW: m x n row-major, leading dimension ldw >= n (elements).
+ *   dX: n x N row-major, ldx >= N.   dY: m x N row-major, ldy >= N; overwritten.
+ *   W, X, Y share `dtype`.  Products are accumulated in fp32 (order unspecified
+ *   but fixed: two calls with the same arguments give identical bits) and
+ *   rounded to nearest-even on store.
+ *   Pointers must be aligned to the element size; 16-byte aligned W / X / Y with
+ *   ldw, ldx, ldy multiples of 8 (f16 / bf16) or 4 (f32) elements take the fast
+ *   vector paths, anything else a slower scalar path with the same results.
+ *   dWorkspace / workspace_bytes: optional scratch (16-byte aligned).  With NULL
+ *   or fewer bytes than lrbi_masked_gemm_workspace_bytes reports, the library
+ *   uses an unsplit kernel (slower for small m * N), unless desc.flags forces a
+ *   split, which then fails with LRBI_ERR_WORKSPACE.
+ * One or two kernel launches on `stream`.
+ */
+int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                     const void *dIp_packed, const void *dIz_packed, const void *dX, int64_t ldx,
+                     int64_t N, void *dY, int64_t ldy, void *dWorkspace, uint64_t workspace_bytes,
+                     void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LRBI_H */

@@ -1,0 +1,11 @@
+"""Low-rank binary index (arXiv 1905.05686) inference path for MI355X.
+
+Thin Python binding over the C ABI in include/lrbi.h (argument marshalling
+only).  Every step of the method runs in the HIP kernels of liblrbi.so; there
+is no CPU or PyTorch fallback: if the library is missing, calls raise.
+"""
+from .binding import (  # noqa: F401
+    BF16, F16, F32, FLAG_DECODE_GENERIC, FLAG_PATH_MFMA, FLAG_PATH_VALU, Desc, LrbiError, csr_bits, decode_mask,
+    flag_splitk, flag_tile, index_bits, library_path, load_library, masked_gemm, masked_gemm_workspace_bytes,
+    pack_factors, strerror, unpack_mask,
+)

@@ -1,0 +1,201 @@
+"""ctypes binding of liblrbi.so.  Function names match include/lrbi.h without the
+`lrbi_` prefix.  Device buffers are torch tensors (PyTorch is used for device
+memory and streams only); host buffers are numpy arrays."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "liblrbi.so")
+_lib = None
+
+F32, F16, BF16 = 0, 1, 2
+FLAG_PATH_VALU = 0x1
+FLAG_PATH_MFMA = 0x2
+FLAG_DECODE_GENERIC = 0x00100000
+
+
+def flag_splitk(s: int) -> int:
+    return (int(s) & 0xFF) << 8
+
+
+def flag_tile(t: int) -> int:
+    return (int(t) & 0xF) << 16
+
+
+class LrbiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, strerror(status)))
+
+
+class Desc(ctypes.Structure):
+    """Mirror of lrbi_desc: W is m x n, tiles r x c, rank k."""
+    _fields_ = [("m", ctypes.c_int64), ("n", ctypes.c_int64), ("r", ctypes.c_int32), ("c", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+    def __init__(self, m, n, r, c, k, flags=0):
+        super().__init__(int(m), int(n), int(r), int(c), int(k), int(flags))
+
+    def with_flags(self, flags: int) -> "Desc":
+        return Desc(self.m, self.n, self.r, self.c, self.k, flags)
+
+    @property
+    def tiles(self) -> int:
+        return (self.m // self.r) * (self.n // self.c)
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load liblrbi.so.  Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("liblrbi.so is missing at %s: build it with `python -m paper_1905_05686_amd.build` "
+                           "(there is no CPU fallback)" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, u64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int32
+    pd = ctypes.POINTER(Desc)
+    pu64 = ctypes.POINTER(ctypes.c_uint64)
+    lib.lrbi_strerror.argtypes = [ctypes.c_int]
+    lib.lrbi_strerror.restype = ctypes.c_char_p
+    lib.lrbi_index_bits.argtypes = [pd, pu64, pu64, pu64, pu64]
+    lib.lrbi_csr_bits.argtypes = [u64, i64, i32, i32, pu64]
+    lib.lrbi_pack_factors.argtypes = [pd, vp, vp, vp, vp]
+    lib.lrbi_unpack_mask.argtypes = [pd, vp, i64, vp]
+    lib.lrbi_decode_mask.argtypes = [pd, vp, vp, vp, i64, vp]
+    lib.lrbi_masked_gemm_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
+    lib.lrbi_masked_gemm.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, u64, vp]
+    for name in ("lrbi_index_bits", "lrbi_csr_bits", "lrbi_pack_factors", "lrbi_unpack_mask", "lrbi_decode_mask",
+                 "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load_library().lrbi_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise LrbiError(status, where)
+
+
+def index_bits(desc: Desc) -> dict:
+    """lrbi_index_bits: factor bits, dense bitmask bits and packed buffer sizes."""
+    a, b, c, d = (ctypes.c_uint64() for _ in range(4))
+    _check(load_library().lrbi_index_bits(ctypes.byref(desc), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                          ctypes.byref(d)), "lrbi_index_bits")
+    return {"lrbi_bits": a.value, "dense_bits": b.value, "packed_ip_bytes": c.value, "packed_iz_bytes": d.value}
+
+
+def csr_bits(nnz: int, m: int, idx_bits: int = 16, ptr_bits: int = 32) -> int:
+    out = ctypes.c_uint64()
+    _check(load_library().lrbi_csr_bits(int(nnz), int(m), int(idx_bits), int(ptr_bits), ctypes.byref(out)),
+           "lrbi_csr_bits")
+    return out.value
+
+
+def pack_factors(desc: Desc, Ip01: np.ndarray, Iz01: np.ndarray):
+    """lrbi_pack_factors: uint8 0/1 factors [T,r,k], [T,k,c] -> packed host arrays
+    (uint32 [T*r, ceil(k/32)], uint64 [T*k, ceil(c/64)])."""
+    Ip01 = np.ascontiguousarray(Ip01, dtype=np.uint8)
+    Iz01 = np.ascontiguousarray(Iz01, dtype=np.uint8)
+    T = desc.tiles
+    if Ip01.shape != (T, desc.r, desc.k) or Iz01.shape != (T, desc.k, desc.c):
+        raise ValueError("factor shapes do not match the descriptor")
+    sizes = index_bits(desc)
+    ip = np.empty((T * desc.r, sizes["packed_ip_bytes"] // (4 * T * desc.r)), dtype=np.uint32)
+    iz = np.empty((T * desc.k, sizes["packed_iz_bytes"] // (8 * T * desc.k)), dtype=np.uint64)
+    _check(load_library().lrbi_pack_factors(ctypes.byref(desc), Ip01.ctypes.data, Iz01.ctypes.data, ip.ctypes.data,
+                                            iz.ctypes.data), "lrbi_pack_factors")
+    return ip, iz
+
+
+def unpack_mask(desc: Desc, mask_bytes: np.ndarray) -> np.ndarray:
+    """lrbi_unpack_mask: packed host mask [m, pitch] (uint8) -> uint8 0/1 [m, n]."""
+    mask_bytes = np.ascontiguousarray(mask_bytes, dtype=np.uint8)
+    if mask_bytes.ndim != 2 or mask_bytes.shape[0] != desc.m:
+        raise ValueError("mask must be [m, pitch_bytes]")
+    out = np.empty((desc.m, desc.n), dtype=np.uint8)
+    _check(load_library().lrbi_unpack_mask(ctypes.byref(desc), mask_bytes.ctypes.data, mask_bytes.shape[1],
+                                           out.ctypes.data), "lrbi_unpack_mask")
+    return out
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_ptr(t, what):
+    if not t.is_cuda:
+        raise ValueError("%s must be a device tensor" % what)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def default_pitch(n: int) -> int:
+    return ((n + 127) // 128) * 16
+
+
+def decode_mask(desc: Desc, dIp, dIz, out=None, pitch_bytes=None, stream=None):
+    """lrbi_decode_mask: packed device factors -> packed device mask [m, pitch] (uint8)."""
+    import torch
+    if pitch_bytes is None:
+        pitch_bytes = out.shape[1] if out is not None else default_pitch(desc.n)
+    if out is None:
+        out = torch.empty((desc.m, pitch_bytes), dtype=torch.uint8, device=dIp.device)
+    if out.dtype != torch.uint8 or not out.is_contiguous() or out.shape != (desc.m, pitch_bytes):
+        raise ValueError("out must be a contiguous uint8 [m, pitch_bytes] tensor")
+    _check(load_library().lrbi_decode_mask(ctypes.byref(desc), _dev_ptr(dIp, "Ip"), _dev_ptr(dIz, "Iz"),
+                                           _dev_ptr(out, "mask"), int(pitch_bytes), _stream_ptr(stream)),
+           "lrbi_decode_mask")
+    return out
+
+
+def _dtype_code(t):
+    import torch
+    return {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}[t.dtype]
+
+
+def masked_gemm_workspace_bytes(desc: Desc, dtype_code: int, N: int) -> int:
+    out = ctypes.c_uint64()
+    _check(load_library().lrbi_masked_gemm_workspace_bytes(ctypes.byref(desc), int(dtype_code), int(N),
+                                                           ctypes.byref(out)), "lrbi_masked_gemm_workspace_bytes")
+    return out.value
+
+
+def masked_gemm(desc: Desc, W, dIp, dIz, X, out=None, workspace=None, stream=None):
+    """lrbi_masked_gemm: Y = (W o decode(Ip, Iz)) X.  W [m, n], X [n, N] (or [n]),
+    row-major device tensors of one dtype; rows may be padded (stride(0) >= width)."""
+    import torch
+    squeeze = X.dim() == 1
+    if squeeze:
+        X = X.unsqueeze(1)
+    if W.dim() != 2 or X.dim() != 2 or W.shape != (desc.m, desc.n) or X.shape[0] != desc.n:
+        raise ValueError("shape mismatch")
+    if W.stride(1) != 1 or (X.shape[1] > 1 and X.stride(1) != 1) or W.dtype != X.dtype:
+        raise ValueError("W and X must be row-major tensors of the same dtype")
+    N = X.shape[1]
+    if out is None:
+        out = torch.empty((desc.m, N), dtype=W.dtype, device=W.device)
+    if out.shape != (desc.m, N) or out.dtype != W.dtype or (N > 1 and out.stride(1) != 1):
+        raise ValueError("bad out tensor")
+    ws_ptr, ws_bytes = ctypes.c_void_p(0), 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    _check(load_library().lrbi_masked_gemm(
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), _dev_ptr(dIp, "Ip"), _dev_ptr(dIz, "Iz"),
+        _dev_ptr(X, "X"), X.stride(0), N, _dev_ptr(out, "Y"), out.stride(0), ws_ptr, ws_bytes, _stream_ptr(stream)),
+        "lrbi_masked_gemm")
+    return out[:, 0] if squeeze else out

@@ -1,0 +1,481 @@
+// Fused masked product on the matrix cores (f16 / bf16, fp32 accumulate):
+// Y = (W o I_a) X with the mask of Eq. 3 rebuilt per K-slab inside the kernel.
+//
+// A workgroup of 4 wavefronts owns a BM x BN tile of Y and walks the n range
+// (the reduction dimension) in slabs of BK = 64 columns of W.  Per slab:
+//   1. 16-byte global loads bring the W slab (BM x 64) and the X slab (64 x BN)
+//      into registers, one slab ahead of the arithmetic;
+//   2. every lane rebuilds one or two 32-bit words of the slab's mask from the
+//      packed factors (OR of the I_z words selected by the set bits of the I_p
+//      row) and publishes them in a small LDS array;
+//   3. when the W registers go to LDS, each 16-byte piece is ANDed with the
+//      16-bit-lane expansion of its 8 mask bits: pruned weights become +0 by
+//      select, so nothing stored under a 0 bit (NaN, Inf) reaches the product,
+//      and the masking cost is paid once per slab, not once per MFMA operand;
+//   4. the wavefronts read their operands from LDS and issue 32x32x16 MFMAs.
+//      X sits in LDS in its natural [k][n] order, and the operand needs 8
+//      consecutive k per lane, so it is gathered column-wise.
+// LDS is double buffered; there is one workgroup barrier per slab.
+//
+// The MFMA is issued as D = X^T-fragment * W^T-fragment, i.e. the accumulator
+// holds a 32(n) x 32(m) block: each lane then owns 4 consecutive n of one output
+// row, which makes the stores of Y 8 bytes wide per lane.
+//
+// When m * N yields too few tiles to fill 256 compute units, the n range is cut
+// into `splitk` slices; slices write fp32 partial tiles to the caller's
+// workspace and a second kernel adds them in slice order (deterministic).
+#include "lrbi_internal.hpp"
+
+namespace lrbi {
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+struct F16Tag {};
+struct BF16Tag {};
+
+__device__ __forceinline__ f32x16 mfma_32x32x16(F16Tag, uint4 a, uint4 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
+                                                  0, 0);
+}
+__device__ __forceinline__ f32x16 mfma_32x32x16(BF16Tag, uint4 a, uint4 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                   0, 0, 0);
+}
+
+// fp32 -> storage dtype, round to nearest even
+__device__ __forceinline__ uint16_t cvt_store(F16Tag, float v)
+{
+    return __builtin_bit_cast(uint16_t, (_Float16)v);
+}
+__device__ __forceinline__ uint16_t cvt_store(BF16Tag, float v)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u); // quiet NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Expand 2 mask bits (bit 0 -> low half, bit 1 -> high half) to a 32-bit AND mask.
+__device__ __forceinline__ uint32_t expand2(uint32_t bits)
+{
+    // (b0 | b1 << 16) * 0xFFFF = b0 * 0x0000FFFF | b1 * 0xFFFF0000
+    const uint32_t pair = (bits | (bits << 15)) & 0x00010001u;
+    return pair * 0xFFFFu;
+}
+__device__ __forceinline__ uint4 apply_mask8(uint4 w, uint32_t bits8)
+{
+    w.x &= expand2(bits8);
+    w.y &= expand2(bits8 >> 2);
+    w.z &= expand2(bits8 >> 4);
+    w.w &= expand2(bits8 >> 6);
+    return w;
+}
+
+static constexpr int kThreads = 256;
+static constexpr int BK = 64;
+static constexpr int WS_STRIDE = BK + 8; // halfs; 16-byte pad keeps 16-byte row alignment
+
+template <int BM, int BN> struct Smem {
+    static constexpr int XS_STRIDE = BN + 8;
+    static constexpr int ws_halfs = BM * WS_STRIDE;
+    static constexpr int xs_halfs = BK * XS_STRIDE;
+    static constexpr int ms_words = BM * 2;
+    static constexpr size_t bytes = 2 * (size_t)(ws_halfs + xs_halfs) * 2 + 2 * (size_t)ms_words * 4;
+};
+
+// Mask word for (row, 32-column half) of the slab starting at column k0.
+// ALIGNED: c % 64 == 0, so the slab lies inside tile column tj = k0 / c.
+template <bool ALIGNED>
+__device__ __forceinline__ uint32_t slab_mask_word(const Geom &g, const uint32_t *__restrict__ Ip,
+                                                   const uint32_t *__restrict__ Iz, int64_t row, int k0, int half,
+                                                   int tj, int wt /* word of the slab inside its tile */)
+{
+    if (row >= g.m) return 0u;
+    const int ti = (int)(row / g.r);
+    const int il = (int)(row - (int64_t)ti * g.r);
+    if (!ALIGNED) return decode_word(g, Ip, Iz, ti, il, (k0 >> 5) + half);
+    const int64_t t = (int64_t)ti * g.tile_cols + tj;
+    const uint32_t *ip = Ip + (t * g.r + il) * g.ipw;
+    const uint32_t *iz = Iz + t * g.k * (int64_t)g.izw + wt + half;
+    uint32_t acc = 0u;
+    for (int iw = 0; iw < g.ipw; ++iw) {
+        uint32_t sel = ip[iw];
+        while (sel) {
+            const int l = __builtin_ctz(sel) + 32 * iw;
+            sel &= sel - 1u;
+            acc |= iz[(int64_t)l * g.izw];
+        }
+    }
+    return acc;
+}
+
+template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N, bool ALIGNED, bool XVEC, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void mfma_gemm_kernel(
+    Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
+    const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ X, int64_t ldx, int N,
+    uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ P, int64_t ldp, int mblocks, int nblocks,
+    int64_t kper, int xcd_remap, int y_vec_ok)
+{
+    static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    static_assert(FM >= 1 && FN >= 1, "wave tile must hold a 32x32 block");
+    using S = Smem<BM, BN>;
+    constexpr int XS_STRIDE = S::XS_STRIDE;
+    constexpr int W_CHUNKS = BM * (BK / 8) / kThreads;  // 16-byte pieces of W per lane per slab
+    constexpr int X_CPR = BN / 8;                       // 16-byte pieces per X row
+    constexpr int X_CHUNKS = (BK * X_CPR + kThreads - 1) / kThreads;
+    constexpr int M_WORDS = (BM * 2 + kThreads - 1) / kThreads;
+    static_assert(BM * (BK / 8) % kThreads == 0, "W slab must split evenly");
+
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    uint16_t *Ws = (uint16_t *)lrbi_dyn_smem;            // [2][BM][WS_STRIDE]
+    uint16_t *Xs = Ws + 2 * S::ws_halfs;                 // [2][BK][XS_STRIDE]
+    uint32_t *Ms = (uint32_t *)(Xs + 2 * S::xs_halfs);   // [2][BM][2]
+
+    // workgroup -> (slice, row block, column block); column block fastest so that
+    // workgroups sharing a W row block are neighbours.  With xcd_remap the hardware's
+    // round-robin of consecutive workgroup ids over the 8 XCDs is undone, so that
+    // neighbours land on the same XCD and share its L2.
+    int64_t bid = blockIdx.x;
+    if (xcd_remap) {
+        const int64_t per = gridDim.x / 8;
+        bid = (bid % 8) * per + bid / 8;
+    }
+    const int ni = (int)(bid % nblocks);
+    const int mi = (int)((bid / nblocks) % mblocks);
+    const int slice = (int)(bid / ((int64_t)nblocks * mblocks));
+    const int64_t m0 = (int64_t)mi * BM;
+    const int n0 = ni * BN;
+    const int kbeg = (int)(slice * kper);
+    const int kend = (int)((kbeg + kper < g.n) ? kbeg + kper : g.n);
+    const int nslabs = (kend - kbeg + BK - 1) / BK;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int l32 = lane & 31, lg = lane >> 5;
+
+    uint4 wreg[W_CHUNKS];
+    uint4 xreg[X_CHUNKS];
+
+    auto load_slab = [&](int slab) {
+        const int k0 = kbeg + slab * BK;
+#pragma unroll
+        for (int i = 0; i < W_CHUNKS; ++i) {
+            const int id = tid + kThreads * i;
+            const int row = id >> 3, kc = id & 7;
+            const int64_t gr = m0 + row;
+            const int kk = k0 + kc * 8;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (gr < g.m && kk < kend) v = *reinterpret_cast<const uint4 *>(W + gr * ldw + kk);
+            wreg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < X_CHUNKS; ++i) {
+            const int id = tid + kThreads * i;
+            const int krow = id / X_CPR, nc = id % X_CPR;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (id < BK * X_CPR) {
+                const int kk = k0 + krow;
+                const int nn = n0 + nc * 8;
+                if (kk < kend) {
+                    if (XVEC) {
+                        if (nn < N) v = *reinterpret_cast<const uint4 *>(X + (int64_t)kk * ldx + nn);
+                    } else {
+                        uint16_t tmp[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) tmp[e] = (nn + e < N) ? X[(int64_t)kk * ldx + nn + e] : (uint16_t)0;
+                        v = *reinterpret_cast<uint4 *>(tmp);
+                    }
+                }
+            }
+            xreg[i] = v;
+        }
+    };
+
+    auto decode_slab = [&](int slab, int buf) {
+        const int k0 = kbeg + slab * BK;
+        int tj = 0, wt = 0;
+        if (ALIGNED) {
+            tj = k0 / g.c;
+            wt = (k0 - tj * g.c) >> 5;
+        }
+#pragma unroll
+        for (int i = 0; i < M_WORDS; ++i) {
+            const int idx = tid + kThreads * i;
+            if (idx < BM * 2) {
+                const int row = idx >> 1, half = idx & 1;
+                Ms[buf * S::ms_words + idx] = slab_mask_word<ALIGNED>(g, Ip, Iz, m0 + row, k0, half, tj, wt);
+            }
+        }
+    };
+
+    auto stage_slab = [&](int buf) {
+        uint16_t *ws = Ws + buf * S::ws_halfs;
+        uint16_t *xs = Xs + buf * S::xs_halfs;
+        const unsigned char *mb = (const unsigned char *)(Ms + buf * S::ms_words);
+#pragma unroll
+        for (int i = 0; i < W_CHUNKS; ++i) {
+            const int id = tid + kThreads * i;
+            const int row = id >> 3, kc = id & 7;
+            const uint32_t bits = mb[row * 8 + kc];
+            *reinterpret_cast<uint4 *>(ws + row * WS_STRIDE + kc * 8) = apply_mask8(wreg[i], bits);
+        }
+#pragma unroll
+        for (int i = 0; i < X_CHUNKS; ++i) {
+            const int id = tid + kThreads * i;
+            if (id < BK * X_CPR) {
+                const int krow = id / X_CPR, nc = id % X_CPR;
+                *reinterpret_cast<uint4 *>(xs + krow * XS_STRIDE + nc * 8) = xreg[i];
+            }
+        }
+    };
+
+    f32x16 acc[FN][FM];
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    // prologue: slab 0 into buffer 0, slab 1 in flight
+    if (nslabs > 0) {
+        load_slab(0);
+        decode_slab(0, 0);
+        __syncthreads();
+        stage_slab(0);
+        if (nslabs > 1) {
+            load_slab(1);
+            decode_slab(1, 1);
+        }
+        __syncthreads();
+    }
+
+    for (int s = 0; s < nslabs; ++s) {
+        const int buf = s & 1;
+        const uint16_t *ws = Ws + buf * S::ws_halfs;
+        const uint16_t *xs = Xs + buf * S::xs_halfs;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            const int kof = kk * 16 + 8 * lg;
+            uint4 wf[FM], xf[FN];
+#pragma unroll
+            for (int b = 0; b < FM; ++b)
+                wf[b] = *reinterpret_cast<const uint4 *>(ws + (wm * WM + b * 32 + l32) * WS_STRIDE + kof);
+#pragma unroll
+            for (int a = 0; a < FN; ++a) {
+                const uint16_t *col = xs + kof * XS_STRIDE + wn * WN + a * 32 + l32;
+                uint16_t tmp[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) tmp[e] = col[e * XS_STRIDE];
+                xf[a] = *reinterpret_cast<uint4 *>(tmp);
+            }
+#pragma unroll
+            for (int a = 0; a < FN; ++a)
+#pragma unroll
+                for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(Tag{}, xf[a], wf[b], acc[a][b]);
+        }
+        if (s + 1 < nslabs) stage_slab(buf ^ 1);
+        if (s + 2 < nslabs) {
+            load_slab(s + 2);
+            decode_slab(s + 2, buf);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: lane holds, per 32x32 block, rows n = 8*(v/4) + 4*lg + (v%4) and column m = l32
+#pragma unroll
+    for (int a = 0; a < FN; ++a) {
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+            const int64_t row = m0 + wm * WM + b * 32 + l32;
+            if (row >= g.m) continue;
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int col = n0 + wn * WN + a * 32 + 8 * v4 + 4 * lg;
+                if (SPLIT) {
+                    if (col < ldp) {
+                        float4 o = make_float4(acc[a][b][4 * v4 + 0], acc[a][b][4 * v4 + 1], acc[a][b][4 * v4 + 2],
+                                               acc[a][b][4 * v4 + 3]);
+                        *reinterpret_cast<float4 *>(P + ((int64_t)slice * g.m + row) * ldp + col) = o;
+                    }
+                } else {
+                    uint16_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = cvt_store(Tag{}, acc[a][b][4 * v4 + e]);
+                    if (y_vec_ok && col + 3 < N) {
+                        *reinterpret_cast<uint2 *>(Y + row * ldy + col) = *reinterpret_cast<uint2 *>(o);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < N) Y[row * ldy + col + e] = o[e];
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Sum the fp32 partial tiles of all slices in slice order and round to the storage dtype.
+template <typename Tag>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ P, int64_t ldp, int64_t m, int N,
+                                                            int splitk, uint16_t *__restrict__ Y, int64_t ldy,
+                                                            int y_vec_ok)
+{
+    const int64_t groups_per_row = ldp / 4;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= m * groups_per_row) return;
+    const int64_t row = e / groups_per_row;
+    const int col = (int)(e - row * groups_per_row) * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int k = 0; k < splitk; ++k) {
+        const float4 p = *reinterpret_cast<const float4 *>(P + ((int64_t)k * m + row) * ldp + col);
+        s.x += p.x;
+        s.y += p.y;
+        s.z += p.z;
+        s.w += p.w;
+    }
+    uint16_t o[4] = {cvt_store(Tag{}, s.x), cvt_store(Tag{}, s.y), cvt_store(Tag{}, s.z), cvt_store(Tag{}, s.w)};
+    if (y_vec_ok && col + 3 < N) {
+        *reinterpret_cast<uint2 *>(Y + row * ldy + col) = *reinterpret_cast<uint2 *>(o);
+    } else {
+        for (int q = 0; q < 4; ++q)
+            if (col + q < N) Y[row * ldy + col + q] = o[q];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+struct TileDef {
+    int bm, bn;
+};
+// tile ids 1..3 (desc.flags bits 16..19); 0 = automatic
+static const TileDef kTiles[] = {{0, 0}, {128, 128}, {128, 64}, {128, 32}};
+static constexpr int kNumTiles = 3;
+
+MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
+{
+    MfmaPlan p;
+    int tile = (int)((flags & LRBI_FLAG_TILE_MASK) >> LRBI_FLAG_TILE_SHIFT);
+    if (tile < 1 || tile > kNumTiles) tile = (N > 64) ? 1 : (N > 32 ? 2 : 3);
+    p.tile = tile;
+    p.bm = kTiles[tile].bm;
+    p.bn = kTiles[tile].bn;
+    const int64_t mblocks = (g.m + p.bm - 1) / p.bm;
+    const int64_t nblocks = (N + p.bn - 1) / p.bn;
+    const int64_t tiles = mblocks * nblocks;
+    const int64_t nslabs = (g.n + BK - 1) / BK;
+    int split = (int)((flags & LRBI_FLAG_SPLITK_MASK) >> LRBI_FLAG_SPLITK_SHIFT);
+    if (split == 0) {
+        split = 1;
+        if (tiles < 192) {
+            // aim at about two workgroups per compute unit, at least 4 slabs per slice
+            int64_t want = (512 + tiles - 1) / tiles;
+            const int64_t cap = nslabs / 4 > 1 ? nslabs / 4 : 1;
+            if (want > cap) want = cap;
+            if (want > 64) want = 64;
+            split = (int)(want < 1 ? 1 : want);
+        }
+    }
+    if (split > nslabs) split = (int)nslabs;
+    int64_t slabs_per = (nslabs + split - 1) / split;
+    split = (int)((nslabs + slabs_per - 1) / slabs_per); // no empty slice
+    p.splitk = split;
+    p.kper = slabs_per * BK;
+    const int64_t ldp = (N + 3) / 4 * 4;
+    p.workspace_bytes = (split > 1) ? (uint64_t)split * (uint64_t)g.m * (uint64_t)ldp * 4u : 0u;
+    return p;
+}
+
+template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N>
+static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
+                       const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
+                       void *dWorkspace, hipStream_t stream)
+{
+    const int64_t mblocks = (g.m + BM - 1) / BM;
+    const int64_t nblocks = (N + BN - 1) / BN;
+    const int64_t blocks = mblocks * nblocks * plan.splitk;
+    if (blocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
+    const bool aligned = (g.c % BK) == 0;
+    const bool xvec = (((uintptr_t)dX & 15) == 0) && (ldx % 8 == 0) && (N % 8 == 0);
+    const bool split = plan.splitk > 1;
+    const int y_vec_ok = (((uintptr_t)dY & 7) == 0) && (ldy % 4 == 0);
+    const int xcd_remap = (blocks % 8 == 0) ? 1 : 0;
+    const int64_t ldp = (N + 3) / 4 * 4;
+    const size_t smem = Smem<BM, BN>::bytes;
+    const dim3 grid((unsigned)blocks), block(kThreads);
+
+#define LRBI_LAUNCH(AL, XV, SP)                                                                                   \
+    do {                                                                                                          \
+        auto kern = mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, AL, XV, SP>;                                  \
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) !=     \
+            hipSuccess)                                                                                           \
+            return LRBI_ERR_LAUNCH;                                                                               \
+        hipLaunchKernelGGL(kern, grid, block, smem, stream, g, (const uint16_t *)dW, ldw, dIp, dIz,               \
+                           (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp,      \
+                           (int)mblocks, (int)nblocks, plan.kper, xcd_remap, y_vec_ok);                           \
+    } while (0)
+
+    if (aligned) {
+        if (xvec) {
+            if (split) LRBI_LAUNCH(true, true, true); else LRBI_LAUNCH(true, true, false);
+        } else {
+            if (split) LRBI_LAUNCH(true, false, true); else LRBI_LAUNCH(true, false, false);
+        }
+    } else {
+        if (xvec) {
+            if (split) LRBI_LAUNCH(false, true, true); else LRBI_LAUNCH(false, true, false);
+        } else {
+            if (split) LRBI_LAUNCH(false, false, true); else LRBI_LAUNCH(false, false, false);
+        }
+    }
+#undef LRBI_LAUNCH
+    LRBI_CHECK_LAUNCH();
+
+    if (split) {
+        const int64_t items = g.m * (ldp / 4);
+        const int64_t rblocks = (items + 255) / 256;
+        if (rblocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
+        hipLaunchKernelGGL(splitk_reduce_kernel<Tag>, dim3((unsigned)rblocks), dim3(256), 0, stream,
+                           (const float *)dWorkspace, ldp, g.m, (int)N, plan.splitk, (uint16_t *)dY, ldy, y_vec_ok);
+        LRBI_CHECK_LAUNCH();
+    }
+    return LRBI_OK;
+}
+
+template <typename Tag>
+static int launch_dtype(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
+                        const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
+                        void *dWorkspace, hipStream_t stream)
+{
+    switch (plan.tile) {
+    case 1: return launch_tile<Tag, 128, 128, 2, 2>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+    case 2: return launch_tile<Tag, 128, 64, 2, 2>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+    case 3: return launch_tile<Tag, 128, 32, 4, 1>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+    default: return LRBI_ERR_FLAGS;
+    }
+}
+
+int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const void *dW, int64_t ldw,
+                     const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY,
+                     int64_t ldy, void *dWorkspace, hipStream_t stream)
+{
+    // the W loads are 16 bytes wide
+    if (((uintptr_t)dW & 15) != 0 || ldw % 8 != 0 || g.n % 8 != 0) return LRBI_ERR_ALIGN;
+    if (dt == LRBI_F16)
+        return launch_dtype<F16Tag>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+    if (dt == LRBI_BF16)
+        return launch_dtype<BF16Tag>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+    return LRBI_ERR_DTYPE;
+}
+
+} // namespace lrbi

@@ -1,0 +1,224 @@
+// Host side of the LRBI library: descriptor validation, index-size accounting,
+// factor packing, and the dispatch of the two GPU entry points.
+#include <string.h>
+
+#include "lrbi_internal.hpp"
+
+namespace lrbi {
+
+int validate_desc(const lrbi_desc *d)
+{
+    if (!d) return LRBI_ERR_NULL;
+    if (d->m <= 0 || d->n <= 0 || d->r <= 0 || d->c <= 0) return LRBI_ERR_SHAPE;
+    if (d->m % d->r != 0 || d->n % d->c != 0) return LRBI_ERR_SHAPE;
+    // columns are indexed with 32-bit integers inside the kernels
+    if (d->n > (int64_t)0x7FFFFF00 || d->m > (int64_t)0x7FFFFF00) return LRBI_ERR_SHAPE;
+    if (d->k < 1 || d->k > LRBI_MAX_RANK) return LRBI_ERR_RANK;
+    const uint32_t known = LRBI_FLAG_PATH_MASK | LRBI_FLAG_SPLITK_MASK | LRBI_FLAG_TILE_MASK |
+                           LRBI_FLAG_DECODE_GENERIC;
+    if (d->flags & ~known) return LRBI_ERR_FLAGS;
+    const uint32_t path = d->flags & LRBI_FLAG_PATH_MASK;
+    if (path > LRBI_FLAG_PATH_MFMA) return LRBI_ERR_FLAGS;
+    return LRBI_OK;
+}
+
+Geom make_geom(const lrbi_desc *d)
+{
+    Geom g;
+    g.m = d->m;
+    g.n = d->n;
+    g.r = d->r;
+    g.c = d->c;
+    g.k = d->k;
+    g.tile_cols = (int32_t)(d->n / d->c);
+    g.tile_rows = (int32_t)(d->m / d->r);
+    g.ipw = (d->k + 31) / 32;
+    g.izw = 2 * ((d->c + 63) / 64);
+    return g;
+}
+
+static inline bool aligned_to(const void *p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+} // namespace lrbi
+
+using namespace lrbi;
+
+extern "C" const char *lrbi_strerror(int status)
+{
+    switch (status) {
+    case LRBI_OK: return "ok";
+    case LRBI_ERR_NULL: return "a required pointer is NULL";
+    case LRBI_ERR_SHAPE: return "bad shape: sizes must be positive, r must divide m, c must divide n";
+    case LRBI_ERR_RANK: return "rank k outside 1..LRBI_MAX_RANK";
+    case LRBI_ERR_DTYPE: return "unknown dtype or dtype not served by the forced kernel path";
+    case LRBI_ERR_PITCH: return "pitch or leading dimension too small or misaligned";
+    case LRBI_ERR_ALIGN: return "pointer not aligned as required";
+    case LRBI_ERR_LAUNCH: return "HIP runtime refused the kernel launch";
+    case LRBI_ERR_WORKSPACE: return "workspace too small for the forced split";
+    case LRBI_ERR_FLAGS: return "unknown bits in desc.flags";
+    default: return "unknown lrbi status";
+    }
+}
+
+extern "C" int lrbi_index_bits(const lrbi_desc *desc, uint64_t *lrbi_bits, uint64_t *dense_bits,
+                               uint64_t *packed_ip_bytes, uint64_t *packed_iz_bytes)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    const Geom g = make_geom(desc);
+    const uint64_t tiles = (uint64_t)g.tile_rows * (uint64_t)g.tile_cols;
+    if (lrbi_bits) *lrbi_bits = tiles * (uint64_t)g.k * ((uint64_t)g.r + (uint64_t)g.c);
+    if (dense_bits) *dense_bits = (uint64_t)g.m * (uint64_t)g.n;
+    if (packed_ip_bytes) *packed_ip_bytes = tiles * (uint64_t)g.r * (uint64_t)g.ipw * 4u;
+    if (packed_iz_bytes) *packed_iz_bytes = tiles * (uint64_t)g.k * (uint64_t)g.izw * 4u;
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_csr_bits(uint64_t nnz, int64_t m, int32_t idx_bits, int32_t ptr_bits, uint64_t *bits)
+{
+    if (!bits) return LRBI_ERR_NULL;
+    if (m <= 0 || idx_bits <= 0 || ptr_bits < 0) return LRBI_ERR_SHAPE;
+    *bits = nnz * (uint64_t)idx_bits + (uint64_t)(m + 1) * (uint64_t)ptr_bits;
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_pack_factors(const lrbi_desc *desc, const uint8_t *hIp01, const uint8_t *hIz01,
+                                 void *hIp_packed, void *hIz_packed)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!hIp01 || !hIz01 || !hIp_packed || !hIz_packed) return LRBI_ERR_NULL;
+    if (!aligned_to(hIp_packed, 4) || !aligned_to(hIz_packed, 8)) return LRBI_ERR_ALIGN;
+    const Geom g = make_geom(desc);
+    const int64_t tiles = (int64_t)g.tile_rows * g.tile_cols;
+    uint8_t *ip = (uint8_t *)hIp_packed;
+    uint8_t *iz = (uint8_t *)hIz_packed;
+    const int64_t ip_row = (int64_t)g.ipw * 4, iz_row = (int64_t)g.izw * 4;
+    memset(ip, 0, (size_t)(tiles * g.r * ip_row));
+    memset(iz, 0, (size_t)(tiles * g.k * iz_row));
+    for (int64_t t = 0; t < tiles; ++t) {
+        for (int64_t i = 0; i < g.r; ++i) {
+            const uint8_t *src = hIp01 + (t * g.r + i) * g.k;
+            uint8_t *dst = ip + (t * g.r + i) * ip_row;
+            for (int l = 0; l < g.k; ++l)
+                if (src[l]) dst[l >> 3] |= (uint8_t)(1u << (l & 7));
+        }
+        for (int64_t l = 0; l < g.k; ++l) {
+            const uint8_t *src = hIz01 + (t * g.k + l) * g.c;
+            uint8_t *dst = iz + (t * g.k + l) * iz_row;
+            for (int j = 0; j < g.c; ++j)
+                if (src[j]) dst[j >> 3] |= (uint8_t)(1u << (j & 7));
+        }
+    }
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_unpack_mask(const lrbi_desc *desc, const void *hMask, int64_t mask_pitch_bytes,
+                                uint8_t *hM01)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!hMask || !hM01) return LRBI_ERR_NULL;
+    if (mask_pitch_bytes < (desc->n + 7) / 8) return LRBI_ERR_PITCH;
+    const uint8_t *src = (const uint8_t *)hMask;
+    for (int64_t i = 0; i < desc->m; ++i) {
+        const uint8_t *row = src + i * mask_pitch_bytes;
+        uint8_t *out = hM01 + i * desc->n;
+        for (int64_t j = 0; j < desc->n; ++j) out[j] = (uint8_t)((row[j >> 3] >> (j & 7)) & 1u);
+    }
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_decode_mask(const lrbi_desc *desc, const void *dIp_packed, const void *dIz_packed,
+                                void *dMask, int64_t mask_pitch_bytes, void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dIp_packed || !dIz_packed || !dMask) return LRBI_ERR_NULL;
+    if (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8) || !aligned_to(dMask, 16))
+        return LRBI_ERR_ALIGN;
+    if (mask_pitch_bytes % 16 != 0 || mask_pitch_bytes < (desc->n + 7) / 8) return LRBI_ERR_PITCH;
+    const Geom g = make_geom(desc);
+    return launch_decode(g, desc->flags, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed, dMask,
+                         mask_pitch_bytes, (hipStream_t)stream);
+}
+
+static int elem_size(lrbi_dtype dt)
+{
+    switch (dt) {
+    case LRBI_F32: return 4;
+    case LRBI_F16: return 2;
+    case LRBI_BF16: return 2;
+    default: return 0;
+    }
+}
+
+// true when the matrix-core kernel serves this call
+static bool use_mfma(const lrbi_desc *desc, lrbi_dtype dt, int64_t N)
+{
+    const uint32_t path = desc->flags & LRBI_FLAG_PATH_MASK;
+    if (dt == LRBI_F32) return false;
+    if (path == LRBI_FLAG_PATH_MFMA) return true;
+    if (path == LRBI_FLAG_PATH_VALU) return false;
+    return N > 4; // below that the product is a bandwidth-bound matrix-vector sweep
+}
+
+extern "C" int lrbi_masked_gemm_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t N,
+                                                uint64_t *bytes)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!bytes) return LRBI_ERR_NULL;
+    if (elem_size(dtype) == 0) return LRBI_ERR_DTYPE;
+    if (N <= 0) return LRBI_ERR_SHAPE;
+    if ((desc->flags & LRBI_FLAG_PATH_MASK) == LRBI_FLAG_PATH_MFMA && dtype == LRBI_F32) return LRBI_ERR_DTYPE;
+    *bytes = 0;
+    if (use_mfma(desc, dtype, N)) {
+        const Geom g = make_geom(desc);
+        *bytes = plan_mfma(g, desc->flags, N).workspace_bytes;
+    }
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                                const void *dIp_packed, const void *dIz_packed, const void *dX, int64_t ldx,
+                                int64_t N, void *dY, int64_t ldy, void *dWorkspace, uint64_t workspace_bytes,
+                                void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dW || !dIp_packed || !dIz_packed || !dX || !dY) return LRBI_ERR_NULL;
+    const int es = elem_size(dtype);
+    if (es == 0) return LRBI_ERR_DTYPE;
+    if (N <= 0 || N > (int64_t)0x7FFFFF00) return LRBI_ERR_SHAPE;
+    if (ldw < desc->n || ldx < N || ldy < N) return LRBI_ERR_PITCH;
+    if (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8)) return LRBI_ERR_ALIGN;
+    if (!aligned_to(dW, (uintptr_t)es) || !aligned_to(dX, (uintptr_t)es) || !aligned_to(dY, (uintptr_t)es))
+        return LRBI_ERR_ALIGN;
+    if ((desc->flags & LRBI_FLAG_PATH_MASK) == LRBI_FLAG_PATH_MFMA && dtype == LRBI_F32) return LRBI_ERR_DTYPE;
+    const Geom g = make_geom(desc);
+    hipStream_t s = (hipStream_t)stream;
+    bool mfma = use_mfma(desc, dtype, N);
+    if (mfma) {
+        // the matrix-core kernel loads W in 16-byte pieces; anything else goes to the vector-ALU kernel
+        const bool w_vec = aligned_to(dW, 16) && (ldw % 8 == 0) && (desc->n % 8 == 0);
+        if (!w_vec) {
+            if ((desc->flags & LRBI_FLAG_PATH_MASK) == LRBI_FLAG_PATH_MFMA) return LRBI_ERR_ALIGN;
+            mfma = false;
+        }
+    }
+    if (!mfma)
+        return launch_valu_gemm(g, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
+                                dX, ldx, N, dY, ldy, s);
+    MfmaPlan plan = plan_mfma(g, desc->flags, N);
+    if (plan.splitk > 1) {
+        const bool ws_ok = dWorkspace && aligned_to(dWorkspace, 16) && workspace_bytes >= plan.workspace_bytes;
+        if (!ws_ok) {
+            if (desc->flags & LRBI_FLAG_SPLITK_MASK) return LRBI_ERR_WORKSPACE;
+            // no scratch: fall back to one slice over the whole n range
+            plan = plan_mfma(g, (desc->flags & ~LRBI_FLAG_SPLITK_MASK) | (1u << LRBI_FLAG_SPLITK_SHIFT), N);
+        }
+    }
+    return launch_mfma_gemm(g, plan, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
+                            dX, ldx, N, dY, ldy, dWorkspace, s);
+}

@@ -1,0 +1,109 @@
+// Internal declarations shared by the host entry points and the gfx950 kernels.
+// Nothing here is part of the C ABI (that is include/lrbi.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lrbi.h"
+
+namespace lrbi {
+
+// Geometry of one problem, precomputed on the host and passed by value to kernels.
+struct Geom {
+    int64_t m, n;      // rows / columns of W
+    int32_t r, c, k;   // tile rows, tile columns, rank
+    int32_t tile_cols; // n / c
+    int32_t tile_rows; // m / r
+    int32_t ipw;       // 32-bit words per packed I_p row  = ceil(k / 32)
+    int32_t izw;       // 32-bit words per packed I_z row  = 2 * ceil(c / 64)
+};
+
+int validate_desc(const lrbi_desc *d);
+Geom make_geom(const lrbi_desc *d);
+
+// kernel launchers (each returns an lrbi_status)
+int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint32_t *dIz, void *dMask,
+                  int64_t pitch_bytes, hipStream_t stream);
+int launch_valu_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
+                     const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
+                     hipStream_t stream);
+
+struct MfmaPlan {
+    int tile;     // tile variant id (1-based, see lrbi_gemm_mfma.hip)
+    int bm, bn;   // workgroup tile
+    int splitk;   // number of slices of the n range
+    int64_t kper; // columns of W per slice (multiple of the kernel's BK)
+    uint64_t workspace_bytes;
+};
+MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N);
+int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const void *dW, int64_t ldw,
+                     const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N,
+                     void *dY, int64_t ldy, void *dWorkspace, hipStream_t stream);
+
+#define LRBI_CHECK_LAUNCH()                                   \
+    do {                                                      \
+        if (hipGetLastError() != hipSuccess) return LRBI_ERR_LAUNCH; \
+    } while (0)
+
+#if defined(__HIPCC__)
+// ---------------------------------------------------------------------------
+// Device helpers for Eq. 3 on packed factors.
+// ---------------------------------------------------------------------------
+
+// 32 consecutive bits of a packed I_z row starting at bit offset `off`
+// (off may be negative: the window starts before the row; off > -32).
+// Words beyond the row read as zero.
+__device__ __forceinline__ uint32_t iz_window(const uint32_t *__restrict__ zr, int izw, int off)
+{
+    if (off >= 0) {
+        const int q = off >> 5, s = off & 31;
+        const uint32_t a = (q < izw) ? zr[q] : 0u;
+        const uint32_t b = (q + 1 < izw) ? zr[q + 1] : 0u;
+        return s ? ((a >> s) | (b << (32 - s))) : a;
+    }
+    return zr[0] << (-off);
+}
+
+// bits [lo, hi) of a 32-bit word set, 0 <= lo, hi <= 32
+__device__ __forceinline__ uint32_t bit_range(int lo, int hi)
+{
+    if (hi <= lo) return 0u;
+    const uint32_t upper = (hi >= 32) ? 0xFFFFFFFFu : ((1u << hi) - 1u);
+    const uint32_t lower = (lo >= 32) ? 0xFFFFFFFFu : ((1u << lo) - 1u);
+    return upper & ~lower;
+}
+
+// One 32-bit word of the decoded mask: bits j = 32*w .. 32*w+31 of mask row
+// (ti * r + il).  Generic in r, c, k; bits at or beyond column n come out zero.
+// Row i of a tile's mask is the OR of the I_z rows selected by row i of I_p (Eq. 3).
+__device__ __forceinline__ uint32_t decode_word(const Geom &g, const uint32_t *__restrict__ Ip,
+                                                const uint32_t *__restrict__ Iz, int ti, int il, int w)
+{
+    const int64_t j0 = (int64_t)w * 32;
+    if (j0 >= g.n) return 0u;
+    const int64_t j1 = (j0 + 32 < g.n) ? j0 + 32 : g.n;
+    int tj = (int)(j0 / g.c);
+    uint32_t acc = 0u;
+    for (int64_t tbeg = (int64_t)tj * g.c; tbeg < j1; tbeg += g.c, ++tj) {
+        const int64_t t = (int64_t)ti * g.tile_cols + tj;
+        const uint32_t *ip = Ip + (t * g.r + il) * g.ipw;
+        const uint32_t *izt = Iz + t * g.k * (int64_t)g.izw;
+        const int off = (int)(j0 - tbeg); // -32 < off < c
+        const uint32_t valid = bit_range(off < 0 ? -off : 0, (g.c - off < 32) ? g.c - off : 32);
+        uint32_t v = 0u;
+        for (int iw = 0; iw < g.ipw; ++iw) {
+            uint32_t sel = ip[iw];
+            while (sel) {
+                const int l = __builtin_ctz(sel) + 32 * iw;
+                sel &= sel - 1u;
+                v |= iz_window(izt + (int64_t)l * g.izw, g.izw, off);
+            }
+        }
+        acc |= v & valid;
+    }
+    return acc;
+}
+#endif // __HIPCC__
+
+} // namespace lrbi

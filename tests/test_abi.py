@@ -1,0 +1,119 @@
+"""C ABI: the library loads without a GPU, exports every symbol the header
+declares, validates arguments before touching the GPU, and its host-only entry
+points agree with independent numpy formulations.  CPU only."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1905_05686_amd as lrbi
+from oracle import lrbi_oracle as orc
+import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "lrbi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lrbi_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = lrbi.load_library()
+    syms = _declared_symbols()
+    assert {"lrbi_decode_mask", "lrbi_masked_gemm", "lrbi_index_bits"} <= set(syms)
+    for s in syms:
+        assert hasattr(lib, s), s
+
+
+def test_strerror_covers_all_codes():
+    for code in range(0, -10, -1):
+        assert lrbi.strerror(code) and "unknown lrbi status" not in lrbi.strerror(code)
+    assert "unknown lrbi status" in lrbi.strerror(-99)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3a", "C4", "C5"])
+def test_index_bits_matches_oracle(name):
+    cfg = workloads.CONFIGS[name]
+    d = lrbi.Desc(cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    got = lrbi.index_bits(d)
+    assert got["lrbi_bits"] == orc.index_bits(cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    assert got["dense_bits"] == orc.dense_bits(cfg.m, cfg.n)
+    assert got["packed_ip_bytes"] == cfg.tiles * cfg.r * 4 * ((cfg.k + 31) // 32)
+    assert got["packed_iz_bytes"] == cfg.tiles * cfg.k * 8 * ((cfg.c + 63) // 64)
+    assert lrbi.csr_bits(12345, cfg.m, 16, 32) == orc.csr_bits(12345, cfg.m, 16, 32)
+
+
+def test_desc_validation():
+    bad = [
+        (lrbi.Desc(0, 8, 1, 1, 1), -2), (lrbi.Desc(8, 8, 3, 4, 1), -2), (lrbi.Desc(8, 8, 4, 3, 1), -2),
+        (lrbi.Desc(8, 8, 4, 4, 0), -3), (lrbi.Desc(8, 8, 4, 4, 257), -3), (lrbi.Desc(8, 8, 4, 4, 1, 1 << 30), -9),
+        (lrbi.Desc(8, 8, 4, 4, 1, 3), -9),
+    ]
+    for d, code in bad:
+        with pytest.raises(lrbi.LrbiError) as e:
+            lrbi.index_bits(d)
+        assert e.value.status == code
+
+
+@pytest.mark.parametrize("r,c,k", [(5, 5, 2), (100, 100, 4), (3, 70, 33), (2, 130, 64), (4, 9, 100)])
+def test_pack_factors_against_numpy_packbits(r, c, k):
+    rng = np.random.default_rng(r * 1000 + c)
+    T = 6
+    d = lrbi.Desc(2 * r, 3 * c, r, c, k)
+    Ip = (rng.random((T, r, k)) < 0.4).astype(np.uint8)
+    Iz = (rng.random((T, k, c)) < 0.4).astype(np.uint8)
+    ip, iz = lrbi.pack_factors(d, Ip * 3, Iz * 255)  # any non-zero byte is a set bit
+    ipb = ip.view(np.uint8).reshape(T * r, -1)
+    izb = iz.view(np.uint8).reshape(T * k, -1)
+    ref_p = np.packbits(Ip.reshape(T * r, k), axis=1, bitorder="little")
+    ref_z = np.packbits(Iz.reshape(T * k, c), axis=1, bitorder="little")
+    assert np.array_equal(ipb[:, :ref_p.shape[1]], ref_p) and not ipb[:, ref_p.shape[1]:].any()
+    assert np.array_equal(izb[:, :ref_z.shape[1]], ref_z) and not izb[:, ref_z.shape[1]:].any()
+    assert ipb.shape[1] == 4 * ((k + 31) // 32) and izb.shape[1] == 8 * ((c + 63) // 64)
+
+
+def test_unpack_mask_against_numpy():
+    rng = np.random.default_rng(0)
+    d = lrbi.Desc(6, 77, 3, 7, 2)
+    M = (rng.random((6, 77)) < 0.5).astype(np.uint8)
+    packed = np.zeros((6, 16), np.uint8)
+    packed[:, :10] = np.packbits(M, axis=1, bitorder="little")
+    assert np.array_equal(lrbi.unpack_mask(d, packed), M)
+
+
+def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
+    lib = lrbi.load_library()
+    d = lrbi.Desc(8, 128, 4, 64, 2)
+    f = lib.lrbi_decode_mask
+    # host memory is fine here: validation fails first, nothing is launched
+    buf = (ctypes.c_uint8 * 4096)()
+    base = (ctypes.addressof(buf) + 63) // 64 * 64  # 64-byte aligned address inside the buffer
+    p = ctypes.c_void_p(base)
+    assert f(ctypes.byref(d), None, p, p, 16, None) == -1
+    assert f(ctypes.byref(d), p, p, p, 8, None) == -5       # pitch < ceil(n/8) and not a multiple of 16
+    assert f(ctypes.byref(d), p, p, p, 24, None) == -5      # not a multiple of 16
+    assert f(ctypes.byref(d), p, p, ctypes.c_void_p(base + 8), 16, None) == -6
+    assert f(ctypes.byref(d), ctypes.c_void_p(base + 2), p, p, 16, None) == -6
+    g = lib.lrbi_masked_gemm
+    args = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128), p, p,
+                         kw.get("X", p), kw.get("ldx", 16), kw.get("N", 16), kw.get("Y", p), kw.get("ldy", 16), None, 0,
+                         None]
+    assert g(*args(W=None)) == -1
+    assert g(*args(dt=7)) == -4
+    assert g(*args(N=0)) == -2
+    assert g(*args(ldw=127)) == -5
+    assert g(*args(ldx=15)) == -5
+    assert g(*args(ldy=8)) == -5
+    assert g(*args(W=ctypes.c_void_p(base + 1))) == -6
+    assert g(*args(d=lrbi.Desc(8, 128, 4, 64, 2, lrbi.FLAG_PATH_MFMA), dt=lrbi.F32)) == -4
+    assert g(*args(d=lrbi.Desc(8, 128, 4, 64, 2, lrbi.FLAG_PATH_MFMA), ldw=132)) == -6  # forced MFMA needs 16-byte rows
+    # a forced split without workspace is refused
+    d2 = lrbi.Desc(8, 1024, 4, 64, 2, lrbi.FLAG_PATH_MFMA | lrbi.flag_splitk(2))
+    assert g(*args(d=d2, ldw=1024)) == -8
+    assert lrbi.masked_gemm_workspace_bytes(d2, lrbi.F16, 16) == 2 * 8 * 16 * 4
+    assert lrbi.masked_gemm_workspace_bytes(lrbi.Desc(4096, 4096, 512, 512, 32), lrbi.BF16, 1024) == 0
+    assert lrbi.masked_gemm_workspace_bytes(lrbi.Desc(4096, 4096, 512, 512, 32), lrbi.BF16, 1) == 0

@@ -1,0 +1,125 @@
+"""GPU parity: lrbi_decode_mask against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1905_05686_amd as lrbi
+import workloads
+from oracle import lrbi_oracle as orc
+from gpu_util import desc_of, dev, device_factors, unpack_device_mask
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(m, n, r, c, k, Ip01, Iz01, flags=0, pitch=None):
+    d = lrbi.Desc(m, n, r, c, k, flags)
+    dIp, dIz = device_factors(d, Ip01, Iz01)
+    if pitch is None:
+        pitch = ((n + 127) // 128) * 16
+    out = torch.full((m, pitch), 0xEE, dtype=torch.uint8, device=dev())
+    lrbi.decode_mask(d, dIp, dIz, out=out)
+    torch.cuda.synchronize()
+    bits = unpack_device_mask(out, n)
+    ref = orc.decode_mask(Ip01, Iz01, m, n, r, c, k)
+    assert np.array_equal(bits[:, :n], ref), "mask differs from the oracle"
+    written = ((n + 127) // 128) * 128
+    assert not bits[:, n:written].any(), "pad bits must be zero"
+    host = out.cpu().numpy()
+    assert (host[:, written // 8:] == 0xEE).all(), "bytes beyond the written pieces must stay untouched"
+    return ref
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3a", "C4", "C5"])
+@pytest.mark.parametrize("flags", [0, lrbi.FLAG_DECODE_GENERIC])
+def test_config_masks_bit_exact(name, flags):
+    cfg = workloads.CONFIGS[name]
+    d = workloads.make(cfg, want_w=False, want_x=False)
+    print("decode", name, "flags", hex(flags), flush=True)
+    ref = _check(cfg.m, cfg.n, cfg.r, cfg.c, cfg.k, d["Ip01"], d["Iz01"], flags=flags)
+    expect = 1 - (1 - cfg.p ** 2) ** cfg.k
+    assert abs(ref.mean() - expect) < 0.01
+
+
+SHAPES = [
+    # m, n, r, c, k, p
+    (5, 5, 5, 5, 2, 0.5),            # the worked example's shape
+    (64, 256, 64, 128, 1, 0.5),      # k = 1: rectangles
+    (96, 384, 32, 128, 33, 0.1),     # two I_p words
+    (40, 640, 20, 320, 64, 0.05),    # c % 128 != 0
+    (66, 1056, 33, 1056, 256, 0.01), # largest rank, odd rows
+    (30, 77, 3, 7, 5, 0.3),          # tiles narrower than a word
+    (12, 93, 4, 31, 3, 0.3),
+    (7, 1, 7, 1, 1, 0.7),            # single column
+    (1, 4097, 1, 4097, 2, 0.4),      # single row, ragged tail
+    (257, 9000, 257, 300, 8, 0.12),  # many unaligned tiles
+    (2048, 8192, 512, 512, 32, 0.06),
+]
+
+
+@pytest.mark.parametrize("m,n,r,c,k,p", SHAPES)
+@pytest.mark.parametrize("flags", [0, lrbi.FLAG_DECODE_GENERIC])
+def test_edge_shapes(m, n, r, c, k, p, flags):
+    rng = np.random.default_rng(m * 7 + n)
+    T = (m // r) * (n // c)
+    Ip = (rng.random((T, r, k)) < p).astype(np.uint8)
+    Iz = (rng.random((T, k, c)) < p).astype(np.uint8)
+    print("decode shape", (m, n, r, c, k), "flags", hex(flags), flush=True)
+    _check(m, n, r, c, k, Ip, Iz, flags=flags)
+
+
+def test_degenerate_factors_and_wide_pitch():
+    m, n, r, c, k = 48, 200, 24, 100, 6
+    T = 4
+    ones_p, ones_z = np.ones((T, r, k), np.uint8), np.ones((T, k, c), np.uint8)
+    assert _check(m, n, r, c, k, ones_p, ones_z, pitch=64).all()
+    assert not _check(m, n, r, c, k, ones_p * 0, ones_z, pitch=64).any()
+    assert not _check(m, n, r, c, k, ones_p, ones_z * 0, pitch=48).any()
+    # only tile 3 set: exactly its block of the mask is set (tile order is row-major)
+    p2, z2 = ones_p * 0, ones_z * 0
+    p2[3], z2[3] = 1, 1
+    ref = _check(m, n, r, c, k, p2, z2)
+    exp = np.zeros((m, n), np.uint8)
+    exp[24:, 100:] = 1
+    assert np.array_equal(ref, exp)
+
+
+def test_scaled_grid_sampled_tiles():
+    """The launch configuration the benchmark times (C3's tile shape on a grid whose mask
+    exceeds 1 GiB), checked on sampled tiles that the oracle decodes one by one."""
+    base = workloads.CONFIGS["C3a"]
+    cfg = workloads.scaled(base, m=65536, n=131072 + 4096)  # 1.03 GiB mask, ragged number of tile columns
+    d = workloads.make_factors_only(cfg)
+    desc = desc_of(cfg)
+    dIp, dIz = device_factors(desc, d["Ip01"], d["Iz01"])
+    print("decode scaled", cfg.m, cfg.n, flush=True)
+    out = lrbi.decode_mask(desc, dIp, dIz)
+    torch.cuda.synchronize()
+    tile_cols = cfg.n // cfg.c
+    rng = np.random.default_rng(1)
+    picks = [(0, 0), (cfg.m // cfg.r - 1, tile_cols - 1)] + [
+        (int(rng.integers(cfg.m // cfg.r)), int(rng.integers(tile_cols))) for _ in range(14)]
+    for ti, tj in picks:
+        t = ti * tile_cols + tj
+        ref = orc.decode_mask(d["Ip01"][t:t + 1], d["Iz01"][t:t + 1], cfg.r, cfg.c, cfg.r, cfg.c, cfg.k)
+        blk = out[ti * cfg.r:(ti + 1) * cfg.r, tj * cfg.c // 8:(tj + 1) * cfg.c // 8].cpu().numpy()
+        got = np.unpackbits(blk, axis=1, bitorder="little")
+        assert np.array_equal(got, ref), (ti, tj)
+    # density over the whole mask follows Eq. 7 (popcount on the device via a byte lookup)
+    lut = torch.tensor([bin(v).count("1") for v in range(256)], dtype=torch.int64, device=out.device)
+    total = 0
+    for lo in range(0, cfg.m, 8192):
+        total += int(lut[out[lo:lo + 8192].long()].sum())
+    assert abs(total / (cfg.m * cfg.n) - (1 - (1 - cfg.p ** 2) ** cfg.k)) < 0.002
+
+
+def test_runs_on_a_side_stream():
+    cfg = workloads.CONFIGS["C5"]
+    d = workloads.make(cfg, want_w=False, want_x=False)
+    desc = desc_of(cfg)
+    dIp, dIz = device_factors(desc, d["Ip01"], d["Iz01"])
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        out = lrbi.decode_mask(desc, dIp, dIz)
+    s.synchronize()
+    ref = orc.decode_mask(d["Ip01"], d["Iz01"], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    assert np.array_equal(unpack_device_mask(out, cfg.n)[:, :cfg.n], ref)

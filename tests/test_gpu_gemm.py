@@ -1,0 +1,191 @@
+"""GPU parity: lrbi_masked_gemm against the fp64 CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1905_05686_amd as lrbi
+import workloads
+from oracle import lrbi_oracle as orc
+from gpu_util import (ORACLE_THREADS, TOL, TORCH_DTYPE, desc_of, dev, device_factors, to_device, to_float64,
+                      workspace_for)
+
+pytestmark = pytest.mark.gpu
+
+DT_CODE = {"f32": lrbi.F32, "f16": lrbi.F16, "bf16": lrbi.BF16}
+
+
+def _run(cfg, data, flags=0, use_workspace=True, ldpad=0):
+    desc = desc_of(cfg, flags)
+    dIp, dIz = device_factors(desc, data["Ip01"], data["Iz01"])
+    W = to_device(data["W"], cfg.dtype)
+    X = to_device(data["X"], cfg.dtype)
+    if ldpad:
+        Wp = torch.zeros((cfg.m, cfg.n + ldpad), dtype=W.dtype, device=dev())
+        Wp[:, :cfg.n] = W
+        W = Wp[:, :cfg.n]
+        Xp = torch.zeros((cfg.n, cfg.N + ldpad), dtype=X.dtype, device=dev())
+        Xp[:, :cfg.N] = X
+        X = Xp[:, :cfg.N]
+    ws = workspace_for(desc, DT_CODE[cfg.dtype], cfg.N) if use_workspace else None
+    Y = lrbi.masked_gemm(desc, W, dIp, dIz, X, workspace=ws)
+    torch.cuda.synchronize()
+    return Y
+
+
+def _oracle(cfg, data):
+    M = orc.decode_mask(data["Ip01"], data["Iz01"], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    return orc.masked_gemm(workloads.to_float64(data["W"], cfg.dtype), M, workloads.to_float64(data["X"], cfg.dtype),
+                           threads=ORACLE_THREADS), M
+
+
+def _assert_close(Y, ref, dtype, what=""):
+    err = orc.rel_err(to_float64(Y), ref)
+    normwise = float(np.max(np.abs(to_float64(Y) - ref)) / max(np.max(np.abs(ref)), 1e-300))
+    print("%s rel_err %.3e (normwise %.3e, tol %.0e)" % (what, err, normwise, TOL[dtype]), flush=True)
+    assert err <= TOL[dtype], (what, err)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3a", "C3b", "C4", "C5"])
+def test_config_parity(name):
+    cfg = workloads.CONFIGS[name]
+    print("gemm config", name, flush=True)
+    data = workloads.make(cfg)
+    ref, _ = _oracle(cfg, data)
+    Y = _run(cfg, data)
+    _assert_close(Y, ref, cfg.dtype, name)
+    # run-to-run identical bits (no floating-point atomics anywhere)
+    Y2 = _run(cfg, data)
+    assert torch.equal(Y.view(torch.int16 if Y.element_size() == 2 else torch.int32),
+                       Y2.view(torch.int16 if Y.element_size() == 2 else torch.int32))
+
+
+def _small(m, n, r, c, k, p, N, dtype, seed=0, sigma=0.05):
+    return workloads.Config("t", m, n, r, c, k, p, N, dtype, sigma, seed)
+
+
+EDGE = [
+    # shape                                         forced flags
+    (_small(96, 200, 48, 100, 4, 0.2, 1, "f32"), 0),
+    (_small(96, 200, 48, 100, 4, 0.2, 7, "f32"), 0),
+    (_small(33, 77, 3, 7, 3, 0.3, 2, "f32"), 0),             # nothing aligned: scalar loads everywhere
+    (_small(130, 4104, 65, 1368, 9, 0.1, 1, "bf16"), 0),     # n spans three 2048-column segments
+    (_small(130, 4104, 65, 1368, 9, 0.1, 3, "f16"), 0),
+    (_small(128, 192, 64, 64, 8, 0.2, 128, "bf16"), 0),      # one 128x128 tile, 3 slabs
+    (_small(300, 600, 300, 300, 8, 0.12, 20, "f16"), 0),     # unaligned tiles, scalar X path, split
+    (_small(384, 1024, 128, 256, 16, 0.1, 72, "f16"), 0),    # 128x64 tile variant (N in 33..64 -> padded)
+    (_small(384, 1024, 128, 256, 16, 0.1, 40, "bf16"), 0),
+    (_small(200, 1000, 100, 500, 40, 0.05, 136, "bf16"), 0), # rank above 32, ragged m and N
+    (_small(256, 2048, 128, 512, 32, 0.06, 256, "bf16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_splitk(4)),
+    (_small(256, 2048, 128, 512, 32, 0.06, 256, "f16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_splitk(1)),
+    (_small(256, 512, 128, 128, 8, 0.2, 2, "f16"), lrbi.FLAG_PATH_MFMA),   # tiny batch forced onto MFMA
+    (_small(256, 512, 128, 128, 8, 0.2, 64, "bf16"), lrbi.FLAG_PATH_VALU), # big batch forced onto the ALUs
+    (_small(256, 512, 128, 128, 8, 0.2, 96, "bf16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_tile(2)),
+    (_small(256, 512, 128, 128, 8, 0.2, 96, "bf16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_tile(3)),
+]
+
+
+@pytest.mark.parametrize("idx", range(len(EDGE)))
+def test_edge_shapes(idx):
+    cfg, flags = EDGE[idx]
+    print("gemm edge", idx, cfg, hex(flags), flush=True)
+    data = workloads.make(cfg)
+    ref, _ = _oracle(cfg, data)
+    _assert_close(_run(cfg, data, flags=flags), ref, cfg.dtype, "edge%d" % idx)
+
+
+def test_padded_leading_dimensions():
+    for cfg in (_small(128, 256, 64, 128, 8, 0.2, 24, "f16"), _small(128, 256, 64, 128, 8, 0.2, 1, "bf16"),
+                _small(50, 120, 25, 60, 4, 0.2, 3, "f32")):
+        for pad in (8, 3):
+            print("gemm ldpad", cfg.dtype, cfg.N, pad, flush=True)
+            data = workloads.make(cfg)
+            ref, _ = _oracle(cfg, data)
+            _assert_close(_run(cfg, data, ldpad=pad), ref, cfg.dtype, "ldpad")
+
+
+def test_without_workspace_falls_back_to_unsplit_kernel():
+    cfg = _small(300, 600, 300, 300, 8, 0.12, 20, "f16")
+    data = workloads.make(cfg)
+    assert lrbi.masked_gemm_workspace_bytes(desc_of(cfg), lrbi.F16, cfg.N) > 0
+    ref, _ = _oracle(cfg, data)
+    _assert_close(_run(cfg, data, use_workspace=False), ref, cfg.dtype, "no-ws")
+    with pytest.raises(lrbi.LrbiError) as e:
+        _run(cfg, data, flags=lrbi.FLAG_PATH_MFMA | lrbi.flag_splitk(2), use_workspace=False)
+    assert e.value.status == -8
+
+
+@pytest.mark.parametrize("dtype,N", [("f16", 256), ("bf16", 256), ("bf16", 1), ("f32", 1), ("f16", 20)])
+def test_identity_x_returns_masked_weights_exactly(dtype, N):
+    # X = [I | 0]: Y[:, q] = (W o M)[:, q] bit for bit, which isolates the masking
+    cfg = _small(256, 256, 128, 128, 8, 0.2, N, dtype)
+    data = workloads.make(cfg)
+    X = np.zeros((cfg.n, N), np.float32)
+    X[np.arange(min(N, cfg.n)), np.arange(min(N, cfg.n))] = 1.0
+    data["X"] = workloads.to_storage(X, dtype)
+    M = orc.decode_mask(data["Ip01"], data["Iz01"], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    Wm = np.where(M == 1, workloads.to_float64(data["W"], dtype), 0.0)
+    Y = to_float64(_run(cfg, data))
+    assert np.array_equal(Y, Wm[:, :N])
+
+
+@pytest.mark.parametrize("dtype,N", [("f16", 128), ("bf16", 128), ("bf16", 1), ("f32", 2)])
+def test_values_under_pruned_bits_never_reach_y(dtype, N):
+    cfg = _small(256, 512, 128, 256, 8, 0.15, N, dtype)
+    data = workloads.make(cfg)
+    ref, M = _oracle(cfg, data)
+    W = workloads.to_float64(data["W"], dtype).astype(np.float32)
+    poison = np.where(np.arange(cfg.n)[None, :] % 2 == 0, np.nan, np.inf).astype(np.float32)
+    W = np.where(M == 1, W, poison)
+    data["W"] = workloads.to_storage(W, dtype)
+    Y = _run(cfg, data)
+    assert torch.isfinite(Y).all()
+    _assert_close(Y, ref, dtype, "poison")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_output_rounding_is_nearest_even(dtype):
+    # small integers: every product and partial sum is exact in fp32, so the only rounding
+    # is the final one, which must be round-to-nearest-even of the exact result
+    cfg = _small(128, 512, 128, 256, 8, 0.3, 128, dtype)
+    rng = np.random.default_rng(5)
+    data = workloads.make(cfg)
+    data["W"] = workloads.to_storage(rng.integers(-8, 9, (cfg.m, cfg.n)).astype(np.float32), dtype)
+    data["X"] = workloads.to_storage(rng.integers(-8, 9, (cfg.n, cfg.N)).astype(np.float32), dtype)
+    ref, _ = _oracle(cfg, data)
+    assert np.abs(ref).max() > 256  # beyond bf16's exact-integer range, so rounding really happens
+    exp = workloads.to_float64(workloads.to_storage(ref, dtype), dtype)
+    Y = to_float64(_run(cfg, data))
+    assert np.array_equal(Y, exp)
+
+
+def test_all_ones_factors_equal_dense_product():
+    cfg = _small(256, 512, 128, 128, 4, 1.0, 128, "bf16")
+    data = workloads.make(cfg)
+    assert data["Ip01"].all() and data["Iz01"].all()
+    Y = _run(cfg, data)
+    ref = workloads.to_float64(data["W"], "bf16") @ workloads.to_float64(data["X"], "bf16")
+    _assert_close(Y, ref, "bf16", "dense")
+    zero = dict(data, Ip01=data["Ip01"] * 0)
+    assert not to_float64(_run(cfg, zero)).any()
+
+
+def test_full_size_sampled_rows_in_bench_configuration():
+    """C2 at full size in the launch configuration bench.py times, checked on rows the
+    oracle computes one by one (independent of test_config_parity's whole-matrix check)."""
+    cfg = workloads.CONFIGS["C2"]
+    data = workloads.make(cfg)
+    Y = to_float64(_run(cfg, data))
+    Wd = workloads.to_float64(data["W"], cfg.dtype)
+    Xd = workloads.to_float64(data["X"], cfg.dtype)
+    tile_cols = cfg.n // cfg.c
+    rng = np.random.default_rng(3)
+    rms = float(np.sqrt(np.mean(Y * Y)))
+    for i in [0, cfg.m - 1] + [int(v) for v in rng.integers(cfg.m, size=30)]:
+        ti, il = divmod(i, cfg.r)
+        row = np.zeros(cfg.N)
+        for tj in range(tile_cols):
+            t = ti * tile_cols + tj
+            bits = orc.decode_mask(data["Ip01"][t:t + 1, il:il + 1], data["Iz01"][t:t + 1], 1, cfg.c, 1, cfg.c, cfg.k)
+            row += orc.masked_gemm(Wd[i:i + 1, tj * cfg.c:(tj + 1) * cfg.c], bits, Xd[tj * cfg.c:(tj + 1) * cfg.c])[0]
+        err = np.max(np.abs(Y[i] - row) / np.maximum(np.abs(row), rms))
+        assert err <= TOL[cfg.dtype], (i, err)
