@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the LRBI hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input of
+configuration C2 (AlexNet 9216->4096 layer: W 4096x9216 fp16, 256x256 tiles,
+rank 16, Bernoulli(0.08) factors, X 9216x128): index-size accounting (host),
+mask decode to HBM, and the fused masked product that rebuilds the mask in the
+kernel.  Inputs are resident in HBM before the timed region.  Weights rotate
+over several buffers so that W streams from HBM and not from the 256 MB
+last-level cache, as it would inside a network whose layers do not fit there.
+
+Prints ONE JSON line (see README for the fields).  `value` is the
+dense-equivalent TFLOP/s of the step; the decode part of the metric (Gbit/s on a
+mask larger than 1 GiB) and the other configurations ride along as extra keys.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0   # dense bf16 / fp16
+
+
+def _die_multi_gpu(n):
+    print("bench.py measures one GPU: this build has no multi-GPU path (the kernels shard by tile "
+          "rows without any exchange step, see DESIGN.md); --gpus %d is not supported." % n, file=sys.stderr)
+    sys.exit(2)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        _die_multi_gpu(max(args.gpus, int(os.environ.get("WORLD_SIZE", "1"))))
+
+    import numpy as np
+    import torch
+
+    import paper_1905_05686_amd as lrbi
+    import workloads
+
+    lrbi.load_library()  # raises if the HIP library has not been built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    TD = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+    DC = {"f32": lrbi.F32, "f16": lrbi.F16, "bf16": lrbi.BF16}
+
+    def to_dev(a, dtype):
+        if dtype == "bf16":
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    def factors_to_dev(desc, Ip01, Iz01):
+        ip, iz = lrbi.pack_factors(desc, Ip01, Iz01)
+        return torch.from_numpy(ip.view(np.int32)).to(dev), torch.from_numpy(iz.view(np.int64)).to(dev)
+
+    def rotated_weights(W, min_total_bytes=600e6):
+        """Enough independent copies of W that one round trip exceeds the last-level cache."""
+        nbytes = W.numel() * W.element_size()
+        copies = max(2, int(np.ceil(min_total_bytes / nbytes)))
+        out = [W]
+        for i in range(1, copies):
+            out.append(torch.roll(W, shifts=i, dims=0).contiguous())  # same values, different rows/addresses
+        return out
+
+    def event_times(fn_list, iters, warmup):
+        """Average GPU milliseconds of fn (rotating over fn_list) from HIP events on the launch stream."""
+        for i in range(warmup):
+            fn_list[i % len(fn_list)]()
+        torch.cuda.synchronize()
+        evs = []
+        for i in range(iters):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn_list[i % len(fn_list)]()
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in evs)
+        return float(np.mean(ts)), float(ts[len(ts) // 2])
+
+    # ------------------------------------------------------------------ headline: C2
+    cfg = workloads.CONFIGS["C2"]
+    data = workloads.make(cfg)
+    desc = lrbi.Desc(cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    dIp, dIz = factors_to_dev(desc, data["Ip01"], data["Iz01"])
+    Ws = rotated_weights(to_dev(data["W"], cfg.dtype))
+    X = to_dev(data["X"], cfg.dtype)
+    Y = torch.empty((cfg.m, cfg.N), dtype=TD[cfg.dtype], device=dev)
+    mask = torch.empty((cfg.m, ((cfg.n + 127) // 128) * 16), dtype=torch.uint8, device=dev)
+    ws_bytes = lrbi.masked_gemm_workspace_bytes(desc, DC[cfg.dtype], cfg.N)
+    ws = torch.empty(max(1, (ws_bytes + 3) // 4), dtype=torch.float32, device=dev) if ws_bytes else None
+
+    gemm_events = []
+
+    def step(i, record=False):
+        lrbi.index_bits(desc)
+        lrbi.decode_mask(desc, dIp, dIz, out=mask)
+        if record:
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+        lrbi.masked_gemm(desc, Ws[i % len(Ws)], dIp, dIz, X, out=Y, workspace=ws)
+        if record:
+            e1.record()
+            gemm_events.append((e0, e1))
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, record=True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flops = 2.0 * cfg.m * cfg.n * cfg.N
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in gemm_events]))
+    es = 2
+    factor_bytes = lrbi.index_bits(desc)["lrbi_bits"] / 8
+    gemm_bytes = cfg.m * cfg.n * es + cfg.n * cfg.N * es + cfg.m * cfg.N * es + factor_bytes
+    achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "lrbi_masked_gemm (mfma_gemm_kernel + splitk_reduce_kernel)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_ms": round(gemm_ms, 5), "algorithmic_bytes": int(gemm_bytes),
+                "tflops_dense_equiv": round(flops / (gemm_ms * 1e-3) / 1e12, 1),
+                "mfma_frac": round(flops / (gemm_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)}
+
+    # decode kernel inside the same step (4.5 MiB mask: launch-latency bound)
+    dec_ms, _ = event_times([lambda: lrbi.decode_mask(desc, dIp, dIz, out=mask)], 100, 10)
+
+    out = {
+        "metric": "mask decode Gbit/s + fused masked-GEMM TFLOP/s (dense-equiv), % of roofline",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "C2: W 4096x9216 fp16 N(0,0.01), tiles 256x256, rank 16, factors Bernoulli(0.08), "
+                               "X 9216x128; step = index_bits + decode_mask to HBM + fused masked_gemm; "
+                               "W rotated over %d buffers (HBM-cold)" % len(Ws)},
+        "value_note": "dense-equivalent 2*m*n*N flops over the whole step (decode + fused product)",
+        "roofline": roofline,
+        "decode_in_step": {"mask_bits": cfg.m * cfg.n, "avg_launch_ms": round(dec_ms, 5),
+                           "gbit_s": round(cfg.m * cfg.n / (dec_ms * 1e-3) / 1e9, 1)},
+    }
+
+    # ------------------------------------------------------------------ extras
+    if not args.no_others:
+        others = {}
+        # decode on a mask above 1 GiB (C3 tile shape), factors drawn on the device
+        try:
+            c3 = workloads.CONFIGS["C3a"]
+            big = workloads.scaled(c3, m=65536, n=131072)
+            bdesc = lrbi.Desc(big.m, big.n, big.r, big.c, big.k)
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(0)
+            sizes = lrbi.index_bits(bdesc)
+            T = big.tiles
+            weights = (2 ** torch.arange(32, device=dev, dtype=torch.int64))
+
+            def packed_bernoulli(rows, bits_per_row, words_per_row):
+                outw = torch.empty((rows, words_per_row), dtype=torch.int32, device=dev)
+                chunk = 1 << 20
+                for lo in range(0, rows, chunk):
+                    hi = min(rows, lo + chunk)
+                    for w in range(words_per_row):
+                        nb = min(32, bits_per_row - 32 * w)
+                        if nb <= 0:
+                            outw[lo:hi, w] = 0
+                            continue
+                        b = (torch.rand((hi - lo, nb), device=dev, generator=gen) < big.p).to(torch.int64)
+                        v = (b * weights[:nb]).sum(dim=1)
+                        outw[lo:hi, w] = torch.where(v >= 2 ** 31, v - 2 ** 32, v).to(torch.int32)
+                return outw
+
+            bIp = packed_bernoulli(T * big.r, big.k, (big.k + 31) // 32)
+            bIz = packed_bernoulli(T * big.k, big.c, 2 * ((big.c + 63) // 64))
+            assert bIp.numel() * 4 == sizes["packed_ip_bytes"] and bIz.numel() * 4 == sizes["packed_iz_bytes"]
+            bmask = torch.empty((big.m, big.n // 8), dtype=torch.uint8, device=dev)
+            ms, med = event_times([lambda: lrbi.decode_mask(bdesc, bIp, bIz, out=bmask)], 20, 3)
+            mask_bytes = big.m * big.n / 8
+            others["decode_scaled"] = {
+                "workload": "C3 tile shape (512x512, rank 32, p=0.06) on a 65536x131072 mask (1 GiB)",
+                "avg_launch_ms": round(ms, 4), "gbit_s": round(big.m * big.n / (ms * 1e-3) / 1e9, 1),
+                "write_GBs": round(mask_bytes / (ms * 1e-3) / 1e9, 1),
+                "hbm_frac_on_mask_bytes_written": round(mask_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del bIp, bIz, bmask
+        except Exception as e:  # keep the headline line even if an extra fails
+            others["decode_scaled"] = {"error": repr(e)}
+
+        for name in ("C3a", "C3b", "C4", "C5", "C1"):
+            try:
+                c = workloads.CONFIGS[name]
+                d = workloads.make(c)
+                de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
+                ip_, iz_ = factors_to_dev(de, d["Ip01"], d["Iz01"])
+                Wl = rotated_weights(to_dev(d["W"], c.dtype))
+                X_ = to_dev(d["X"], c.dtype)
+                Y_ = torch.empty((c.m, c.N), dtype=TD[c.dtype], device=dev)
+                wb = lrbi.masked_gemm_workspace_bytes(de, DC[c.dtype], c.N)
+                w_ = torch.empty(max(1, (wb + 3) // 4), dtype=torch.float32, device=dev) if wb else None
+                fns = [(lambda Wi=Wi: lrbi.masked_gemm(de, Wi, ip_, iz_, X_, out=Y_, workspace=w_)) for Wi in Wl]
+                ms, med = event_times(fns, 60, 10)
+                ms_warm, _ = event_times(fns[:1], 60, 10)
+                esz = 4 if c.dtype == "f32" else 2
+                byts = (c.m * c.n + c.n * c.N + c.m * c.N) * esz + lrbi.index_bits(de)["lrbi_bits"] / 8
+                fl = 2.0 * c.m * c.n * c.N
+                others[name] = {"N": c.N, "dtype": c.dtype, "avg_launch_ms_cold": round(ms, 5),
+                                "avg_launch_ms_warm": round(ms_warm, 5),
+                                "tflops_dense_equiv": round(fl / (ms * 1e-3) / 1e12, 2),
+                                "mfma_frac": round(fl / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
+                                "GBs": round(byts / (ms * 1e-3) / 1e9, 1),
+                                "hbm_frac": round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                del Wl, X_, Y_
+            except Exception as e:
+                others[name] = {"error": repr(e)}
+        out["others"] = others
+
+    # ------------------------------------------------------------------ oracle on the host cores
+    if not args.no_cpu:
+        from oracle import lrbi_oracle as orc
+        cores = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)))
+        Wd = workloads.to_float64(data["W"], cfg.dtype)
+        Xd = workloads.to_float64(data["X"], cfg.dtype)
+        c0 = time.perf_counter()
+        M = orc.decode_mask(data["Ip01"], data["Iz01"], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+        c1 = time.perf_counter()
+        orc.masked_gemm(Wd, M, Xd, threads=cores)
+        c2 = time.perf_counter()
+        out["cpu_baseline"] = {
+            "value": round(flops / (c2 - c0) / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "the whole C2 step once: plain-C decode of the 4096x9216 mask (1 thread, %.2f s) + fp64 masked "
+                      "product at N=128 (OpenMP over rows, %d threads, %.2f s)" % (c1 - c0, cores, c2 - c1),
+            "decode_gbit_s": round(cfg.m * cfg.n / (c1 - c0) / 1e9, 4)}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
