@@ -24,9 +24,22 @@
 // When m * N yields too few tiles to fill 256 compute units, the n range is cut
 // into `splitk` slices; slices write fp32 partial tiles to the caller's
 // workspace and a second kernel adds them in slice order (deterministic).
+#include <type_traits>
+#include <utility>
+
 #include "lrbi_internal.hpp"
 
 namespace lrbi {
+
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <typename F, int... Is> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -352,51 +365,398 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 }
 
 // ---------------------------------------------------------------------------
+// Panel kernel: the fast path for tile shapes that line up with the kernel's
+// blocking (c % 128 == 0, r % BM == 0, k <= 64).
+//
+// Differences from the kernel above:
+//   * The mask is rebuilt one PANEL (512 columns = 8 slabs) at a time and two
+//     slabs ahead of its first use, entirely from LDS: the panel's slice of the
+//     I_z rows ("Fz", k x 512 bits) and the I_p words of the workgroup's rows
+//     ("Fip") are fetched with plain loads while earlier slabs are multiplied,
+//     so no dependent global load sits in front of an MFMA.
+//   * X operands come out of LDS with the gfx950 transposing read
+//     (ds_read_b64_tr_b16): X stays in its natural [k][n] order and each lane
+//     still receives 8 consecutive k of one column.
+//   * Global loads run RS slabs ahead of the LDS staging (register stages).
+// ---------------------------------------------------------------------------
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// 4(k) x 16(n) block of 16-bit values -> lane d of each 16-lane group gets column d, rows 0..3.
+// Lane s of the group passes the address of row s / 4, columns 4 * (s % 4) .. + 3.
+__device__ __forceinline__ uint2 lds_read_tr16(const uint16_t *p)
+{
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
+    return __builtin_bit_cast(uint2, v);
+}
+
+static constexpr int PW = 512;           // panel width in columns
+static constexpr int PANEL_SLABS = PW / BK;
+static constexpr int PANEL_WORDS = PW / 32;
+static constexpr int PANEL_UNITS = PW / 128; // 128-column units; each lies inside one tile
+static constexpr int FAST_MAX_K = 64;
+
+template <int BM, int BN> struct SmemPanel {
+    static constexpr int XPAD = (BN >= 64) ? 32 : 8; // halfs; keeps the transposing reads off shared banks
+    static constexpr int XS_STRIDE = BN + XPAD;
+    static constexpr int ws_halfs = BM * WS_STRIDE;
+    static constexpr int xs_halfs = BK * XS_STRIDE;
+    static constexpr int ms_words = BM * PANEL_WORDS;
+    static constexpr int fz_words = FAST_MAX_K * PANEL_WORDS;
+    static constexpr int fip_words = BM * PANEL_UNITS * 2;
+    static constexpr size_t bytes =
+        2 * (size_t)(ws_halfs + xs_halfs) * 2 + 2 * (size_t)(ms_words + fz_words + fip_words) * 4;
+};
+
+template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N, int RS, bool XVEC, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
+    Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
+    const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ X, int64_t ldx, int N,
+    uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ P, int64_t ldp, int mblocks, int nblocks,
+    int64_t kper, int xcd_remap, int y_vec_ok)
+{
+    static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    static_assert(FM >= 1 && FN >= 1, "wave tile must hold a 32x32 block");
+    using S = SmemPanel<BM, BN>;
+    constexpr int XS_STRIDE = S::XS_STRIDE;
+    constexpr int W_CHUNKS = BM * (BK / 8) / kThreads;
+    constexpr int X_CPR = BN / 8;
+    constexpr int X_CHUNKS = (BK * X_CPR + kThreads - 1) / kThreads;
+    constexpr int FZ_LOADS = FAST_MAX_K * PANEL_WORDS / kThreads;      // 4
+    constexpr int FIP_LOADS = (BM * PANEL_UNITS * 2 + kThreads - 1) / kThreads; // 4 for BM = 128
+    constexpr int UNITS = (BM * PANEL_UNITS + kThreads - 1) / kThreads; // 2 for BM = 128
+    static_assert(BM * (BK / 8) % kThreads == 0, "W slab must split evenly");
+
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    uint16_t *Ws = (uint16_t *)lrbi_dyn_smem;            // [2][BM][WS_STRIDE]
+    uint16_t *Xs = Ws + 2 * S::ws_halfs;                 // [2][BK][XS_STRIDE]
+    uint32_t *Ms = (uint32_t *)(Xs + 2 * S::xs_halfs);   // [2][BM][PANEL_WORDS]   mask panels
+    uint32_t *Fz = Ms + 2 * S::ms_words;                 // [2][64][PANEL_WORDS]   I_z rows under the panel
+    uint32_t *Fip = Fz + 2 * S::fz_words;                // [2][BM][PANEL_UNITS][2] I_p words per row and unit
+
+    int64_t bid = blockIdx.x;
+    if (xcd_remap) {
+        const int64_t per = gridDim.x / 8;
+        bid = (bid % 8) * per + bid / 8;
+    }
+    const int ni = (int)(bid % nblocks);
+    const int mi = (int)((bid / nblocks) % mblocks);
+    const int slice = (int)(bid / ((int64_t)nblocks * mblocks));
+    const int64_t m0 = (int64_t)mi * BM;
+    const int n0 = ni * BN;
+    const int kbeg = (int)(slice * kper);
+    const int kend = (int)((kbeg + kper < g.n) ? kbeg + kper : g.n);
+    const int nslabs = (kend - kbeg + BK - 1) / BK;
+    const int npanels = (nslabs + PANEL_SLABS - 1) / PANEL_SLABS;
+    // the workgroup's rows lie inside one tile row (r % BM == 0)
+    const int ti = (int)(m0 / g.r);
+    const int il0 = (int)(m0 - (int64_t)ti * g.r);
+    const int64_t trow = (int64_t)ti * g.tile_cols;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int l32 = lane & 31, lg = lane >> 5;
+
+    uint4 wreg[RS][W_CHUNKS];
+    uint4 xreg[RS][X_CHUNKS];
+    uint32_t fzreg[FZ_LOADS];
+    uint32_t fipreg[FIP_LOADS];
+
+    auto load_slab = [&](int slab, auto stage_c) {
+        constexpr int st = decltype(stage_c)::value;
+        const int k0 = kbeg + slab * BK;
+#pragma unroll
+        for (int i = 0; i < W_CHUNKS; ++i) {
+            const int id = tid + kThreads * i;
+            const int row = id >> 3, kc = id & 7;
+            const int64_t gr = m0 + row;
+            const int kk = k0 + kc * 8;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (gr < g.m && kk < kend) v = *reinterpret_cast<const uint4 *>(W + gr * ldw + kk);
+            wreg[st][i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < X_CHUNKS; ++i) {
+            const int id = tid + kThreads * i;
+            const int krow = id / X_CPR, nc = id % X_CPR;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (id < BK * X_CPR) {
+                const int kk = k0 + krow;
+                const int nn = n0 + nc * 8;
+                if (kk < kend) {
+                    if (XVEC) {
+                        if (nn < N) v = *reinterpret_cast<const uint4 *>(X + (int64_t)kk * ldx + nn);
+                    } else {
+                        uint16_t tmp[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) tmp[e] = (nn + e < N) ? X[(int64_t)kk * ldx + nn + e] : (uint16_t)0;
+                        v = *reinterpret_cast<uint4 *>(tmp);
+                    }
+                }
+            }
+            xreg[st][i] = v;
+        }
+    };
+
+    auto stage_slab = [&](int slab, auto stage_c) {
+        constexpr int st = decltype(stage_c)::value;
+        const int buf = slab & 1;
+        uint16_t *ws = Ws + buf * S::ws_halfs;
+        uint16_t *xs = Xs + buf * S::xs_halfs;
+        const int panel = slab / PANEL_SLABS;
+        const unsigned char *mb =
+            (const unsigned char *)(Ms + (panel & 1) * S::ms_words) + (slab % PANEL_SLABS) * (BK / 8);
+#pragma unroll
+        for (int i = 0; i < W_CHUNKS; ++i) {
+            const int id = tid + kThreads * i;
+            const int row = id >> 3, kc = id & 7;
+            const uint32_t bits = mb[row * (PANEL_WORDS * 4) + kc];
+            *reinterpret_cast<uint4 *>(ws + row * WS_STRIDE + kc * 8) = apply_mask8(wreg[st][i], bits);
+        }
+#pragma unroll
+        for (int i = 0; i < X_CHUNKS; ++i) {
+            const int id = tid + kThreads * i;
+            if (id < BK * X_CPR) {
+                const int krow = id / X_CPR, nc = id % X_CPR;
+                *reinterpret_cast<uint4 *>(xs + krow * XS_STRIDE + nc * 8) = xreg[st][i];
+            }
+        }
+    };
+
+    // factor slices of one panel: global -> registers
+    auto load_factors = [&](int panel) {
+        const int kp = kbeg + panel * PW;
+#pragma unroll
+        for (int i = 0; i < FZ_LOADS; ++i) {
+            const int idx = tid + kThreads * i;
+            const int l = idx / PANEL_WORDS, w = idx % PANEL_WORDS;
+            const int col = kp + 32 * w;
+            uint32_t v = 0u;
+            if (l < g.k && col < kend) {
+                const int tj = col / g.c;
+                v = Iz[((trow + tj) * g.k + l) * g.izw + ((col - tj * g.c) >> 5)];
+            }
+            fzreg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < FIP_LOADS; ++i) {
+            const int idx = tid + kThreads * i;
+            const int row = idx / (PANEL_UNITS * 2), u = (idx / 2) % PANEL_UNITS, iw = idx & 1;
+            const int col = kp + 128 * u;
+            uint32_t v = 0u;
+            if (idx < BM * PANEL_UNITS * 2 && iw < g.ipw && m0 + row < g.m && col < kend) {
+                const int tj = col / g.c;
+                v = Ip[((trow + tj) * g.r + il0 + row) * g.ipw + iw];
+            }
+            fipreg[i] = v;
+        }
+    };
+    // registers -> LDS
+    auto store_factors = [&](int panel) {
+        uint32_t *fz = Fz + (panel & 1) * S::fz_words;
+        uint32_t *fip = Fip + (panel & 1) * S::fip_words;
+#pragma unroll
+        for (int i = 0; i < FZ_LOADS; ++i) fz[tid + kThreads * i] = fzreg[i];
+#pragma unroll
+        for (int i = 0; i < FIP_LOADS; ++i) {
+            const int idx = tid + kThreads * i;
+            if (idx < BM * PANEL_UNITS * 2) fip[idx] = fipreg[i];
+        }
+    };
+    // Eq. 3 for the panel: mask row piece = OR of the Fz pieces selected by the set bits of the I_p words
+    auto decode_panel = [&](int panel) {
+        const uint32_t *fz = Fz + (panel & 1) * S::fz_words;
+        const uint32_t *fip = Fip + (panel & 1) * S::fip_words;
+        uint32_t *ms = Ms + (panel & 1) * S::ms_words;
+#pragma unroll
+        for (int i = 0; i < UNITS; ++i) {
+            const int uid = tid + kThreads * i;
+            if (uid < BM * PANEL_UNITS) {
+                const int row = uid / PANEL_UNITS, u = uid % PANEL_UNITS;
+                uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+                for (int iw = 0; iw < 2; ++iw) {
+                    uint32_t sel = fip[(row * PANEL_UNITS + u) * 2 + iw];
+                    while (sel) {
+                        const int l = __builtin_ctz(sel) + 32 * iw;
+                        sel &= sel - 1u;
+                        const uint4 z = *reinterpret_cast<const uint4 *>(fz + l * PANEL_WORDS + 4 * u);
+                        acc.x |= z.x;
+                        acc.y |= z.y;
+                        acc.z |= z.z;
+                        acc.w |= z.w;
+                    }
+                }
+                *reinterpret_cast<uint4 *>(ms + row * PANEL_WORDS + 4 * u) = acc;
+            }
+        }
+    };
+
+    f32x16 acc[FN][FM];
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    auto compute_slab = [&](int slab) {
+        const int buf = slab & 1;
+        const uint16_t *ws = Ws + buf * S::ws_halfs;
+        const uint16_t *xs = Xs + buf * S::xs_halfs;
+        // transposing read: 16-lane group G = lane / 16 serves columns 16 * (G % 2) .. + 15 of a
+        // 32-column block and k group G / 2; lane d of the group addresses row d / 4, columns 4 * (d % 4)
+        const int d16 = lane & 15, G = lane >> 4;
+        const uint16_t *xbase = xs + (8 * (G >> 1) + (d16 >> 2)) * XS_STRIDE + wn * WN + 16 * (G & 1) + 4 * (d16 & 3);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            uint4 wf[FM], xf[FN];
+#pragma unroll
+            for (int b = 0; b < FM; ++b)
+                wf[b] = *reinterpret_cast<const uint4 *>(ws + (wm * WM + b * 32 + l32) * WS_STRIDE + kk * 16 + 8 * lg);
+#pragma unroll
+            for (int a = 0; a < FN; ++a) {
+                const uint16_t *p = xbase + (kk * 16) * XS_STRIDE + a * 32;
+                const uint2 lo = lds_read_tr16(p);
+                const uint2 hi = lds_read_tr16(p + 4 * XS_STRIDE);
+                xf[a] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            }
+#pragma unroll
+            for (int a = 0; a < FN; ++a)
+#pragma unroll
+                for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(Tag{}, xf[a], wf[b], acc[a][b]);
+        }
+    };
+
+    // ---- prologue: factors and mask of panel 0, slabs 0 .. RS-1 in flight, slab 0 staged
+    load_factors(0);
+    static_for<RS>([&](auto sc) {
+        constexpr int st = decltype(sc)::value;
+        if (st < nslabs) load_slab(st, sc);
+    });
+    store_factors(0);
+    __syncthreads();
+    decode_panel(0);
+    __syncthreads();
+    stage_slab(0, std::integral_constant<int, 0>{});
+    if (RS < nslabs) load_slab(RS, std::integral_constant<int, 0>{});
+    __syncthreads();
+
+    // ---- main loop, unrolled by RS so that register stages are compile-time
+    for (int s0 = 0; s0 < nslabs; s0 += RS) {
+        static_for<RS>([&](auto sc) {
+            constexpr int j = decltype(sc)::value;
+            const int s = s0 + j;
+            if (s < nslabs) {
+                using NextStage = std::integral_constant<int, (j + 1) % RS>;
+                compute_slab(s);
+                if (s + 1 < nslabs) stage_slab(s + 1, NextStage{});
+                if (s + 1 + RS < nslabs) load_slab(s + 1 + RS, NextStage{});
+                // next panel's factors and mask, spread over three slabs
+                const int ps = s % PANEL_SLABS;
+                const int next_panel = s / PANEL_SLABS + 1;
+                if (next_panel < npanels) {
+                    if (ps == 0) load_factors(next_panel);
+                    if (ps == 1) store_factors(next_panel);
+                    if (ps == 2) decode_panel(next_panel);
+                }
+                __syncthreads();
+            }
+        });
+    }
+
+    // epilogue: lane holds, per 32x32 block, rows n = 8*(v/4) + 4*lg + (v%4) and column m = l32
+#pragma unroll
+    for (int a = 0; a < FN; ++a) {
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+            const int64_t row = m0 + wm * WM + b * 32 + l32;
+            if (row >= g.m) continue;
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int col = n0 + wn * WN + a * 32 + 8 * v4 + 4 * lg;
+                if (SPLIT) {
+                    if (col < ldp) {
+                        float4 o = make_float4(acc[a][b][4 * v4 + 0], acc[a][b][4 * v4 + 1], acc[a][b][4 * v4 + 2],
+                                               acc[a][b][4 * v4 + 3]);
+                        *reinterpret_cast<float4 *>(P + ((int64_t)slice * g.m + row) * ldp + col) = o;
+                    }
+                } else {
+                    uint16_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = cvt_store(Tag{}, acc[a][b][4 * v4 + e]);
+                    if (y_vec_ok && col + 3 < N) {
+                        *reinterpret_cast<uint2 *>(Y + row * ldy + col) = *reinterpret_cast<uint2 *>(o);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < N) Y[row * ldy + col + e] = o[e];
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 
 struct TileDef {
     int bm, bn;
+    bool panel; // panel kernel (needs c % 128 == 0, r % bm == 0, k <= 64)
 };
-// tile ids 1..3 (desc.flags bits 16..19); 0 = automatic
-static const TileDef kTiles[] = {{0, 0}, {128, 128}, {128, 64}, {128, 32}};
-static constexpr int kNumTiles = 3;
+// tile ids (desc.flags bits 16..19); 0 = automatic.  1-3: generic kernel, 4-8: panel kernel.
+static const TileDef kTiles[] = {{0, 0, false},   {128, 128, false}, {128, 64, false}, {128, 32, false},
+                                 {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
+                                 {128, 128, true}};
+static constexpr int kNumTiles = 8;
+
+static bool panel_ok(const Geom &g, int bm) { return (g.c % 128 == 0) && (g.r % bm == 0) && (g.k <= FAST_MAX_K); }
 
 MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
 {
     MfmaPlan p;
     int tile = (int)((flags & LRBI_FLAG_TILE_MASK) >> LRBI_FLAG_TILE_SHIFT);
-    if (tile < 1 || tile > kNumTiles) tile = (N > 64) ? 1 : (N > 32 ? 2 : 3);
+    if (tile >= 1 && tile <= kNumTiles && kTiles[tile].panel && !panel_ok(g, kTiles[tile].bm)) tile = 0;
+    if (tile < 1 || tile > kNumTiles) {
+        tile = (N > 64) ? 1 : (N > 32 ? 2 : 3);
+        if (panel_ok(g, 128)) tile = (N > 64) ? 4 : (N > 32 ? 6 : 7);
+    }
     p.tile = tile;
     p.bm = kTiles[tile].bm;
     p.bn = kTiles[tile].bn;
     const int64_t mblocks = (g.m + p.bm - 1) / p.bm;
     const int64_t nblocks = (N + p.bn - 1) / p.bn;
     const int64_t tiles = mblocks * nblocks;
-    const int64_t nslabs = (g.n + BK - 1) / BK;
+    const int64_t npairs = (g.n + 2 * BK - 1) / (2 * BK); // slices are cut at multiples of 128 columns
     int split = (int)((flags & LRBI_FLAG_SPLITK_MASK) >> LRBI_FLAG_SPLITK_SHIFT);
     if (split == 0) {
         split = 1;
         if (tiles < 192) {
-            // aim at about two workgroups per compute unit, at least 4 slabs per slice
+            // aim at about two workgroups per compute unit, at least 8 slabs per slice
             int64_t want = (512 + tiles - 1) / tiles;
-            const int64_t cap = nslabs / 4 > 1 ? nslabs / 4 : 1;
+            const int64_t cap = npairs / 4 > 1 ? npairs / 4 : 1;
             if (want > cap) want = cap;
             if (want > 64) want = 64;
             split = (int)(want < 1 ? 1 : want);
         }
     }
-    if (split > nslabs) split = (int)nslabs;
-    int64_t slabs_per = (nslabs + split - 1) / split;
-    split = (int)((nslabs + slabs_per - 1) / slabs_per); // no empty slice
+    if (split > npairs) split = (int)npairs;
+    int64_t pairs_per = (npairs + split - 1) / split;
+    split = (int)((npairs + pairs_per - 1) / pairs_per); // no empty slice
     p.splitk = split;
-    p.kper = slabs_per * BK;
+    p.kper = pairs_per * 2 * BK;
     const int64_t ldp = (N + 3) / 4 * 4;
     p.workspace_bytes = (split > 1) ? (uint64_t)split * (uint64_t)g.m * (uint64_t)ldp * 4u : 0u;
     return p;
 }
 
-template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N>
+template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N, int RS /* 0: generic kernel */>
 static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
                        const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
                        void *dWorkspace, hipStream_t stream)
@@ -411,31 +771,46 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
     const int y_vec_ok = (((uintptr_t)dY & 7) == 0) && (ldy % 4 == 0);
     const int xcd_remap = (blocks % 8 == 0) ? 1 : 0;
     const int64_t ldp = (N + 3) / 4 * 4;
-    const size_t smem = Smem<BM, BN>::bytes;
     const dim3 grid((unsigned)blocks), block(kThreads);
 
-#define LRBI_LAUNCH(AL, XV, SP)                                                                                   \
+#define LRBI_LAUNCH(KERN, SMEM)                                                                                   \
     do {                                                                                                          \
-        auto kern = mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, AL, XV, SP>;                                  \
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) !=     \
+        auto kern = KERN;                                                                                         \
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(SMEM)) !=   \
             hipSuccess)                                                                                           \
             return LRBI_ERR_LAUNCH;                                                                               \
-        hipLaunchKernelGGL(kern, grid, block, smem, stream, g, (const uint16_t *)dW, ldw, dIp, dIz,               \
+        hipLaunchKernelGGL(kern, grid, block, (SMEM), stream, g, (const uint16_t *)dW, ldw, dIp, dIz,             \
                            (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp,      \
                            (int)mblocks, (int)nblocks, plan.kper, xcd_remap, y_vec_ok);                           \
     } while (0)
 
-    if (aligned) {
+    if constexpr (RS > 0) {
+        const size_t smem = SmemPanel<BM, BN>::bytes;
         if (xvec) {
-            if (split) LRBI_LAUNCH(true, true, true); else LRBI_LAUNCH(true, true, false);
+            if (split) LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, RS, true, true>), smem);
+            else LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, RS, true, false>), smem);
         } else {
-            if (split) LRBI_LAUNCH(true, false, true); else LRBI_LAUNCH(true, false, false);
+            if (split) LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, RS, false, true>), smem);
+            else LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, RS, false, false>), smem);
         }
     } else {
-        if (xvec) {
-            if (split) LRBI_LAUNCH(false, true, true); else LRBI_LAUNCH(false, true, false);
+        const size_t smem = Smem<BM, BN>::bytes;
+        if (aligned) {
+            if (xvec) {
+                if (split) LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, true>), smem);
+                else LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, false>), smem);
+            } else {
+                if (split) LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, true>), smem);
+                else LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, false>), smem);
+            }
         } else {
-            if (split) LRBI_LAUNCH(false, false, true); else LRBI_LAUNCH(false, false, false);
+            if (xvec) {
+                if (split) LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, true>), smem);
+                else LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, false>), smem);
+            } else {
+                if (split) LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, true>), smem);
+                else LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, false>), smem);
+            }
         }
     }
 #undef LRBI_LAUNCH
@@ -452,18 +827,25 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
     return LRBI_OK;
 }
 
+#define LRBI_TILE_ARGS g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream
 template <typename Tag>
 static int launch_dtype(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
                         const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
                         void *dWorkspace, hipStream_t stream)
 {
     switch (plan.tile) {
-    case 1: return launch_tile<Tag, 128, 128, 2, 2>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
-    case 2: return launch_tile<Tag, 128, 64, 2, 2>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
-    case 3: return launch_tile<Tag, 128, 32, 4, 1>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+    case 1: return launch_tile<Tag, 128, 128, 2, 2, 0>(LRBI_TILE_ARGS);
+    case 2: return launch_tile<Tag, 128, 64, 2, 2, 0>(LRBI_TILE_ARGS);
+    case 3: return launch_tile<Tag, 128, 32, 4, 1, 0>(LRBI_TILE_ARGS);
+    case 4: return launch_tile<Tag, 128, 128, 2, 2, 2>(LRBI_TILE_ARGS);
+    case 5: return launch_tile<Tag, 128, 128, 2, 2, 3>(LRBI_TILE_ARGS);
+    case 6: return launch_tile<Tag, 128, 64, 2, 2, 2>(LRBI_TILE_ARGS);
+    case 7: return launch_tile<Tag, 128, 32, 4, 1, 3>(LRBI_TILE_ARGS);
+    case 8: return launch_tile<Tag, 128, 128, 2, 2, 1>(LRBI_TILE_ARGS);
     default: return LRBI_ERR_FLAGS;
     }
 }
+#undef LRBI_TILE_ARGS
 
 int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const void *dW, int64_t ldw,
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY,
