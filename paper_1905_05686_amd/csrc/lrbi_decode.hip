@@ -1,24 +1,36 @@
 // Mask decode to HBM: I_a,t = I_p,t (x) I_z,t for every tile (Eq. 3, Sec. 3.1),
 // written as the one-bit-per-weight binary index form (Fig. 1).
 //
-// The kernel is bound by HBM stores when the integer work per 32-bit mask word
-// stays small, so the design spends almost nothing per word:
-//   * a workgroup owns a band of rows of one tile row and a span of columns;
-//   * it first copies the I_z rows of every tile under that span into LDS,
-//     shifted to their absolute bit position in the mask row ("Z table":
-//     Z[l] is the concatenation over tiles of row l of each tile's I_z), so
-//     tile boundaries that fall inside a word are resolved once per band and
-//     not once per mask row;
-//   * a lane then produces 128 mask bits at a time: it walks the SET bits of the
-//     I_p row (about k*p of them) and ORs the matching 16-byte pieces of Z;
+// The kernel should be bound by HBM stores, so the integer work per 32-bit mask
+// word is kept small and every load is taken off the path of the stores:
+//   * a work item is a band of rows of one tile row times a span of columns
+//     (at most 64 16-byte pieces, i.e. one wavefront across);
+//   * for an item the workgroup holds in LDS (a) the "Z table": the I_z rows of
+//     every tile under the span, shifted to their absolute bit position in the
+//     mask row (Z[l] is the concatenation over tiles of row l of each tile's
+//     I_z), so tile boundaries that fall inside a word are resolved once per
+//     item and not once per mask row, and (b) the I_p words of the band's rows;
+//   * a lane produces 128 mask bits at a time: it walks the SET bits of the I_p
+//     word (about k*p of them) and ORs the matching 16-byte pieces of Z;
 //   * consecutive lanes hold consecutive 16-byte pieces of one mask row, so the
 //     stores are full-width and coalesced.
+// Two kernels share that code.  The one-shot kernel takes one item per
+// workgroup (small masks).  The streaming kernel is persistent: one workgroup of
+// 1024 lanes per compute unit walks many items with the two LDS tables double
+// buffered, and the global loads of the next item's factors are in flight while
+// the current item's rows are decoded and stored, so stores never wait for loads.
+#include <stdlib.h>
+
 #include "lrbi_internal.hpp"
 
 namespace lrbi {
 
 static constexpr int kDecodeThreads = 256;
-static constexpr int kZTableBudgetBytes = 32 * 1024;
+static constexpr int kStreamThreads = 1024;
+static constexpr int kZTableBudgetBytes = 32 * 1024; // (k + 1) * span pieces * 16 bytes
+static constexpr int kIpBudgetBytes = 12 * 1024;     // tiles under the span * (rows + 1) * ipw * 4 bytes
+static constexpr int kMaxZPerLane = kZTableBudgetBytes / 16 / kStreamThreads;  // 16-byte pieces per lane and item
+static constexpr int kMaxIpPerLane = kIpBudgetBytes / 4 / kStreamThreads;      // words per lane and item
 
 // Fallback without LDS: every lane decodes its four words straight from global memory.
 __global__ __launch_bounds__(kDecodeThreads) void decode_generic_kernel(Geom g, const uint32_t *__restrict__ Ip,
@@ -40,18 +52,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_generic_kernel(Geom g, 
     mask[row * pitch16 + q] = out;
 }
 
-// One 32-bit word of Z[l] at absolute word index w of the mask row (tile row ti).
-template <bool ALIGNED>
+// One 32-bit word of Z[l] at absolute word index w of the mask row (tile row ti); any c.
 __device__ __forceinline__ uint32_t ztable_word(const Geom &g, const uint32_t *__restrict__ Iz, int ti, int l, int w)
 {
     const int64_t j0 = (int64_t)w * 32;
     if (j0 >= g.n) return 0u;
-    if (ALIGNED) { // c is a multiple of 32: the word lies inside one tile
-        const int wpt = g.c >> 5;
-        const int tj = w / wpt;
-        const int64_t t = (int64_t)ti * g.tile_cols + tj;
-        return Iz[(t * g.k + l) * g.izw + (w - tj * wpt)];
-    }
     const int64_t j1 = (j0 + 32 < g.n) ? j0 + 32 : g.n;
     int tj = (int)(j0 / g.c);
     uint32_t acc = 0u;
@@ -69,69 +74,124 @@ __device__ __forceinline__ uint4 or4(uint4 a, uint4 b)
     return make_uint4(a.x | b.x, a.y | b.y, a.z | b.z, a.w | b.w);
 }
 
-// ALIGNED: c % 128 == 0, every 128-bit piece lies inside one tile.
-// Grid: blockIdx.x enumerates (row band, column span) with the span fastest.
-template <bool ALIGNED>
-__global__ __launch_bounds__(kDecodeThreads) void decode_ztable_kernel(
-    Geom g, const uint32_t *__restrict__ Ip, const uint32_t *__restrict__ Iz, uint4 *__restrict__ mask,
-    int64_t pitch16, int chunks /* 16-byte pieces per mask row */, int span_chunks, int spans,
-    int rows_per_band, int bands_per_tile_row, int tx_log2)
+// OR of the Z-table pieces selected by the set bits of one I_p word.  The first two reads are
+// issued back to back (their LDS latencies overlap); `zero_row` is an all-zero row of the table
+// that absorbs the slots of words with fewer set bits.  Leftover bits take the loop.
+__device__ __forceinline__ uint4 or_selected(uint4 acc, uint32_t sel, int l_base, const uint4 *__restrict__ Zq,
+                                             int zstride, int zero_row)
 {
-    extern __shared__ uint4 lrbi_dyn_smem[];
-    uint4 *Z = lrbi_dyn_smem; // [k][span_chunks]
-    const int64_t bid = blockIdx.x;
-    const int span = (int)(bid % spans);
-    const int64_t band = bid / spans;
-    const int ti = (int)(band / bands_per_tile_row);
-    const int row_lo = (int)(band - (int64_t)ti * bands_per_tile_row) * rows_per_band;
-    const int row_hi = (row_lo + rows_per_band < g.r) ? row_lo + rows_per_band : g.r;
-    const int q_lo = span * span_chunks;
-    const int nq = (q_lo + span_chunks <= chunks) ? span_chunks : chunks - q_lo;
-
-    // build the Z table for this span
-    {
-        uint32_t *Zw = (uint32_t *)Z;
-        const int words = 4 * nq;
-        for (int idx = threadIdx.x; idx < g.k * words; idx += kDecodeThreads) {
-            const int l = idx / words;
-            const int w = idx - l * words;
-            Zw[l * (4 * span_chunks) + w] = ztable_word<ALIGNED>(g, Iz, ti, l, 4 * q_lo + w);
-        }
+    int l0 = zero_row, l1 = zero_row;
+    if (sel) { l0 = __builtin_ctz(sel) + l_base; sel &= sel - 1u; }
+    if (sel) { l1 = __builtin_ctz(sel) + l_base; sel &= sel - 1u; }
+    const uint4 z0 = Zq[l0 * zstride], z1 = Zq[l1 * zstride];
+    acc.x |= z0.x | z1.x;
+    acc.y |= z0.y | z1.y;
+    acc.z |= z0.z | z1.z;
+    acc.w |= z0.w | z1.w;
+    while (sel) {
+        const int l = __builtin_ctz(sel) + l_base;
+        sel &= sel - 1u;
+        acc = or4(acc, Zq[l * zstride]);
     }
-    __syncthreads();
+    return acc;
+}
 
-    const int TX = 1 << tx_log2;
+// Launch-time constants of the item decomposition.
+struct DecodePlan {
+    int chunks;             // 16-byte pieces per mask row
+    int span_chunks;        // pieces per span
+    int spans;              // spans per row
+    int rows_per_band;
+    int bands_per_tile_row;
+    int tx_log2;            // lanes across a span = 1 << tx_log2
+    int span_tiles;         // upper bound of tiles under a span
+    int iz16;               // I_z base pointer is 16-byte aligned
+    int64_t pitch16;        // mask pitch in 16-byte pieces
+    int64_t items;          // spans * tile_rows * bands_per_tile_row
+};
+
+// Geometry of one item.
+struct Item {
+    int ti, row_lo, nrows, q_lo, nq, tj_first, ntiles;
+};
+__device__ __forceinline__ Item make_item(const Geom &g, const DecodePlan &p, int64_t id)
+{
+    Item it;
+    const int span = (int)(id % p.spans);
+    const int64_t band = id / p.spans;
+    it.ti = (int)(band / p.bands_per_tile_row);
+    it.row_lo = (int)(band - (int64_t)it.ti * p.bands_per_tile_row) * p.rows_per_band;
+    const int row_hi = (it.row_lo + p.rows_per_band < g.r) ? it.row_lo + p.rows_per_band : g.r;
+    it.nrows = row_hi - it.row_lo;
+    it.q_lo = span * p.span_chunks;
+    it.nq = (it.q_lo + p.span_chunks <= p.chunks) ? p.span_chunks : p.chunks - it.q_lo;
+    it.tj_first = (int)(((int64_t)it.q_lo * 128) / g.c);
+    const int64_t last_col = ((int64_t)(it.q_lo + it.nq) * 128 < g.n ? (int64_t)(it.q_lo + it.nq) * 128 : g.n) - 1;
+    it.ntiles = (int)(last_col / g.c) - it.tj_first + 1;
+    return it;
+}
+
+// 16-byte piece (l, q) of the item's Z table, straight from the packed I_z.
+// ALIGNED (c % 128 == 0): the piece lies inside one tile.
+template <bool ALIGNED>
+__device__ __forceinline__ uint4 z_piece(const Geom &g, const DecodePlan &p, const Item &it,
+                                         const uint32_t *__restrict__ Iz, int l, int q)
+{
+    const int Q = it.q_lo + q;
+    if (ALIGNED) {
+        const int pieces_per_tile = g.c >> 7;
+        const int tj = Q / pieces_per_tile;
+        const uint32_t *src =
+            Iz + (((int64_t)it.ti * g.tile_cols + tj) * g.k + l) * (int64_t)g.izw + 4 * (Q - tj * pieces_per_tile);
+        if (p.iz16) return *reinterpret_cast<const uint4 *>(src);
+        return make_uint4(src[0], src[1], src[2], src[3]);
+    }
+    uint4 v;
+    v.x = ztable_word(g, Iz, it.ti, l, 4 * Q + 0);
+    v.y = ztable_word(g, Iz, it.ti, l, 4 * Q + 1);
+    v.z = ztable_word(g, Iz, it.ti, l, 4 * Q + 2);
+    v.w = ztable_word(g, Iz, it.ti, l, 4 * Q + 3);
+    return v;
+}
+
+// Decode and store the rows of one item from its LDS tables.
+//   Z   [k + 1][span_chunks] (last row zero)
+//   IpL [tiles under the span][rows_per_band + 1][ipw]  (the + 1 keeps tiles on different banks)
+// Lane layout: TX = 1 << tx_log2 lanes across the span's pieces, TY = nthreads / TX rows at a time.
+template <bool ALIGNED>
+__device__ __forceinline__ void decode_item_rows(const Geom &g, const DecodePlan &p, const Item &it,
+                                                 const uint4 *__restrict__ Z, const uint32_t *__restrict__ IpL,
+                                                 uint4 *__restrict__ mask, int nthreads)
+{
+    const int TX = 1 << p.tx_log2;
     const int tx = threadIdx.x & (TX - 1);
-    const int ty = threadIdx.x >> tx_log2;
-    const int TY = kDecodeThreads >> tx_log2;
-    for (int q = tx; q < nq; q += TX) {
-        const int Q = q_lo + q;        // absolute 16-byte piece of the mask row
+    const int ty = threadIdx.x >> p.tx_log2;
+    const int TY = nthreads >> p.tx_log2;
+    const int zero_row = g.k;
+    const int ip_rows = p.rows_per_band + 1;
+    for (int q = tx; q < it.nq; q += TX) {
+        const int Q = it.q_lo + q;           // absolute 16-byte piece of the mask row
         const int64_t cb = (int64_t)Q * 128; // first column of the piece
+        const uint4 *Zq = Z + q;
+        uint4 *out = mask + ((int64_t)it.ti * g.r + it.row_lo + ty) * p.pitch16 + Q;
+        const int64_t out_step = (int64_t)TY * p.pitch16;
         if (ALIGNED) {
-            const int tj = (int)(cb / g.c);
-            const int64_t t = (int64_t)ti * g.tile_cols + tj;
-            const uint32_t *ipt = Ip + t * g.r * g.ipw;
-            for (int il = row_lo + ty; il < row_hi; il += TY) {
+            const int tl = (int)(cb / g.c) - it.tj_first;
+            const uint32_t *ipr = IpL + (tl * ip_rows + ty) * g.ipw;
+            const int ip_step = TY * g.ipw;
+            for (int i = ty; i < it.nrows; i += TY, ipr += ip_step, out += out_step) {
                 uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-                for (int iw = 0; iw < g.ipw; ++iw) {
-                    uint32_t sel = ipt[(int64_t)il * g.ipw + iw];
-                    while (sel) {
-                        const int l = __builtin_ctz(sel) + 32 * iw;
-                        sel &= sel - 1u;
-                        acc = or4(acc, Z[l * span_chunks + q]);
-                    }
-                }
-                mask[((int64_t)ti * g.r + il) * pitch16 + Q] = acc;
+                for (int iw = 0; iw < g.ipw; ++iw) acc = or_selected(acc, ipr[iw], 32 * iw, Zq, p.span_chunks, zero_row);
+                *out = acc;
             }
         } else {
             const int64_t ce = (cb + 128 < g.n) ? cb + 128 : g.n;
             const int tj_lo = (int)(cb / g.c);
-            for (int il = row_lo + ty; il < row_hi; il += TY) {
+            for (int i = ty; i < it.nrows; i += TY, out += out_step) {
                 uint4 acc = make_uint4(0u, 0u, 0u, 0u);
                 int tj = tj_lo;
                 for (int64_t tbeg = (int64_t)tj * g.c; tbeg < ce; tbeg += g.c, ++tj) {
-                    const int64_t t = (int64_t)ti * g.tile_cols + tj;
-                    const uint32_t *ipr = Ip + (t * g.r + il) * g.ipw;
+                    const uint32_t *ipr = IpL + ((tj - it.tj_first) * ip_rows + i) * g.ipw;
                     // bits of this piece that belong to tile tj
                     const int lo = (int)((tbeg > cb ? tbeg : cb) - cb);
                     const int hi = (int)((tbeg + g.c < ce ? tbeg + g.c : ce) - cb);
@@ -141,22 +201,172 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_ztable_kernel(
                     tm.z = bit_range(lo - 64 < 0 ? 0 : lo - 64, hi - 64 > 32 ? 32 : hi - 64);
                     tm.w = bit_range(lo - 96 < 0 ? 0 : lo - 96, hi - 96 > 32 ? 32 : hi - 96);
                     uint4 v = make_uint4(0u, 0u, 0u, 0u);
-                    for (int iw = 0; iw < g.ipw; ++iw) {
-                        uint32_t sel = ipr[iw];
-                        while (sel) {
-                            const int l = __builtin_ctz(sel) + 32 * iw;
-                            sel &= sel - 1u;
-                            v = or4(v, Z[l * span_chunks + q]);
-                        }
-                    }
+                    for (int iw = 0; iw < g.ipw; ++iw) v = or_selected(v, ipr[iw], 32 * iw, Zq, p.span_chunks, zero_row);
                     acc.x |= v.x & tm.x;
                     acc.y |= v.y & tm.y;
                     acc.z |= v.z & tm.z;
                     acc.w |= v.w & tm.w;
                 }
-                mask[((int64_t)ti * g.r + il) * pitch16 + Q] = acc;
+                *out = acc;
             }
         }
+    }
+}
+
+// One-shot kernel: one item per workgroup of 256 lanes.
+template <bool ALIGNED>
+__global__ __launch_bounds__(kDecodeThreads) void decode_ztable_kernel(Geom g, DecodePlan p,
+                                                                       const uint32_t *__restrict__ Ip,
+                                                                       const uint32_t *__restrict__ Iz,
+                                                                       uint4 *__restrict__ mask)
+{
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    uint4 *Z = lrbi_dyn_smem; // [k + 1][span_chunks]
+    uint32_t *IpL = (uint32_t *)(Z + (size_t)(g.k + 1) * p.span_chunks);
+    const Item it = make_item(g, p, blockIdx.x);
+    const int TX = 1 << p.tx_log2;
+    const int tx = threadIdx.x & (TX - 1);
+    const int ty = threadIdx.x >> p.tx_log2;
+    const int TY = kDecodeThreads >> p.tx_log2;
+    const int ip_rows = p.rows_per_band + 1;
+
+    // Loads go out in batches before any is consumed (a few memory round trips per workgroup).
+    constexpr int kBatch = 8;
+    for (int w = threadIdx.x; w < 4 * p.span_chunks; w += kDecodeThreads) ((uint32_t *)Z)[g.k * (4 * p.span_chunks) + w] = 0u;
+    for (int q = tx; q < it.nq; q += TX) {
+        for (int l0 = ty; l0 < g.k; l0 += TY * kBatch) {
+            uint4 tmp[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int l = l0 + TY * j;
+                tmp[j] = make_uint4(0u, 0u, 0u, 0u);
+                if (l < g.k) tmp[j] = z_piece<ALIGNED>(g, p, it, Iz, l, q);
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int l = l0 + TY * j;
+                if (l < g.k) Z[l * p.span_chunks + q] = tmp[j];
+            }
+        }
+    }
+    // I_p words of the band: per tile a contiguous run of nrows * ipw words; the flat index walks
+    // (tile, word) without divisions
+    const int per_tile = it.nrows * g.ipw;
+    int tl = 0, e = threadIdx.x;
+    while (e >= per_tile && tl < it.ntiles) { e -= per_tile; ++tl; }
+    while (tl < it.ntiles) {
+        uint32_t tmp[kBatch];
+        int dst[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            tmp[j] = 0u;
+            dst[j] = -1;
+            if (tl < it.ntiles) {
+                const int64_t t = (int64_t)it.ti * g.tile_cols + it.tj_first + tl;
+                tmp[j] = Ip[(t * g.r + it.row_lo) * g.ipw + e];
+                dst[j] = (tl * ip_rows) * g.ipw + e;
+                e += kDecodeThreads;
+                while (e >= per_tile && tl < it.ntiles) { e -= per_tile; ++tl; }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j)
+            if (dst[j] >= 0) IpL[dst[j]] = tmp[j];
+    }
+    __syncthreads();
+    decode_item_rows<ALIGNED>(g, p, it, Z, IpL, mask, kDecodeThreads);
+}
+
+// Streaming kernel: persistent workgroups of 1024 lanes, items id = blockIdx.x, + gridDim.x, ...
+// LDS holds two copies of (Z, IpL).  While item j is decoded and stored from one copy, the loads
+// of item j + 1 are in flight into registers; they are written to the other copy afterwards.
+template <bool ALIGNED>
+__global__ __launch_bounds__(kStreamThreads) void decode_stream_kernel(Geom g, DecodePlan p,
+                                                                       const uint32_t *__restrict__ Ip,
+                                                                       const uint32_t *__restrict__ Iz,
+                                                                       uint4 *__restrict__ mask)
+{
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    const int z_pieces = (g.k + 1) * p.span_chunks;
+    const int ip_rows = p.rows_per_band + 1;
+    const int ip_words = p.span_tiles * ip_rows * g.ipw;
+    const int buf_pieces = z_pieces + (ip_words + 3) / 4;
+    uint4 *Zb[2] = {lrbi_dyn_smem, lrbi_dyn_smem + buf_pieces};
+    uint32_t *Ipb[2] = {(uint32_t *)(Zb[0] + z_pieces), (uint32_t *)(Zb[1] + z_pieces)};
+
+    uint4 zreg[kMaxZPerLane];
+    uint32_t ipreg[kMaxIpPerLane];
+    int ipdst[kMaxIpPerLane];
+
+    // the zero rows never change
+    for (int w = threadIdx.x; w < 2 * p.span_chunks; w += kStreamThreads) {
+        const int b = w / p.span_chunks, q = w - b * p.span_chunks;
+        Zb[b][g.k * p.span_chunks + q] = make_uint4(0u, 0u, 0u, 0u);
+    }
+
+    auto load_item = [&](const Item &it) {
+        const int total = g.k * it.nq;
+#pragma unroll
+        for (int j = 0; j < kMaxZPerLane; ++j) {
+            const int idx = threadIdx.x + kStreamThreads * j;
+            zreg[j] = make_uint4(0u, 0u, 0u, 0u);
+            if (idx < total) {
+                const int l = idx / it.nq, q = idx - l * it.nq;
+                zreg[j] = z_piece<ALIGNED>(g, p, it, Iz, l, q);
+            }
+        }
+        const int per_tile = it.nrows * g.ipw;
+        const int ip_total = it.ntiles * per_tile;
+#pragma unroll
+        for (int j = 0; j < kMaxIpPerLane; ++j) {
+            const int idx = threadIdx.x + kStreamThreads * j;
+            ipreg[j] = 0u;
+            ipdst[j] = -1;
+            if (idx < ip_total) {
+                const int tl = idx / per_tile, e = idx - tl * per_tile;
+                const int64_t t = (int64_t)it.ti * g.tile_cols + it.tj_first + tl;
+                ipreg[j] = Ip[(t * g.r + it.row_lo) * g.ipw + e];
+                ipdst[j] = (tl * ip_rows) * g.ipw + e;
+            }
+        }
+    };
+    auto store_item = [&](const Item &it, int b) {
+        const int total = g.k * it.nq;
+#pragma unroll
+        for (int j = 0; j < kMaxZPerLane; ++j) {
+            const int idx = threadIdx.x + kStreamThreads * j;
+            if (idx < total) {
+                const int l = idx / it.nq, q = idx - l * it.nq;
+                Zb[b][l * p.span_chunks + q] = zreg[j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kMaxIpPerLane; ++j)
+            if (ipdst[j] >= 0) Ipb[b][ipdst[j]] = ipreg[j];
+    };
+
+    int64_t id = blockIdx.x;
+    if (id >= p.items) return;
+    Item cur = make_item(g, p, id);
+    load_item(cur);
+    store_item(cur, 0);
+    __syncthreads();
+    int b = 0;
+    for (;;) {
+        const int64_t next_id = id + gridDim.x;
+        const bool has_next = next_id < p.items;
+        Item nxt = cur;
+        if (has_next) {
+            nxt = make_item(g, p, next_id);
+            load_item(nxt); // in flight while the current item is decoded
+        }
+        decode_item_rows<ALIGNED>(g, p, cur, Zb[b], Ipb[b], mask, kStreamThreads);
+        if (!has_next) break;
+        store_item(nxt, b ^ 1); // the other copy was last read before the previous barrier
+        __syncthreads();
+        b ^= 1;
+        cur = nxt;
+        id = next_id;
     }
 }
 
@@ -164,47 +374,66 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
                   int64_t pitch_bytes, hipStream_t stream)
 {
     const int64_t chunks64 = (g.n + 127) / 128;
-    const int chunks = (int)chunks64;
-    const int64_t pitch16 = pitch_bytes / 16;
+    DecodePlan p;
+    p.chunks = (int)chunks64;
+    p.pitch16 = pitch_bytes / 16;
 
-    if (flags & LRBI_FLAG_DECODE_GENERIC) {
+    auto launch_generic = [&]() -> int {
         const int64_t items = g.m * chunks64;
         const int64_t blocks = (items + kDecodeThreads - 1) / kDecodeThreads;
         if (blocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
         hipLaunchKernelGGL(decode_generic_kernel, dim3((unsigned)blocks), dim3(kDecodeThreads), 0, stream, g, dIp,
-                           dIz, (uint4 *)dMask, pitch16, chunks);
+                           dIz, (uint4 *)dMask, p.pitch16, p.chunks);
         LRBI_CHECK_LAUNCH();
         return LRBI_OK;
-    }
+    };
+    if (flags & LRBI_FLAG_DECODE_GENERIC) return launch_generic();
 
-    // column span per workgroup: as wide as the Z table budget allows
-    int span_chunks = kZTableBudgetBytes / (16 * g.k);
-    if (span_chunks < 1) span_chunks = 1;
-    if (span_chunks > chunks) span_chunks = chunks;
-    const int spans = (chunks + span_chunks - 1) / span_chunks;
-    // lanes along the row: a power of two covering the span, at most one wavefront
-    int tx_log2 = 0;
-    while ((1 << tx_log2) < span_chunks && tx_log2 < 6) ++tx_log2;
-    // rows per band: whole tile height unless that leaves the chip idle; building
-    // the Z table costs about k words per column word, so keep bands well above k rows
-    int rows_per_band = g.r;
-    const int min_rows = (4 * g.k > 32) ? 4 * g.k : 32;
-    while (rows_per_band > min_rows &&
-           (int64_t)spans * g.tile_rows * ((g.r + rows_per_band - 1) / rows_per_band) < 2048)
-        rows_per_band = (rows_per_band + 1) / 2;
-    const int bands_per_tile_row = (g.r + rows_per_band - 1) / rows_per_band;
-    const int64_t blocks = (int64_t)spans * g.tile_rows * bands_per_tile_row;
-    if (blocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
-    const size_t lds = (size_t)g.k * span_chunks * 16;
+    // Column span per item: as wide as the Z table budget allows, at most 64 pieces (one
+    // wavefront across).  Rows per band: as many as the I_p budget allows (one table build per
+    // band), cut down only when that leaves compute units without work.
+    p.span_chunks = kZTableBudgetBytes / (16 * (g.k + 1));
+    if (p.span_chunks < 1) p.span_chunks = 1;
+    if (p.span_chunks > 64) p.span_chunks = 64;
+    if (p.span_chunks > p.chunks) p.span_chunks = p.chunks;
+    p.spans = (p.chunks + p.span_chunks - 1) / p.span_chunks;
+    p.tx_log2 = 0;
+    while ((1 << p.tx_log2) < p.span_chunks && p.tx_log2 < 6) ++p.tx_log2;
+    p.span_tiles = (int)(((int64_t)p.span_chunks * 128 + g.c - 1) / g.c) + 1;
+    p.rows_per_band = g.r;
+    const int cap_rows = kIpBudgetBytes / (4 * g.ipw * p.span_tiles) - 1;
+    if (p.rows_per_band > cap_rows) p.rows_per_band = cap_rows;
+    if (p.rows_per_band < 1) return launch_generic(); // not even one row of I_p words fits next to the table
+    const int min_rows = (2 * g.k > 32) ? 2 * g.k : 32;
+    while (p.rows_per_band > min_rows &&
+           (int64_t)p.spans * g.tile_rows * ((g.r + p.rows_per_band - 1) / p.rows_per_band) < 2048)
+        p.rows_per_band = (p.rows_per_band + 1) / 2;
+    p.bands_per_tile_row = (g.r + p.rows_per_band - 1) / p.rows_per_band;
+    p.items = (int64_t)p.spans * g.tile_rows * p.bands_per_tile_row;
+    if (p.items > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
+    p.iz16 = (((uintptr_t)dIz & 15) == 0) ? 1 : 0;
+    const size_t z_bytes = (size_t)(g.k + 1) * p.span_chunks * 16;
+    const size_t ip_bytes = ((size_t)p.span_tiles * (p.rows_per_band + 1) * g.ipw * 4 + 15) / 16 * 16;
     const bool aligned = (g.c % 128) == 0;
-    if (aligned)
-        hipLaunchKernelGGL(decode_ztable_kernel<true>, dim3((unsigned)blocks), dim3(kDecodeThreads), lds, stream, g,
-                           dIp, dIz, (uint4 *)dMask, pitch16, chunks, span_chunks, spans, rows_per_band,
-                           bands_per_tile_row, tx_log2);
-    else
-        hipLaunchKernelGGL(decode_ztable_kernel<false>, dim3((unsigned)blocks), dim3(kDecodeThreads), lds, stream, g,
-                           dIp, dIz, (uint4 *)dMask, pitch16, chunks, span_chunks, spans, rows_per_band,
-                           bands_per_tile_row, tx_log2);
+
+    int device = 0, cus = 256;
+    if (hipGetDevice(&device) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && v > 0) cus = v;
+    }
+    // streaming pays off once every compute unit gets several items
+    if (p.items >= 4 * (int64_t)cus) {
+        const size_t lds = 2 * (z_bytes + ip_bytes);
+        auto kern = aligned ? decode_stream_kernel<true> : decode_stream_kernel<false>;
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return LRBI_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3((unsigned)cus), dim3(kStreamThreads), lds, stream, g, p, dIp, dIz, (uint4 *)dMask);
+    } else {
+        const size_t lds = z_bytes + ip_bytes;
+        auto kern = aligned ? decode_ztable_kernel<true> : decode_ztable_kernel<false>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)p.items), dim3(kDecodeThreads), lds, stream, g, p, dIp, dIz,
+                           (uint4 *)dMask);
+    }
     LRBI_CHECK_LAUNCH();
     return LRBI_OK;
 }

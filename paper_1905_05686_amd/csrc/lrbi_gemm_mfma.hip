@@ -24,6 +24,7 @@
 // When m * N yields too few tiles to fill 256 compute units, the n range is cut
 // into `splitk` slices; slices write fp32 partial tiles to the caller's
 // workspace and a second kernel adds them in slice order (deterministic).
+#include <stdlib.h>
 #include <type_traits>
 #include <utility>
 
@@ -72,19 +73,22 @@ __device__ __forceinline__ uint16_t cvt_store(BF16Tag, float v)
     return (uint16_t)(u >> 16);
 }
 
-// Expand 2 mask bits (bit 0 -> low half, bit 1 -> high half) to a 32-bit AND mask.
-__device__ __forceinline__ uint32_t expand2(uint32_t bits)
+// Zero the 16-bit halves of w whose mask bit is clear.  `pair` holds 0 or 1 in each half; a packed
+// 16-bit integer multiply by 0 / 1 is an exact select on the bit pattern (no floating-point
+// arithmetic touches the value, so NaN and Inf under a 0 bit disappear).
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t select2(uint32_t w, uint32_t pair)
 {
-    // (b0 | b1 << 16) * 0xFFFF = b0 * 0x0000FFFF | b1 * 0xFFFF0000
-    const uint32_t pair = (bits | (bits << 15)) & 0x00010001u;
-    return pair * 0xFFFFu;
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, w) * __builtin_bit_cast(u16x2, pair));
 }
 __device__ __forceinline__ uint4 apply_mask8(uint4 w, uint32_t bits8)
 {
-    w.x &= expand2(bits8);
-    w.y &= expand2(bits8 >> 2);
-    w.z &= expand2(bits8 >> 4);
-    w.w &= expand2(bits8 >> 6);
+    // y holds bit j of bits8 at positions j and j + 15: (y >> 2q) & 0x00010001 = (b_2q, b_2q+1) per half
+    const uint32_t y = bits8 | (bits8 << 15);
+    w.x = select2(w.x, y & 0x00010001u);
+    w.y = select2(w.y, (y >> 2) & 0x00010001u);
+    w.z = select2(w.z, (y >> 4) & 0x00010001u);
+    w.w = select2(w.w, (y >> 6) & 0x00010001u);
     return w;
 }
 
@@ -366,18 +370,24 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 
 // ---------------------------------------------------------------------------
 // Panel kernel: the fast path for tile shapes that line up with the kernel's
-// blocking (c % 128 == 0, r % BM == 0, k <= 64).
+// blocking (c % 128 == 0, r % BM == 0, k <= 64; hence no row or reduction tails).
 //
 // Differences from the kernel above:
-//   * The mask is rebuilt one PANEL (512 columns = 8 slabs) at a time and two
-//     slabs ahead of its first use, entirely from LDS: the panel's slice of the
-//     I_z rows ("Fz", k x 512 bits) and the I_p words of the workgroup's rows
+//   * The mask is rebuilt one PANEL (512 columns = 8 slabs) at a time and well
+//     ahead of its first use, entirely from LDS: the panel's slice of the I_z
+//     rows ("Fz", k x 512 bits) and the I_p words of the workgroup's rows
 //     ("Fip") are fetched with plain loads while earlier slabs are multiplied,
 //     so no dependent global load sits in front of an MFMA.
 //   * X operands come out of LDS with the gfx950 transposing read
 //     (ds_read_b64_tr_b16): X stays in its natural [k][n] order and each lane
 //     still receives 8 consecutive k of one column.
 //   * Global loads run RS slabs ahead of the LDS staging (register stages).
+//   * With KGROUPS = 2 the workgroup has 8 wavefronts: two groups of four, each
+//     group covering the whole BM x BN tile for half of every slab's 64 columns.
+//     Two wavefronts then share each SIMD, so one's mask arithmetic and LDS traffic
+//     overlap the other's MFMAs, while LDS operand traffic per flop stays that of a
+//     64 x 64 wave tile.  The two groups' accumulators are added through LDS at the end
+//     (fixed order: group 0 + group 1).
 // ---------------------------------------------------------------------------
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -404,30 +414,40 @@ template <int BM, int BN> struct SmemPanel {
     static constexpr int ms_words = BM * PANEL_WORDS;
     static constexpr int fz_words = FAST_MAX_K * PANEL_WORDS;
     static constexpr int fip_words = BM * PANEL_UNITS * 2;
-    static constexpr size_t bytes =
+    static constexpr size_t loop_bytes =
         2 * (size_t)(ws_halfs + xs_halfs) * 2 + 2 * (size_t)(ms_words + fz_words + fip_words) * 4;
+    static constexpr size_t reduce_bytes = (size_t)BM * BN * 4; // one group's fp32 accumulators
+    static constexpr size_t bytes = loop_bytes > reduce_bytes ? loop_bytes : reduce_bytes;
 };
 
-template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N, int RS, bool XVEC, bool SPLIT>
-__global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
+template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N, int KGROUPS, int RS, bool XVEC, bool SPLIT>
+__global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
     Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
     const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ X, int64_t ldx, int N,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ P, int64_t ldp, int mblocks, int nblocks,
-    int64_t kper, int xcd_remap, int y_vec_ok)
+    int64_t kper, int xcd_remap, int y_vec_ok, int dbg)
 {
-    static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+    static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per group");
+    static_assert(KGROUPS == 1 || KGROUPS == 2, "one or two wave groups");
+    constexpr int NT = 256 * KGROUPS;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int FM = WM / 32, FN = WN / 32;
     static_assert(FM >= 1 && FN >= 1, "wave tile must hold a 32x32 block");
+    constexpr int KK_PER = (BK / 16) / KGROUPS; // 16-column MFMA steps per slab and group
     using S = SmemPanel<BM, BN>;
     constexpr int XS_STRIDE = S::XS_STRIDE;
-    constexpr int W_CHUNKS = BM * (BK / 8) / kThreads;
+    constexpr int W_CHUNKS = BM * (BK / 8) / NT;
     constexpr int X_CPR = BN / 8;
-    constexpr int X_CHUNKS = (BK * X_CPR + kThreads - 1) / kThreads;
-    constexpr int FZ_LOADS = FAST_MAX_K * PANEL_WORDS / kThreads;      // 4
-    constexpr int FIP_LOADS = (BM * PANEL_UNITS * 2 + kThreads - 1) / kThreads; // 4 for BM = 128
-    constexpr int UNITS = (BM * PANEL_UNITS + kThreads - 1) / kThreads; // 2 for BM = 128
-    static_assert(BM * (BK / 8) % kThreads == 0, "W slab must split evenly");
+    constexpr int X_TOTAL = BK * X_CPR;
+    constexpr int X_CHUNKS = (X_TOTAL + NT - 1) / NT;
+    constexpr bool X_EVEN = (X_TOTAL % NT) == 0;
+    constexpr int FZ_LOADS = FAST_MAX_K * PANEL_WORDS / NT;
+    constexpr int FIP_TOTAL = BM * PANEL_UNITS * 2;
+    constexpr int FIP_LOADS = (FIP_TOTAL + NT - 1) / NT;
+    constexpr int UNITS_TOTAL = BM * PANEL_UNITS;
+    constexpr int UNITS = (UNITS_TOTAL + NT - 1) / NT;
+    static_assert(BM * (BK / 8) % NT == 0, "W slab must split evenly");
+    static_assert(FAST_MAX_K * PANEL_WORDS % NT == 0, "Fz must split evenly");
 
     extern __shared__ uint4 lrbi_dyn_smem[];
     uint16_t *Ws = (uint16_t *)lrbi_dyn_smem;            // [2][BM][WS_STRIDE]
@@ -437,18 +457,22 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
     uint32_t *Fip = Fz + 2 * S::fz_words;                // [2][BM][PANEL_UNITS][2] I_p words per row and unit
 
     int64_t bid = blockIdx.x;
-    if (xcd_remap) {
+    if (xcd_remap && !(dbg & 64)) {
         const int64_t per = gridDim.x / 8;
         bid = (bid % 8) * per + bid / 8;
     }
-    const int ni = (int)(bid % nblocks);
-    const int mi = (int)((bid / nblocks) % mblocks);
+    int ni = (int)(bid % nblocks);
+    int mi = (int)((bid / nblocks) % mblocks);
+    if (dbg & 128) {
+        mi = (int)(bid % mblocks);
+        ni = (int)((bid / mblocks) % nblocks);
+    }
     const int slice = (int)(bid / ((int64_t)nblocks * mblocks));
     const int64_t m0 = (int64_t)mi * BM;
     const int n0 = ni * BN;
     const int kbeg = (int)(slice * kper);
     const int kend = (int)((kbeg + kper < g.n) ? kbeg + kper : g.n);
-    const int nslabs = (kend - kbeg + BK - 1) / BK;
+    const int nslabs = (kend - kbeg) / BK; // n % 128 == 0 and kper % 128 == 0: whole slabs only
     const int npanels = (nslabs + PANEL_SLABS - 1) / PANEL_SLABS;
     // the workgroup's rows lie inside one tile row (r % BM == 0)
     const int ti = (int)(m0 / g.r);
@@ -458,48 +482,75 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int kg = wave >> 2;       // wave group (k half of every slab)
+    const int w4 = wave & 3;
+    const int wm = w4 / WAVES_N, wn = w4 % WAVES_N;
     const int l32 = lane & 31, lg = lane >> 5;
 
     uint4 wreg[RS][W_CHUNKS];
     uint4 xreg[RS][X_CHUNKS];
     uint32_t fzreg[FZ_LOADS];
     uint32_t fipreg[FIP_LOADS];
+    uint32_t mbits[W_CHUNKS]; // mask bytes of the slab that is staged next
+
+    // W loads need no guards (no tails).  Addresses are a uniform base that advances per slab
+    // plus a per-lane 32-bit offset that never changes.
+    const uint16_t *wbase = W + m0 * ldw + kbeg;
+    const uint16_t *xbase_g = X + (int64_t)kbeg * ldx + n0;
+    uint32_t woff[W_CHUNKS], wlds[W_CHUNKS], moff[W_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < W_CHUNKS; ++i) {
+        const int id = tid + NT * i;
+        const int row = id >> 3, kc = id & 7;
+        woff[i] = (uint32_t)(row * ldw + kc * 8);
+        wlds[i] = (uint32_t)(row * WS_STRIDE + kc * 8);
+        moff[i] = (uint32_t)(row * (PANEL_WORDS * 4) + kc);
+    }
+    uint32_t xoff[X_CHUNKS], xlds[X_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < X_CHUNKS; ++i) {
+        const int id = (tid + NT * i) % X_TOTAL; // lanes beyond the slab repeat a valid piece (never stored)
+        int krow = id / X_CPR, nc = id % X_CPR;
+        if ((dbg & 256) && X_CPR == 16) { // 8 lanes per 128-byte line, neighbouring 8-lane groups on different rows
+            const int q = id / 32, w = id % 32;
+            krow = 2 * q + ((w >> 3) & 1);
+            nc = (w & 7) + 8 * (w >> 4);
+        }
+        int nn = nc * 8;
+        if (XVEC && n0 + nn + 8 > N) nn = N - 8 - n0; // piece beyond N: read a valid piece instead, its columns are dropped
+        xoff[i] = (uint32_t)(krow * ldx + nn);
+        xlds[i] = (uint32_t)(krow * XS_STRIDE + nc * 8);
+    }
 
     auto load_slab = [&](int slab, auto stage_c) {
         constexpr int st = decltype(stage_c)::value;
-        const int k0 = kbeg + slab * BK;
+        const uint16_t *wb = wbase + slab * BK;
+        const uint16_t *xb = xbase_g + (int64_t)slab * BK * ldx;
+        if (!(dbg & 16)) {
 #pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i) {
-            const int id = tid + kThreads * i;
-            const int row = id >> 3, kc = id & 7;
-            const int64_t gr = m0 + row;
-            const int kk = k0 + kc * 8;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (gr < g.m && kk < kend) v = *reinterpret_cast<const uint4 *>(W + gr * ldw + kk);
-            wreg[st][i] = v;
+        for (int i = 0; i < W_CHUNKS; ++i) wreg[st][i] = *reinterpret_cast<const uint4 *>(wb + woff[i]);
         }
+        if (dbg & 32) return;
 #pragma unroll
         for (int i = 0; i < X_CHUNKS; ++i) {
-            const int id = tid + kThreads * i;
-            const int krow = id / X_CPR, nc = id % X_CPR;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (id < BK * X_CPR) {
-                const int kk = k0 + krow;
-                const int nn = n0 + nc * 8;
-                if (kk < kend) {
-                    if (XVEC) {
-                        if (nn < N) v = *reinterpret_cast<const uint4 *>(X + (int64_t)kk * ldx + nn);
-                    } else {
-                        uint16_t tmp[8];
+            if (XVEC) {
+                xreg[st][i] = *reinterpret_cast<const uint4 *>(xb + xoff[i]);
+            } else {
+                const int nn = n0 + (((tid + NT * i) % X_TOTAL) % X_CPR) * 8;
+                uint16_t tmp[8];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) tmp[e] = (nn + e < N) ? X[(int64_t)kk * ldx + nn + e] : (uint16_t)0;
-                        v = *reinterpret_cast<uint4 *>(tmp);
-                    }
-                }
+                for (int e = 0; e < 8; ++e) tmp[e] = (nn + e < N) ? xb[xoff[i] + e] : (uint16_t)0;
+                xreg[st][i] = *reinterpret_cast<uint4 *>(tmp);
             }
-            xreg[st][i] = v;
         }
+    };
+
+    // mask bytes of `slab` (its panel is decoded and visible by now)
+    auto fetch_mask_bytes = [&](int slab) {
+        const unsigned char *mb = (const unsigned char *)(Ms + ((slab / PANEL_SLABS) & 1) * S::ms_words) +
+                                  (slab % PANEL_SLABS) * (BK / 8);
+#pragma unroll
+        for (int i = 0; i < W_CHUNKS; ++i) mbits[i] = mb[moff[i]];
     };
 
     auto stage_slab = [&](int slab, auto stage_c) {
@@ -507,24 +558,12 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
         const int buf = slab & 1;
         uint16_t *ws = Ws + buf * S::ws_halfs;
         uint16_t *xs = Xs + buf * S::xs_halfs;
-        const int panel = slab / PANEL_SLABS;
-        const unsigned char *mb =
-            (const unsigned char *)(Ms + (panel & 1) * S::ms_words) + (slab % PANEL_SLABS) * (BK / 8);
 #pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i) {
-            const int id = tid + kThreads * i;
-            const int row = id >> 3, kc = id & 7;
-            const uint32_t bits = mb[row * (PANEL_WORDS * 4) + kc];
-            *reinterpret_cast<uint4 *>(ws + row * WS_STRIDE + kc * 8) = apply_mask8(wreg[st][i], bits);
-        }
+        for (int i = 0; i < W_CHUNKS; ++i)
+            *reinterpret_cast<uint4 *>(ws + wlds[i]) = apply_mask8(wreg[st][i], mbits[i]);
 #pragma unroll
-        for (int i = 0; i < X_CHUNKS; ++i) {
-            const int id = tid + kThreads * i;
-            if (id < BK * X_CPR) {
-                const int krow = id / X_CPR, nc = id % X_CPR;
-                *reinterpret_cast<uint4 *>(xs + krow * XS_STRIDE + nc * 8) = xreg[st][i];
-            }
-        }
+        for (int i = 0; i < X_CHUNKS; ++i)
+            if (X_EVEN || tid + NT * i < X_TOTAL) *reinterpret_cast<uint4 *>(xs + xlds[i]) = xreg[st][i];
     };
 
     // factor slices of one panel: global -> registers
@@ -532,7 +571,7 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
         const int kp = kbeg + panel * PW;
 #pragma unroll
         for (int i = 0; i < FZ_LOADS; ++i) {
-            const int idx = tid + kThreads * i;
+            const int idx = tid + NT * i;
             const int l = idx / PANEL_WORDS, w = idx % PANEL_WORDS;
             const int col = kp + 32 * w;
             uint32_t v = 0u;
@@ -544,11 +583,11 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
         }
 #pragma unroll
         for (int i = 0; i < FIP_LOADS; ++i) {
-            const int idx = tid + kThreads * i;
+            const int idx = tid + NT * i;
             const int row = idx / (PANEL_UNITS * 2), u = (idx / 2) % PANEL_UNITS, iw = idx & 1;
             const int col = kp + 128 * u;
             uint32_t v = 0u;
-            if (idx < BM * PANEL_UNITS * 2 && iw < g.ipw && m0 + row < g.m && col < kend) {
+            if (idx < FIP_TOTAL && iw < g.ipw && col < kend) {
                 const int tj = col / g.c;
                 v = Ip[((trow + tj) * g.r + il0 + row) * g.ipw + iw];
             }
@@ -560,11 +599,11 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
         uint32_t *fz = Fz + (panel & 1) * S::fz_words;
         uint32_t *fip = Fip + (panel & 1) * S::fip_words;
 #pragma unroll
-        for (int i = 0; i < FZ_LOADS; ++i) fz[tid + kThreads * i] = fzreg[i];
+        for (int i = 0; i < FZ_LOADS; ++i) fz[tid + NT * i] = fzreg[i];
 #pragma unroll
         for (int i = 0; i < FIP_LOADS; ++i) {
-            const int idx = tid + kThreads * i;
-            if (idx < BM * PANEL_UNITS * 2) fip[idx] = fipreg[i];
+            const int idx = tid + NT * i;
+            if (idx < FIP_TOTAL) fip[idx] = fipreg[i];
         }
     };
     // Eq. 3 for the panel: mask row piece = OR of the Fz pieces selected by the set bits of the I_p words
@@ -574,8 +613,8 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
         uint32_t *ms = Ms + (panel & 1) * S::ms_words;
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) {
-            const int uid = tid + kThreads * i;
-            if (uid < BM * PANEL_UNITS) {
+            const int uid = tid + NT * i;
+            if (uid < UNITS_TOTAL) {
                 const int row = uid / PANEL_UNITS, u = uid % PANEL_UNITS;
                 uint4 acc = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
@@ -604,23 +643,26 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
+    // transposing read: 16-lane group G = lane / 16 serves columns 16 * (G % 2) .. + 15 of a
+    // 32-column block and k group G / 2; lane d of the group addresses row d / 4, columns 4 * (d % 4)
+    const int d16 = lane & 15, G16 = lane >> 4;
+    const uint32_t xfrag_off = (uint32_t)((kg * KK_PER * 16 + 8 * (G16 >> 1) + (d16 >> 2)) * XS_STRIDE + wn * WN +
+                                          16 * (G16 & 1) + 4 * (d16 & 3));
+    const uint32_t wfrag_off = (uint32_t)((wm * WM + l32) * WS_STRIDE + kg * KK_PER * 16 + 8 * lg);
+
     auto compute_slab = [&](int slab) {
         const int buf = slab & 1;
-        const uint16_t *ws = Ws + buf * S::ws_halfs;
-        const uint16_t *xs = Xs + buf * S::xs_halfs;
-        // transposing read: 16-lane group G = lane / 16 serves columns 16 * (G % 2) .. + 15 of a
-        // 32-column block and k group G / 2; lane d of the group addresses row d / 4, columns 4 * (d % 4)
-        const int d16 = lane & 15, G = lane >> 4;
-        const uint16_t *xbase = xs + (8 * (G >> 1) + (d16 >> 2)) * XS_STRIDE + wn * WN + 16 * (G & 1) + 4 * (d16 & 3);
+        const uint16_t *ws = Ws + buf * S::ws_halfs + wfrag_off;
+        const uint16_t *xs = Xs + buf * S::xs_halfs + xfrag_off;
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
+        for (int kk = 0; kk < KK_PER; ++kk) {
             uint4 wf[FM], xf[FN];
 #pragma unroll
             for (int b = 0; b < FM; ++b)
-                wf[b] = *reinterpret_cast<const uint4 *>(ws + (wm * WM + b * 32 + l32) * WS_STRIDE + kk * 16 + 8 * lg);
+                wf[b] = *reinterpret_cast<const uint4 *>(ws + b * 32 * WS_STRIDE + kk * 16);
 #pragma unroll
             for (int a = 0; a < FN; ++a) {
-                const uint16_t *p = xbase + (kk * 16) * XS_STRIDE + a * 32;
+                const uint16_t *p = xs + (kk * 16) * XS_STRIDE + a * 32;
                 const uint2 lo = lds_read_tr16(p);
                 const uint2 hi = lds_read_tr16(p + 4 * XS_STRIDE);
                 xf[a] = make_uint4(lo.x, lo.y, hi.x, hi.y);
@@ -633,29 +675,34 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
     };
 
     // ---- prologue: factors and mask of panel 0, slabs 0 .. RS-1 in flight, slab 0 staged
+    const int last = nslabs - 1;
     load_factors(0);
     static_for<RS>([&](auto sc) {
         constexpr int st = decltype(sc)::value;
-        if (st < nslabs) load_slab(st, sc);
+        load_slab(st < last ? st : last, sc);
     });
     store_factors(0);
     __syncthreads();
     decode_panel(0);
     __syncthreads();
+    fetch_mask_bytes(0);
     stage_slab(0, std::integral_constant<int, 0>{});
-    if (RS < nslabs) load_slab(RS, std::integral_constant<int, 0>{});
+    load_slab(RS < last ? RS : last, std::integral_constant<int, 0>{});
     __syncthreads();
 
-    // ---- main loop, unrolled by RS so that register stages are compile-time
+    // ---- main loop, unrolled by RS so that register stages are compile-time.
+    // The body has no data-dependent guards: past the end it stages and reloads the last slab
+    // again (into the LDS buffer nobody reads).
     for (int s0 = 0; s0 < nslabs; s0 += RS) {
         static_for<RS>([&](auto sc) {
             constexpr int j = decltype(sc)::value;
             const int s = s0 + j;
-            if (s < nslabs) {
+            if (RS == 1 || s < nslabs) {
                 using NextStage = std::integral_constant<int, (j + 1) % RS>;
-                compute_slab(s);
-                if (s + 1 < nslabs) stage_slab(s + 1, NextStage{});
-                if (s + 1 + RS < nslabs) load_slab(s + 1 + RS, NextStage{});
+                fetch_mask_bytes(s + 1 < last ? s + 1 : last);
+                if (!(dbg & 1)) compute_slab(s);
+                if (!(dbg & 2)) stage_slab(s + 1, NextStage{});
+                if (!(dbg & 4)) load_slab(s + 1 + RS < last ? s + 1 + RS : last, NextStage{});
                 // next panel's factors and mask, spread over three slabs
                 const int ps = s % PANEL_SLABS;
                 const int next_panel = s / PANEL_SLABS + 1;
@@ -664,9 +711,31 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_panel_kernel(
                     if (ps == 1) store_factors(next_panel);
                     if (ps == 2) decode_panel(next_panel);
                 }
-                __syncthreads();
+                if (!(dbg & 8)) __syncthreads();
             }
         });
+    }
+
+    // ---- two wave groups: group 1 hands its accumulators to group 0 through LDS
+    if (KGROUPS == 2) {
+        float *red = (float *)lrbi_dyn_smem; // [4 waves][FN][FM][16][64 lanes]; the loop buffers are dead now
+        float *mine = red + (size_t)w4 * (FN * FM * 16 * 64) + lane;
+        if (kg == 1) {
+#pragma unroll
+            for (int a = 0; a < FN; ++a)
+#pragma unroll
+                for (int b = 0; b < FM; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) mine[((a * FM + b) * 16 + v) * 64] = acc[a][b][v];
+        }
+        __syncthreads();
+        if (kg == 1) return;
+#pragma unroll
+        for (int a = 0; a < FN; ++a)
+#pragma unroll
+            for (int b = 0; b < FM; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[a][b][v] += mine[((a * FM + b) * 16 + v) * 64];
     }
 
     // epilogue: lane holds, per 32x32 block, rows n = 8*(v/4) + 4*lg + (v%4) and column m = l32
@@ -710,11 +779,11 @@ struct TileDef {
     int bm, bn;
     bool panel; // panel kernel (needs c % 128 == 0, r % bm == 0, k <= 64)
 };
-// tile ids (desc.flags bits 16..19); 0 = automatic.  1-3: generic kernel, 4-8: panel kernel.
-static const TileDef kTiles[] = {{0, 0, false},   {128, 128, false}, {128, 64, false}, {128, 32, false},
+// tile ids (desc.flags bits 16..19); 0 = automatic.  1-3: generic kernel, 4-11: panel kernel.
+static const TileDef kTiles[] = {{0, 0, false},    {128, 128, false}, {128, 64, false}, {128, 32, false},
                                  {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
-                                 {128, 128, true}};
-static constexpr int kNumTiles = 8;
+                                 {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true}};
+static constexpr int kNumTiles = 11;
 
 static bool panel_ok(const Geom &g, int bm) { return (g.c % 128 == 0) && (g.r % bm == 0) && (g.k <= FAST_MAX_K); }
 
@@ -725,7 +794,7 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
     if (tile >= 1 && tile <= kNumTiles && kTiles[tile].panel && !panel_ok(g, kTiles[tile].bm)) tile = 0;
     if (tile < 1 || tile > kNumTiles) {
         tile = (N > 64) ? 1 : (N > 32 ? 2 : 3);
-        if (panel_ok(g, 128)) tile = (N > 64) ? 4 : (N > 32 ? 6 : 7);
+        if (panel_ok(g, 128)) tile = (N > 64) ? 9 : (N > 32 ? 10 : 11);
     }
     p.tile = tile;
     p.bm = kTiles[tile].bm;
@@ -756,7 +825,7 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
     return p;
 }
 
-template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N, int RS /* 0: generic kernel */>
+template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N, int RS /* 0: generic kernel */, int KGROUPS = 1>
 static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
                        const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
                        void *dWorkspace, hipStream_t stream)
@@ -771,7 +840,7 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
     const int y_vec_ok = (((uintptr_t)dY & 7) == 0) && (ldy % 4 == 0);
     const int xcd_remap = (blocks % 8 == 0) ? 1 : 0;
     const int64_t ldp = (N + 3) / 4 * 4;
-    const dim3 grid((unsigned)blocks), block(kThreads);
+    const dim3 grid((unsigned)blocks), block(RS > 0 ? 256 * KGROUPS : kThreads);
 
 #define LRBI_LAUNCH(KERN, SMEM)                                                                                   \
     do {                                                                                                          \
@@ -783,15 +852,26 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
                            (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp,      \
                            (int)mblocks, (int)nblocks, plan.kper, xcd_remap, y_vec_ok);                           \
     } while (0)
+#define LRBI_LAUNCH_P(KERN, SMEM)                                                                                   \
+    do {                                                                                                          \
+        auto kern = KERN;                                                                                         \
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(SMEM)) !=   \
+            hipSuccess)                                                                                           \
+            return LRBI_ERR_LAUNCH;                                                                               \
+        hipLaunchKernelGGL(kern, grid, block, (SMEM), stream, g, (const uint16_t *)dW, ldw, dIp, dIz,             \
+                           (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp,      \
+                           (int)mblocks, (int)nblocks, plan.kper, xcd_remap, y_vec_ok, dbg);                      \
+    } while (0)
 
     if constexpr (RS > 0) {
         const size_t smem = SmemPanel<BM, BN>::bytes;
+        static const int dbg = getenv("LRBI_DBG") ? atoi(getenv("LRBI_DBG")) : 0;
         if (xvec) {
-            if (split) LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, RS, true, true>), smem);
-            else LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, RS, true, false>), smem);
+            if (split) LRBI_LAUNCH_P((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, true>), smem);
+            else LRBI_LAUNCH_P((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, false>), smem);
         } else {
-            if (split) LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, RS, false, true>), smem);
-            else LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, RS, false, false>), smem);
+            if (split) LRBI_LAUNCH_P((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, true>), smem);
+            else LRBI_LAUNCH_P((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, false>), smem);
         }
     } else {
         const size_t smem = Smem<BM, BN>::bytes;
@@ -814,6 +894,7 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
         }
     }
 #undef LRBI_LAUNCH
+#undef LRBI_LAUNCH_P
     LRBI_CHECK_LAUNCH();
 
     if (split) {
@@ -833,7 +914,10 @@ static int launch_dtype(const Geom &g, const MfmaPlan &plan, const void *dW, int
                         const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
                         void *dWorkspace, hipStream_t stream)
 {
-    switch (plan.tile) {
+    int tile = plan.tile;
+    // the panel kernel keeps per-lane element offsets in 32 bits
+    if (kTiles[tile].panel && (ldw > (1 << 24) || ldx > (1 << 24))) tile = (kTiles[tile].bn == 128) ? 1 : (kTiles[tile].bn == 64 ? 2 : 3);
+    switch (tile) {
     case 1: return launch_tile<Tag, 128, 128, 2, 2, 0>(LRBI_TILE_ARGS);
     case 2: return launch_tile<Tag, 128, 64, 2, 2, 0>(LRBI_TILE_ARGS);
     case 3: return launch_tile<Tag, 128, 32, 4, 1, 0>(LRBI_TILE_ARGS);
@@ -842,6 +926,9 @@ static int launch_dtype(const Geom &g, const MfmaPlan &plan, const void *dW, int
     case 6: return launch_tile<Tag, 128, 64, 2, 2, 2>(LRBI_TILE_ARGS);
     case 7: return launch_tile<Tag, 128, 32, 4, 1, 3>(LRBI_TILE_ARGS);
     case 8: return launch_tile<Tag, 128, 128, 2, 2, 1>(LRBI_TILE_ARGS);
+    case 9: return launch_tile<Tag, 128, 128, 2, 2, 2, 2>(LRBI_TILE_ARGS);
+    case 10: return launch_tile<Tag, 128, 64, 2, 2, 2, 2>(LRBI_TILE_ARGS);
+    case 11: return launch_tile<Tag, 128, 32, 4, 1, 2, 2>(LRBI_TILE_ARGS);
     default: return LRBI_ERR_FLAGS;
     }
 }

@@ -71,7 +71,7 @@ EDGE = [
     (_small(130, 4104, 65, 1368, 9, 0.1, 1, "bf16"), 0),     # n spans three 2048-column segments
     (_small(130, 4104, 65, 1368, 9, 0.1, 3, "f16"), 0),
     (_small(128, 192, 64, 64, 8, 0.2, 128, "bf16"), 0),      # one 128x128 tile, 3 slabs
-    (_small(300, 600, 300, 300, 8, 0.12, 20, "f16"), 0),     # unaligned tiles, scalar X path, split
+    (_small(300, 2400, 300, 300, 8, 0.12, 20, "f16"), 0),    # unaligned tiles, scalar X path, split
     (_small(384, 1024, 128, 256, 16, 0.1, 72, "f16"), 0),    # 128x64 tile variant (N in 33..64 -> padded)
     (_small(384, 1024, 128, 256, 16, 0.1, 40, "bf16"), 0),
     (_small(200, 1000, 100, 500, 40, 0.05, 136, "bf16"), 0), # rank above 32, ragged m and N
@@ -104,7 +104,7 @@ def test_padded_leading_dimensions():
 
 
 def test_without_workspace_falls_back_to_unsplit_kernel():
-    cfg = _small(300, 600, 300, 300, 8, 0.12, 20, "f16")
+    cfg = _small(300, 2400, 300, 300, 8, 0.12, 20, "f16")
     data = workloads.make(cfg)
     assert lrbi.masked_gemm_workspace_bytes(desc_of(cfg), lrbi.F16, cfg.N) > 0
     ref, _ = _oracle(cfg, data)
