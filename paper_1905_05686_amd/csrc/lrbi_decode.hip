@@ -78,12 +78,12 @@ __device__ __forceinline__ uint4 or4(uint4 a, uint4 b)
 // issued back to back (their LDS latencies overlap); `zero_row` is an all-zero row of the table
 // that absorbs the slots of words with fewer set bits.  Leftover bits take the loop.
 __device__ __forceinline__ uint4 or_selected(uint4 acc, uint32_t sel, int l_base, const uint4 *__restrict__ Zq,
-                                             int zstride, int zero_row)
+                                             int zshift, int zero_row)
 {
     int l0 = zero_row, l1 = zero_row;
     if (sel) { l0 = __builtin_ctz(sel) + l_base; sel &= sel - 1u; }
     if (sel) { l1 = __builtin_ctz(sel) + l_base; sel &= sel - 1u; }
-    const uint4 z0 = Zq[l0 * zstride], z1 = Zq[l1 * zstride];
+    const uint4 z0 = Zq[l0 << zshift], z1 = Zq[l1 << zshift];
     acc.x |= z0.x | z1.x;
     acc.y |= z0.y | z1.y;
     acc.z |= z0.z | z1.z;
@@ -91,7 +91,7 @@ __device__ __forceinline__ uint4 or_selected(uint4 acc, uint32_t sel, int l_base
     while (sel) {
         const int l = __builtin_ctz(sel) + l_base;
         sel &= sel - 1u;
-        acc = or4(acc, Zq[l * zstride]);
+        acc = or4(acc, Zq[l << zshift]);
     }
     return acc;
 }
@@ -99,7 +99,8 @@ __device__ __forceinline__ uint4 or_selected(uint4 acc, uint32_t sel, int l_base
 // Launch-time constants of the item decomposition.
 struct DecodePlan {
     int chunks;             // 16-byte pieces per mask row
-    int span_chunks;        // pieces per span
+    int span_chunks;        // pieces per span (a power of two, so the table's row stride is a shift)
+    int zshift;             // log2(span_chunks)
     int spans;              // spans per row
     int rows_per_band;
     int bands_per_tile_row;
@@ -181,7 +182,7 @@ __device__ __forceinline__ void decode_item_rows(const Geom &g, const DecodePlan
             const int ip_step = TY * g.ipw;
             for (int i = ty; i < it.nrows; i += TY, ipr += ip_step, out += out_step) {
                 uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-                for (int iw = 0; iw < g.ipw; ++iw) acc = or_selected(acc, ipr[iw], 32 * iw, Zq, p.span_chunks, zero_row);
+                for (int iw = 0; iw < g.ipw; ++iw) acc = or_selected(acc, ipr[iw], 32 * iw, Zq, p.zshift, zero_row);
                 *out = acc;
             }
         } else {
@@ -201,7 +202,7 @@ __device__ __forceinline__ void decode_item_rows(const Geom &g, const DecodePlan
                     tm.z = bit_range(lo - 64 < 0 ? 0 : lo - 64, hi - 64 > 32 ? 32 : hi - 64);
                     tm.w = bit_range(lo - 96 < 0 ? 0 : lo - 96, hi - 96 > 32 ? 32 : hi - 96);
                     uint4 v = make_uint4(0u, 0u, 0u, 0u);
-                    for (int iw = 0; iw < g.ipw; ++iw) v = or_selected(v, ipr[iw], 32 * iw, Zq, p.span_chunks, zero_row);
+                    for (int iw = 0; iw < g.ipw; ++iw) v = or_selected(v, ipr[iw], 32 * iw, Zq, p.zshift, zero_row);
                     acc.x |= v.x & tm.x;
                     acc.y |= v.y & tm.y;
                     acc.z |= v.z & tm.z;
@@ -291,8 +292,10 @@ __global__ __launch_bounds__(kStreamThreads) void decode_stream_kernel(Geom g, D
     const int ip_rows = p.rows_per_band + 1;
     const int ip_words = p.span_tiles * ip_rows * g.ipw;
     const int buf_pieces = z_pieces + (ip_words + 3) / 4;
-    uint4 *Zb[2] = {lrbi_dyn_smem, lrbi_dyn_smem + buf_pieces};
-    uint32_t *Ipb[2] = {(uint32_t *)(Zb[0] + z_pieces), (uint32_t *)(Zb[1] + z_pieces)};
+    // buffer b: Z at lrbi_dyn_smem + b * buf_pieces, IpL right behind it (kept as offsets from the
+    // LDS symbol so that the compiler emits LDS instructions, not generic ones)
+#define LRBI_ZB(b) (lrbi_dyn_smem + (b) * buf_pieces)
+#define LRBI_IPB(b) ((uint32_t *)(lrbi_dyn_smem + (b) * buf_pieces + z_pieces))
 
     uint4 zreg[kMaxZPerLane];
     uint32_t ipreg[kMaxIpPerLane];
@@ -301,7 +304,7 @@ __global__ __launch_bounds__(kStreamThreads) void decode_stream_kernel(Geom g, D
     // the zero rows never change
     for (int w = threadIdx.x; w < 2 * p.span_chunks; w += kStreamThreads) {
         const int b = w / p.span_chunks, q = w - b * p.span_chunks;
-        Zb[b][g.k * p.span_chunks + q] = make_uint4(0u, 0u, 0u, 0u);
+        LRBI_ZB(b)[g.k * p.span_chunks + q] = make_uint4(0u, 0u, 0u, 0u);
     }
 
     auto load_item = [&](const Item &it) {
@@ -337,12 +340,12 @@ __global__ __launch_bounds__(kStreamThreads) void decode_stream_kernel(Geom g, D
             const int idx = threadIdx.x + kStreamThreads * j;
             if (idx < total) {
                 const int l = idx / it.nq, q = idx - l * it.nq;
-                Zb[b][l * p.span_chunks + q] = zreg[j];
+                LRBI_ZB(b)[l * p.span_chunks + q] = zreg[j];
             }
         }
 #pragma unroll
         for (int j = 0; j < kMaxIpPerLane; ++j)
-            if (ipdst[j] >= 0) Ipb[b][ipdst[j]] = ipreg[j];
+            if (ipdst[j] >= 0) LRBI_IPB(b)[ipdst[j]] = ipreg[j];
     };
 
     int64_t id = blockIdx.x;
@@ -360,7 +363,7 @@ __global__ __launch_bounds__(kStreamThreads) void decode_stream_kernel(Geom g, D
             nxt = make_item(g, p, next_id);
             load_item(nxt); // in flight while the current item is decoded
         }
-        decode_item_rows<ALIGNED>(g, p, cur, Zb[b], Ipb[b], mask, kStreamThreads);
+        decode_item_rows<ALIGNED>(g, p, cur, LRBI_ZB(b), LRBI_IPB(b), mask, kStreamThreads);
         if (!has_next) break;
         store_item(nxt, b ^ 1); // the other copy was last read before the previous barrier
         __syncthreads();
@@ -368,6 +371,8 @@ __global__ __launch_bounds__(kStreamThreads) void decode_stream_kernel(Geom g, D
         cur = nxt;
         id = next_id;
     }
+#undef LRBI_ZB
+#undef LRBI_IPB
 }
 
 int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint32_t *dIz, void *dMask,
@@ -395,10 +400,12 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
     p.span_chunks = kZTableBudgetBytes / (16 * (g.k + 1));
     if (p.span_chunks < 1) p.span_chunks = 1;
     if (p.span_chunks > 64) p.span_chunks = 64;
-    if (p.span_chunks > p.chunks) p.span_chunks = p.chunks;
+    p.zshift = 0;
+    while ((2 << p.zshift) <= p.span_chunks) ++p.zshift;
+    while (p.zshift > 0 && (1 << (p.zshift - 1)) >= p.chunks) --p.zshift; // no wider than the row needs
+    p.span_chunks = 1 << p.zshift;
     p.spans = (p.chunks + p.span_chunks - 1) / p.span_chunks;
-    p.tx_log2 = 0;
-    while ((1 << p.tx_log2) < p.span_chunks && p.tx_log2 < 6) ++p.tx_log2;
+    p.tx_log2 = p.zshift;
     p.span_tiles = (int)(((int64_t)p.span_chunks * 128 + g.c - 1) / g.c) + 1;
     p.rows_per_band = g.r;
     const int cap_rows = kIpBudgetBytes / (4 * g.ipw * p.span_tiles) - 1;
