@@ -375,6 +375,245 @@ __global__ __launch_bounds__(kStreamThreads) void decode_stream_kernel(Geom g, D
 #undef LRBI_IPB
 }
 
+// ---------------------------------------------------------------------------
+// Nibble-table kernel (tile widths that are multiples of 128 columns).
+//
+// Walking the set bits of an I_p word costs a data-dependent loop per lane, and a wavefront
+// runs as long as its busiest lane.  Here the OR over the selected I_z rows is tabulated
+// instead: the k rank indices are cut into G = ceil(k / 4) groups of 4, and for every tile
+// under the span and every group the 16 possible ORs of that group's I_z rows are built
+// once per item in LDS ("four Russians").  A mask row piece is then the OR of exactly G table
+// entries picked by the nibbles of the I_p word: no loop, no divergence, G independent LDS
+// reads in flight.  Persistent workgroups of 1024 lanes; the factor loads of the next item
+// are in flight while the current item's rows are decoded and stored.
+//   T   [tiles][G][16][cpt] 16-byte pieces (cpt = c / 128 pieces per tile row), double buffered
+//   IpL [tiles][rows + 1][ipw] words, double buffered
+//   Zs  [tiles][k][cpt] pieces: the raw I_z rows of the item being built
+// ---------------------------------------------------------------------------
+struct NibblePlan {
+    int chunks;        // 16-byte pieces per mask row
+    int cpt;           // pieces per tile row (c / 128)
+    int G;             // nibble groups per I_p row
+    int span_tiles;    // tiles per span
+    int spans;         // spans per mask row
+    int rows_per_band;
+    int bands_per_tile_row;
+    int tx_log2;       // lanes across a span (power of two >= span_tiles * cpt)
+    int iz16;
+    int64_t pitch16;
+    int64_t items;
+    int t_pieces;      // pieces in one T buffer
+    int ip_words;      // words in one IpL buffer (multiple of 4)
+    int zs_pieces;     // pieces in Zs
+    int dbg;
+};
+static constexpr int kNibTableBytes = 32 * 1024;
+static constexpr int kNibIpBytes = 10 * 1024;
+static constexpr int kNibMaxIpPerLane = (kNibIpBytes / 4 + kStreamThreads - 1) / kStreamThreads;
+
+struct NibItem {
+    int ti, row_lo, nrows, tj_first, ntiles;
+};
+__device__ __forceinline__ NibItem make_nib_item(const Geom &g, const NibblePlan &p, int64_t id)
+{
+    NibItem it;
+    const int span = (int)(id % p.spans);
+    const int64_t band = id / p.spans;
+    it.ti = (int)(band / p.bands_per_tile_row);
+    it.row_lo = (int)(band - (int64_t)it.ti * p.bands_per_tile_row) * p.rows_per_band;
+    const int row_hi = (it.row_lo + p.rows_per_band < g.r) ? it.row_lo + p.rows_per_band : g.r;
+    it.nrows = row_hi - it.row_lo;
+    it.tj_first = span * p.span_tiles;
+    it.ntiles = (it.tj_first + p.span_tiles <= g.tile_cols) ? p.span_tiles : g.tile_cols - it.tj_first;
+    return it;
+}
+
+__device__ __forceinline__ uint4 or3x4(uint4 a, uint4 b, uint4 c)
+{
+    return make_uint4(a.x | b.x | c.x, a.y | b.y | c.y, a.z | b.z | c.z, a.w | b.w | c.w);
+}
+
+template <int GT /* compile-time G, 0 = run-time */>
+__global__ __launch_bounds__(kStreamThreads) void decode_nibble_kernel(Geom g, NibblePlan p,
+                                                                       const uint32_t *__restrict__ Ip,
+                                                                       const uint32_t *__restrict__ Iz,
+                                                                       uint4 *__restrict__ mask)
+{
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    const int G = GT ? GT : p.G;
+    const int ip_rows = p.rows_per_band + 1;
+    const int buf_pieces = p.t_pieces + p.ip_words / 4;
+#define LRBI_TB(b) (lrbi_dyn_smem + (b) * buf_pieces)
+#define LRBI_IPB(b) ((uint32_t *)(lrbi_dyn_smem + (b) * buf_pieces + p.t_pieces))
+    uint4 *Zs = lrbi_dyn_smem + 2 * buf_pieces;
+
+    uint4 zreg;                       // at most one I_z piece per lane and item
+    int zdst;
+    uint32_t ipreg[kNibMaxIpPerLane];
+    int ipdst[kNibMaxIpPerLane];
+
+    auto load_item = [&](const NibItem &it) {
+        // I_z rows of the item's tiles: piece index = (tile, l, piece in tile row)
+        const int total = it.ntiles * g.k * p.cpt;
+        zdst = -1;
+        zreg = make_uint4(0u, 0u, 0u, 0u);
+        if ((int)threadIdx.x < total) {
+            const int per_tile = g.k * p.cpt;
+            const int tl = threadIdx.x / per_tile, e = threadIdx.x - tl * per_tile;
+            const uint32_t *src = Iz + ((int64_t)it.ti * g.tile_cols + it.tj_first + tl) * g.k * (int64_t)g.izw + 4 * e;
+            // a tile's k rows are contiguous (izw = 4 * cpt words per row), so e indexes them linearly
+            if (p.iz16) zreg = *reinterpret_cast<const uint4 *>(src);
+            else zreg = make_uint4(src[0], src[1], src[2], src[3]);
+            zdst = threadIdx.x;
+        }
+        const int ip_per_tile = it.nrows * g.ipw;
+        const int ip_total = it.ntiles * ip_per_tile;
+#pragma unroll
+        for (int j = 0; j < kNibMaxIpPerLane; ++j) {
+            const int idx = threadIdx.x + kStreamThreads * j;
+            ipreg[j] = 0u;
+            ipdst[j] = -1;
+            if (idx < ip_total) {
+                const int tl = idx / ip_per_tile, e = idx - tl * ip_per_tile;
+                const int64_t t = (int64_t)it.ti * g.tile_cols + it.tj_first + tl;
+                ipreg[j] = Ip[(t * g.r + it.row_lo) * g.ipw + e];
+                ipdst[j] = (tl * ip_rows) * g.ipw + e;
+            }
+        }
+    };
+    auto stash_item = [&](int b) {
+        if (zdst >= 0) Zs[zdst] = zreg;
+#pragma unroll
+        for (int j = 0; j < kNibMaxIpPerLane; ++j)
+            if (ipdst[j] >= 0) LRBI_IPB(b)[ipdst[j]] = ipreg[j];
+    };
+    // T[tile][g][nib][piece] = OR of the I_z rows 4g + bit, bit in nib
+    auto build_table = [&](const NibItem &it, int b) {
+        const int total = it.ntiles * G * 16 * p.cpt;
+        for (int idx = threadIdx.x; idx < total; idx += kStreamThreads) {
+            const int cq = idx % p.cpt;
+            const int rest = idx / p.cpt;
+            const int nib = rest & 15;
+            const int tg = rest >> 4; // tile * G + g
+            const int tl = tg / G, gg = tg - tl * G;
+            uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int bit = 0; bit < 4; ++bit) {
+                const int l = 4 * gg + bit;
+                if (((nib >> bit) & 1) && l < g.k) acc = or4(acc, Zs[(tl * g.k + l) * p.cpt + cq]);
+            }
+            LRBI_TB(b)[idx] = acc;
+        }
+    };
+    auto decode_rows = [&](const NibItem &it, int b) {
+        const int TX = 1 << p.tx_log2;
+        const int tx = threadIdx.x & (TX - 1);
+        const int ty = threadIdx.x >> p.tx_log2;
+        const int TY = kStreamThreads >> p.tx_log2;
+        if (tx >= it.ntiles * p.cpt) return;
+        const int tl = tx / p.cpt, cq = tx - tl * p.cpt;
+        const uint4 *Tq = LRBI_TB(b) + (tl * G * 16) * p.cpt + cq;
+        const uint32_t *ipr = LRBI_IPB(b) + (tl * ip_rows + ty) * g.ipw;
+        const int ip_step = TY * g.ipw;
+        uint4 *out = mask + ((int64_t)it.ti * g.r + it.row_lo + ty) * p.pitch16 + (int64_t)(it.tj_first + tl) * p.cpt + cq;
+        const int64_t out_step = (int64_t)TY * p.pitch16;
+        const uint4 *zero_piece = LRBI_TB(b); // entry (tile 0, group 0, nibble 0): all zero
+        const int nstride = p.cpt;       // pieces between nibble values
+        const int gstride = 16 * p.cpt;  // pieces between groups
+        for (int i = ty; i < it.nrows; i += TY, ipr += ip_step, out += out_step) {
+            uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+            if (p.dbg & 1) {
+            } else if (GT == 1 || GT == 2 || GT == 4 || GT == 8) {
+                // one I_p word holds all nibbles; GT independent table reads, OR tree of 3-input ORs
+                const uint32_t w = ipr[0];
+                uint4 e[GT ? GT : 1];
+#pragma unroll
+                for (int gg = 0; gg < GT; ++gg) {
+                    // A zero nibble selects an all-zero entry.  Most nibbles are zero, so those lanes
+                    // all read ONE shared zero piece (a broadcast, no bank pressure) instead of their
+                    // own tile's zero entry; LDS time then goes with the lanes that carry set bits.
+                    const uint32_t nib = (w >> (4 * gg)) & 15u;
+                    const uint4 *src = nib ? (Tq + gg * gstride + nib * nstride) : zero_piece;
+                    e[gg] = *src;
+                }
+                if (GT == 1) acc = e[0];
+                if (GT == 2) acc = or4(e[0], e[1]);
+                if (GT == 4) acc = or4(or3x4(e[0], e[1], e[2]), e[3]);
+                if (GT == 8) acc = or3x4(or3x4(e[0], e[1], e[2]), or3x4(e[3], e[4], e[5]), or4(e[6], e[7]));
+            } else {
+                for (int gg = 0; gg < G; ++gg) {
+                    const uint32_t w = ipr[gg >> 3];
+                    acc = or4(acc, Tq[gg * gstride + ((w >> (4 * (gg & 7))) & 15u) * nstride]);
+                }
+            }
+            if (!(p.dbg & 2) || acc.x == 0xdeadbeefu) *out = acc;
+        }
+    };
+
+    int64_t id = blockIdx.x;
+    if (id >= p.items) return;
+    NibItem cur = make_nib_item(g, p, id);
+    load_item(cur);
+    stash_item(0);
+    __syncthreads();
+    build_table(cur, 0);
+    __syncthreads();
+    int b = 0;
+    for (;;) {
+        const int64_t next_id = id + gridDim.x;
+        const bool has_next = next_id < p.items;
+        NibItem nxt = cur;
+        if (has_next) {
+            nxt = make_nib_item(g, p, next_id);
+            load_item(nxt); // in flight while the current item is decoded
+        }
+        decode_rows(cur, b);
+        if (!has_next) break;
+        stash_item(b ^ 1);   // Zs and buffer b^1 were last read before the previous barrier
+        __syncthreads();
+        build_table(nxt, b ^ 1);
+        __syncthreads();
+        b ^= 1;
+        cur = nxt;
+        id = next_id;
+    }
+#undef LRBI_TB
+#undef LRBI_IPB
+}
+
+// Fills the plan and returns true when the nibble-table kernel can serve the geometry.
+static bool plan_nibble(const Geom &g, NibblePlan &p, int64_t pitch_bytes, const void *dIz, int cus)
+{
+    if (g.c % 128 != 0) return false;
+    p.cpt = g.c / 128;
+    if (p.cpt > 64) return false;
+    p.G = (g.k + 3) / 4;
+    const int per_tile_pieces = p.G * 16 * p.cpt;
+    p.span_tiles = (kNibTableBytes / 16) / per_tile_pieces;
+    if (p.span_tiles > 64 / p.cpt) p.span_tiles = 64 / p.cpt;
+    if (p.span_tiles > g.tile_cols) p.span_tiles = g.tile_cols;
+    if (p.span_tiles < 1) return false;
+    if (p.span_tiles * g.k * p.cpt > kStreamThreads) return false; // one I_z piece per lane
+    p.chunks = (int)((g.n + 127) / 128);
+    p.spans = (g.tile_cols + p.span_tiles - 1) / p.span_tiles;
+    p.tx_log2 = 0;
+    while ((1 << p.tx_log2) < p.span_tiles * p.cpt) ++p.tx_log2;
+    p.rows_per_band = g.r;
+    const int cap_rows = kNibIpBytes / (4 * g.ipw * p.span_tiles) - 1;
+    if (p.rows_per_band > cap_rows) p.rows_per_band = cap_rows;
+    if (p.rows_per_band < 16 && p.rows_per_band < g.r) return false;
+    p.bands_per_tile_row = (g.r + p.rows_per_band - 1) / p.rows_per_band;
+    p.items = (int64_t)p.spans * g.tile_rows * p.bands_per_tile_row;
+    if (p.items < 4 * (int64_t)cus || p.items > 0x7FFFFFFF) return false;
+    p.iz16 = (((uintptr_t)dIz & 15) == 0) ? 1 : 0;
+    p.pitch16 = pitch_bytes / 16;
+    p.t_pieces = p.span_tiles * per_tile_pieces;
+    p.ip_words = (p.span_tiles * (p.rows_per_band + 1) * g.ipw + 3) / 4 * 4;
+    p.zs_pieces = p.span_tiles * g.k * p.cpt;
+    p.dbg = getenv("LRBI_DBG_DEC") ? atoi(getenv("LRBI_DBG_DEC")) : 0;
+    return true;
+}
+
 int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint32_t *dIz, void *dMask,
                   int64_t pitch_bytes, hipStream_t stream)
 {
@@ -393,6 +632,32 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
         return LRBI_OK;
     };
     if (flags & LRBI_FLAG_DECODE_GENERIC) return launch_generic();
+
+    int device = 0, cus = 256;
+    if (hipGetDevice(&device) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && v > 0) cus = v;
+    }
+    {
+        NibblePlan np;
+        if (plan_nibble(g, np, pitch_bytes, dIz, cus)) {
+            const size_t lds = ((size_t)2 * (np.t_pieces + np.ip_words / 4) + np.zs_pieces) * 16;
+            auto kern = decode_nibble_kernel<0>;
+            switch (np.G) {
+            case 1: kern = decode_nibble_kernel<1>; break;
+            case 2: kern = decode_nibble_kernel<2>; break;
+            case 4: kern = decode_nibble_kernel<4>; break;
+            case 8: kern = decode_nibble_kernel<8>; break;
+            default: break;
+            }
+            if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                return LRBI_ERR_LAUNCH;
+            hipLaunchKernelGGL(kern, dim3((unsigned)cus), dim3(kStreamThreads), lds, stream, g, np, dIp, dIz,
+                               (uint4 *)dMask);
+            LRBI_CHECK_LAUNCH();
+            return LRBI_OK;
+        }
+    }
 
     // Column span per item: as wide as the Z table budget allows, at most 64 pieces (one
     // wavefront across).  Rows per band: as many as the I_p budget allows (one table build per
@@ -423,11 +688,6 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
     const size_t ip_bytes = ((size_t)p.span_tiles * (p.rows_per_band + 1) * g.ipw * 4 + 15) / 16 * 16;
     const bool aligned = (g.c % 128) == 0;
 
-    int device = 0, cus = 256;
-    if (hipGetDevice(&device) == hipSuccess) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && v > 0) cus = v;
-    }
     // streaming pays off once every compute unit gets several items
     if (p.items >= 4 * (int64_t)cus) {
         const size_t lds = 2 * (z_bytes + ip_bytes);

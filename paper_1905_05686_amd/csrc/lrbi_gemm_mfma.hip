@@ -524,6 +524,7 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
 
     auto load_slab = [&](int slab, auto stage_c) {
         constexpr int st = decltype(stage_c)::value;
+        if (dbg & 512) slab = (slab + 2 * ((mi * 3) % (nslabs / 2))) % nslabs;
         const uint16_t *wb = wbase + slab * BK;
         const uint16_t *xb = xbase_g + (int64_t)slab * BK * ldx;
         if (!(dbg & 16)) {
@@ -700,8 +701,15 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
             if (RS == 1 || s < nslabs) {
                 using NextStage = std::integral_constant<int, (j + 1) % RS>;
                 fetch_mask_bytes(s + 1 < last ? s + 1 : last);
-                if (!(dbg & 1)) compute_slab(s);
-                if (!(dbg & 2)) stage_slab(s + 1, NextStage{});
+                // the two wave groups run the two halves of the iteration in opposite order, so that on
+                // every SIMD one wavefront issues MFMAs while the other does the mask arithmetic
+                if (KGROUPS == 2 && kg == 1 && !(dbg & 1024)) {
+                    if (!(dbg & 2)) stage_slab(s + 1, NextStage{});
+                    if (!(dbg & 1)) compute_slab(s);
+                } else {
+                    if (!(dbg & 1)) compute_slab(s);
+                    if (!(dbg & 2)) stage_slab(s + 1, NextStage{});
+                }
                 if (!(dbg & 4)) load_slab(s + 1 + RS < last ? s + 1 + RS : last, NextStage{});
                 // next panel's factors and mask, spread over three slabs
                 const int ps = s % PANEL_SLABS;
@@ -782,8 +790,9 @@ struct TileDef {
 // tile ids (desc.flags bits 16..19); 0 = automatic.  1-3: generic kernel, 4-11: panel kernel.
 static const TileDef kTiles[] = {{0, 0, false},    {128, 128, false}, {128, 64, false}, {128, 32, false},
                                  {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
-                                 {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true}};
-static constexpr int kNumTiles = 11;
+                                 {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
+                                 {128, 128, true}, {128, 128, true}};
+static constexpr int kNumTiles = 13;
 
 static bool panel_ok(const Geom &g, int bm) { return (g.c % 128 == 0) && (g.r % bm == 0) && (g.k <= FAST_MAX_K); }
 
@@ -929,6 +938,8 @@ static int launch_dtype(const Geom &g, const MfmaPlan &plan, const void *dW, int
     case 9: return launch_tile<Tag, 128, 128, 2, 2, 2, 2>(LRBI_TILE_ARGS);
     case 10: return launch_tile<Tag, 128, 64, 2, 2, 2, 2>(LRBI_TILE_ARGS);
     case 11: return launch_tile<Tag, 128, 32, 4, 1, 2, 2>(LRBI_TILE_ARGS);
+    case 12: return launch_tile<Tag, 128, 128, 2, 2, 3, 2>(LRBI_TILE_ARGS);
+    case 13: return launch_tile<Tag, 128, 128, 2, 2, 4, 2>(LRBI_TILE_ARGS);
     default: return LRBI_ERR_FLAGS;
     }
 }
