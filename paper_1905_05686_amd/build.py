@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
@@ -17,8 +18,28 @@ FLAGS = [
     # packed fp32 ALU forms are kept out of the generated code on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
+    # per-kernel register / private-memory report, checked below
+    "-Rpass-analysis=kernel-resource-usage",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
+
+
+def _private_memory_users(remarks: str):
+    """Kernels whose compiled code keeps per-lane data in private (scratch) memory.
+
+    Every kernel here is written to live in registers: private memory means that a register
+    array was indexed in a way the compiler could not resolve, which turns prefetches into
+    synchronous round trips through memory."""
+    bad = []
+    name = None
+    for line in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and int(m.group(1)) > 0:
+            bad.append((name, int(m.group(1))))
+    return bad
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
@@ -34,7 +55,13 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     failed = False
     for src, p in procs:
         out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l and l.strip())
+        for name, nbytes in _private_memory_users(out):
+            failed = True
+            print("FAILED: %s: kernel %s uses %d bytes of private memory per lane" % (src, name, nbytes),
+                  file=sys.stderr)
+        out = "\n".join(l for l in out.splitlines()
+                        if "packed-fp32-ops" not in l and "-Rpass-analysis" not in l and l.strip()
+                        and not re.match(r"\s*(\d+\s*)?\|", l))
         if p.returncode != 0:
             failed = True
             print("FAILED: %s\n%s" % (src, out), file=sys.stderr)

@@ -81,6 +81,19 @@ __device__ __forceinline__ uint32_t select2(uint32_t w, uint32_t pair)
 {
     return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, w) * __builtin_bit_cast(u16x2, pair));
 }
+// 16-byte register piece as a native vector (kept in registers by construction; an array of
+// class-type vectors indexed by pipeline stage was demoted to private memory by the compiler)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4 apply_mask8(u32x4 w, uint32_t bits8)
+{
+    const uint32_t y = bits8 | (bits8 << 15);
+    u32x4 o;
+    o.x = select2(w.x, y & 0x00010001u);
+    o.y = select2(w.y, (y >> 2) & 0x00010001u);
+    o.z = select2(w.z, (y >> 4) & 0x00010001u);
+    o.w = select2(w.w, (y >> 6) & 0x00010001u);
+    return o;
+}
 __device__ __forceinline__ uint4 apply_mask8(uint4 w, uint32_t bits8)
 {
     // y holds bit j of bits8 at positions j and j + 15: (y >> 2q) & 0x00010001 = (b_2q, b_2q+1) per half
@@ -425,7 +438,7 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
     Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
     const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ X, int64_t ldx, int N,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ P, int64_t ldp, int mblocks, int nblocks,
-    int64_t kper, int xcd_remap, int y_vec_ok, int dbg)
+    int64_t kper, int xcd_remap, int y_vec_ok)
 {
     static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per group");
     static_assert(KGROUPS == 1 || KGROUPS == 2, "one or two wave groups");
@@ -457,16 +470,12 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
     uint32_t *Fip = Fz + 2 * S::fz_words;                // [2][BM][PANEL_UNITS][2] I_p words per row and unit
 
     int64_t bid = blockIdx.x;
-    if (xcd_remap && !(dbg & 64)) {
+    if (xcd_remap) {
         const int64_t per = gridDim.x / 8;
         bid = (bid % 8) * per + bid / 8;
     }
-    int ni = (int)(bid % nblocks);
-    int mi = (int)((bid / nblocks) % mblocks);
-    if (dbg & 128) {
-        mi = (int)(bid % mblocks);
-        ni = (int)((bid / mblocks) % nblocks);
-    }
+    const int ni = (int)(bid % nblocks);
+    const int mi = (int)((bid / nblocks) % mblocks);
     const int slice = (int)(bid / ((int64_t)nblocks * mblocks));
     const int64_t m0 = (int64_t)mi * BM;
     const int n0 = ni * BN;
@@ -487,8 +496,8 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
     const int wm = w4 / WAVES_N, wn = w4 % WAVES_N;
     const int l32 = lane & 31, lg = lane >> 5;
 
-    uint4 wreg[RS][W_CHUNKS];
-    uint4 xreg[RS][X_CHUNKS];
+    u32x4 wreg[RS][W_CHUNKS];
+    u32x4 xreg[RS][X_CHUNKS];
     uint32_t fzreg[FZ_LOADS];
     uint32_t fipreg[FIP_LOADS];
     uint32_t mbits[W_CHUNKS]; // mask bytes of the slab that is staged next
@@ -510,12 +519,7 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
 #pragma unroll
     for (int i = 0; i < X_CHUNKS; ++i) {
         const int id = (tid + NT * i) % X_TOTAL; // lanes beyond the slab repeat a valid piece (never stored)
-        int krow = id / X_CPR, nc = id % X_CPR;
-        if ((dbg & 256) && X_CPR == 16) { // 8 lanes per 128-byte line, neighbouring 8-lane groups on different rows
-            const int q = id / 32, w = id % 32;
-            krow = 2 * q + ((w >> 3) & 1);
-            nc = (w & 7) + 8 * (w >> 4);
-        }
+        const int krow = id / X_CPR, nc = id % X_CPR;
         int nn = nc * 8;
         if (XVEC && n0 + nn + 8 > N) nn = N - 8 - n0; // piece beyond N: read a valid piece instead, its columns are dropped
         xoff[i] = (uint32_t)(krow * ldx + nn);
@@ -524,24 +528,24 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
 
     auto load_slab = [&](int slab, auto stage_c) {
         constexpr int st = decltype(stage_c)::value;
-        if (dbg & 512) slab = (slab + 2 * ((mi * 3) % (nslabs / 2))) % nslabs;
         const uint16_t *wb = wbase + slab * BK;
         const uint16_t *xb = xbase_g + (int64_t)slab * BK * ldx;
-        if (!(dbg & 16)) {
 #pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i) wreg[st][i] = *reinterpret_cast<const uint4 *>(wb + woff[i]);
-        }
-        if (dbg & 32) return;
+        for (int i = 0; i < W_CHUNKS; ++i) wreg[st][i] = *reinterpret_cast<const u32x4 *>(wb + woff[i]);
 #pragma unroll
         for (int i = 0; i < X_CHUNKS; ++i) {
-            if (XVEC) {
-                xreg[st][i] = *reinterpret_cast<const uint4 *>(xb + xoff[i]);
+            if constexpr (XVEC) {
+                xreg[st][i] = *reinterpret_cast<const u32x4 *>(xb + xoff[i]);
             } else {
                 const int nn = n0 + (((tid + NT * i) % X_TOTAL) % X_CPR) * 8;
-                uint16_t tmp[8];
+                u32x4 v;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) tmp[e] = (nn + e < N) ? xb[xoff[i] + e] : (uint16_t)0;
-                xreg[st][i] = *reinterpret_cast<uint4 *>(tmp);
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t lo = (nn + 2 * e < N) ? xb[xoff[i] + 2 * e] : 0u;
+                    const uint32_t hi = (nn + 2 * e + 1 < N) ? xb[xoff[i] + 2 * e + 1] : 0u;
+                    v[e] = lo | (hi << 16);
+                }
+                xreg[st][i] = v;
             }
         }
     };
@@ -561,10 +565,10 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
         uint16_t *xs = Xs + buf * S::xs_halfs;
 #pragma unroll
         for (int i = 0; i < W_CHUNKS; ++i)
-            *reinterpret_cast<uint4 *>(ws + wlds[i]) = apply_mask8(wreg[st][i], mbits[i]);
+            *reinterpret_cast<u32x4 *>(ws + wlds[i]) = apply_mask8(wreg[st][i], mbits[i]);
 #pragma unroll
         for (int i = 0; i < X_CHUNKS; ++i)
-            if (X_EVEN || tid + NT * i < X_TOTAL) *reinterpret_cast<uint4 *>(xs + xlds[i]) = xreg[st][i];
+            if (X_EVEN || tid + NT * i < X_TOTAL) *reinterpret_cast<u32x4 *>(xs + xlds[i]) = xreg[st][i];
     };
 
     // factor slices of one panel: global -> registers
@@ -703,14 +707,14 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
                 fetch_mask_bytes(s + 1 < last ? s + 1 : last);
                 // the two wave groups run the two halves of the iteration in opposite order, so that on
                 // every SIMD one wavefront issues MFMAs while the other does the mask arithmetic
-                if (KGROUPS == 2 && kg == 1 && !(dbg & 1024)) {
-                    if (!(dbg & 2)) stage_slab(s + 1, NextStage{});
-                    if (!(dbg & 1)) compute_slab(s);
+                if (KGROUPS == 2 && kg == 1) {
+                    stage_slab(s + 1, NextStage{});
+                    compute_slab(s);
                 } else {
-                    if (!(dbg & 1)) compute_slab(s);
-                    if (!(dbg & 2)) stage_slab(s + 1, NextStage{});
+                    compute_slab(s);
+                    stage_slab(s + 1, NextStage{});
                 }
-                if (!(dbg & 4)) load_slab(s + 1 + RS < last ? s + 1 + RS : last, NextStage{});
+                load_slab(s + 1 + RS < last ? s + 1 + RS : last, NextStage{});
                 // next panel's factors and mask, spread over three slabs
                 const int ps = s % PANEL_SLABS;
                 const int next_panel = s / PANEL_SLABS + 1;
@@ -719,7 +723,7 @@ __global__ __launch_bounds__(256 * KGROUPS) void mfma_gemm_panel_kernel(
                     if (ps == 1) store_factors(next_panel);
                     if (ps == 2) decode_panel(next_panel);
                 }
-                if (!(dbg & 8)) __syncthreads();
+                __syncthreads();
             }
         });
     }
@@ -861,26 +865,15 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
                            (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp,      \
                            (int)mblocks, (int)nblocks, plan.kper, xcd_remap, y_vec_ok);                           \
     } while (0)
-#define LRBI_LAUNCH_P(KERN, SMEM)                                                                                   \
-    do {                                                                                                          \
-        auto kern = KERN;                                                                                         \
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(SMEM)) !=   \
-            hipSuccess)                                                                                           \
-            return LRBI_ERR_LAUNCH;                                                                               \
-        hipLaunchKernelGGL(kern, grid, block, (SMEM), stream, g, (const uint16_t *)dW, ldw, dIp, dIz,             \
-                           (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp,      \
-                           (int)mblocks, (int)nblocks, plan.kper, xcd_remap, y_vec_ok, dbg);                      \
-    } while (0)
 
     if constexpr (RS > 0) {
         const size_t smem = SmemPanel<BM, BN>::bytes;
-        static const int dbg = getenv("LRBI_DBG") ? atoi(getenv("LRBI_DBG")) : 0;
         if (xvec) {
-            if (split) LRBI_LAUNCH_P((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, true>), smem);
-            else LRBI_LAUNCH_P((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, false>), smem);
+            if (split) LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, true>), smem);
+            else LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, false>), smem);
         } else {
-            if (split) LRBI_LAUNCH_P((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, true>), smem);
-            else LRBI_LAUNCH_P((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, false>), smem);
+            if (split) LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, true>), smem);
+            else LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, false>), smem);
         }
     } else {
         const size_t smem = Smem<BM, BN>::bytes;
@@ -903,7 +896,6 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
         }
     }
 #undef LRBI_LAUNCH
-#undef LRBI_LAUNCH_P
     LRBI_CHECK_LAUNCH();
 
     if (split) {
