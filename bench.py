@@ -33,6 +33,21 @@ def _die_multi_gpu(n):
     sys.exit(2)
 
 
+def _recorded_traffic():
+    """HBM bytes per launch of the C2 fused product (kernel + split-K reduction), from the rocprofv3
+    FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (counters cannot be read from inside
+    this process); None when no summary is there."""
+    path = os.path.join(ROOT, "profiles", "C2_masked_gemm_hbm_traffic.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(line.split(":")[1].strip())
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,6 +55,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: run a plain 1 GiB device copy "
+                         "(calibration of the counter) and the C2 fused product on HBM-cold weights, then exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         _die_multi_gpu(max(args.gpus, int(os.environ.get("WORLD_SIZE", "1"))))
@@ -124,6 +142,19 @@ def main():
     ws_bytes = lrbi.masked_gemm_workspace_bytes(desc, DC[cfg.dtype], cfg.N)
     ws = torch.empty(max(1, (ws_bytes + 3) // 4), dtype=torch.float32, device=dev) if ws_bytes else None
 
+    if args.traffic_probe:
+        src = torch.full((1 << 30,), 1, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        for i in range(2 * len(Ws)):
+            lrbi.masked_gemm(desc, Ws[i % len(Ws)], dIp, dIz, X, out=Y, workspace=ws)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": 1 << 30, "copies": 3,
+                          "gemm_launches": 2 * len(Ws)}))
+        return
+
     def gpu_step(i):
         lrbi.decode_mask(desc, dIp, dIz, out=mask)
         lrbi.masked_gemm(desc, Ws[i % len(Ws)], dIp, dIz, X, out=Y, workspace=ws)
@@ -170,7 +201,7 @@ def main():
     achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "lrbi_masked_gemm (mfma_gemm_panel_kernel + splitk_reduce_kernel)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _recorded_traffic(),
                 "avg_launch_ms": round(gemm_ms, 5), "algorithmic_bytes": int(gemm_bytes),
                 "tflops_dense_equiv": round(flops / (gemm_ms * 1e-3) / 1e12, 1),
                 "mfma_frac": round(flops / (gemm_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)}

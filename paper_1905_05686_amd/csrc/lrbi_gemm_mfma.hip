@@ -820,8 +820,10 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
     if (split == 0) {
         split = 1;
         if (tiles < 192) {
-            // aim at about two workgroups per compute unit, at least 8 slabs per slice
-            int64_t want = (512 + tiles - 1) / tiles;
+            // at least 8 slabs per slice; the 512-lane panel kernels run one workgroup per compute unit
+            // (measured best: one slice per unit), the 256-lane kernels two
+            const int64_t target = (tile >= 9) ? 256 : 512;
+            int64_t want = (target + tiles - 1) / tiles;
             const int64_t cap = npairs / 4 > 1 ? npairs / 4 : 1;
             if (want > cap) want = cap;
             if (want > 64) want = 64;
