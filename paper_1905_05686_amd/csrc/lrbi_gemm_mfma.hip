@@ -29,84 +29,11 @@
 #include <utility>
 
 #include "lrbi_internal.hpp"
+#include "lrbi_mfma_common.hpp"
 
 namespace lrbi {
 
-// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
-template <typename F, int... Is> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-struct F16Tag {};
-struct BF16Tag {};
-
-__device__ __forceinline__ f32x16 mfma_32x32x16(F16Tag, uint4 a, uint4 b, f32x16 c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
-                                                  0, 0);
-}
-__device__ __forceinline__ f32x16 mfma_32x32x16(BF16Tag, uint4 a, uint4 b, f32x16 c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
-                                                   0, 0, 0);
-}
-
-// fp32 -> storage dtype, round to nearest even
-__device__ __forceinline__ uint16_t cvt_store(F16Tag, float v)
-{
-    return __builtin_bit_cast(uint16_t, (_Float16)v);
-}
-__device__ __forceinline__ uint16_t cvt_store(BF16Tag, float v)
-{
-    uint32_t u = __builtin_bit_cast(uint32_t, v);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u); // quiet NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
-// Zero the 16-bit halves of w whose mask bit is clear.  `pair` holds 0 or 1 in each half; a packed
-// 16-bit integer multiply by 0 / 1 is an exact select on the bit pattern (no floating-point
-// arithmetic touches the value, so NaN and Inf under a 0 bit disappear).
-typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t select2(uint32_t w, uint32_t pair)
-{
-    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, w) * __builtin_bit_cast(u16x2, pair));
-}
-// 16-byte register piece as a native vector (kept in registers by construction; an array of
-// class-type vectors indexed by pipeline stage was demoted to private memory by the compiler)
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ u32x4 apply_mask8(u32x4 w, uint32_t bits8)
-{
-    const uint32_t y = bits8 | (bits8 << 15);
-    u32x4 o;
-    o.x = select2(w.x, y & 0x00010001u);
-    o.y = select2(w.y, (y >> 2) & 0x00010001u);
-    o.z = select2(w.z, (y >> 4) & 0x00010001u);
-    o.w = select2(w.w, (y >> 6) & 0x00010001u);
-    return o;
-}
-__device__ __forceinline__ uint4 apply_mask8(uint4 w, uint32_t bits8)
-{
-    // y holds bit j of bits8 at positions j and j + 15: (y >> 2q) & 0x00010001 = (b_2q, b_2q+1) per half
-    const uint32_t y = bits8 | (bits8 << 15);
-    w.x = select2(w.x, y & 0x00010001u);
-    w.y = select2(w.y, (y >> 2) & 0x00010001u);
-    w.z = select2(w.z, (y >> 4) & 0x00010001u);
-    w.w = select2(w.w, (y >> 6) & 0x00010001u);
-    return w;
-}
-
 static constexpr int kThreads = 256;
-static constexpr int BK = 64;
 static constexpr int WS_STRIDE = BK + 8; // halfs; 16-byte pad keeps 16-byte row alignment
 
 template <int BM, int BN> struct Smem {
@@ -402,22 +329,6 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 //     64 x 64 wave tile.  The two groups' accumulators are added through LDS at the end
 //     (fixed order: group 0 + group 1).
 // ---------------------------------------------------------------------------
-
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-
-// 4(k) x 16(n) block of 16-bit values -> lane d of each 16-lane group gets column d, rows 0..3.
-// Lane s of the group passes the address of row s / 4, columns 4 * (s % 4) .. + 3.
-__device__ __forceinline__ uint2 lds_read_tr16(const uint16_t *p)
-{
-    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
-    return __builtin_bit_cast(uint2, v);
-}
-
-static constexpr int PW = 512;           // panel width in columns
-static constexpr int PANEL_SLABS = PW / BK;
-static constexpr int PANEL_WORDS = PW / 32;
-static constexpr int PANEL_UNITS = PW / 128; // 128-column units; each lies inside one tile
-static constexpr int FAST_MAX_K = 64;
 
 template <int BM, int BN> struct SmemPanel {
     static constexpr int XPAD = (BN >= 64) ? 32 : 8; // halfs; keeps the transposing reads off shared banks
@@ -791,7 +702,7 @@ struct TileDef {
     int bm, bn;
     bool panel; // panel kernel (needs c % 128 == 0, r % bm == 0, k <= 64)
 };
-// tile ids (desc.flags bits 16..19); 0 = automatic.  1-3: generic kernel, 4-11: panel kernel.
+// tile ids (desc.flags bits 16..19); 0 = automatic.  1-3: generic kernel, 4-13: panel kernel.
 static const TileDef kTiles[] = {{0, 0, false},    {128, 128, false}, {128, 64, false}, {128, 32, false},
                                  {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
                                  {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
@@ -838,6 +749,22 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
     const int64_t ldp = (N + 3) / 4 * 4;
     p.workspace_bytes = (split > 1) ? (uint64_t)split * (uint64_t)g.m * (uint64_t)ldp * 4u : 0u;
     return p;
+}
+
+// adds the split-K partial planes in slice order and rounds to the storage dtype
+template <typename Tag>
+static int launch_reduce(const Geom &g, const MfmaPlan &plan, int64_t N, void *dY, int64_t ldy, void *dWorkspace,
+                         hipStream_t stream)
+{
+    const int64_t ldp = (N + 3) / 4 * 4;
+    const int y_vec_ok = (((uintptr_t)dY & 7) == 0) && (ldy % 4 == 0);
+    const int64_t items = g.m * (ldp / 4);
+    const int64_t rblocks = (items + 255) / 256;
+    if (rblocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
+    hipLaunchKernelGGL(splitk_reduce_kernel<Tag>, dim3((unsigned)rblocks), dim3(256), 0, stream,
+                       (const float *)dWorkspace, ldp, g.m, (int)N, plan.splitk, (uint16_t *)dY, ldy, y_vec_ok);
+    LRBI_CHECK_LAUNCH();
+    return LRBI_OK;
 }
 
 template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N, int RS /* 0: generic kernel */, int KGROUPS = 1>
@@ -900,14 +827,7 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
 #undef LRBI_LAUNCH
     LRBI_CHECK_LAUNCH();
 
-    if (split) {
-        const int64_t items = g.m * (ldp / 4);
-        const int64_t rblocks = (items + 255) / 256;
-        if (rblocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
-        hipLaunchKernelGGL(splitk_reduce_kernel<Tag>, dim3((unsigned)rblocks), dim3(256), 0, stream,
-                           (const float *)dWorkspace, ldp, g.m, (int)N, plan.splitk, (uint16_t *)dY, ldy, y_vec_ok);
-        LRBI_CHECK_LAUNCH();
-    }
+    if (split) return launch_reduce<Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
     return LRBI_OK;
 }
 
