@@ -405,9 +405,9 @@ struct NibblePlan {
     int t_pieces;      // pieces in one T buffer
     int ip_words;      // words in one IpL buffer (multiple of 4)
     int zs_pieces;     // pieces in Zs
-    int dbg;
+    int wgs_per_cu;    // resident workgroups per compute unit the launch aims at
 };
-static constexpr int kNibTableBytes = 32 * 1024;
+static constexpr int kNibTableBytes = 32 * 1024; // halved when two workgroups share a compute unit
 static constexpr int kNibIpBytes = 10 * 1024;
 static constexpr int kNibMaxIpPerLane = (kNibIpBytes / 4 + kStreamThreads - 1) / kStreamThreads;
 
@@ -434,7 +434,7 @@ __device__ __forceinline__ uint4 or3x4(uint4 a, uint4 b, uint4 c)
 }
 
 template <int GT /* compile-time G, 0 = run-time */>
-__global__ __launch_bounds__(kStreamThreads) void decode_nibble_kernel(Geom g, NibblePlan p,
+__global__ __launch_bounds__(kStreamThreads) LRBI_WAVES_PER_SIMD(GT == 8 ? 4 : 8) void decode_nibble_kernel(Geom g, NibblePlan p,
                                                                        const uint32_t *__restrict__ Ip,
                                                                        const uint32_t *__restrict__ Iz,
                                                                        uint4 *__restrict__ mask)
@@ -522,8 +522,7 @@ __global__ __launch_bounds__(kStreamThreads) void decode_nibble_kernel(Geom g, N
         const int gstride = 16 * p.cpt;  // pieces between groups
         for (int i = ty; i < it.nrows; i += TY, ipr += ip_step, out += out_step) {
             uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-            if (p.dbg & 1) {
-            } else if (GT == 1 || GT == 2 || GT == 4 || GT == 8) {
+            if (GT == 1 || GT == 2 || GT == 4 || GT == 8) {
                 // one I_p word holds all nibbles; GT independent table reads, OR tree of 3-input ORs
                 const uint32_t w = ipr[0];
                 uint4 e[GT ? GT : 1];
@@ -546,7 +545,7 @@ __global__ __launch_bounds__(kStreamThreads) void decode_nibble_kernel(Geom g, N
                     acc = or4(acc, Tq[gg * gstride + ((w >> (4 * (gg & 7))) & 15u) * nstride]);
                 }
             }
-            if (!(p.dbg & 2) || acc.x == 0xdeadbeefu) *out = acc;
+            *out = acc;
         }
     };
 
@@ -589,7 +588,11 @@ static bool plan_nibble(const Geom &g, NibblePlan &p, int64_t pitch_bytes, const
     if (p.cpt > 64) return false;
     p.G = (g.k + 3) / 4;
     const int per_tile_pieces = p.G * 16 * p.cpt;
-    p.span_tiles = (kNibTableBytes / 16) / per_tile_pieces;
+    // Up to four nibble groups the kernel fits in 64 registers per lane, so two 1024-lane
+    // workgroups can share a compute unit (and its LDS): while one waits at its item boundary
+    // (loads of the next item, table build, two barriers) the other keeps the store path busy.
+    p.wgs_per_cu = (p.G <= 4) ? 2 : 1;
+    p.span_tiles = (kNibTableBytes / p.wgs_per_cu / 16) / per_tile_pieces;
     if (p.span_tiles > 64 / p.cpt) p.span_tiles = 64 / p.cpt;
     if (p.span_tiles > g.tile_cols) p.span_tiles = g.tile_cols;
     if (p.span_tiles < 1) return false;
@@ -610,7 +613,6 @@ static bool plan_nibble(const Geom &g, NibblePlan &p, int64_t pitch_bytes, const
     p.t_pieces = p.span_tiles * per_tile_pieces;
     p.ip_words = (p.span_tiles * (p.rows_per_band + 1) * g.ipw + 3) / 4 * 4;
     p.zs_pieces = p.span_tiles * g.k * p.cpt;
-    p.dbg = getenv("LRBI_DBG_DEC") ? atoi(getenv("LRBI_DBG_DEC")) : 0;
     return true;
 }
 
@@ -652,7 +654,9 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
             }
             if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                 return LRBI_ERR_LAUNCH;
-            hipLaunchKernelGGL(kern, dim3((unsigned)cus), dim3(kStreamThreads), lds, stream, g, np, dIp, dIz,
+            const int64_t want = (int64_t)np.wgs_per_cu * cus;
+            const int64_t grid = (np.items < want) ? np.items : want;
+            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kStreamThreads), lds, stream, g, np, dIp, dIz,
                                (uint4 *)dMask);
             LRBI_CHECK_LAUNCH();
             return LRBI_OK;

@@ -41,6 +41,13 @@ int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const v
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N,
                      void *dY, int64_t ldy, void *dWorkspace, hipStream_t stream);
 
+// register budget of a kernel, as resident wavefronts per SIMD (a host-only build ignores it)
+#if defined(__HIP__)
+#define LRBI_WAVES_PER_SIMD(n) __attribute__((amdgpu_waves_per_eu(n, n)))
+#else
+#define LRBI_WAVES_PER_SIMD(n)
+#endif
+
 #define LRBI_CHECK_LAUNCH()                                   \
     do {                                                      \
         if (hipGetLastError() != hipSuccess) return LRBI_ERR_LAUNCH; \
