@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
+    ap.add_argument("--extras", default="all",
+                    help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
+                         "C4, C5, C1); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: run a plain 1 GiB device copy "
@@ -224,6 +227,7 @@ def main():
     }
 
     # ------------------------------------------------------------------ extras
+    wanted = None if args.extras == "all" else set(x for x in args.extras.split(",") if x)
     if not args.no_others:
         others = {}
         # decode on masks above 1 GiB (tile shape, rank and p of C2 and of C3), factors drawn on the device
@@ -246,6 +250,8 @@ def main():
             return outw
 
         for key, base, big_m, big_n in (("decode_scaled_C2", "C2", 65536, 147456), ("decode_scaled_C3", "C3a", 65536, 131072)):
+            if wanted is not None and key not in wanted:
+                continue
             try:
                 big = workloads.scaled(workloads.CONFIGS[base], m=big_m, n=big_n)
                 bdesc = lrbi.Desc(big.m, big.n, big.r, big.c, big.k)
@@ -268,6 +274,8 @@ def main():
                 others[key] = {"error": repr(e)}
 
         for name in ("C3a", "C3b", "C4", "C5", "C1"):
+            if wanted is not None and name not in wanted:
+                continue
             try:
                 c = workloads.CONFIGS[name]
                 d = workloads.make(c)
