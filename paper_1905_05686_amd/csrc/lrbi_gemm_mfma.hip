@@ -702,12 +702,12 @@ struct TileDef {
     int bm, bn;
     bool panel; // panel kernel (needs c % 128 == 0, r % bm == 0, k <= 64)
 };
-// tile ids (desc.flags bits 16..19); 0 = automatic.  1-3: generic kernel, 4-13: panel kernel.
+// tile ids (desc.flags bits 16..19); 0 = automatic.  1-3: generic kernel, 4-8: panel kernel with 4
+// wavefronts, 9-11: panel kernel with 8 wavefronts (two wave groups).
 static const TileDef kTiles[] = {{0, 0, false},    {128, 128, false}, {128, 64, false}, {128, 32, false},
                                  {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
-                                 {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
-                                 {128, 128, true}, {128, 128, true}};
-static constexpr int kNumTiles = 13;
+                                 {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true}};
+static constexpr int kNumTiles = 11;
 
 static bool panel_ok(const Geom &g, int bm) { return (g.c % 128 == 0) && (g.r % bm == 0) && (g.k <= FAST_MAX_K); }
 
@@ -852,8 +852,6 @@ static int launch_dtype(const Geom &g, const MfmaPlan &plan, const void *dW, int
     case 9: return launch_tile<Tag, 128, 128, 2, 2, 2, 2>(LRBI_TILE_ARGS);
     case 10: return launch_tile<Tag, 128, 64, 2, 2, 2, 2>(LRBI_TILE_ARGS);
     case 11: return launch_tile<Tag, 128, 32, 4, 1, 2, 2>(LRBI_TILE_ARGS);
-    case 12: return launch_tile<Tag, 128, 128, 2, 2, 3, 2>(LRBI_TILE_ARGS);
-    case 13: return launch_tile<Tag, 128, 128, 2, 2, 4, 2>(LRBI_TILE_ARGS);
     default: return LRBI_ERR_FLAGS;
     }
 }
