@@ -303,6 +303,33 @@ def main():
                 others[name] = {"error": repr(e)}
         out["others"] = others
 
+        # measured ceilings on this machine (context for the fractions above, not product code):
+        # a plain 1 GiB fill, and the vendor library's dense GEMM of the same shape and dtype
+        if wanted is None or "ceilings" in wanted:
+            ceilings = {}
+            try:
+                buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+                ms, _ = event_times([lambda: buf.fill_(1)], 10, 3)
+                ceilings["fill_1GiB_GBs"] = round((1 << 30) / (ms * 1e-3) / 1e9, 1)
+                del buf
+            except Exception as e:
+                ceilings["fill_1GiB_GBs"] = {"error": repr(e)}
+            for name in ("C2", "C3b", "C5"):
+                try:
+                    c = workloads.CONFIGS[name]
+                    A = torch.randn((c.m, c.n), device=dev, dtype=torch.float32).to(TD[c.dtype])
+                    B = torch.randn((c.n, c.N), device=dev, dtype=torch.float32).to(TD[c.dtype])
+                    C = torch.empty((c.m, c.N), device=dev, dtype=TD[c.dtype])
+                    ms, _ = event_times([lambda: torch.matmul(A, B, out=C)], 20, 5)
+                    ceilings["dense_matmul_" + name] = {
+                        "avg_launch_ms": round(ms, 5),
+                        "tflops": round(2.0 * c.m * c.n * c.N / (ms * 1e-3) / 1e12, 1),
+                        "note": "torch.matmul (hipBLASLt), unmasked, same buffer every launch"}
+                    del A, B, C
+                except Exception as e:
+                    ceilings["dense_matmul_" + name] = {"error": repr(e)}
+            out["measured_ceilings"] = ceilings
+
     # ------------------------------------------------------------------ oracle on the host cores
     if not args.no_cpu:
         from oracle import lrbi_oracle as orc
