@@ -19,6 +19,11 @@
  * formulation, closed forms of Table 1 / Table 3, the density law of Eq. 7.
  * The LSTM recurrence and the CSR size formula (oracle/lstm.py, csr_bits) are
  * the builder's own definitions: parity unpinned.
+ * Candidate evaluation of Algorithm 1 (threshold, decode, S_a, Cost): pinned by the
+ * printed example (Eq. 4 with T_p = 0.5, T_z = 0.6 gives Eq. 5 and Eq. 6; its two
+ * mismatches are kept weights, so Cost = 0), by an independent array formulation, by
+ * the limits T = -inf / +inf and by monotonicity in the thresholds
+ * (tests/test_oracle_threshold.py).
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -109,4 +114,54 @@ uint64_t lrbi_oracle_popcount(int64_t m, int64_t n, const uint8_t *M)
 uint64_t lrbi_oracle_csr_bits(uint64_t nnz, int64_t m, int idx_bits, int ptr_bits)
 {
     return nnz * (uint64_t)idx_bits + (uint64_t)(m + 1) * (uint64_t)ptr_bits;
+}
+
+/* Algorithm 1, the step "convert (M_p, M_z) into (I_p, I_z)" (Sec. 2.2): a factor entry
+ * becomes 1 when it reaches the threshold, (I_p)_{i,l} = 1 iff (M_p)_{i,l} >= T_p, and the
+ * same for I_z with T_z.  Every tile has its own pair of thresholds (the algorithm runs per
+ * matrix, and a tiled layer is factorised tile by tile, Sec. 3.1).
+ *   Mp [T][r][k], Mz [T][k][c] single precision; Tp, Tz [T]. */
+int lrbi_oracle_threshold(int64_t T, int64_t r, int64_t c, int64_t k, const float *Mp, const float *Mz,
+                          const float *Tp, const float *Tz, uint8_t *Ip01, uint8_t *Iz01)
+{
+    if (T <= 0 || r <= 0 || c <= 0 || k <= 0) return -1;
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t i = 0; i < r; ++i)
+            for (int64_t l = 0; l < k; ++l)
+                Ip01[(t * r + i) * k + l] = (Mp[(t * r + i) * k + l] >= Tp[t]) ? 1 : 0;
+        for (int64_t l = 0; l < k; ++l)
+            for (int64_t j = 0; j < c; ++j)
+                Iz01[(t * k + l) * c + j] = (Mz[(t * k + l) * c + j] >= Tz[t]) ? 1 : 0;
+    }
+    return 0;
+}
+
+/* Algorithm 1, what is measured for one candidate pair of thresholds (Sec. 2.2), per tile:
+ *   kept[t] = number of ones of I_a in the tile (S_a = 1 - kept / (r c)),
+ *   cost[t] = sum of |W_{i,j}| over the tile's entries with I_{i,j} = 1 and (I_a)_{i,j} = 0,
+ * where I is the magnitude-pruning mask I_{i,j} = 1 iff |W_{i,j}| >= w_threshold (Eq. 1 -> Eq. 2)
+ * and I_a (M here) the decoded mask of the candidate factors.  Sums in double, row-major order. */
+int lrbi_oracle_candidate_cost(int64_t m, int64_t n, int64_t r, int64_t c, const double *W, double w_threshold,
+                               const uint8_t *M, uint64_t *kept, double *cost)
+{
+    if (m <= 0 || n <= 0 || r <= 0 || c <= 0) return -1;
+    if (m % r != 0 || n % c != 0) return -2;
+    const int64_t tile_cols = n / c;
+    for (int64_t ti = 0; ti < m / r; ++ti) {
+        for (int64_t tj = 0; tj < tile_cols; ++tj) {
+            uint64_t ones = 0;
+            double sum = 0.0;
+            for (int64_t i = 0; i < r; ++i) {
+                for (int64_t j = 0; j < c; ++j) {
+                    const int64_t at = (ti * r + i) * n + (tj * c + j);
+                    const double mag = W[at] < 0.0 ? -W[at] : W[at];
+                    if (M[at]) ones += 1;
+                    if (mag >= w_threshold && !M[at]) sum += mag;
+                }
+            }
+            kept[ti * tile_cols + tj] = ones;
+            cost[ti * tile_cols + tj] = sum;
+        }
+    }
+    return 0;
 }

@@ -52,6 +52,10 @@ def _load():
         lib.lrbi_oracle_popcount.restype = u64
         lib.lrbi_oracle_csr_bits.argtypes = [u64, i64, ctypes.c_int, ctypes.c_int]
         lib.lrbi_oracle_csr_bits.restype = u64
+        lib.lrbi_oracle_threshold.argtypes = [i64] * 4 + [p] * 6
+        lib.lrbi_oracle_threshold.restype = ctypes.c_int
+        lib.lrbi_oracle_candidate_cost.argtypes = [i64] * 4 + [p, ctypes.c_double, p, p, p]
+        lib.lrbi_oracle_candidate_cost.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -76,6 +80,45 @@ def decode_mask(Ip01, Iz01, m: int, n: int, r: int, c: int, k: int) -> np.ndarra
     if rc != 0:
         raise ValueError("lrbi_oracle_decode failed: %d" % rc)
     return M
+
+
+def threshold_factors(Mp, Mz, Tp, Tz):
+    """Algorithm 1, "convert (M_p, M_z) into (I_p, I_z)" (Sec. 2.2): entry >= threshold -> 1, per tile.
+    Mp [T][r][k], Mz [T][k][c] float32; Tp, Tz [T] float32.  Returns (Ip01, Iz01)."""
+    Mp = _c(Mp, np.float32)
+    Mz = _c(Mz, np.float32)
+    Tp = _c(Tp, np.float32)
+    Tz = _c(Tz, np.float32)
+    T, r, k = Mp.shape
+    c = Mz.shape[2]
+    if Mz.shape != (T, k, c) or Tp.shape != (T,) or Tz.shape != (T,):
+        raise ValueError("shapes do not match")
+    Ip01 = np.empty((T, r, k), dtype=np.uint8)
+    Iz01 = np.empty((T, k, c), dtype=np.uint8)
+    rc = _load().lrbi_oracle_threshold(T, r, c, k, Mp.ctypes.data, Mz.ctypes.data, Tp.ctypes.data,
+                                       Tz.ctypes.data, Ip01.ctypes.data, Iz01.ctypes.data)
+    if rc != 0:
+        raise ValueError("lrbi_oracle_threshold failed: %d" % rc)
+    return Ip01, Iz01
+
+
+def candidate_cost(W, w_threshold: float, M, r: int, c: int):
+    """Algorithm 1, the quantities measured for one candidate (Sec. 2.2), per tile: number of ones of
+    I_a, and Cost = sum of |W| over entries with |W| >= w_threshold (I = 1) that I_a prunes.
+    W float64 m x n (storage-rounded values), M the decoded 0/1 mask.  Returns (kept uint64 [T], cost float64 [T])."""
+    W = _c(W, np.float64)
+    M = _c(M, np.uint8)
+    m, n = W.shape
+    if M.shape != (m, n) or m % r or n % c:
+        raise ValueError("shapes do not match")
+    T = (m // r) * (n // c)
+    kept = np.empty(T, dtype=np.uint64)
+    cost = np.empty(T, dtype=np.float64)
+    rc = _load().lrbi_oracle_candidate_cost(m, n, r, c, W.ctypes.data, float(w_threshold), M.ctypes.data,
+                                            kept.ctypes.data, cost.ctypes.data)
+    if rc != 0:
+        raise ValueError("lrbi_oracle_candidate_cost failed: %d" % rc)
+    return kept, cost
 
 
 def masked_gemm(W, M, X, threads: int = 1) -> np.ndarray:

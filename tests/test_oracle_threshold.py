@@ -1,0 +1,130 @@
+"""Pins for the oracle's candidate evaluation of Algorithm 1 (threshold, decode, S_a, Cost).  CPU only."""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import lrbi_oracle as orc
+from golden_io import read_sections
+
+
+def _eval(W, Tw, Mp, Mz, Tp, Tz, r, c):
+    Ip, Iz = orc.threshold_factors(Mp, Mz, Tp, Tz)
+    m, n = W.shape
+    k = Mp.shape[2]
+    M = orc.decode_mask(Ip, Iz, m, n, r, c, k)
+    kept, cost = orc.candidate_cost(W, Tw, M, r, c)
+    return Ip, Iz, M, kept, cost
+
+
+def test_worked_example_eq4_to_eq5_and_cost():
+    # Eq. 4 thresholded at T_p = 0.5, T_z = 0.6 is Eq. 5; its product is Eq. 6; against Eq. 2 the two
+    # mismatches are extra keeps, so nothing that magnitude pruning keeps is lost: Cost = 0.
+    # Sparsity of Eq. 6: 10 zeros of 25 (S_a = 0.40), i.e. 15 ones.
+    g = read_sections("worked_example.txt")
+    Mp = g["Mp"].astype(np.float32)[None]
+    Mz = g["Mz"].astype(np.float32)[None]
+    Ip, Iz, M, kept, cost = _eval(g["W"], 0.7, Mp, Mz, np.float32([0.5]), np.float32([0.6]), 5, 5)
+    assert np.array_equal(Ip[0], g["Ip"].astype(np.uint8))
+    assert np.array_equal(Iz[0], g["Iz"].astype(np.uint8))
+    assert np.array_equal(M, g["Ia"].astype(np.uint8))
+    assert int(kept[0]) == 15
+    assert cost[0] == 0.0
+
+
+def test_worked_example_cost_by_hand_at_a_harsher_threshold():
+    # T_z = 1.25 keeps only Mz[0,0] = 1.3, Mz[1,1] = 1.8, Mz[1,4] = 1.3:
+    #   Iz = [[1 0 0 0 0], [0 1 0 0 1]], Ip as Eq. 5  ->  rows {0,2,3} = [0 1 0 0 1], rows {1,4} = [1 0 0 0 0].
+    # Entries of Eq. 2 (I = 1) now pruned: (0,2) 1.2, (1,2) 0.7, (1,3) 1.6, (3,2) 0.9, (4,2) 1.0, (4,3) 1.0 -> 6.4.
+    g = read_sections("worked_example.txt")
+    Mp = g["Mp"].astype(np.float32)[None]
+    Mz = g["Mz"].astype(np.float32)[None]
+    _, Iz, M, kept, cost = _eval(g["W"], 0.7, Mp, Mz, np.float32([0.5]), np.float32([1.25]), 5, 5)
+    assert np.array_equal(Iz[0], np.array([[1, 0, 0, 0, 0], [0, 1, 0, 0, 1]], dtype=np.uint8))
+    assert int(kept[0]) == 3 * 2 + 2 * 1
+    assert cost[0] == pytest.approx(6.4, abs=1e-12)
+
+
+@pytest.mark.parametrize("m,n,r,c,k", [(6, 8, 3, 4, 2), (20, 30, 5, 10, 3), (64, 96, 32, 48, 9)])
+def test_against_array_formulation(m, n, r, c, k):
+    # independent statement with whole-array numpy operations (integer product > 0, boolean selection)
+    rng = np.random.default_rng(7)
+    T = (m // r) * (n // c)
+    W = rng.normal(0, 1, (m, n))
+    Mp = rng.random((T, r, k), dtype=np.float32)
+    Mz = rng.random((T, k, c), dtype=np.float32)
+    Tp = rng.uniform(0.3, 0.9, T).astype(np.float32)
+    Tz = rng.uniform(0.3, 0.9, T).astype(np.float32)
+    Ip, Iz, M, kept, cost = _eval(W, 0.8, Mp, Mz, Tp, Tz, r, c)
+    for t in range(T):
+        ti, tj = divmod(t, n // c)
+        ip = (Mp[t] >= Tp[t]).astype(np.int64)
+        iz = (Mz[t] >= Tz[t]).astype(np.int64)
+        ia = (ip @ iz) > 0
+        w = np.abs(W[ti * r:(ti + 1) * r, tj * c:(tj + 1) * c])
+        assert np.array_equal(Ip[t], ip.astype(np.uint8)) and np.array_equal(Iz[t], iz.astype(np.uint8))
+        assert int(kept[t]) == int(ia.sum())
+        assert cost[t] == pytest.approx(float(w[(w >= 0.8) & ~ia].sum()), rel=1e-12, abs=1e-12)
+
+
+def test_threshold_limits():
+    rng = np.random.default_rng(3)
+    m, n, r, c, k = 12, 20, 6, 10, 4
+    T = 4
+    W = rng.normal(0, 1, (m, n))
+    Mp = rng.random((T, r, k), dtype=np.float32)
+    Mz = rng.random((T, k, c), dtype=np.float32)
+    lo = np.full(T, -np.inf, dtype=np.float32)
+    hi = np.full(T, np.inf, dtype=np.float32)
+    # everything selected: all-ones mask, nothing lost
+    _, _, M, kept, cost = _eval(W, 0.5, Mp, Mz, lo, lo, r, c)
+    assert M.all() and np.all(kept == r * c) and np.all(cost == 0.0)
+    # nothing selected on one side: empty mask, the cost is the whole magnitude-pruned sum of the tile
+    for Tp, Tz in ((hi, lo), (lo, hi)):
+        _, _, M, kept, cost = _eval(W, 0.5, Mp, Mz, Tp, Tz, r, c)
+        assert not M.any() and np.all(kept == 0)
+        a = np.abs(W)
+        full = np.where(a >= 0.5, a, 0.0).reshape(m // r, r, n // c, c).sum(axis=(1, 3)).reshape(-1)
+        assert np.allclose(cost, full, rtol=1e-12)
+    # a threshold equal to an entry keeps it (">=")
+    Mp1 = np.float32([[[0.25]]]); Mz1 = np.float32([[[0.5]]])
+    _, _, M, _, _ = _eval(np.ones((1, 1)), 0.0, Mp1, Mz1, np.float32([0.25]), np.float32([0.5]), 1, 1)
+    assert M[0, 0] == 1
+
+
+def test_monotone_in_the_thresholds():
+    # raising a threshold clears factor bits, so it can only clear mask bits and only add to the cost
+    rng = np.random.default_rng(11)
+    m, n, r, c, k = 32, 48, 16, 24, 6
+    T = 4
+    W = rng.normal(0, 1, (m, n))
+    Mp = rng.random((T, r, k), dtype=np.float32)
+    Mz = rng.random((T, k, c), dtype=np.float32)
+    prev_kept, prev_cost, prev_M = None, None, None
+    for tz in (0.2, 0.4, 0.6, 0.8, 0.95):
+        _, _, M, kept, cost = _eval(W, 0.7, Mp, Mz, np.full(T, 0.5, np.float32), np.full(T, tz, np.float32), r, c)
+        if prev_M is not None:
+            assert np.all(M <= prev_M) and np.all(kept <= prev_kept) and np.all(cost >= prev_cost - 1e-12)
+        prev_kept, prev_cost, prev_M = kept, cost, M
+
+
+def test_tiles_are_independent():
+    rng = np.random.default_rng(5)
+    m, n, r, c, k = 20, 20, 10, 10, 3
+    T = 4
+    W = rng.normal(0, 1, (m, n))
+    Mp = rng.random((T, r, k), dtype=np.float32)
+    Mz = rng.random((T, k, c), dtype=np.float32)
+    Tp = np.full(T, 0.5, np.float32); Tz = np.full(T, 0.5, np.float32)
+    _, _, _, kept0, cost0 = _eval(W, 0.7, Mp, Mz, Tp, Tz, r, c)
+    Tz2 = Tz.copy(); Tz2[2] = 0.9
+    _, _, _, kept1, cost1 = _eval(W, 0.7, Mp, Mz, Tp, Tz2, r, c)
+    same = [0, 1, 3]
+    assert np.array_equal(kept0[same], kept1[same]) and np.array_equal(cost0[same], cost1[same])
+    assert kept1[2] <= kept0[2]
+
+
+def test_generator_density_matches_the_configurations():
+    cfg = workloads.scaled(workloads.CONFIGS["C2"], m=512, n=1024)
+    f = workloads.make_real_factors(cfg)
+    Ip, Iz = orc.threshold_factors(f["Mp"], f["Mz"], f["Tp"], f["Tz"])
+    assert abs(Ip.mean() - cfg.p) < 0.01 and abs(Iz.mean() - cfg.p) < 0.01

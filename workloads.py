@@ -134,6 +134,22 @@ def make(cfg: Config, want_w: bool = True, want_x: bool = True) -> dict:
     return out
 
 
+def make_real_factors(cfg: Config, seed_offset: int = 1000) -> dict:
+    """Stand-ins for the real-valued non-negative factors that Algorithm 1 thresholds (Sec. 2.2 obtains
+    them from an NMF library; none is used here).  Entries are i.i.d. Uniform(0, 1) float32, so that the
+    threshold 1 - p turns each factor into Bernoulli(p) bits, the density of the benchmark configurations:
+      Mp [T, r, k], Mz [T, k, c] ~ U(0, 1);  Tp = Tz = 1 - p for every tile (float32);
+      w_threshold = the value below which W ~ N(0, sigma_w) falls with probability 0.9 in magnitude
+      (1.6449 sigma_w: a 90 % magnitude-pruning target, the paper's usual setting)."""
+    rng = np.random.default_rng(cfg.seed + seed_offset)
+    T = cfg.tiles
+    Mp = rng.random((T, cfg.r, cfg.k), dtype=np.float32)
+    Mz = rng.random((T, cfg.k, cfg.c), dtype=np.float32)
+    Tp = np.full(T, 1.0 - cfg.p, dtype=np.float32)
+    Tz = np.full(T, 1.0 - cfg.p, dtype=np.float32)
+    return {"Mp": Mp, "Mz": Mz, "Tp": Tp, "Tz": Tz, "w_threshold": float(np.float32(1.6449 * cfg.sigma_w))}
+
+
 def make_factors_only(cfg: Config) -> dict:
     """Factors of a (possibly scaled) configuration without touching W / X.
     Uses its own stream so very large decode-only grids stay cheap."""
