@@ -171,6 +171,33 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
                      int64_t N, void *dY, int64_t ldy, void *dWorkspace, uint64_t workspace_bytes,
                      void *stream);
 
+/*
+ * One candidate of Algorithm 1 (Sec. 2.2), evaluated for every tile in one launch:
+ * the real-valued non-negative factors M_p (r x k) and M_z (k x c) of a tile are turned
+ * into binary factors with the tile's thresholds, (I_p)_{i,l} = 1 iff (M_p)_{i,l} >= T_p
+ * and (I_z)_{l,j} = 1 iff (M_z)_{l,j} >= T_z; the mask I_a = I_p (x) I_z of Eq. 3 is
+ * formed on chip; and the two quantities the search needs come back per tile:
+ *   dKept[t]  number of ones of I_a in tile t (its sparsity is S_a = 1 - kept / (r c)),
+ *   dCost[t]  sum of |W_{i,j}| over the tile's entries that magnitude pruning keeps
+ *             (I_{i,j} = 1 iff |W_{i,j}| >= w_threshold, Eq. 1 -> Eq. 2) but I_a prunes,
+ *             the cost function of Sec. 2.2.
+ * The caller drives the sweep over S_p and the binary search on S_z with repeated calls.
+ *   dW: m x n row-major, ldw >= n elements, of `dtype`; magnitudes are taken exactly.
+ *   dMp: [T][r][k] float, dMz: [T][k][c] float, dTp, dTz: [T] float (T = tiles, row-major
+ *   tile order); comparisons are made in single precision.
+ *   dIp_packed, dIz_packed: when not NULL, receive the packed binary factors (layouts
+ *   above), e.g. for the final conversion with the best thresholds; both or neither.
+ *   dKept: [T] uint64, dCost: [T] double (sums accumulated in double, fixed order:
+ *   identical bits from call to call).
+ * Limits: 4 * (k * 2 * ceil(c / 64) + r * ceil(k / 32)) bytes of factor bits must fit
+ * in 64 KiB of on-chip memory (LRBI_ERR_SHAPE otherwise).
+ * One kernel launch on `stream`.
+ */
+int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                        float w_threshold, const float *dMp, const float *dMz, const float *dTp,
+                        const float *dTz, void *dIp_packed, void *dIz_packed, uint64_t *dKept,
+                        double *dCost, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

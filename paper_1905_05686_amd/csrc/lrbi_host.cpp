@@ -222,3 +222,25 @@ extern "C" int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const v
     return launch_mfma_gemm(g, plan, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
                             dX, ldx, N, dY, ldy, dWorkspace, s);
 }
+
+extern "C" int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                                   float w_threshold, const float *dMp, const float *dMz, const float *dTp,
+                                   const float *dTz, void *dIp_packed, void *dIz_packed, uint64_t *dKept,
+                                   double *dCost, void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dW || !dMp || !dMz || !dTp || !dTz || !dKept || !dCost) return LRBI_ERR_NULL;
+    if ((dIp_packed == nullptr) != (dIz_packed == nullptr)) return LRBI_ERR_NULL;
+    const int es = elem_size(dtype);
+    if (es == 0) return LRBI_ERR_DTYPE;
+    if (ldw < desc->n) return LRBI_ERR_PITCH;
+    if (!aligned_to(dW, (uintptr_t)es) || !aligned_to(dMp, 4) || !aligned_to(dMz, 4) || !aligned_to(dTp, 4) ||
+        !aligned_to(dTz, 4) || !aligned_to(dKept, 8) || !aligned_to(dCost, 8))
+        return LRBI_ERR_ALIGN;
+    if (dIp_packed && (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8))) return LRBI_ERR_ALIGN;
+    const Geom g = make_geom(desc);
+    if (threshold_eval_lds_bytes(g) > 64 * 1024) return LRBI_ERR_SHAPE;
+    return launch_threshold_eval(g, dtype, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp_packed, dIz_packed, dKept,
+                                 dCost, (hipStream_t)stream);
+}

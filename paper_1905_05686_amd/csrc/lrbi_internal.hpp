@@ -29,6 +29,12 @@ int launch_valu_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, 
                      const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
                      hipStream_t stream);
 
+// candidate evaluation of Algorithm 1 (lrbi_alg1.hip)
+size_t threshold_eval_lds_bytes(const Geom &g);
+int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold,
+                          const float *dMp, const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz,
+                          uint64_t *dKept, double *dCost, hipStream_t stream);
+
 struct MfmaPlan {
     int tile;     // tile variant id (1-based, see lrbi_gemm_mfma.hip)
     int bm, bn;   // workgroup tile

@@ -117,3 +117,26 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
     assert lrbi.masked_gemm_workspace_bytes(d2, lrbi.F16, 16) == 2 * 8 * 16 * 4
     assert lrbi.masked_gemm_workspace_bytes(lrbi.Desc(4096, 4096, 512, 512, 32), lrbi.BF16, 1024) == 0
     assert lrbi.masked_gemm_workspace_bytes(lrbi.Desc(4096, 4096, 512, 512, 32), lrbi.BF16, 1) == 0
+
+
+def test_threshold_eval_rejects_bad_arguments_before_any_launch():
+    lib = lrbi.load_library()
+    d = lrbi.Desc(8, 128, 4, 64, 2)
+    buf = (ctypes.c_uint8 * 4096)()
+    base = (ctypes.addressof(buf) + 63) // 64 * 64
+    p = ctypes.c_void_p(base)
+    f = lib.lrbi_threshold_eval
+    args = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128), 0.5,
+                         kw.get("Mp", p), p, p, p, kw.get("Ip", None), kw.get("Iz", None), kw.get("kept", p), p, None]
+    assert f(*args(W=None)) == -1
+    assert f(*args(Mp=None)) == -1
+    assert f(*args(kept=None)) == -1
+    assert f(*args(Ip=p)) == -1                       # packed factors: both or neither
+    assert f(*args(dt=9)) == -4
+    assert f(*args(ldw=100)) == -5
+    assert f(*args(W=ctypes.c_void_p(base + 1))) == -6
+    assert f(*args(kept=ctypes.c_void_p(base + 4))) == -6
+    assert f(*args(Ip=p, Iz=ctypes.c_void_p(base + 4))) == -6
+    # factor bits of one tile must fit in 64 KiB of on-chip memory
+    big = lrbi.Desc(4096, 65536, 4096, 65536, 8)
+    assert f(*args(d=big, ldw=65536)) == -2

@@ -1,0 +1,117 @@
+"""GPU parity of lrbi_threshold_eval (one candidate of Algorithm 1 for every tile) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1905_05686_amd as lrbi
+import workloads
+from oracle import lrbi_oracle as orc
+from gpu_util import desc_of, dev, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle(cfg, W64, f, w_threshold):
+    Ip, Iz = orc.threshold_factors(f["Mp"], f["Mz"], f["Tp"], f["Tz"])
+    M = orc.decode_mask(Ip, Iz, cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    kept, cost = orc.candidate_cost(W64, w_threshold, M, cfg.r, cfg.c)
+    return Ip, Iz, kept, cost
+
+
+def _gpu(cfg, Wdev, f, w_threshold, want_factors=True):
+    d = desc_of(cfg)
+    t = lambda a: torch.from_numpy(a).to(dev())
+    return lrbi.threshold_eval(d, Wdev, w_threshold, t(f["Mp"]), t(f["Mz"]), t(f["Tp"]), t(f["Tz"]),
+                               want_factors=want_factors)
+
+
+def _check(cfg, f, w_threshold, ldpad=0):
+    data = workloads.make(cfg, want_x=False)
+    W64 = workloads.to_float64(data["W"], cfg.dtype)
+    W = to_device(data["W"], cfg.dtype)
+    if ldpad:
+        Wp = torch.zeros((cfg.m, cfg.n + ldpad), dtype=W.dtype, device=dev())
+        Wp[:, :cfg.n] = W
+        W = Wp[:, :cfg.n]
+    Ip, Iz, kept_ref, cost_ref = _oracle(cfg, W64, f, w_threshold)
+    kept, cost, ip, iz = _gpu(cfg, W, f, w_threshold)
+    torch.cuda.synchronize()
+    # integer work: bit-exact
+    assert np.array_equal(kept.cpu().numpy().astype(np.uint64), kept_ref)
+    ip_ref, iz_ref = lrbi.pack_factors(desc_of(cfg), Ip, Iz)
+    assert np.array_equal(ip.cpu().numpy().view(np.uint32).reshape(-1), np.asarray(ip_ref).view(np.uint32).reshape(-1))
+    assert np.array_equal(iz.cpu().numpy().view(np.uint32).reshape(-1), np.asarray(iz_ref).view(np.uint32).reshape(-1))
+    # sums of exactly representable magnitudes, accumulated in double on both sides in different orders:
+    # at most 2^18 terms per tile, so 1e-12 relative is generous
+    c = cost.cpu().numpy()
+    assert np.all(np.abs(c - cost_ref) <= 1e-12 * np.maximum(cost_ref, 1.0)), float(np.abs(c - cost_ref).max())
+    # run-to-run identical bits, also without the factor outputs
+    kept2, cost2 = _gpu(cfg, W, f, w_threshold, want_factors=False)
+    assert torch.equal(kept, kept2) and torch.equal(cost.view(torch.int64), cost2.view(torch.int64))
+    return kept_ref, cost_ref
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3a", "C4", "C5"])
+def test_config_parity(name):
+    cfg = workloads.CONFIGS[name]
+    print("threshold_eval config", name, flush=True)
+    f = workloads.make_real_factors(cfg)
+    kept, cost = _check(cfg, f, f["w_threshold"])
+    # the stand-in factors at threshold 1 - p reproduce the configuration's mask density (Eq. 7)
+    dens = kept.sum() / float(cfg.m * cfg.n)
+    assert abs(dens - (1.0 - (1.0 - cfg.p ** 2) ** cfg.k)) < 0.02
+    assert cost.sum() > 0.0
+
+
+def _small(m, n, r, c, k, p, dtype, seed=0):
+    return workloads.Config("t", m, n, r, c, k, p, 1, dtype, 0.05, seed)
+
+
+EDGE = [
+    (_small(10, 10, 5, 5, 2, 0.4, "f32"), 0),
+    (_small(33, 77, 3, 7, 3, 0.3, "f32"), 0),           # nothing aligned
+    (_small(130, 4104, 65, 1368, 9, 0.1, "bf16"), 0),   # tile width not a multiple of 32, many words per row
+    (_small(200, 1000, 100, 500, 40, 0.05, "bf16"), 0), # rank above 32: two I_p words per row
+    (_small(64, 256, 32, 128, 70, 0.05, "f16"), 0),     # rank above 64
+    (_small(128, 256, 64, 128, 8, 0.2, "f16"), 8),      # padded rows, still 16-byte aligned
+    (_small(128, 256, 64, 128, 8, 0.2, "f16"), 3),      # padded rows, scalar loads
+    (_small(50, 120, 25, 60, 4, 0.2, "f32"), 3),
+]
+
+
+@pytest.mark.parametrize("idx", range(len(EDGE)))
+def test_edge_shapes(idx):
+    cfg, ldpad = EDGE[idx]
+    print("threshold_eval edge", idx, cfg, ldpad, flush=True)
+    f = workloads.make_real_factors(cfg)
+    _check(cfg, f, f["w_threshold"], ldpad=ldpad)
+
+
+def test_degenerate_thresholds():
+    cfg = _small(128, 256, 64, 128, 8, 0.2, "bf16")
+    f = workloads.make_real_factors(cfg)
+    T = cfg.tiles
+    lo = np.full(T, -np.inf, np.float32)
+    hi = np.full(T, np.inf, np.float32)
+    for Tp, Tz in ((lo, lo), (hi, lo), (lo, hi)):
+        g = dict(f, Tp=Tp, Tz=Tz)
+        kept, cost = _check(cfg, g, 0.0)
+        if Tp is lo and Tz is lo:
+            assert np.all(kept == cfg.r * cfg.c) and np.all(cost == 0.0)
+        else:
+            assert np.all(kept == 0)
+
+
+def test_nan_weights_are_never_counted():
+    # |NaN| >= threshold is false: a NaN weight is neither kept by magnitude pruning nor part of the cost
+    cfg = _small(64, 128, 32, 64, 4, 0.2, "f16")
+    f = workloads.make_real_factors(cfg)
+    data = workloads.make(cfg, want_x=False)
+    Wh = data["W"].copy()
+    Wh[::7, ::5] = np.float16(np.nan)
+    W64 = Wh.astype(np.float64)
+    Ip, Iz, kept_ref, cost_ref = _oracle(cfg, W64, f, 0.05)
+    kept, cost = _gpu(cfg, to_device(Wh, "f16"), f, 0.05, want_factors=False)
+    assert np.array_equal(kept.cpu().numpy().astype(np.uint64), kept_ref)
+    assert np.all(np.isfinite(cost.cpu().numpy()))
+    assert np.allclose(cost.cpu().numpy(), cost_ref, rtol=1e-12)
