@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, C1); used to profile one workload at a time")
+                         "C4, C5, C1, alg1_eval_C2, alg1_eval_C3, ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: run a plain 1 GiB device copy "
@@ -301,6 +301,33 @@ def main():
                 del Wl, X_, Y_
             except Exception as e:
                 others[name] = {"error": repr(e)}
+        # one candidate of Algorithm 1 per launch (threshold, decode on chip, ones and cost per tile)
+        for name in ("C2", "C3a"):
+            key = "alg1_eval_" + name[:2]
+            if wanted is not None and key not in wanted:
+                continue
+            try:
+                c = workloads.CONFIGS[name]
+                d = workloads.make(c, want_x=False)
+                f = workloads.make_real_factors(c)
+                de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
+                Wl = rotated_weights(to_dev(d["W"], c.dtype))
+                tens = [torch.from_numpy(f[k_]).to(dev) for k_ in ("Mp", "Mz", "Tp", "Tz")]
+                res = (torch.empty(c.tiles, dtype=torch.int64, device=dev), torch.empty(c.tiles, dtype=torch.float64, device=dev))
+                wsb = lrbi.threshold_eval_workspace_bytes(de)
+                ews = torch.empty(max(1, wsb // 8), dtype=torch.int64, device=dev) if wsb else None
+                fns = [(lambda Wi=Wi: lrbi.threshold_eval(de, Wi, f["w_threshold"], *tens, out=res, workspace=ews))
+                       for Wi in Wl]
+                ms, _ = event_times(fns, 6 * len(fns), len(fns))
+                byts = c.m * c.n * 2 + c.tiles * c.k * (c.r + c.c) * 4 + c.tiles * 16
+                others[key] = {"workload": "%s: W %dx%d %s, U(0,1) factors thresholded at 1 - p, cost threshold 1.645 sigma"
+                                           % (name[:2], c.m, c.n, c.dtype),
+                               "avg_launch_ms_cold": round(ms, 5), "GBs": round(byts / (ms * 1e-3) / 1e9, 1),
+                               "hbm_frac": round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                               "candidates_per_s": round(1.0 / (ms * 1e-3), 1)}
+                del Wl, tens
+            except Exception as e:
+                others[key] = {"error": repr(e)}
         out["others"] = others
 
         # measured ceilings on this machine (context for the fractions above, not product code):

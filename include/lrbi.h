@@ -191,12 +191,21 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
  *   identical bits from call to call).
  * Limits: 4 * (k * 2 * ceil(c / 64) + r * ceil(k / 32)) bytes of factor bits must fit
  * in 64 KiB of on-chip memory (LRBI_ERR_SHAPE otherwise).
- * One kernel launch on `stream`.
+ *   dWorkspace / workspace_bytes: optional scratch (8-byte aligned) of at least
+ *   lrbi_threshold_eval_workspace_bytes bytes.  With it, a layer of few large tiles is
+ *   spread over more workgroups (row bands per tile, partial results added in band order
+ *   by a second launch); with NULL or too few bytes one workgroup serves a whole tile.
+ *   Results are identical either way for dKept and the packed factors; dCost may differ in
+ *   the last bits between the two arrangements (different, each fixed, summation orders).
+ * One or two kernel launches on `stream`.
  */
 int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
                         float w_threshold, const float *dMp, const float *dMz, const float *dTp,
                         const float *dTz, void *dIp_packed, void *dIz_packed, uint64_t *dKept,
-                        double *dCost, void *stream);
+                        double *dCost, void *dWorkspace, uint64_t workspace_bytes, void *stream);
+
+/* Scratch lrbi_threshold_eval can use for this geometry.  Host only.  *bytes may be 0. */
+int lrbi_threshold_eval_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
 
 #ifdef __cplusplus
 }

@@ -73,9 +73,12 @@ def load_library():
     lib.lrbi_decode_mask.argtypes = [pd, vp, vp, vp, i64, vp]
     lib.lrbi_masked_gemm_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
     lib.lrbi_masked_gemm.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, u64, vp]
-    lib.lrbi_threshold_eval.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.lrbi_threshold_eval.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64,
+                                        vp]
+    lib.lrbi_threshold_eval_workspace_bytes.argtypes = [pd, pu64]
     for name in ("lrbi_index_bits", "lrbi_csr_bits", "lrbi_pack_factors", "lrbi_unpack_mask", "lrbi_decode_mask",
-                 "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm", "lrbi_threshold_eval"):
+                 "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm", "lrbi_threshold_eval",
+                 "lrbi_threshold_eval_workspace_bytes"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -202,10 +205,20 @@ def masked_gemm(desc: Desc, W, dIp, dIz, X, out=None, workspace=None, stream=Non
     return out[:, 0] if squeeze else out
 
 
-def threshold_eval(desc: Desc, W, w_threshold: float, Mp, Mz, Tp, Tz, want_factors: bool = False, stream=None):
+def threshold_eval_workspace_bytes(desc: Desc) -> int:
+    out = ctypes.c_uint64()
+    _check(load_library().lrbi_threshold_eval_workspace_bytes(ctypes.byref(desc), ctypes.byref(out)),
+           "lrbi_threshold_eval_workspace_bytes")
+    return out.value
+
+
+def threshold_eval(desc: Desc, W, w_threshold: float, Mp, Mz, Tp, Tz, want_factors: bool = False, out=None,
+                   workspace=None, stream=None):
     """lrbi_threshold_eval: one candidate of Algorithm 1 for every tile.  W [m, n] (f32 / f16 / bf16),
     Mp [T, r, k], Mz [T, k, c], Tp, Tz [T] float32 device tensors.  Returns (kept int64 [T], cost float64 [T])
-    and, with want_factors, also the packed factors (Ip int32 [T*r, ipw], Iz int32 [T*k, izw])."""
+    and, with want_factors, also the packed factors (Ip int32 [T*r, ipw], Iz int32 [T*k, izw]).
+    `out` = (kept, cost) reuses existing result tensors; `workspace` = device scratch of at least
+    threshold_eval_workspace_bytes(desc) bytes (optional)."""
     import torch
     T = desc.tiles
     if W.dim() != 2 or W.shape != (desc.m, desc.n) or W.stride(1) != 1:
@@ -213,8 +226,13 @@ def threshold_eval(desc: Desc, W, w_threshold: float, Mp, Mz, Tp, Tz, want_facto
     for t, shape in ((Mp, (T, desc.r, desc.k)), (Mz, (T, desc.k, desc.c)), (Tp, (T,)), (Tz, (T,))):
         if t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_contiguous():
             raise ValueError("factor / threshold tensors must be contiguous float32 of shape %s" % (shape,))
-    kept = torch.empty(T, dtype=torch.int64, device=W.device)
-    cost = torch.empty(T, dtype=torch.float64, device=W.device)
+    if out is not None:
+        kept, cost = out
+        if kept.dtype != torch.int64 or cost.dtype != torch.float64 or kept.numel() != T or cost.numel() != T:
+            raise ValueError("out must be (int64 [T], float64 [T])")
+    else:
+        kept = torch.empty(T, dtype=torch.int64, device=W.device)
+        cost = torch.empty(T, dtype=torch.float64, device=W.device)
     ip = iz = None
     if want_factors:
         ip = torch.empty((T * desc.r, (desc.k + 31) // 32), dtype=torch.int32, device=W.device)
@@ -223,5 +241,7 @@ def threshold_eval(desc: Desc, W, w_threshold: float, Mp, Mz, Tp, Tz, want_facto
         ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), float(w_threshold), _dev_ptr(Mp, "Mp"),
         _dev_ptr(Mz, "Mz"), _dev_ptr(Tp, "Tp"), _dev_ptr(Tz, "Tz"), _dev_ptr(ip, "Ip") if want_factors else None,
         _dev_ptr(iz, "Iz") if want_factors else None, _dev_ptr(kept, "kept"), _dev_ptr(cost, "cost"),
+        _dev_ptr(workspace, "workspace") if workspace is not None else None,
+        workspace.numel() * workspace.element_size() if workspace is not None else 0,
         _stream_ptr(stream)), "lrbi_threshold_eval")
     return (kept, cost, ip, iz) if want_factors else (kept, cost)

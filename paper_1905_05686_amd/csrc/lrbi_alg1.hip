@@ -2,17 +2,18 @@
 // tile, form I_a = I_p (x) I_z (Eq. 3) on chip, and return per tile the number of ones of I_a
 // and the cost (sum of the magnitudes that magnitude pruning keeps and I_a prunes).
 //
-// One workgroup per tile.
+// One workgroup per tile, or per band of rows of a tile when the tiles alone would not fill the chip
+// (the bands' partial results then go through a caller-provided workspace).
 //   1. The tile's M_z (k x c floats) and M_p (r x k floats) are compared with the tile's
 //      thresholds; the resulting bits go to LDS in the packed layouts (I_z rows of
 //      2 * ceil(c / 64) words, I_p rows of ceil(k / 32) words) and, when asked for, to global
 //      memory as the packed factors.
-//   2. Wavefronts take the tile's rows in turn.  A lane owns 8 (16-bit types) or 4 (fp32)
-//      consecutive columns per step: it rebuilds the 32-bit mask word over them (OR of the I_z
-//      words selected by the set bits of the row's I_p words, all from LDS), counts the ones,
-//      loads its 16 bytes of W and adds |w| for every column with w kept by magnitude and
-//      pruned by the mask.  Per-lane sums are kept in double; lanes, then wavefronts, are added
-//      in a fixed order.
+//   2. The tile is walked as a row-major list of 16-byte pieces of W (8 columns of a 16-bit
+//      type, 4 of fp32), four pieces per lane in flight.  For a piece the lane rebuilds the
+//      32-bit mask word over it (OR of the I_z words selected by the set bits of the row's I_p
+//      words, all from LDS), counts the ones, and adds |w| for every column with w kept by
+//      magnitude and pruned by the mask.  Per-lane sums are kept in double; lanes, then
+//      wavefronts, are added in a fixed order.
 // The kernel is bound by the single sweep over W (HBM); the factor reads are k (r + c) floats
 // per tile against r c weights.
 #include <hip/hip_bf16.h>
@@ -63,7 +64,8 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
                                                                       uint32_t *__restrict__ IpOut,
                                                                       uint32_t *__restrict__ IzOut,
                                                                       unsigned long long *__restrict__ Kept,
-                                                                      double *__restrict__ Cost, int w_vec_ok)
+                                                                      double *__restrict__ Cost, int w_vec_ok,
+                                                                      int bands, int rows_per_band)
 {
     constexpr int VEC = Mag<T>::VEC;
     extern __shared__ uint4 lrbi_dyn_smem[];
@@ -72,77 +74,106 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
     static __shared__ double wave_cost[kEvalWaves];
     static __shared__ unsigned long long wave_kept[kEvalWaves];
 
-    const int64_t t = blockIdx.x;
+    // workgroup = (tile, band of rows); with several bands per tile the results are partial sums
+    // (one slot per workgroup) that a second kernel adds in band order
+    const int64_t t = blockIdx.x / bands;
+    const int band = (int)(blockIdx.x - t * bands);
+    const int row_lo = band * rows_per_band;
+    const int row_hi = (row_lo + rows_per_band < g.r) ? row_lo + rows_per_band : g.r;
+    const int nrows = row_hi - row_lo;
     const int ti = (int)(t / g.tile_cols), tj = (int)(t - (int64_t)ti * g.tile_cols);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float tp = Tp[t], tz = Tz[t];
 
     // ---- 1. binary factors of the tile
+    // I_z: a wavefront compares 64 consecutive entries of one row of M_z per step (one coalesced
+    // read) and the 64 outcomes, gathered across the lanes, are the two packed words of that step
     const float *mz = Mz + t * (int64_t)g.k * g.c;
-    for (int idx = tid; idx < g.k * g.izw; idx += kEvalThreads) {
-        const int l = idx / g.izw, wq = idx - l * g.izw;
-        uint32_t bits = 0u;
-        const int j0 = 32 * wq;
-#pragma unroll 8
-        for (int b = 0; b < 32; ++b)
-            if (j0 + b < g.c && mz[(int64_t)l * g.c + j0 + b] >= tz) bits |= 1u << b;
-        iz[idx] = bits;
-        if (IzOut) IzOut[(t * g.k + l) * (int64_t)g.izw + wq] = bits;
+    const int steps_per_row = g.izw / 2;
+    for (int st = wave; st < g.k * steps_per_row; st += kEvalWaves) {
+        const int l = st / steps_per_row, sq = st - l * steps_per_row;
+        const int j = 64 * sq + lane;
+        const int hit = (j < g.c) && (mz[(int64_t)l * g.c + j] >= tz);
+        const unsigned long long b = __ballot(hit);
+        if (lane < 2) {
+            const uint32_t bits = (uint32_t)(lane ? (b >> 32) : b);
+            iz[l * g.izw + 2 * sq + lane] = bits;
+            if (IzOut && band == 0) IzOut[(t * g.k + l) * (int64_t)g.izw + 2 * sq + lane] = bits;
+        }
     }
-    const float *mp = Mp + t * (int64_t)g.r * g.k;
-    for (int idx = tid; idx < g.r * g.ipw; idx += kEvalThreads) {
-        const int i = idx / g.ipw, wq = idx - i * g.ipw;
+    const float *mp = Mp + (t * (int64_t)g.r + row_lo) * g.k;
+    for (int idx = tid; idx < nrows * g.ipw; idx += kEvalThreads) {
+        const int i = idx / g.ipw, wq = idx - i * g.ipw; // row of the band
         uint32_t bits = 0u;
         const int l0 = 32 * wq;
         for (int b = 0; b < 32; ++b)
             if (l0 + b < g.k && mp[(int64_t)i * g.k + l0 + b] >= tp) bits |= 1u << b;
         ip[idx] = bits;
-        if (IpOut) IpOut[(t * g.r + i) * (int64_t)g.ipw + wq] = bits;
+        if (IpOut) IpOut[(t * g.r + row_lo + i) * (int64_t)g.ipw + wq] = bits;
     }
     __syncthreads();
 
-    // ---- 2. rows of the tile: ones of I_a, and magnitudes kept by pruning but cleared by I_a
+    // ---- 2. the tile as a list of 16-byte pieces (row-major): ones of I_a, and magnitudes kept by
+    // pruning but cleared by I_a.  Four pieces per lane are in flight: their W loads are issued
+    // before the first is consumed (the loads do not depend on the mask).
     double cost = 0.0;
     unsigned long long kept = 0ull;
     const int64_t col0 = (int64_t)tj * g.c;
-    for (int i = wave; i < g.r; i += kEvalWaves) {
-        const T *wrow = W + ((int64_t)ti * g.r + i) * ldw + col0;
-        const uint32_t *ipr = ip + i * g.ipw;
-        for (int j = lane * VEC; j < g.c; j += 64 * VEC) {
-            // mask bits of columns j .. j + VEC - 1 (inside one 32-bit word, VEC divides 32)
-            uint32_t word = 0u;
-            for (int q = 0; q < g.ipw; ++q) {
-                uint32_t sel = ipr[q];
-                while (sel) {
-                    const int l = __builtin_ctz(sel) + 32 * q;
-                    sel &= sel - 1u;
-                    word |= iz[l * g.izw + (j >> 5)];
+    const int P = (g.c + VEC - 1) / VEC;   // pieces per tile row
+    const int items = nrows * P;
+    const T *wtile = W + ((int64_t)ti * g.r + row_lo) * ldw + col0;
+    constexpr int U = 4;
+    for (int base = tid; base < items; base += U * kEvalThreads) {
+        uint32_t w4[U][4];
+        uint32_t bits_u[U], valid_u[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int id = base + u * kEvalThreads;
+            bits_u[u] = 0u;
+            valid_u[u] = 0u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w4[u][e] = 0u;
+            if (id < items) {
+                const int i = id / P, j = (id - i * P) * VEC;
+                const T *wrow = wtile + (int64_t)i * ldw;
+                const int nvalid = (g.c - j < VEC) ? g.c - j : VEC;
+                const bool vec = w_vec_ok && (nvalid == VEC) && (((col0 + j) % VEC) == 0);
+                if (vec) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(wrow + j);
+                    w4[u][0] = v.x; w4[u][1] = v.y; w4[u][2] = v.z; w4[u][3] = v.w;
+                } else if (sizeof(T) == 4) {
+                    const uint32_t *wr = reinterpret_cast<const uint32_t *>(wrow);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w4[u][e] = (e < nvalid) ? wr[j + e] : 0u;
+                } else {
+                    const uint16_t *wr = reinterpret_cast<const uint16_t *>(wrow);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e < nvalid) w4[u][e >> 1] |= (uint32_t)wr[j + e] << (16 * (e & 1));
                 }
+                // mask bits of columns j .. j + VEC - 1 (inside one 32-bit word: VEC divides 32)
+                const uint32_t *ipr = ip + i * g.ipw;
+                uint32_t word = 0u;
+                for (int q = 0; q < g.ipw; ++q) {
+                    uint32_t sel = ipr[q];
+                    while (sel) {
+                        const int l = __builtin_ctz(sel) + 32 * q;
+                        sel &= sel - 1u;
+                        word |= iz[l * g.izw + (j >> 5)];
+                    }
+                }
+                valid_u[u] = (1u << nvalid) - 1u;
+                bits_u[u] = (word >> (j & 31)) & valid_u[u];
             }
-            const int nvalid = (g.c - j < VEC) ? g.c - j : VEC;
-            const uint32_t valid = (nvalid >= 32) ? 0xFFFFFFFFu : ((1u << nvalid) - 1u);
-            const uint32_t bits = (word >> (j & 31)) & valid;
-            kept += (unsigned long long)__builtin_popcount(bits);
-            if (bits == valid) continue; // nothing pruned here
-            uint32_t w4[4] = {0u, 0u, 0u, 0u};
-            const bool vec = w_vec_ok && (j + VEC <= g.c) && (((col0 + j) % VEC) == 0);
-            if (vec) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(wrow + j);
-                w4[0] = v.x; w4[1] = v.y; w4[2] = v.z; w4[3] = v.w;
-            } else if (sizeof(T) == 4) {
-                const uint32_t *wr = reinterpret_cast<const uint32_t *>(wrow);
+        }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w4[e] = (e < nvalid) ? wr[j + e] : 0u;
-            } else {
-                const uint16_t *wr = reinterpret_cast<const uint16_t *>(wrow);
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (e < nvalid) w4[e >> 1] |= (uint32_t)wr[j + e] << (16 * (e & 1));
-            }
+        for (int u = 0; u < U; ++u) {
+            kept += (unsigned long long)__builtin_popcount(bits_u[u]);
+            const uint32_t lost = valid_u[u] & ~bits_u[u];
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
-                const float a = piece_abs<T>(w4, e);
-                if (e < nvalid && !((bits >> e) & 1u) && a >= w_threshold) cost += (double)a;
+                const float a = piece_abs<T>(w4[u], e);
+                if (((lost >> e) & 1u) && a >= w_threshold) cost += (double)a;
             }
         }
     }
@@ -164,9 +195,27 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
             c += wave_cost[w];
             kk += wave_kept[w];
         }
-        Cost[t] = c;
-        Kept[t] = kk;
+        Cost[blockIdx.x] = c;
+        Kept[blockIdx.x] = kk;
     }
+}
+
+// adds the bands' partial results of every tile in band order
+__global__ __launch_bounds__(256) void threshold_eval_reduce_kernel(const unsigned long long *__restrict__ pk,
+                                                                    const double *__restrict__ pc, int64_t tiles,
+                                                                    int bands, unsigned long long *__restrict__ Kept,
+                                                                    double *__restrict__ Cost)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= tiles) return;
+    unsigned long long kk = 0ull;
+    double c = 0.0;
+    for (int b = 0; b < bands; ++b) {
+        kk += pk[t * bands + b];
+        c += pc[t * bands + b];
+    }
+    Kept[t] = kk;
+    Cost[t] = c;
 }
 
 size_t threshold_eval_lds_bytes(const Geom &g)
@@ -174,34 +223,70 @@ size_t threshold_eval_lds_bytes(const Geom &g)
     return ((size_t)g.k * g.izw + (size_t)g.r * g.ipw) * 4;
 }
 
+// Bands of rows per tile: enough workgroups to fill the chip when there are few tiles, at
+// least 32 rows per band.  Depends on the geometry only, so that the workspace query and the
+// launch agree.
+EvalPlan plan_threshold_eval(const Geom &g)
+{
+    EvalPlan p;
+    const int64_t tiles = (int64_t)g.tile_rows * g.tile_cols;
+    int64_t bands = (512 + tiles - 1) / tiles;
+    const int64_t max_bands = g.r / 32 > 1 ? g.r / 32 : 1;
+    if (bands > max_bands) bands = max_bands;
+    if (bands < 1) bands = 1;
+    p.rows_per_band = (int)((g.r + bands - 1) / bands);
+    p.bands = (int)((g.r + p.rows_per_band - 1) / p.rows_per_band);
+    p.workspace_bytes = (p.bands > 1) ? (uint64_t)tiles * p.bands * 16u : 0u;
+    return p;
+}
+
 template <typename T>
 static int launch_eval_t(const Geom &g, const void *dW, int64_t ldw, float w_threshold, const float *dMp,
                          const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz, uint64_t *dKept,
-                         double *dCost, hipStream_t stream)
+                         double *dCost, void *dWorkspace, hipStream_t stream)
 {
     const int64_t tiles = (int64_t)g.tile_rows * g.tile_cols;
-    if (tiles > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
+    EvalPlan plan = plan_threshold_eval(g);
+    if (!dWorkspace) { // no room for partial results: one workgroup per tile
+        plan.bands = 1;
+        plan.rows_per_band = g.r;
+    }
+    if (tiles * plan.bands > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
+    unsigned long long *pk = (unsigned long long *)dKept;
+    double *pc = dCost;
+    if (plan.bands > 1) {
+        pk = (unsigned long long *)dWorkspace;
+        pc = (double *)((char *)dWorkspace + (size_t)tiles * plan.bands * 8);
+    }
     const size_t smem = (threshold_eval_lds_bytes(g) + 15) / 16 * 16;
     const int w_vec_ok = (((uintptr_t)dW & 15) == 0) && (ldw % Mag<T>::VEC == 0);
     auto kern = threshold_eval_kernel<T>;
     if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
         return LRBI_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(kEvalThreads), smem, stream, g, (const T *)dW, ldw,
-                       w_threshold, dMp, dMz, dTp, dTz, (uint32_t *)dIp, (uint32_t *)dIz,
-                       (unsigned long long *)dKept, dCost, w_vec_ok);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles * plan.bands)), dim3(kEvalThreads), smem, stream, g, (const T *)dW,
+                       ldw, w_threshold, dMp, dMz, dTp, dTz, (uint32_t *)dIp, (uint32_t *)dIz, pk, pc, w_vec_ok,
+                       plan.bands, plan.rows_per_band);
     LRBI_CHECK_LAUNCH();
+    if (plan.bands > 1) {
+        hipLaunchKernelGGL(threshold_eval_reduce_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, stream, pk,
+                           pc, tiles, plan.bands, (unsigned long long *)dKept, dCost);
+        LRBI_CHECK_LAUNCH();
+    }
     return LRBI_OK;
 }
 
 int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold,
                           const float *dMp, const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz,
-                          uint64_t *dKept, double *dCost, hipStream_t stream)
+                          uint64_t *dKept, double *dCost, void *dWorkspace, hipStream_t stream)
 {
     switch (dt) {
-    case LRBI_F32: return launch_eval_t<float>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, stream);
-    case LRBI_F16: return launch_eval_t<__half>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, stream);
+    case LRBI_F32:
+        return launch_eval_t<float>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream);
+    case LRBI_F16:
+        return launch_eval_t<__half>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream);
     case LRBI_BF16:
-        return launch_eval_t<__hip_bfloat16>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, stream);
+        return launch_eval_t<__hip_bfloat16>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace,
+                                             stream);
     default: return LRBI_ERR_DTYPE;
     }
 }

@@ -226,7 +226,7 @@ extern "C" int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const v
 extern "C" int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
                                    float w_threshold, const float *dMp, const float *dMz, const float *dTp,
                                    const float *dTz, void *dIp_packed, void *dIz_packed, uint64_t *dKept,
-                                   double *dCost, void *stream)
+                                   double *dCost, void *dWorkspace, uint64_t workspace_bytes, void *stream)
 {
     const int rc = validate_desc(desc);
     if (rc != LRBI_OK) return rc;
@@ -241,6 +241,17 @@ extern "C" int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, cons
     if (dIp_packed && (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8))) return LRBI_ERR_ALIGN;
     const Geom g = make_geom(desc);
     if (threshold_eval_lds_bytes(g) > 64 * 1024) return LRBI_ERR_SHAPE;
+    const EvalPlan plan = plan_threshold_eval(g);
+    const bool ws_ok = dWorkspace && aligned_to(dWorkspace, 8) && workspace_bytes >= plan.workspace_bytes;
     return launch_threshold_eval(g, dtype, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp_packed, dIz_packed, dKept,
-                                 dCost, (hipStream_t)stream);
+                                 dCost, (plan.bands > 1 && ws_ok) ? dWorkspace : nullptr, (hipStream_t)stream);
+}
+
+extern "C" int lrbi_threshold_eval_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!bytes) return LRBI_ERR_NULL;
+    *bytes = plan_threshold_eval(make_geom(desc)).workspace_bytes;
+    return LRBI_OK;
 }

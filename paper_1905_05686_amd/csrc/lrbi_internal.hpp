@@ -30,10 +30,16 @@ int launch_valu_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, 
                      hipStream_t stream);
 
 // candidate evaluation of Algorithm 1 (lrbi_alg1.hip)
+struct EvalPlan {
+    int bands;         // row bands per tile (workgroups per tile)
+    int rows_per_band;
+    uint64_t workspace_bytes;
+};
+EvalPlan plan_threshold_eval(const Geom &g);
 size_t threshold_eval_lds_bytes(const Geom &g);
 int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold,
                           const float *dMp, const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz,
-                          uint64_t *dKept, double *dCost, hipStream_t stream);
+                          uint64_t *dKept, double *dCost, void *dWorkspace, hipStream_t stream);
 
 struct MfmaPlan {
     int tile;     // tile variant id (1-based, see lrbi_gemm_mfma.hip)

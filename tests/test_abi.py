@@ -127,7 +127,8 @@ def test_threshold_eval_rejects_bad_arguments_before_any_launch():
     p = ctypes.c_void_p(base)
     f = lib.lrbi_threshold_eval
     args = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128), 0.5,
-                         kw.get("Mp", p), p, p, p, kw.get("Ip", None), kw.get("Iz", None), kw.get("kept", p), p, None]
+                         kw.get("Mp", p), p, p, p, kw.get("Ip", None), kw.get("Iz", None), kw.get("kept", p), p, None, 0,
+                         None]
     assert f(*args(W=None)) == -1
     assert f(*args(Mp=None)) == -1
     assert f(*args(kept=None)) == -1
@@ -140,3 +141,7 @@ def test_threshold_eval_rejects_bad_arguments_before_any_launch():
     # factor bits of one tile must fit in 64 KiB of on-chip memory
     big = lrbi.Desc(4096, 65536, 4096, 65536, 8)
     assert f(*args(d=big, ldw=65536)) == -2
+    # workspace: none needed when the tiles alone fill the chip, 16 bytes per (tile, band) otherwise
+    assert lrbi.threshold_eval_workspace_bytes(lrbi.Desc(4096, 9216, 256, 256, 16)) == 0
+    assert lrbi.threshold_eval_workspace_bytes(lrbi.Desc(4096, 4096, 512, 512, 32)) == 64 * 8 * 16
+    assert lrbi.threshold_eval_workspace_bytes(lrbi.Desc(8, 128, 4, 64, 2)) == 0   # 4-row tiles: one band

@@ -18,11 +18,15 @@ def _oracle(cfg, W64, f, w_threshold):
     return Ip, Iz, kept, cost
 
 
-def _gpu(cfg, Wdev, f, w_threshold, want_factors=True):
+def _gpu(cfg, Wdev, f, w_threshold, want_factors=True, use_workspace=True):
     d = desc_of(cfg)
     t = lambda a: torch.from_numpy(a).to(dev())
+    ws = None
+    nbytes = lrbi.threshold_eval_workspace_bytes(d)
+    if use_workspace and nbytes:
+        ws = torch.empty(nbytes // 8, dtype=torch.int64, device=dev())
     return lrbi.threshold_eval(d, Wdev, w_threshold, t(f["Mp"]), t(f["Mz"]), t(f["Tp"]), t(f["Tz"]),
-                               want_factors=want_factors)
+                               want_factors=want_factors, workspace=ws)
 
 
 def _check(cfg, f, w_threshold, ldpad=0):
@@ -48,6 +52,10 @@ def _check(cfg, f, w_threshold, ldpad=0):
     # run-to-run identical bits, also without the factor outputs
     kept2, cost2 = _gpu(cfg, W, f, w_threshold, want_factors=False)
     assert torch.equal(kept, kept2) and torch.equal(cost.view(torch.int64), cost2.view(torch.int64))
+    # without workspace (one workgroup per tile): same integers, same cost up to summation order
+    kept3, cost3, ip3, iz3 = _gpu(cfg, W, f, w_threshold, use_workspace=False)
+    assert torch.equal(kept, kept3) and torch.equal(ip, ip3) and torch.equal(iz, iz3)
+    assert np.all(np.abs(cost3.cpu().numpy() - cost_ref) <= 1e-12 * np.maximum(cost_ref, 1.0))
     return kept_ref, cost_ref
 
 
@@ -76,6 +84,8 @@ EDGE = [
     (_small(128, 256, 64, 128, 8, 0.2, "f16"), 8),      # padded rows, still 16-byte aligned
     (_small(128, 256, 64, 128, 8, 0.2, "f16"), 3),      # padded rows, scalar loads
     (_small(50, 120, 25, 60, 4, 0.2, "f32"), 3),
+    (_small(600, 300, 300, 300, 8, 0.12, "f16"), 0),    # two tiles of 300 rows: 9 bands of 34 rows, ragged last band
+    (_small(512, 512, 512, 512, 32, 0.06, "bf16"), 0),  # one tile, 16 bands
 ]
 
 
