@@ -731,11 +731,15 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
     if (split == 0) {
         split = 1;
         if (tiles < 192) {
-            // at least 8 slabs per slice; the 512-lane panel kernels run one workgroup per compute unit
-            // (measured best: one slice per unit), the 256-lane kernels two
-            const int64_t target = (tile >= 9) ? 256 : 512;
+            // The 512-lane panel kernels run one workgroup per compute unit (measured best: one slice per
+            // unit, at least 8 slabs per slice), the 256-lane panel kernels two.  The general kernel pays a
+            // round of dependent factor loads per slab, so short slices and more workgroups in flight pay off
+            // (C4: 12 slices of 4 slabs, 23 us against 32 us with 6 slices).
+            const bool general = tile < 4;
+            const int64_t target = (tile >= 9) ? 256 : (general ? 1024 : 512);
             int64_t want = (target + tiles - 1) / tiles;
-            const int64_t cap = npairs / 4 > 1 ? npairs / 4 : 1;
+            const int64_t min_pairs = general ? 2 : 4;
+            const int64_t cap = npairs / min_pairs > 1 ? npairs / min_pairs : 1;
             if (want > cap) want = cap;
             if (want > 64) want = 64;
             split = (int)(want < 1 ? 1 : want);
