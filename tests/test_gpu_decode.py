@@ -53,6 +53,8 @@ SHAPES = [
     (1, 4097, 1, 4097, 2, 0.4),      # single row, ragged tail
     (257, 9000, 257, 300, 8, 0.12),  # many unaligned tiles
     (2048, 8192, 512, 512, 32, 0.06),
+    (1152, 2048, 576, 512, 145, 0.02),   # the tile shape (576 x 512) and a rank (145) the paper itself uses (Sec. 4)
+    (1152, 1024, 576, 512, 256, 0.015),  # same tiles at the largest rank of Table 1
 ]
 
 

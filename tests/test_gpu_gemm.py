@@ -81,6 +81,9 @@ EDGE = [
     (_small(256, 512, 128, 128, 8, 0.2, 64, "bf16"), lrbi.FLAG_PATH_VALU), # big batch forced onto the ALUs
     (_small(256, 512, 128, 128, 8, 0.2, 96, "bf16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_tile(2)),
     (_small(256, 512, 128, 128, 8, 0.2, 96, "bf16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_tile(3)),
+    # tile shape and ranks of the paper's own experiments (Sec. 4: 576 x 512 tiles, rank 145; Table 1: rank 256)
+    (_small(1152, 1024, 576, 512, 145, 0.02, 64, "f16"), 0),
+    (_small(1152, 1024, 576, 512, 256, 0.015, 1, "bf16"), 0),
 ]
 
 

@@ -86,6 +86,7 @@ EDGE = [
     (_small(50, 120, 25, 60, 4, 0.2, "f32"), 3),
     (_small(600, 300, 300, 300, 8, 0.12, "f16"), 0),    # two tiles of 300 rows: 9 bands of 34 rows, ragged last band
     (_small(512, 512, 512, 512, 32, 0.06, "bf16"), 0),  # one tile, 16 bands
+    (_small(1152, 1024, 576, 512, 145, 0.02, "f16"), 0), # the paper's 576 x 512 tiles at rank 145 (Sec. 4)
 ]
 
 
