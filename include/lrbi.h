@@ -207,6 +207,43 @@ int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW,
 /* Scratch lrbi_threshold_eval can use for this geometry.  Host only.  *bytes may be 0. */
 int lrbi_threshold_eval_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
 
+/*
+ * The threshold search of Algorithm 1 (Sec. 2.2) for every tile of a layer, entirely on
+ * the device: for each S_p of the caller's list (the sweep of the outer loop), T_p is the
+ * entry of the tile's ascending-sorted M_p at index round(S_p r k) (+inf at r k: I_p all
+ * zero), and S_z is found by bisection on [0, 1], starting from Eq. 7 solved for S_z,
+ * S_z = (S^(1/k) - S_p) / (1 - S_p) clipped to [0, 1] (0 when S_p = 1); each of the `steps`
+ * probes converts with (T_p, T_z), forms I_a (Eq. 3) and takes its number of ones and
+ * its cost exactly as lrbi_threshold_eval does; more ones than round((1 - S) r c) moves
+ * the lower end of the interval to the probe, otherwise the upper end, and the next probe is
+ * the midpoint.  The probe whose count of ones is closest to that target (the first such)
+ * stands for its S_p; it is eligible when it is within `tolerance` ones of the target.
+ * Per tile the result is the eligible candidate of least cost (the first in list order on
+ * ties); when no S_p has an eligible candidate, the one closest to the target.
+ *   dW, ldw, w_threshold, dMp, dMz: as for lrbi_threshold_eval.  M_p, M_z must hold no NaN.
+ *   target_sparsity: S, in (0, 1).  sp_values: HOST array of n_sp values in [0, 1].
+ *   dTp, dTz [T] float, dKept [T] uint64, dCost [T] double: the winning thresholds of every
+ *   tile with their number of ones and cost.  dIp_packed, dIz_packed: when not NULL, the
+ *   binary factors converted with the winning thresholds; both or neither.
+ *   dWorkspace: required, 16-byte aligned, at least lrbi_search_workspace_bytes bytes (the
+ *   sorted factors, per-tile search state, and the evaluation's own scratch).
+ * Limits: those of lrbi_threshold_eval (a factor of up to 16384 entries per tile is sorted in
+ * on-chip memory, a larger one in the workspace, more slowly); LRBI_ERR_SHAPE otherwise, and
+ * for n_sp < 1, steps < 1, tolerance < 0, S outside (0, 1) or an S_p outside [0, 1].
+ * Costs of candidates that differ by less than the rounding of a double-precision sum may
+ * rank either way.  2 + n_sp (1 + 2 steps .. 3 steps) + (0 .. 2) launches on `stream`; the
+ * host does not wait for the device.
+ */
+int lrbi_search_thresholds(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                           float w_threshold, const float *dMp, const float *dMz,
+                           double target_sparsity, const double *sp_values, int32_t n_sp,
+                           int32_t steps, int64_t tolerance, float *dTp, float *dTz,
+                           uint64_t *dKept, double *dCost, void *dIp_packed, void *dIz_packed,
+                           void *dWorkspace, uint64_t workspace_bytes, void *stream);
+
+/* Scratch lrbi_search_thresholds needs for this geometry.  Host only. */
+int lrbi_search_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -76,9 +76,13 @@ def load_library():
     lib.lrbi_threshold_eval.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64,
                                         vp]
     lib.lrbi_threshold_eval_workspace_bytes.argtypes = [pd, pu64]
+    lib.lrbi_search_thresholds.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, vp, vp, ctypes.c_double,
+                                           ctypes.POINTER(ctypes.c_double), i32, i32, i64, vp, vp, vp, vp, vp, vp, vp, u64,
+                                           vp]
+    lib.lrbi_search_workspace_bytes.argtypes = [pd, pu64]
     for name in ("lrbi_index_bits", "lrbi_csr_bits", "lrbi_pack_factors", "lrbi_unpack_mask", "lrbi_decode_mask",
                  "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm", "lrbi_threshold_eval",
-                 "lrbi_threshold_eval_workspace_bytes"):
+                 "lrbi_threshold_eval_workspace_bytes", "lrbi_search_thresholds", "lrbi_search_workspace_bytes"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -245,3 +249,44 @@ def threshold_eval(desc: Desc, W, w_threshold: float, Mp, Mz, Tp, Tz, want_facto
         workspace.numel() * workspace.element_size() if workspace is not None else 0,
         _stream_ptr(stream)), "lrbi_threshold_eval")
     return (kept, cost, ip, iz) if want_factors else (kept, cost)
+
+
+def search_workspace_bytes(desc: Desc) -> int:
+    out = ctypes.c_uint64()
+    _check(load_library().lrbi_search_workspace_bytes(ctypes.byref(desc), ctypes.byref(out)),
+           "lrbi_search_workspace_bytes")
+    return out.value
+
+
+def search_thresholds(desc: Desc, W, w_threshold: float, Mp, Mz, target_sparsity: float, sp_values, steps: int,
+                      tolerance: int, want_factors: bool = False, workspace=None, stream=None):
+    """lrbi_search_thresholds: the threshold search of Algorithm 1 for every tile.  W [m, n] (f32 / f16 / bf16),
+    Mp [T, r, k], Mz [T, k, c] float32 device tensors; sp_values a host sequence of floats.  Returns
+    (Tp float32 [T], Tz float32 [T], kept int64 [T], cost float64 [T]) and, with want_factors, also the packed
+    factors (Ip int32 [T*r, ipw], Iz int32 [T*k, izw]) converted with the winning thresholds.  `workspace` =
+    device scratch of at least search_workspace_bytes(desc) bytes (allocated here when None)."""
+    import torch
+    T = desc.tiles
+    if W.dim() != 2 or W.shape != (desc.m, desc.n) or W.stride(1) != 1:
+        raise ValueError("W must be a row-major [m, n] tensor")
+    for t, shape in ((Mp, (T, desc.r, desc.k)), (Mz, (T, desc.k, desc.c))):
+        if t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError("factor tensors must be contiguous float32 of shape %s" % (shape,))
+    if workspace is None:
+        workspace = torch.empty(search_workspace_bytes(desc), dtype=torch.uint8, device=W.device)
+    sp = (ctypes.c_double * len(sp_values))(*[float(v) for v in sp_values])
+    Tp = torch.empty(T, dtype=torch.float32, device=W.device)
+    Tz = torch.empty(T, dtype=torch.float32, device=W.device)
+    kept = torch.empty(T, dtype=torch.int64, device=W.device)
+    cost = torch.empty(T, dtype=torch.float64, device=W.device)
+    ip = iz = None
+    if want_factors:
+        ip = torch.empty((T * desc.r, (desc.k + 31) // 32), dtype=torch.int32, device=W.device)
+        iz = torch.empty((T * desc.k, 2 * ((desc.c + 63) // 64)), dtype=torch.int32, device=W.device)
+    _check(load_library().lrbi_search_thresholds(
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), float(w_threshold), _dev_ptr(Mp, "Mp"),
+        _dev_ptr(Mz, "Mz"), float(target_sparsity), sp, len(sp_values), int(steps), int(tolerance), _dev_ptr(Tp, "Tp"),
+        _dev_ptr(Tz, "Tz"), _dev_ptr(kept, "kept"), _dev_ptr(cost, "cost"), _dev_ptr(ip, "Ip") if want_factors else None,
+        _dev_ptr(iz, "Iz") if want_factors else None, _dev_ptr(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), _stream_ptr(stream)), "lrbi_search_thresholds")
+    return (Tp, Tz, kept, cost, ip, iz) if want_factors else (Tp, Tz, kept, cost)

@@ -19,6 +19,8 @@
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
+#include <math.h>
+
 #include "lrbi_internal.hpp"
 
 namespace lrbi {
@@ -272,6 +274,231 @@ static int launch_eval_t(const Geom &g, const void *dW, int64_t ldw, float w_thr
                            pc, tiles, plan.bands, (unsigned long long *)dKept, dCost);
         LRBI_CHECK_LAUNCH();
     }
+    return LRBI_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Threshold search of Algorithm 1 (Sec. 2.2), all tiles in lockstep: for every S_p of the
+// caller's list, a bisection on S_z whose probes are evaluated by the kernel above (one launch
+// per probe for all tiles); the per-tile search state lives in the caller's workspace and is
+// advanced by two small kernels, so the host never waits for the device.
+// ---------------------------------------------------------------------------
+struct SearchState {
+    double lo, hi, sz;     // bisection interval and current probe of S_z
+    double rep_cost;       // representative of the current S_p: the probe closest to the target
+    long long rep_diff;    // |ones - target| of the representative, -1 = none yet
+    unsigned long long rep_kept;
+    float rep_tz;
+    float tp;              // threshold of I_p for the current S_p
+    long long best_diff;   // winner so far, -1 = none
+    int best_eligible;
+    int pad;
+};
+
+// Sorts the n values of one tile's factor (ascending, bitonic network over `padded` = 2^j >= n slots, the
+// tail filled with +inf).  One workgroup per tile.  Up to 16384 slots the network runs in on-chip memory and
+// the n sorted values are written to out + tile * stride; beyond that it runs in place in out + tile * stride
+// (stride >= padded), slower, the workgroup's own barriers ordering its global accesses.
+__global__ __launch_bounds__(512) void tile_sort_kernel(const float *__restrict__ in, float *out, int n, int padded,
+                                                        int64_t stride, int on_chip)
+{
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    float *dst = out + (int64_t)blockIdx.x * stride;
+    float *v = on_chip ? reinterpret_cast<float *>(lrbi_dyn_smem) : dst;
+    const float *src = in + (int64_t)blockIdx.x * n;
+    for (int i = threadIdx.x; i < padded; i += 512) v[i] = (i < n) ? src[i] : __builtin_inff();
+    __syncthreads();
+    for (int size = 2; size <= padded; size <<= 1) {
+        for (int stride2 = size >> 1; stride2 > 0; stride2 >>= 1) {
+            for (int i = threadIdx.x; i < padded / 2; i += 512) {
+                const int lo = 2 * i - (i & (stride2 - 1)); // lower index of the pair at this distance
+                const int hi = lo + stride2;
+                const bool up = (lo & size) == 0;
+                const float a = v[lo], b = v[hi];
+                if ((a > b) == up) {
+                    v[lo] = b;
+                    v[hi] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (on_chip)
+        for (int i = threadIdx.x; i < n; i += 512) dst[i] = v[i];
+}
+
+// entry of the sorted factor at index round(sparsity * count): entries below it become 0
+__device__ __forceinline__ float threshold_at(const float *sorted, int count, double sparsity)
+{
+    // separate multiply and add (no fused operation): the index must be the same as in plain double arithmetic
+    long long idx = (long long)floor(__dadd_rn(__dmul_rn(sparsity, (double)count), 0.5));
+    if (idx < 0) idx = 0;
+    return (idx >= count) ? __builtin_inff() : sorted[idx];
+}
+
+__global__ __launch_bounds__(256) void search_begin_kernel(SearchState *__restrict__ st, const float *__restrict__ sortedMp,
+                                                           const float *__restrict__ sortedMz, int np, int nz,
+                                                           int64_t stride_p, int64_t stride_z, int64_t tiles, int idx_p, double sz0, int first,
+                                                           float *__restrict__ Tp, float *__restrict__ Tz)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= tiles) return;
+    SearchState s = st[t];
+    if (first) {
+        s.best_diff = -1;
+        s.best_eligible = 0;
+    }
+    s.tp = (idx_p >= np) ? __builtin_inff() : sortedMp[t * stride_p + idx_p];
+    s.lo = 0.0;
+    s.hi = 1.0;
+    s.sz = sz0;
+    s.rep_diff = -1;
+    st[t] = s;
+    Tp[t] = s.tp;
+    Tz[t] = threshold_at(sortedMz + t * stride_z, nz, sz0);
+}
+
+__global__ __launch_bounds__(256) void search_step_kernel(SearchState *__restrict__ st, const float *__restrict__ sortedMz,
+                                                          int nz, int64_t stride_z, int64_t tiles, long long target, long long tolerance,
+                                                          int last_step, const unsigned long long *__restrict__ kept,
+                                                          const double *__restrict__ cost, float *__restrict__ Tz,
+                                                          float *__restrict__ TpBest, float *__restrict__ TzBest,
+                                                          unsigned long long *__restrict__ KeptBest,
+                                                          double *__restrict__ CostBest)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= tiles) return;
+    SearchState s = st[t];
+    const long long k = (long long)kept[t];
+    const long long diff = (k > target) ? k - target : target - k;
+    if (s.rep_diff < 0 || diff < s.rep_diff) {
+        s.rep_diff = diff;
+        s.rep_tz = Tz[t];
+        s.rep_kept = kept[t];
+        s.rep_cost = cost[t];
+    }
+    if (k > target) s.lo = s.sz; // too many ones: I_z must get sparser
+    else s.hi = s.sz;
+    s.sz = 0.5 * (s.lo + s.hi);
+    Tz[t] = threshold_at(sortedMz + t * stride_z, nz, s.sz);
+    if (last_step) {
+        const int eligible = s.rep_diff <= tolerance;
+        bool better;
+        if (s.best_diff < 0) better = true;
+        else if (eligible != s.best_eligible) better = eligible != 0;
+        else if (eligible) better = s.rep_cost < CostBest[t];
+        else better = s.rep_diff < s.best_diff;
+        if (better) {
+            s.best_diff = s.rep_diff;
+            s.best_eligible = eligible;
+            TpBest[t] = s.tp;
+            TzBest[t] = s.rep_tz;
+            KeptBest[t] = s.rep_kept;
+            CostBest[t] = s.rep_cost;
+        }
+    }
+    st[t] = s;
+}
+
+constexpr int kSortOnChip = 16384; // floats: 64 KiB of on-chip memory
+
+static int64_t pow2_at_least(int64_t n)
+{
+    int64_t p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
+
+SearchPlan plan_search(const Geom &g)
+{
+    SearchPlan p;
+    const uint64_t tiles = (uint64_t)g.tile_rows * g.tile_cols;
+    auto up = [](uint64_t v) { return (v + 255) / 256 * 256; };
+    p.np = g.r * g.k;
+    p.nz = g.k * g.c;
+    // a factor of more than kSortOnChip entries is sorted in place in the workspace, in 2^j slots
+    p.stride_p = p.np <= kSortOnChip ? p.np : pow2_at_least(p.np);
+    p.stride_z = p.nz <= kSortOnChip ? p.nz : pow2_at_least(p.nz);
+    p.off_sorted_mp = 0;
+    p.off_sorted_mz = up(p.off_sorted_mp + tiles * (uint64_t)p.stride_p * 4);
+    p.off_state = up(p.off_sorted_mz + tiles * (uint64_t)p.stride_z * 4);
+    p.off_tp = up(p.off_state + tiles * sizeof(SearchState));
+    p.off_tz = up(p.off_tp + tiles * 4);
+    p.off_kept = up(p.off_tz + tiles * 4);
+    p.off_cost = up(p.off_kept + tiles * 8);
+    p.off_eval = up(p.off_cost + tiles * 8);
+    p.bytes = p.off_eval + plan_threshold_eval(g).workspace_bytes;
+    return p;
+}
+
+int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, const float *dMp,
+                  const float *dMz, double target_sparsity, int n_sp, const double *sp_values, int steps,
+                  int64_t tolerance, float *dTpBest, float *dTzBest, uint64_t *dKeptBest, double *dCostBest, void *dIp,
+                  void *dIz, void *dWorkspace, hipStream_t stream)
+{
+    const SearchPlan p = plan_search(g);
+    const int64_t tiles = (int64_t)g.tile_rows * g.tile_cols;
+    char *ws = (char *)dWorkspace;
+    float *sortedMp = (float *)(ws + p.off_sorted_mp);
+    float *sortedMz = (float *)(ws + p.off_sorted_mz);
+    SearchState *state = (SearchState *)(ws + p.off_state);
+    float *Tp = (float *)(ws + p.off_tp);
+    float *Tz = (float *)(ws + p.off_tz);
+    uint64_t *kept = (uint64_t *)(ws + p.off_kept);
+    double *cost = (double *)(ws + p.off_cost);
+    void *eval_ws = plan_threshold_eval(g).workspace_bytes ? (void *)(ws + p.off_eval) : nullptr;
+
+    // 1. sorted factors of every tile (the quantile look-up of "convert with (S_p, S_z)")
+    for (int which = 0; which < 2; ++which) {
+        const int n = which ? p.nz : p.np;
+        const int padded = (int)pow2_at_least(n);
+        const int on_chip = n <= kSortOnChip;
+        const size_t smem = on_chip ? (size_t)padded * 4 : 0;
+        if (hipFuncSetAttribute((const void *)tile_sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kSortOnChip * 4) != hipSuccess)
+            return LRBI_ERR_LAUNCH;
+        hipLaunchKernelGGL(tile_sort_kernel, dim3((unsigned)tiles), dim3(512), smem, stream, which ? dMz : dMp,
+                           which ? sortedMz : sortedMp, n, padded, which ? p.stride_z : p.stride_p, on_chip);
+        LRBI_CHECK_LAUNCH();
+    }
+    // 2. sweep over S_p, bisection on S_z
+    // products and sums below are rounded one by one (volatile: no fused multiply-add), so that the
+    // indices are the ones plain double arithmetic gives
+    volatile double prod = (1.0 - target_sparsity) * (double)g.r;
+    prod = prod * (double)g.c;
+    prod = prod + 0.5;
+    const long long target = (long long)floor(prod);
+    const unsigned sblocks = (unsigned)((tiles + 255) / 256);
+    for (int a = 0; a < n_sp; ++a) {
+        const double sp = sp_values[a];
+        prod = sp * (double)p.np;
+        prod = prod + 0.5;
+        long long idx_p = (long long)floor(prod);
+        if (idx_p < 0) idx_p = 0;
+        if (idx_p > p.np) idx_p = p.np;
+        double sz0 = 0.0;
+        if (sp < 1.0) {
+            sz0 = (pow(target_sparsity, 1.0 / (double)g.k) - sp) / (1.0 - sp); // Eq. 7 solved for S_z
+            if (sz0 < 0.0) sz0 = 0.0;
+            if (sz0 > 1.0) sz0 = 1.0;
+        }
+        hipLaunchKernelGGL(search_begin_kernel, dim3(sblocks), dim3(256), 0, stream, state, sortedMp, sortedMz, p.np, p.nz,
+                           p.stride_p, p.stride_z, tiles, (int)idx_p, sz0, a == 0 ? 1 : 0, Tp, Tz);
+        LRBI_CHECK_LAUNCH();
+        for (int step = 0; step < steps; ++step) {
+            const int rc = launch_threshold_eval(g, dt, dW, ldw, w_threshold, dMp, dMz, Tp, Tz, nullptr, nullptr, kept,
+                                                 cost, eval_ws, stream);
+            if (rc != LRBI_OK) return rc;
+            hipLaunchKernelGGL(search_step_kernel, dim3(sblocks), dim3(256), 0, stream, state, sortedMz, p.nz, p.stride_z, tiles, target,
+                               (long long)tolerance, step == steps - 1 ? 1 : 0, (const unsigned long long *)kept, cost, Tz,
+                               dTpBest, dTzBest, (unsigned long long *)dKeptBest, dCostBest);
+            LRBI_CHECK_LAUNCH();
+        }
+    }
+    // 3. the winning thresholds once more, now writing the packed binary factors
+    if (dIp)
+        return launch_threshold_eval(g, dt, dW, ldw, w_threshold, dMp, dMz, dTpBest, dTzBest, dIp, dIz, dKeptBest,
+                                     dCostBest, eval_ws, stream);
     return LRBI_OK;
 }
 

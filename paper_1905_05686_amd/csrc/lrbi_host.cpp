@@ -255,3 +255,41 @@ extern "C" int lrbi_threshold_eval_workspace_bytes(const lrbi_desc *desc, uint64
     *bytes = plan_threshold_eval(make_geom(desc)).workspace_bytes;
     return LRBI_OK;
 }
+
+extern "C" int lrbi_search_thresholds(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                                      float w_threshold, const float *dMp, const float *dMz, double target_sparsity,
+                                      const double *sp_values, int32_t n_sp, int32_t steps, int64_t tolerance,
+                                      float *dTp, float *dTz, uint64_t *dKept, double *dCost, void *dIp_packed,
+                                      void *dIz_packed, void *dWorkspace, uint64_t workspace_bytes, void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dW || !dMp || !dMz || !sp_values || !dTp || !dTz || !dKept || !dCost || !dWorkspace) return LRBI_ERR_NULL;
+    if ((dIp_packed == nullptr) != (dIz_packed == nullptr)) return LRBI_ERR_NULL;
+    const int es = elem_size(dtype);
+    if (es == 0) return LRBI_ERR_DTYPE;
+    if (ldw < desc->n) return LRBI_ERR_PITCH;
+    if (n_sp < 1 || steps < 1 || tolerance < 0) return LRBI_ERR_SHAPE;
+    if (!(target_sparsity > 0.0 && target_sparsity < 1.0)) return LRBI_ERR_SHAPE;
+    for (int32_t a = 0; a < n_sp; ++a)
+        if (!(sp_values[a] >= 0.0 && sp_values[a] <= 1.0)) return LRBI_ERR_SHAPE;
+    if (!aligned_to(dW, (uintptr_t)es) || !aligned_to(dMp, 4) || !aligned_to(dMz, 4) || !aligned_to(dTp, 4) ||
+        !aligned_to(dTz, 4) || !aligned_to(dKept, 8) || !aligned_to(dCost, 8) || !aligned_to(dWorkspace, 16))
+        return LRBI_ERR_ALIGN;
+    if (dIp_packed && (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8))) return LRBI_ERR_ALIGN;
+    const Geom g = make_geom(desc);
+    if (threshold_eval_lds_bytes(g) > 64 * 1024) return LRBI_ERR_SHAPE;
+    const SearchPlan plan = plan_search(g);
+    if (workspace_bytes < plan.bytes) return LRBI_ERR_WORKSPACE;
+    return launch_search(g, dtype, dW, ldw, w_threshold, dMp, dMz, target_sparsity, n_sp, sp_values, steps, tolerance,
+                         dTp, dTz, dKept, dCost, dIp_packed, dIz_packed, dWorkspace, (hipStream_t)stream);
+}
+
+extern "C" int lrbi_search_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!bytes) return LRBI_ERR_NULL;
+    *bytes = plan_search(make_geom(desc)).bytes;
+    return LRBI_OK;
+}

@@ -41,6 +41,18 @@ int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t 
                           const float *dMp, const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz,
                           uint64_t *dKept, double *dCost, void *dWorkspace, hipStream_t stream);
 
+// threshold search of Algorithm 1 (lrbi_alg1.hip): workspace layout (byte offsets) and sizes
+struct SearchPlan {
+    int np, nz;                 // entries of one tile's M_p, M_z
+    int64_t stride_p, stride_z; // floats between two tiles' sorted factors in the workspace
+    uint64_t off_sorted_mp, off_sorted_mz, off_state, off_tp, off_tz, off_kept, off_cost, off_eval, bytes;
+};
+SearchPlan plan_search(const Geom &g);
+int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, const float *dMp,
+                  const float *dMz, double target_sparsity, int n_sp, const double *sp_values, int steps,
+                  int64_t tolerance, float *dTpBest, float *dTzBest, uint64_t *dKeptBest, double *dCostBest, void *dIp,
+                  void *dIz, void *dWorkspace, hipStream_t stream);
+
 struct MfmaPlan {
     int tile;     // tile variant id (1-based, see lrbi_gemm_mfma.hip)
     int bm, bn;   // workgroup tile

@@ -145,3 +145,43 @@ def test_threshold_eval_rejects_bad_arguments_before_any_launch():
     assert lrbi.threshold_eval_workspace_bytes(lrbi.Desc(4096, 9216, 256, 256, 16)) == 0
     assert lrbi.threshold_eval_workspace_bytes(lrbi.Desc(4096, 4096, 512, 512, 32)) == 64 * 8 * 16
     assert lrbi.threshold_eval_workspace_bytes(lrbi.Desc(8, 128, 4, 64, 2)) == 0   # 4-row tiles: one band
+
+
+def test_search_thresholds_rejects_bad_arguments_before_any_launch():
+    lib = lrbi.load_library()
+    d = lrbi.Desc(8, 128, 4, 64, 2)
+    buf = (ctypes.c_uint8 * 4096)()
+    base = (ctypes.addressof(buf) + 63) // 64 * 64
+    p = ctypes.c_void_p(base)
+    sweep = (ctypes.c_double * 3)(0.2, 0.5, 0.8)
+    f = lib.lrbi_search_thresholds
+    big = 1 << 30
+    args = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128), 0.5,
+                         kw.get("Mp", p), p, kw.get("S", 0.9), kw.get("sweep", sweep), kw.get("n_sp", 3),
+                         kw.get("steps", 4), kw.get("tol", 1), kw.get("Tp", p), p, kw.get("kept", p), p,
+                         kw.get("Ip", None), kw.get("Iz", None), kw.get("ws", p), kw.get("wsb", big), None]
+    assert f(*args(W=None)) == -1
+    assert f(*args(Mp=None)) == -1
+    assert f(*args(sweep=None)) == -1
+    assert f(*args(Tp=None)) == -1
+    assert f(*args(ws=None)) == -1
+    assert f(*args(Ip=p)) == -1
+    assert f(*args(dt=9)) == -4
+    assert f(*args(ldw=100)) == -5
+    assert f(*args(n_sp=0)) == -2
+    assert f(*args(steps=0)) == -2
+    assert f(*args(tol=-1)) == -2
+    assert f(*args(S=0.0)) == -2
+    assert f(*args(S=1.0)) == -2
+    assert f(*args(S=float("nan"))) == -2
+    assert f(*args(sweep=(ctypes.c_double * 3)(0.2, 1.5, 0.8))) == -2
+    assert f(*args(kept=ctypes.c_void_p(base + 4))) == -6
+    assert f(*args(ws=ctypes.c_void_p(base + 8))) == -6
+    assert f(*args(wsb=lrbi.search_workspace_bytes(d) - 1)) == -8
+    # workspace: both sorted factors, the search state and the evaluation's scratch
+    d2 = lrbi.Desc(4096, 9216, 256, 256, 16)
+    assert lrbi.search_workspace_bytes(d2) >= 2 * 576 * 4096 * 4 + 576 * (64 + 4 + 4 + 8 + 8)
+    assert lrbi.search_workspace_bytes(d2) < 2 * 576 * 4096 * 4 + 576 * 256
+    # factors of more than 16384 entries take 2^j slots per tile
+    d3 = lrbi.Desc(576, 1024, 576, 512, 145)
+    assert lrbi.search_workspace_bytes(d3) >= 2 * (131072 + 131072) * 4
