@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, C1, alg1_eval_C2, alg1_eval_C3, ceilings); used to profile one workload at a time")
+                         "C4, C5, C1, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: run a plain 1 GiB device copy "
@@ -335,6 +335,43 @@ def main():
                 del Wl, tens
             except Exception as e:
                 others[key] = {"error": repr(e)}
+        # the whole threshold search of Algorithm 1 for a layer: sort, then n_sp x steps candidates (W stays in the
+        # last-level cache between candidates, as it would in real use); eager launches, HIP events around them
+        if wanted is None or "alg1_search_C2" in wanted:
+            try:
+                c = workloads.CONFIGS["C2"]
+                d = workloads.make(c, want_x=False)
+                f = workloads.make_real_factors(c)
+                de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
+                W_ = to_dev(d["W"], c.dtype)
+                Mp_, Mz_ = torch.from_numpy(f["Mp"]).to(dev), torch.from_numpy(f["Mz"]).to(dev)
+                sws = torch.empty(lrbi.search_workspace_bytes(de), dtype=torch.uint8, device=dev)
+                S_, sweep, steps_, tol = 0.90, [0.86 + 0.0125 * i for i in range(8)], 10, int(0.005 * c.r * c.c)
+                run = lambda: lrbi.search_thresholds(de, W_, f["w_threshold"], Mp_, Mz_, S_, sweep, steps_, tol,
+                                                     want_factors=True, workspace=sws)
+                run()
+                torch.cuda.synchronize()
+                ts = []
+                for _ in range(5):
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    res_ = run()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ts.append(e0.elapsed_time(e1))
+                ms = float(sorted(ts)[2])
+                ncand = len(sweep) * steps_
+                eligible = int(((res_[2] - round((1 - S_) * c.r * c.c)).abs() <= tol).sum())
+                others["alg1_search_C2"] = {
+                    "workload": "C2: W %dx%d %s, U(0,1) factors, S = %.2f, %d S_p values x %d bisection steps, "
+                                "tolerance %d ones" % (c.m, c.n, c.dtype, S_, len(sweep), steps_, tol),
+                    "search_ms": round(ms, 4), "candidates": ncand, "ms_per_candidate": round(ms / ncand, 5),
+                    "tile_candidates_per_s": round(c.tiles * ncand / (ms * 1e-3), 1),
+                    "tiles_with_eligible_winner": eligible, "tiles": c.tiles}
+                del W_, Mp_, Mz_, sws
+            except Exception as e:
+                others["alg1_search_C2"] = {"error": repr(e)}
         out["others"] = others
 
         # measured ceilings on this machine (context for the fractions above, not product code):

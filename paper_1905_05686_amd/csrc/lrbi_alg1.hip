@@ -89,27 +89,55 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
 
     // ---- 1. binary factors of the tile
     // I_z: a wavefront compares 64 consecutive entries of one row of M_z per step (one coalesced
-    // read) and the 64 outcomes, gathered across the lanes, are the two packed words of that step
+    // read) and the 64 outcomes, gathered across the lanes, are the two packed words of that step;
+    // eight steps' reads are requested together
     const float *mz = Mz + t * (int64_t)g.k * g.c;
     const int steps_per_row = g.izw / 2;
-    for (int st = wave; st < g.k * steps_per_row; st += kEvalWaves) {
-        const int l = st / steps_per_row, sq = st - l * steps_per_row;
-        const int j = 64 * sq + lane;
-        const int hit = (j < g.c) && (mz[(int64_t)l * g.c + j] >= tz);
-        const unsigned long long b = __ballot(hit);
-        if (lane < 2) {
-            const uint32_t bits = (uint32_t)(lane ? (b >> 32) : b);
-            iz[l * g.izw + 2 * sq + lane] = bits;
-            if (IzOut && band == 0) IzOut[(t * g.k + l) * (int64_t)g.izw + 2 * sq + lane] = bits;
+    const int zsteps = g.k * steps_per_row;
+    constexpr int ZB = 8;
+    for (int st0 = wave; st0 < zsteps; st0 += ZB * kEvalWaves) {
+        float v[ZB];
+        bool ok[ZB];
+#pragma unroll
+        for (int q = 0; q < ZB; ++q) {
+            const int st = st0 + q * kEvalWaves;
+            const int l = st / steps_per_row, sq = st - l * steps_per_row;
+            const int j = 64 * sq + lane;
+            ok[q] = (st < zsteps) && (j < g.c);
+            v[q] = ok[q] ? mz[(int64_t)l * g.c + j] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < ZB; ++q) {
+            const int st = st0 + q * kEvalWaves;
+            if (st < zsteps) { // uniform over the wavefront
+                const int l = st / steps_per_row, sq = st - l * steps_per_row;
+                const unsigned long long b = __ballot(ok[q] && v[q] >= tz);
+                if (lane < 2) {
+                    const uint32_t bits = (uint32_t)(lane ? (b >> 32) : b);
+                    iz[l * g.izw + 2 * sq + lane] = bits;
+                    if (IzOut && band == 0) IzOut[(t * g.k + l) * (int64_t)g.izw + 2 * sq + lane] = bits;
+                }
+            }
         }
     }
+    // I_p: one lane per (row, 32-bit word); its up to 32 entries are read eight at a time
     const float *mp = Mp + (t * (int64_t)g.r + row_lo) * g.k;
     for (int idx = tid; idx < nrows * g.ipw; idx += kEvalThreads) {
         const int i = idx / g.ipw, wq = idx - i * g.ipw; // row of the band
         uint32_t bits = 0u;
         const int l0 = 32 * wq;
-        for (int b = 0; b < 32; ++b)
-            if (l0 + b < g.k && mp[(int64_t)i * g.k + l0 + b] >= tp) bits |= 1u << b;
+        const float *mrow = mp + (int64_t)i * g.k;
+        for (int b0 = 0; b0 < 32 && l0 + b0 < g.k; b0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const int l = l0 + b0 + b;
+                v[b] = mrow[l < g.k ? l : g.k - 1]; // clamped: always a valid address
+            }
+#pragma unroll
+            for (int b = 0; b < 8; ++b)
+                if (l0 + b0 + b < g.k && v[b] >= tp) bits |= 1u << (b0 + b);
+        }
         ip[idx] = bits;
         if (IpOut) IpOut[(t * g.r + row_lo + i) * (int64_t)g.ipw + wq] = bits;
     }
