@@ -8,9 +8,15 @@
  *
  * Conventions (one byte per bit, row-major everywhere):
  *   W     m x n      weights (already rounded to the storage dtype, widened to double)
- *   Ip01  [T][r][k]  left binary factor of every tile,  T = (m/r)*(n/c)
+ *   Ip01  [T][r][k]  left binary factor of every tile,  T = ceil(m/r)*ceil(n/c)
  *   Iz01  [T][k][c]  right binary factor of every tile
- *   tile t = ti*(n/c) + tj covers rows ti*r .. ti*r+r-1, columns tj*c .. tj*c+c-1
+ *   tile t = ti*ceil(n/c) + tj covers rows ti*r .. ti*r+r-1, columns tj*c .. tj*c+c-1,
+ *   cut off at the matrix edge: a tile of the last tile row / column that sticks out keeps
+ *   its full-size factors and uses only their first m - ti*r rows (of I_p) and first
+ *   n - tj*c columns (of I_z).  The paper's tilings all divide (Sec. 3.1); this is the
+ *   builder's reading for the ones that do not.
+ *   tile_rank [T] (optional): tile t uses only the first tile_rank[t] <= k columns of its
+ *   I_p and rows of its I_z ("each submatrix can choose a different rank", Sec. 3.2).
  *   M     m x n      decoded mask, 1 = weight kept, 0 = weight pruned (Sec. 2, Eq. 2)
  *   X     n x N,  Y  m x N
  *
@@ -19,6 +25,9 @@
  * formulation, closed forms of Table 1 / Table 3, the density law of Eq. 7.
  * The LSTM recurrence and the CSR size formula (oracle/lstm.py, csr_bits) are
  * the builder's own definitions: parity unpinned.
+ * Edge tiles and per-tile ranks (tests/test_oracle_general.py): brute force from the set
+ * definition, the crop of the zero-padded matrix's decode, tile-by-tile decodes at each
+ * tile's own rank, and the closed form k (ceil(n/c) m + ceil(m/r) n) of the size.
  * Candidate evaluation of Algorithm 1 (threshold, decode, S_a, Cost): pinned by the
  * printed example (Eq. 4 with T_p = 0.5, T_z = 0.6 gives Eq. 5 and Eq. 6; its two
  * mismatches are kept weights, so Cost = 0), by an independent array formulation, by
@@ -29,22 +38,23 @@
 #include <stdint.h>
 
 /* Eq. 3, applied independently to every tile (Sec. 3.1):
- * (I_a)_{i,j} = OR_{l=1..k} (I_p)_{i,l} AND (I_z)_{l,j}. */
-int lrbi_oracle_decode(int64_t m, int64_t n, int64_t r, int64_t c, int64_t k,
-                       const uint8_t *Ip01, const uint8_t *Iz01, uint8_t *M)
+ * (I_a)_{i,j} = OR_{l=1..k_t} (I_p)_{i,l} AND (I_z)_{l,j}, k_t = tile_rank[t] (k when tile_rank is NULL). */
+int lrbi_oracle_decode_ranked(int64_t m, int64_t n, int64_t r, int64_t c, int64_t k, const int32_t *tile_rank,
+                              const uint8_t *Ip01, const uint8_t *Iz01, uint8_t *M)
 {
     if (m <= 0 || n <= 0 || r <= 0 || c <= 0 || k <= 0) return -1;
-    if (m % r != 0 || n % c != 0) return -2;
-    const int64_t tile_rows = m / r, tile_cols = n / c;
+    const int64_t tile_rows = (m + r - 1) / r, tile_cols = (n + c - 1) / c;
     for (int64_t ti = 0; ti < tile_rows; ++ti) {
         for (int64_t tj = 0; tj < tile_cols; ++tj) {
             const int64_t t = ti * tile_cols + tj;
             const uint8_t *Ip = Ip01 + t * r * k;   /* r x k */
             const uint8_t *Iz = Iz01 + t * k * c;   /* k x c */
-            for (int64_t i = 0; i < r; ++i) {
-                for (int64_t j = 0; j < c; ++j) {
+            const int64_t kt = tile_rank ? tile_rank[t] : k;
+            if (kt < 0 || kt > k) return -3;
+            for (int64_t i = 0; i < r && ti * r + i < m; ++i) {
+                for (int64_t j = 0; j < c && tj * c + j < n; ++j) {
                     uint8_t bit = 0;
-                    for (int64_t l = 0; l < k; ++l) {
+                    for (int64_t l = 0; l < kt; ++l) {
                         const uint8_t a = Ip[i * k + l] != 0;
                         const uint8_t b = Iz[l * c + j] != 0;
                         bit = bit | (a & b);
@@ -55,6 +65,12 @@ int lrbi_oracle_decode(int64_t m, int64_t n, int64_t r, int64_t c, int64_t k,
         }
     }
     return 0;
+}
+
+int lrbi_oracle_decode(int64_t m, int64_t n, int64_t r, int64_t c, int64_t k,
+                       const uint8_t *Ip01, const uint8_t *Iz01, uint8_t *M)
+{
+    return lrbi_oracle_decode_ranked(m, n, r, c, k, NULL, Ip01, Iz01, M);
 }
 
 /* Masked layer product (Sec. 2: the mask is a "binary masking layer" on W):
@@ -84,13 +100,27 @@ int lrbi_oracle_masked_gemm(int64_t m, int64_t n, int64_t N,
 
 /* Index size of the factor pair: k(m+n) bits for one matrix (Sec. 2.2, the
  * compression ratio mn/(k(m+n))); with tiling every tile stores its own
- * r x k and k x c factors (Sec. 3.1), so tiles * k * (r + c) bits. */
-uint64_t lrbi_oracle_index_bits(int64_t m, int64_t n, int64_t r, int64_t c, int64_t k)
+ * r_t x k_t and k_t x c_t factors (Sec. 3.1), r_t x c_t the part of the tile inside
+ * the matrix and k_t its rank: the sum over tiles of k_t (r_t + c_t) bits. */
+uint64_t lrbi_oracle_index_bits_ranked(int64_t m, int64_t n, int64_t r, int64_t c, int64_t k, const int32_t *tile_rank)
 {
     if (m <= 0 || n <= 0 || r <= 0 || c <= 0 || k <= 0) return 0;
-    if (m % r != 0 || n % c != 0) return 0;
-    const uint64_t tiles = (uint64_t)(m / r) * (uint64_t)(n / c);
-    return tiles * (uint64_t)k * (uint64_t)(r + c);
+    const int64_t tile_rows = (m + r - 1) / r, tile_cols = (n + c - 1) / c;
+    uint64_t bits = 0;
+    for (int64_t ti = 0; ti < tile_rows; ++ti) {
+        for (int64_t tj = 0; tj < tile_cols; ++tj) {
+            const int64_t rt = (m - ti * r < r) ? m - ti * r : r;
+            const int64_t ct = (n - tj * c < c) ? n - tj * c : c;
+            const int64_t kt = tile_rank ? tile_rank[ti * tile_cols + tj] : k;
+            bits += (uint64_t)kt * (uint64_t)(rt + ct);
+        }
+    }
+    return bits;
+}
+
+uint64_t lrbi_oracle_index_bits(int64_t m, int64_t n, int64_t r, int64_t c, int64_t k)
+{
+    return lrbi_oracle_index_bits_ranked(m, n, r, c, k, NULL);
 }
 
 /* The "binary" format of Fig. 1 / Table 1: one bit per weight. */
@@ -138,21 +168,21 @@ int lrbi_oracle_threshold(int64_t T, int64_t r, int64_t c, int64_t k, const floa
 
 /* Algorithm 1, what is measured for one candidate pair of thresholds (Sec. 2.2), per tile:
  *   kept[t] = number of ones of I_a in the tile (S_a = 1 - kept / (r c)),
- *   cost[t] = sum of |W_{i,j}| over the tile's entries with I_{i,j} = 1 and (I_a)_{i,j} = 0,
+ *   cost[t] = sum of |W_{i,j}| over the tile's entries with I_{i,j} = 1 and (I_a)_{i,j} = 0
+ *   (the part of an edge tile inside the matrix),
  * where I is the magnitude-pruning mask I_{i,j} = 1 iff |W_{i,j}| >= w_threshold (Eq. 1 -> Eq. 2)
  * and I_a (M here) the decoded mask of the candidate factors.  Sums in double, row-major order. */
 int lrbi_oracle_candidate_cost(int64_t m, int64_t n, int64_t r, int64_t c, const double *W, double w_threshold,
                                const uint8_t *M, uint64_t *kept, double *cost)
 {
     if (m <= 0 || n <= 0 || r <= 0 || c <= 0) return -1;
-    if (m % r != 0 || n % c != 0) return -2;
-    const int64_t tile_cols = n / c;
-    for (int64_t ti = 0; ti < m / r; ++ti) {
+    const int64_t tile_cols = (n + c - 1) / c;
+    for (int64_t ti = 0; ti < (m + r - 1) / r; ++ti) {
         for (int64_t tj = 0; tj < tile_cols; ++tj) {
             uint64_t ones = 0;
             double sum = 0.0;
-            for (int64_t i = 0; i < r; ++i) {
-                for (int64_t j = 0; j < c; ++j) {
+            for (int64_t i = 0; i < r && ti * r + i < m; ++i) {
+                for (int64_t j = 0; j < c && tj * c + j < n; ++j) {
                     const int64_t at = (ti * r + i) * n + (tj * c + j);
                     const double mag = W[at] < 0.0 ? -W[at] : W[at];
                     if (M[at]) ones += 1;

@@ -42,6 +42,10 @@ def _load():
         i64, u64, p = ctypes.c_int64, ctypes.c_uint64, ctypes.c_void_p
         lib.lrbi_oracle_decode.argtypes = [i64] * 5 + [p, p, p]
         lib.lrbi_oracle_decode.restype = ctypes.c_int
+        lib.lrbi_oracle_decode_ranked.argtypes = [i64] * 5 + [p, p, p, p]
+        lib.lrbi_oracle_decode_ranked.restype = ctypes.c_int
+        lib.lrbi_oracle_index_bits_ranked.argtypes = [i64] * 5 + [p]
+        lib.lrbi_oracle_index_bits_ranked.restype = u64
         lib.lrbi_oracle_masked_gemm.argtypes = [i64] * 3 + [p, p, p, p, ctypes.c_int]
         lib.lrbi_oracle_masked_gemm.restype = ctypes.c_int
         lib.lrbi_oracle_index_bits.argtypes = [i64] * 5
@@ -64,19 +68,28 @@ def _c(a, dtype):
     return np.ascontiguousarray(a, dtype=dtype)
 
 
-def decode_mask(Ip01, Iz01, m: int, n: int, r: int, c: int, k: int) -> np.ndarray:
-    """Eq. 3 per tile (Sec. 3.1): returns the m x n 0/1 mask, 1 = kept."""
+def num_tiles(m: int, n: int, r: int, c: int) -> int:
+    return (-(-m // r)) * (-(-n // c))
+
+
+def decode_mask(Ip01, Iz01, m: int, n: int, r: int, c: int, k: int, tile_rank=None) -> np.ndarray:
+    """Eq. 3 per tile (Sec. 3.1): returns the m x n 0/1 mask, 1 = kept.  Tiles that stick out of the
+    matrix are cut off at its edge; tile_rank [T] (optional) limits tile t to its first tile_rank[t] ranks."""
     Ip01 = _c(Ip01, np.uint8)
     Iz01 = _c(Iz01, np.uint8)
-    if m % r or n % c:
-        raise ValueError("tiles must divide the matrix")
-    T = (m // r) * (n // c)
+    T = num_tiles(m, n, r, c)
     if Ip01.shape != (T, r, k) or Iz01.shape != (T, k, c):
         raise ValueError("factor shapes %s %s do not match T=%d r=%d c=%d k=%d"
                          % (Ip01.shape, Iz01.shape, T, r, c, k))
+    rank_ptr = None
+    if tile_rank is not None:
+        tile_rank = _c(tile_rank, np.int32)
+        if tile_rank.shape != (T,):
+            raise ValueError("tile_rank must have one entry per tile")
+        rank_ptr = tile_rank.ctypes.data
     M = np.empty((m, n), dtype=np.uint8)
-    rc = _load().lrbi_oracle_decode(m, n, r, c, k, Ip01.ctypes.data, Iz01.ctypes.data,
-                                    M.ctypes.data)
+    rc = _load().lrbi_oracle_decode_ranked(m, n, r, c, k, rank_ptr, Ip01.ctypes.data, Iz01.ctypes.data,
+                                           M.ctypes.data)
     if rc != 0:
         raise ValueError("lrbi_oracle_decode failed: %d" % rc)
     return M
@@ -109,9 +122,9 @@ def candidate_cost(W, w_threshold: float, M, r: int, c: int):
     W = _c(W, np.float64)
     M = _c(M, np.uint8)
     m, n = W.shape
-    if M.shape != (m, n) or m % r or n % c:
+    if M.shape != (m, n):
         raise ValueError("shapes do not match")
-    T = (m // r) * (n // c)
+    T = num_tiles(m, n, r, c)
     kept = np.empty(T, dtype=np.uint64)
     cost = np.empty(T, dtype=np.float64)
     rc = _load().lrbi_oracle_candidate_cost(m, n, r, c, W.ctypes.data, float(w_threshold), M.ctypes.data,
@@ -140,9 +153,16 @@ def masked_gemm(W, M, X, threads: int = 1) -> np.ndarray:
     return Y
 
 
-def index_bits(m: int, n: int, r: int, c: int, k: int) -> int:
-    """tiles * k * (r + c): Sec. 2.2's k(m+n) applied to every tile of Sec. 3.1."""
-    v = int(_load().lrbi_oracle_index_bits(m, n, r, c, k))
+def index_bits(m: int, n: int, r: int, c: int, k: int, tile_rank=None) -> int:
+    """Sum over tiles of k_t (r_t + c_t): Sec. 2.2's k(m+n) applied to every tile of Sec. 3.1
+    (tiles * k * (r + c) when the tiles divide the matrix and share one rank)."""
+    rank_ptr = None
+    if tile_rank is not None:
+        tile_rank = _c(tile_rank, np.int32)
+        if tile_rank.shape != (num_tiles(m, n, r, c),):
+            raise ValueError("tile_rank must have one entry per tile")
+        rank_ptr = tile_rank.ctypes.data
+    v = int(_load().lrbi_oracle_index_bits_ranked(m, n, r, c, k, rank_ptr))
     if v == 0:
         raise ValueError("invalid shape")
     return v

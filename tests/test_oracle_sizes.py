@@ -58,4 +58,8 @@ def test_csr_bits_builder_formula():
 
 def test_invalid_shapes():
     with pytest.raises(ValueError):
-        orc.index_bits(10, 10, 3, 5, 2)
+        orc.index_bits(10, 10, 0, 5, 2)
+    with pytest.raises(ValueError):
+        orc.index_bits(10, 10, 5, 5, 0)
+    # tiles that do not divide the matrix are cut off at its edge (sizes in tests/test_oracle_general.py)
+    assert orc.index_bits(10, 10, 3, 5, 2) == 2 * (2 * 10 + 4 * 10)
