@@ -25,10 +25,20 @@
  *     and the library trusts them.
  *
  * Logical layout
- *   Tiles are numbered row-major: t = ti * (n / c) + tj, T = (m / r) * (n / c).
+ *   Tiles are numbered row-major: t = ti * ceil(n / c) + tj, T = ceil(m / r) * ceil(n / c).
  *   Mask bit (i, j) of W belongs to tile (i / r, j / c) at (i mod r, j mod c).
- *   Every tile has the same rank k (Sec. 3.1).  r must divide m and c must
- *   divide n.
+ *   Every tile stores factors of the same rank k (Sec. 3.1).
+ *   Edge tiles: when r does not divide m (c does not divide n) the last tile row
+ *   (column) is cut off at the matrix edge.  Such a tile keeps full-size factors
+ *   in the layouts below and only their first m - ti r rows of I_p and first
+ *   n - tj c columns of I_z are used; the kernels ignore the rest, and
+ *   lrbi_pack_factors / lrbi_threshold_eval / lrbi_search_thresholds write it as
+ *   zero.  (The paper's tilings all divide; this is the library's reading.)  The
+ *   tuned kernels need dividing tiles: shapes with edge tiles run on the general
+ *   kernels, with the same results.
+ *   Per-tile rank (Sec. 3.2: every submatrix may choose its own rank): tile t of rank
+ *   k_t <= k has zero columns l >= k_t in I_p and zero rows l >= k_t in I_z;
+ *   lrbi_pack_factors_ranked writes them so, lrbi_index_bits_ranked counts only k_t.
  *
  * Packed layouts (defined as byte images, little-endian bit order: bit b of a
  * row sits in byte b >> 3 at position b & 7)
@@ -78,8 +88,8 @@ typedef enum lrbi_dtype { LRBI_F32 = 0, LRBI_F16 = 1, LRBI_BF16 = 2 } lrbi_dtype
 typedef enum lrbi_status {
     LRBI_OK = 0,
     LRBI_ERR_NULL = -1,      /* a required pointer is NULL                       */
-    LRBI_ERR_SHAPE = -2,     /* non-positive size, r does not divide m, c not n  */
-    LRBI_ERR_RANK = -3,      /* k outside 1 .. LRBI_MAX_RANK                     */
+    LRBI_ERR_SHAPE = -2,     /* non-positive size, or beyond an entry point's limit */
+    LRBI_ERR_RANK = -3,      /* k outside 1 .. LRBI_MAX_RANK, tile rank outside 0 .. k */
     LRBI_ERR_DTYPE = -4,     /* unknown dtype, or dtype not served by forced path */
     LRBI_ERR_PITCH = -5,     /* pitch / leading dimension too small or misaligned */
     LRBI_ERR_ALIGN = -6,     /* a pointer is not aligned as stated               */
@@ -95,12 +105,17 @@ const char *lrbi_strerror(int status);
  * Index size accounting (Sec. 2.2: compression ratio mn / (k(m+n)); Sec. 3.1:
  * every tile is factorised on its own with the same rank; Tables 1 and 3).
  * Host only.  Any out pointer may be NULL.
- *   lrbi_bits   = T * k * (r + c)      bits of the factor pair of all tiles
+ *   lrbi_bits   = k * (ceil(n / c) * m + ceil(m / r) * n): bits of the factor pair of all
+ *                 tiles, edge tiles counted with the rows / columns they use
+ *                 (= T * k * (r + c) when the tiles divide the matrix)
  *   dense_bits  = m * n                bits of the plain binary mask
  *   packed_ip_bytes / packed_iz_bytes  sizes of the packed factor buffers above
  */
 int lrbi_index_bits(const lrbi_desc *desc, uint64_t *lrbi_bits, uint64_t *dense_bits,
                     uint64_t *packed_ip_bytes, uint64_t *packed_iz_bytes);
+
+/* The same with a rank per tile (hTileRank [T], 0 <= k_t <= k): sum over tiles of k_t (r_t + c_t). */
+int lrbi_index_bits_ranked(const lrbi_desc *desc, const int32_t *hTileRank, uint64_t *lrbi_bits);
 
 /*
  * CSR index size under this library's stated accounting (the paper compares
@@ -113,10 +128,19 @@ int lrbi_csr_bits(uint64_t nnz, int64_t m, int32_t idx_bits, int32_t ptr_bits, u
  * Pack factors given one byte per bit into the packed layouts (host only).
  *   hIp01 [T][r][k], hIz01 [T][k][c]: any non-zero byte is a set bit.
  *   hIp_packed: packed_ip_bytes, 4-byte aligned.  hIz_packed: packed_iz_bytes,
- *   8-byte aligned.  Both are fully overwritten (pad bits zero).
+ *   8-byte aligned.  Both are fully overwritten (pad bits zero; also zero: what a
+ *   cut-off edge tile leaves outside the matrix).
  */
 int lrbi_pack_factors(const lrbi_desc *desc, const uint8_t *hIp01, const uint8_t *hIz01,
                       void *hIp_packed, void *hIz_packed);
+
+/*
+ * The same for tiles of different ranks (Sec. 3.2): hTileRank [T], 0 <= k_t <= k.  The inputs
+ * keep the uniform shapes [T][r][k] and [T][k][c]; ranks l >= k_t of tile t are not read and
+ * are packed as zero, so every entry point sees a tile of rank k_t.
+ */
+int lrbi_pack_factors_ranked(const lrbi_desc *desc, const int32_t *hTileRank, const uint8_t *hIp01,
+                             const uint8_t *hIz01, void *hIp_packed, void *hIz_packed);
 
 /*
  * Unpack a packed mask (host only): hM01 [m][n] receives 0 / 1 bytes.

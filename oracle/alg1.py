@@ -24,6 +24,8 @@ Readings where the paper is silent (the same ones as the library's header states
     candidate beats an ineligible one; two eligible ones compare by cost (first wins ties); two
     ineligible ones by distance to the target (first wins ties).
   * target ones = round((1 - S) r c); all sparsity comparisons are made on these integers.
+  * a tile cut off at the matrix edge is searched as the smaller tile it is: its target, its quantiles and
+    its cost use only the part inside the matrix.
 Pins: tests/test_oracle_search.py (the printed example is recovered: S_p = 0.5 finds Eq. 5 and
 Eq. 6 with cost 0; planted two-level factors are recovered exactly; the result is always one of
 the visited candidates and re-evaluates to the reported numbers).
@@ -59,17 +61,24 @@ def search_thresholds(W, w_threshold, Mp, Mz, r, c, S, sp_values, steps, toleran
     Mz = np.asarray(Mz, dtype=np.float32)
     m, n = W.shape
     T, _, k = Mp.shape
-    tile_cols = n // c
-    target = int(math.floor((1.0 - S) * r * c + 0.5))
+    tile_cols = -(-n // c)
+    if T != -(-m // r) * tile_cols:
+        raise ValueError("one pair of factors per tile")
     out_tp = np.zeros(T, np.float32)
     out_tz = np.zeros(T, np.float32)
     out_kept = np.zeros(T, np.uint64)
     out_cost = np.zeros(T, np.float64)
     for t in range(T):
         ti, tj = divmod(t, tile_cols)
+        # the tile's part inside the matrix (an edge tile is cut off): rt x ct; only the factor entries that
+        # belong to it take part, in the quantiles as well
         Wt = W[ti * r:(ti + 1) * r, tj * c:(tj + 1) * c]
-        sp_sorted = np.sort(Mp[t].reshape(-1))
-        sz_sorted = np.sort(Mz[t].reshape(-1))
+        rt, ct = Wt.shape
+        Mp_t = np.ascontiguousarray(Mp[t, :rt, :])[None]
+        Mz_t = np.ascontiguousarray(Mz[t, :, :ct])[None]
+        target = int(math.floor((1.0 - S) * rt * ct + 0.5))
+        sp_sorted = np.sort(Mp_t.reshape(-1))
+        sz_sorted = np.sort(Mz_t.reshape(-1))
         best = None  # (eligible, cost, diff, Tp, Tz, kept)
         for sp in sp_values:
             tp = threshold_at(sp_sorted, quantile_index(sp, sp_sorted.size))
@@ -78,10 +87,9 @@ def search_thresholds(W, w_threshold, Mp, Mz, r, c, S, sp_values, steps, toleran
             rep = None  # (diff, Tz, kept, cost): the probe closest to the target
             for _ in range(steps):
                 tz = threshold_at(sz_sorted, quantile_index(sz, sz_sorted.size))
-                Ip, Iz = orc.threshold_factors(Mp[t:t + 1], Mz[t:t + 1], np.array([tp], np.float32),
-                                               np.array([tz], np.float32))
-                Ia = orc.decode_mask(Ip, Iz, r, c, r, c, k)
-                kept, cost = orc.candidate_cost(Wt, w_threshold, Ia, r, c)
+                Ip, Iz = orc.threshold_factors(Mp_t, Mz_t, np.array([tp], np.float32), np.array([tz], np.float32))
+                Ia = orc.decode_mask(Ip, Iz, rt, ct, rt, ct, k)
+                kept, cost = orc.candidate_cost(Wt, w_threshold, Ia, rt, ct)
                 kept, cost = int(kept[0]), float(cost[0])
                 diff = abs(kept - target)
                 if rep is None or diff < rep[0]:

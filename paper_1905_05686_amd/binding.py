@@ -45,7 +45,7 @@ class Desc(ctypes.Structure):
 
     @property
     def tiles(self) -> int:
-        return (self.m // self.r) * (self.n // self.c)
+        return (-(-self.m // self.r)) * (-(-self.n // self.c))
 
 
 def library_path() -> str:
@@ -69,6 +69,8 @@ def load_library():
     lib.lrbi_index_bits.argtypes = [pd, pu64, pu64, pu64, pu64]
     lib.lrbi_csr_bits.argtypes = [u64, i64, i32, i32, pu64]
     lib.lrbi_pack_factors.argtypes = [pd, vp, vp, vp, vp]
+    lib.lrbi_pack_factors_ranked.argtypes = [pd, vp, vp, vp, vp, vp]
+    lib.lrbi_index_bits_ranked.argtypes = [pd, vp, pu64]
     lib.lrbi_unpack_mask.argtypes = [pd, vp, i64, vp]
     lib.lrbi_decode_mask.argtypes = [pd, vp, vp, vp, i64, vp]
     lib.lrbi_masked_gemm_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
@@ -80,7 +82,8 @@ def load_library():
                                            ctypes.POINTER(ctypes.c_double), i32, i32, i64, vp, vp, vp, vp, vp, vp, vp, u64,
                                            vp]
     lib.lrbi_search_workspace_bytes.argtypes = [pd, pu64]
-    for name in ("lrbi_index_bits", "lrbi_csr_bits", "lrbi_pack_factors", "lrbi_unpack_mask", "lrbi_decode_mask",
+    for name in ("lrbi_index_bits", "lrbi_index_bits_ranked", "lrbi_pack_factors_ranked", "lrbi_csr_bits",
+                 "lrbi_pack_factors", "lrbi_unpack_mask", "lrbi_decode_mask",
                  "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm", "lrbi_threshold_eval",
                  "lrbi_threshold_eval_workspace_bytes", "lrbi_search_thresholds", "lrbi_search_workspace_bytes"):
         getattr(lib, name).restype = ctypes.c_int
@@ -112,9 +115,20 @@ def csr_bits(nnz: int, m: int, idx_bits: int = 16, ptr_bits: int = 32) -> int:
     return out.value
 
 
-def pack_factors(desc: Desc, Ip01: np.ndarray, Iz01: np.ndarray):
-    """lrbi_pack_factors: uint8 0/1 factors [T,r,k], [T,k,c] -> packed host arrays
-    (uint32 [T*r, ceil(k/32)], uint64 [T*k, ceil(c/64)])."""
+def index_bits_ranked(desc: Desc, tile_rank) -> int:
+    """lrbi_index_bits_ranked: factor bits with a rank per tile (int32 [T])."""
+    tile_rank = np.ascontiguousarray(tile_rank, dtype=np.int32)
+    if tile_rank.shape != (desc.tiles,):
+        raise ValueError("tile_rank must have one entry per tile")
+    out = ctypes.c_uint64()
+    _check(load_library().lrbi_index_bits_ranked(ctypes.byref(desc), tile_rank.ctypes.data, ctypes.byref(out)),
+           "lrbi_index_bits_ranked")
+    return out.value
+
+
+def pack_factors(desc: Desc, Ip01: np.ndarray, Iz01: np.ndarray, tile_rank=None):
+    """lrbi_pack_factors / lrbi_pack_factors_ranked: uint8 0/1 factors [T,r,k], [T,k,c] -> packed host arrays
+    (uint32 [T*r, ceil(k/32)], uint64 [T*k, ceil(c/64)]); tile_rank int32 [T] (optional) = rank of every tile."""
     Ip01 = np.ascontiguousarray(Ip01, dtype=np.uint8)
     Iz01 = np.ascontiguousarray(Iz01, dtype=np.uint8)
     T = desc.tiles
@@ -123,6 +137,14 @@ def pack_factors(desc: Desc, Ip01: np.ndarray, Iz01: np.ndarray):
     sizes = index_bits(desc)
     ip = np.empty((T * desc.r, sizes["packed_ip_bytes"] // (4 * T * desc.r)), dtype=np.uint32)
     iz = np.empty((T * desc.k, sizes["packed_iz_bytes"] // (8 * T * desc.k)), dtype=np.uint64)
+    if tile_rank is not None:
+        tile_rank = np.ascontiguousarray(tile_rank, dtype=np.int32)
+        if tile_rank.shape != (T,):
+            raise ValueError("tile_rank must have one entry per tile")
+        _check(load_library().lrbi_pack_factors_ranked(ctypes.byref(desc), tile_rank.ctypes.data, Ip01.ctypes.data,
+                                                       Iz01.ctypes.data, ip.ctypes.data, iz.ctypes.data),
+               "lrbi_pack_factors_ranked")
+        return ip, iz
     _check(load_library().lrbi_pack_factors(ctypes.byref(desc), Ip01.ctypes.data, Iz01.ctypes.data, ip.ctypes.data,
                                             iz.ctypes.data), "lrbi_pack_factors")
     return ip, iz

@@ -80,10 +80,14 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
     // (one slot per workgroup) that a second kernel adds in band order
     const int64_t t = blockIdx.x / bands;
     const int band = (int)(blockIdx.x - t * bands);
-    const int row_lo = band * rows_per_band;
-    const int row_hi = (row_lo + rows_per_band < g.r) ? row_lo + rows_per_band : g.r;
-    const int nrows = row_hi - row_lo;
     const int ti = (int)(t / g.tile_cols), tj = (int)(t - (int64_t)ti * g.tile_cols);
+    // the part of the tile inside the matrix (an edge tile may be cut off): rt x ct
+    const int rt = (int)((g.m - (int64_t)ti * g.r < g.r) ? g.m - (int64_t)ti * g.r : g.r);
+    const int ct = (int)((g.n - (int64_t)tj * g.c < g.c) ? g.n - (int64_t)tj * g.c : g.c);
+    const int row_lo = band * rows_per_band;
+    const int band_hi = (row_lo + rows_per_band < g.r) ? row_lo + rows_per_band : g.r; // rows of the stored factor
+    const int row_hi = (band_hi < rt) ? band_hi : rt;
+    const int nrows = (row_hi > row_lo) ? row_hi - row_lo : 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float tp = Tp[t], tz = Tz[t];
 
@@ -103,7 +107,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
             const int st = st0 + q * kEvalWaves;
             const int l = st / steps_per_row, sq = st - l * steps_per_row;
             const int j = 64 * sq + lane;
-            ok[q] = (st < zsteps) && (j < g.c);
+            ok[q] = (st < zsteps) && (j < ct); // columns a cut-off tile leaves outside the matrix stay 0
             v[q] = ok[q] ? mz[(int64_t)l * g.c + j] : 0.f;
         }
 #pragma unroll
@@ -141,6 +145,10 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
         ip[idx] = bits;
         if (IpOut) IpOut[(t * g.r + row_lo + i) * (int64_t)g.ipw + wq] = bits;
     }
+    // stored rows of I_p that a cut-off tile leaves outside the matrix are written as zero
+    if (IpOut)
+        for (int idx = nrows * g.ipw + tid; idx < (band_hi - row_lo) * g.ipw; idx += kEvalThreads)
+            IpOut[(t * g.r + row_lo) * (int64_t)g.ipw + idx] = 0u;
     __syncthreads();
 
     // ---- 2. the tile as a list of 16-byte pieces (row-major): ones of I_a, and magnitudes kept by
@@ -149,7 +157,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
     double cost = 0.0;
     unsigned long long kept = 0ull;
     const int64_t col0 = (int64_t)tj * g.c;
-    const int P = (g.c + VEC - 1) / VEC;   // pieces per tile row
+    const int P = (ct + VEC - 1) / VEC;    // pieces per row of the tile's part inside the matrix
     const int items = nrows * P;
     const T *wtile = W + ((int64_t)ti * g.r + row_lo) * ldw + col0;
     constexpr int U = 4;
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
             if (id < items) {
                 const int i = id / P, j = (id - i * P) * VEC;
                 const T *wrow = wtile + (int64_t)i * ldw;
-                const int nvalid = (g.c - j < VEC) ? g.c - j : VEC;
+                const int nvalid = (ct - j < VEC) ? ct - j : VEC;
                 const bool vec = w_vec_ok && (nvalid == VEC) && (((col0 + j) % VEC) == 0);
                 if (vec) {
                     const uint4 v = *reinterpret_cast<const uint4 *>(wrow + j);
@@ -323,18 +331,40 @@ struct SearchState {
     int pad;
 };
 
-// Sorts the n values of one tile's factor (ascending, bitonic network over `padded` = 2^j >= n slots, the
-// tail filled with +inf).  One workgroup per tile.  Up to 16384 slots the network runs in on-chip memory and
-// the n sorted values are written to out + tile * stride; beyond that it runs in place in out + tile * stride
-// (stride >= padded), slower, the workgroup's own barriers ordering its global accesses.
-__global__ __launch_bounds__(512) void tile_sort_kernel(const float *__restrict__ in, float *out, int n, int padded,
-                                                        int64_t stride, int on_chip)
+// rows x columns of tile t's part inside the matrix
+__device__ __forceinline__ void tile_extent(const Geom &g, int64_t t, int &rt, int &ct)
+{
+    const int64_t ti = t / g.tile_cols, tj = t - ti * g.tile_cols;
+    rt = (int)((g.m - ti * g.r < g.r) ? g.m - ti * g.r : g.r);
+    ct = (int)((g.n - tj * g.c < g.c) ? g.n - tj * g.c : g.c);
+}
+
+// Sorts the used entries of one tile's factor (ascending, bitonic network over `padded` = 2^j slots, the
+// tail filled with +inf).  which = 0: M_p, the first rt rows of k entries; which = 1: M_z, the first ct
+// entries of each of the k rows (rt x ct = the tile's part inside the matrix).  One workgroup per tile.  Up
+// to 16384 slots the network runs in on-chip memory and the sorted values are written to out + tile *
+// stride; beyond that it runs in place in out + tile * stride (stride >= padded), slower, the workgroup's
+// own barriers ordering its global accesses.
+__global__ __launch_bounds__(512) void tile_sort_kernel(Geom g, int which, const float *__restrict__ in, float *out,
+                                                        int padded, int64_t stride, int on_chip)
 {
     extern __shared__ uint4 lrbi_dyn_smem[];
+    int rt, ct;
+    tile_extent(g, blockIdx.x, rt, ct);
+    const int cols = which ? ct : g.k;           // used entries per stored row
+    const int pitch = which ? g.c : g.k;         // entries per stored row
+    const int n = which ? g.k * ct : rt * g.k;
     float *dst = out + (int64_t)blockIdx.x * stride;
     float *v = on_chip ? reinterpret_cast<float *>(lrbi_dyn_smem) : dst;
-    const float *src = in + (int64_t)blockIdx.x * n;
-    for (int i = threadIdx.x; i < padded; i += 512) v[i] = (i < n) ? src[i] : __builtin_inff();
+    const float *src = in + (int64_t)blockIdx.x * (which ? (int64_t)g.k * g.c : (int64_t)g.r * g.k);
+    for (int i = threadIdx.x; i < padded; i += 512) {
+        float x = __builtin_inff();
+        if (i < n) {
+            const int row = i / cols;
+            x = src[(int64_t)row * pitch + (i - row * cols)];
+        }
+        v[i] = x;
+    }
     __syncthreads();
     for (int size = 2; size <= padded; size <<= 1) {
         for (int stride2 = size >> 1; stride2 > 0; stride2 >>= 1) {
@@ -364,30 +394,34 @@ __device__ __forceinline__ float threshold_at(const float *sorted, int count, do
     return (idx >= count) ? __builtin_inff() : sorted[idx];
 }
 
-__global__ __launch_bounds__(256) void search_begin_kernel(SearchState *__restrict__ st, const float *__restrict__ sortedMp,
-                                                           const float *__restrict__ sortedMz, int np, int nz,
-                                                           int64_t stride_p, int64_t stride_z, int64_t tiles, int idx_p, double sz0, int first,
-                                                           float *__restrict__ Tp, float *__restrict__ Tz)
+__global__ __launch_bounds__(256) void search_begin_kernel(Geom g, SearchState *__restrict__ st,
+                                                           const float *__restrict__ sortedMp,
+                                                           const float *__restrict__ sortedMz, int64_t stride_p,
+                                                           int64_t stride_z, int64_t tiles, double sp, double sz0,
+                                                           int first, float *__restrict__ Tp, float *__restrict__ Tz)
 {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= tiles) return;
+    int rt, ct;
+    tile_extent(g, t, rt, ct);
     SearchState s = st[t];
     if (first) {
         s.best_diff = -1;
         s.best_eligible = 0;
     }
-    s.tp = (idx_p >= np) ? __builtin_inff() : sortedMp[t * stride_p + idx_p];
+    s.tp = threshold_at(sortedMp + t * stride_p, rt * g.k, sp);
     s.lo = 0.0;
     s.hi = 1.0;
     s.sz = sz0;
     s.rep_diff = -1;
     st[t] = s;
     Tp[t] = s.tp;
-    Tz[t] = threshold_at(sortedMz + t * stride_z, nz, sz0);
+    Tz[t] = threshold_at(sortedMz + t * stride_z, g.k * ct, sz0);
 }
 
-__global__ __launch_bounds__(256) void search_step_kernel(SearchState *__restrict__ st, const float *__restrict__ sortedMz,
-                                                          int nz, int64_t stride_z, int64_t tiles, long long target, long long tolerance,
+__global__ __launch_bounds__(256) void search_step_kernel(Geom g, SearchState *__restrict__ st,
+                                                          const float *__restrict__ sortedMz, int64_t stride_z,
+                                                          int64_t tiles, double keep_fraction, long long tolerance,
                                                           int last_step, const unsigned long long *__restrict__ kept,
                                                           const double *__restrict__ cost, float *__restrict__ Tz,
                                                           float *__restrict__ TpBest, float *__restrict__ TzBest,
@@ -396,6 +430,11 @@ __global__ __launch_bounds__(256) void search_step_kernel(SearchState *__restric
 {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= tiles) return;
+    int rt, ct;
+    tile_extent(g, t, rt, ct);
+    // target number of ones of this tile, round((1 - S) rt ct), in plain double arithmetic
+    const long long target =
+        (long long)floor(__dadd_rn(__dmul_rn(__dmul_rn(keep_fraction, (double)rt), (double)ct), 0.5));
     SearchState s = st[t];
     const long long k = (long long)kept[t];
     const long long diff = (k > target) ? k - target : target - k;
@@ -408,7 +447,7 @@ __global__ __launch_bounds__(256) void search_step_kernel(SearchState *__restric
     if (k > target) s.lo = s.sz; // too many ones: I_z must get sparser
     else s.hi = s.sz;
     s.sz = 0.5 * (s.lo + s.hi);
-    Tz[t] = threshold_at(sortedMz + t * stride_z, nz, s.sz);
+    Tz[t] = threshold_at(sortedMz + t * stride_z, g.k * ct, s.sz);
     if (last_step) {
         const int eligible = s.rep_diff <= tolerance;
         bool better;
@@ -485,41 +524,31 @@ int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, flo
         if (hipFuncSetAttribute((const void *)tile_sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kSortOnChip * 4) != hipSuccess)
             return LRBI_ERR_LAUNCH;
-        hipLaunchKernelGGL(tile_sort_kernel, dim3((unsigned)tiles), dim3(512), smem, stream, which ? dMz : dMp,
-                           which ? sortedMz : sortedMp, n, padded, which ? p.stride_z : p.stride_p, on_chip);
+        hipLaunchKernelGGL(tile_sort_kernel, dim3((unsigned)tiles), dim3(512), smem, stream, g, which, which ? dMz : dMp,
+                           which ? sortedMz : sortedMp, padded, which ? p.stride_z : p.stride_p, on_chip);
         LRBI_CHECK_LAUNCH();
     }
     // 2. sweep over S_p, bisection on S_z
-    // products and sums below are rounded one by one (volatile: no fused multiply-add), so that the
-    // indices are the ones plain double arithmetic gives
-    volatile double prod = (1.0 - target_sparsity) * (double)g.r;
-    prod = prod * (double)g.c;
-    prod = prod + 0.5;
-    const long long target = (long long)floor(prod);
     const unsigned sblocks = (unsigned)((tiles + 255) / 256);
     for (int a = 0; a < n_sp; ++a) {
         const double sp = sp_values[a];
-        prod = sp * (double)p.np;
-        prod = prod + 0.5;
-        long long idx_p = (long long)floor(prod);
-        if (idx_p < 0) idx_p = 0;
-        if (idx_p > p.np) idx_p = p.np;
         double sz0 = 0.0;
         if (sp < 1.0) {
             sz0 = (pow(target_sparsity, 1.0 / (double)g.k) - sp) / (1.0 - sp); // Eq. 7 solved for S_z
             if (sz0 < 0.0) sz0 = 0.0;
             if (sz0 > 1.0) sz0 = 1.0;
         }
-        hipLaunchKernelGGL(search_begin_kernel, dim3(sblocks), dim3(256), 0, stream, state, sortedMp, sortedMz, p.np, p.nz,
-                           p.stride_p, p.stride_z, tiles, (int)idx_p, sz0, a == 0 ? 1 : 0, Tp, Tz);
+        hipLaunchKernelGGL(search_begin_kernel, dim3(sblocks), dim3(256), 0, stream, g, state, sortedMp, sortedMz,
+                           p.stride_p, p.stride_z, tiles, sp, sz0, a == 0 ? 1 : 0, Tp, Tz);
         LRBI_CHECK_LAUNCH();
         for (int step = 0; step < steps; ++step) {
             const int rc = launch_threshold_eval(g, dt, dW, ldw, w_threshold, dMp, dMz, Tp, Tz, nullptr, nullptr, kept,
                                                  cost, eval_ws, stream);
             if (rc != LRBI_OK) return rc;
-            hipLaunchKernelGGL(search_step_kernel, dim3(sblocks), dim3(256), 0, stream, state, sortedMz, p.nz, p.stride_z, tiles, target,
-                               (long long)tolerance, step == steps - 1 ? 1 : 0, (const unsigned long long *)kept, cost, Tz,
-                               dTpBest, dTzBest, (unsigned long long *)dKeptBest, dCostBest);
+            hipLaunchKernelGGL(search_step_kernel, dim3(sblocks), dim3(256), 0, stream, g, state, sortedMz, p.stride_z,
+                               tiles, 1.0 - target_sparsity, (long long)tolerance, step == steps - 1 ? 1 : 0,
+                               (const unsigned long long *)kept, cost, Tz, dTpBest, dTzBest,
+                               (unsigned long long *)dKeptBest, dCostBest);
             LRBI_CHECK_LAUNCH();
         }
     }

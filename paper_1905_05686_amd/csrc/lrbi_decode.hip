@@ -633,7 +633,8 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
         LRBI_CHECK_LAUNCH();
         return LRBI_OK;
     };
-    if (flags & LRBI_FLAG_DECODE_GENERIC) return launch_generic();
+    // cut-off edge tiles: only the generic kernel bounds its rows and columns by the matrix
+    if ((flags & LRBI_FLAG_DECODE_GENERIC) || g.ragged) return launch_generic();
 
     int device = 0, cus = 256;
     if (hipGetDevice(&device) == hipSuccess) {

@@ -709,7 +709,10 @@ static const TileDef kTiles[] = {{0, 0, false},    {128, 128, false}, {128, 64, 
                                  {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true}};
 static constexpr int kNumTiles = 11;
 
-static bool panel_ok(const Geom &g, int bm) { return (g.c % 128 == 0) && (g.r % bm == 0) && (g.k <= FAST_MAX_K); }
+static bool panel_ok(const Geom &g, int bm)
+{
+    return (g.c % 128 == 0) && (g.r % bm == 0) && (g.k <= FAST_MAX_K) && !g.ragged;
+}
 
 MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
 {

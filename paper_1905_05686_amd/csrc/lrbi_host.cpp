@@ -10,7 +10,6 @@ int validate_desc(const lrbi_desc *d)
 {
     if (!d) return LRBI_ERR_NULL;
     if (d->m <= 0 || d->n <= 0 || d->r <= 0 || d->c <= 0) return LRBI_ERR_SHAPE;
-    if (d->m % d->r != 0 || d->n % d->c != 0) return LRBI_ERR_SHAPE;
     // columns are indexed with 32-bit integers inside the kernels
     if (d->n > (int64_t)0x7FFFFF00 || d->m > (int64_t)0x7FFFFF00) return LRBI_ERR_SHAPE;
     if (d->k < 1 || d->k > LRBI_MAX_RANK) return LRBI_ERR_RANK;
@@ -30,8 +29,9 @@ Geom make_geom(const lrbi_desc *d)
     g.r = d->r;
     g.c = d->c;
     g.k = d->k;
-    g.tile_cols = (int32_t)(d->n / d->c);
-    g.tile_rows = (int32_t)(d->m / d->r);
+    g.tile_cols = (int32_t)((d->n + d->c - 1) / d->c);
+    g.tile_rows = (int32_t)((d->m + d->r - 1) / d->r);
+    g.ragged = (d->m % d->r != 0 || d->n % d->c != 0) ? 1 : 0;
     g.ipw = (d->k + 31) / 32;
     g.izw = 2 * ((d->c + 63) / 64);
     return g;
@@ -48,7 +48,7 @@ extern "C" const char *lrbi_strerror(int status)
     switch (status) {
     case LRBI_OK: return "ok";
     case LRBI_ERR_NULL: return "a required pointer is NULL";
-    case LRBI_ERR_SHAPE: return "bad shape: sizes must be positive, r must divide m, c must divide n";
+    case LRBI_ERR_SHAPE: return "bad shape: a size is not positive or exceeds a limit of the entry point";
     case LRBI_ERR_RANK: return "rank k outside 1..LRBI_MAX_RANK";
     case LRBI_ERR_DTYPE: return "unknown dtype or dtype not served by the forced kernel path";
     case LRBI_ERR_PITCH: return "pitch or leading dimension too small or misaligned";
@@ -67,7 +67,9 @@ extern "C" int lrbi_index_bits(const lrbi_desc *desc, uint64_t *lrbi_bits, uint6
     if (rc != LRBI_OK) return rc;
     const Geom g = make_geom(desc);
     const uint64_t tiles = (uint64_t)g.tile_rows * (uint64_t)g.tile_cols;
-    if (lrbi_bits) *lrbi_bits = tiles * (uint64_t)g.k * ((uint64_t)g.r + (uint64_t)g.c);
+    // every tile column stores m rows of I_p, every tile row n columns of I_z (edge tiles are cut off)
+    if (lrbi_bits)
+        *lrbi_bits = (uint64_t)g.k * ((uint64_t)g.tile_cols * (uint64_t)g.m + (uint64_t)g.tile_rows * (uint64_t)g.n);
     if (dense_bits) *dense_bits = (uint64_t)g.m * (uint64_t)g.n;
     if (packed_ip_bytes) *packed_ip_bytes = tiles * (uint64_t)g.r * (uint64_t)g.ipw * 4u;
     if (packed_iz_bytes) *packed_iz_bytes = tiles * (uint64_t)g.k * (uint64_t)g.izw * 4u;
@@ -82,8 +84,10 @@ extern "C" int lrbi_csr_bits(uint64_t nnz, int64_t m, int32_t idx_bits, int32_t 
     return LRBI_OK;
 }
 
-extern "C" int lrbi_pack_factors(const lrbi_desc *desc, const uint8_t *hIp01, const uint8_t *hIz01,
-                                 void *hIp_packed, void *hIz_packed)
+// Packs 0/1 factors; bits that no mask entry uses are written as zero: ranks at or beyond a tile's
+// own rank, rows of I_p and columns of I_z that a cut-off edge tile leaves outside the matrix.
+static int pack_impl(const lrbi_desc *desc, const int32_t *hTileRank, const uint8_t *hIp01, const uint8_t *hIz01,
+                     void *hIp_packed, void *hIz_packed)
 {
     const int rc = validate_desc(desc);
     if (rc != LRBI_OK) return rc;
@@ -91,25 +95,65 @@ extern "C" int lrbi_pack_factors(const lrbi_desc *desc, const uint8_t *hIp01, co
     if (!aligned_to(hIp_packed, 4) || !aligned_to(hIz_packed, 8)) return LRBI_ERR_ALIGN;
     const Geom g = make_geom(desc);
     const int64_t tiles = (int64_t)g.tile_rows * g.tile_cols;
+    if (hTileRank)
+        for (int64_t t = 0; t < tiles; ++t)
+            if (hTileRank[t] < 0 || hTileRank[t] > g.k) return LRBI_ERR_RANK;
     uint8_t *ip = (uint8_t *)hIp_packed;
     uint8_t *iz = (uint8_t *)hIz_packed;
     const int64_t ip_row = (int64_t)g.ipw * 4, iz_row = (int64_t)g.izw * 4;
     memset(ip, 0, (size_t)(tiles * g.r * ip_row));
     memset(iz, 0, (size_t)(tiles * g.k * iz_row));
     for (int64_t t = 0; t < tiles; ++t) {
-        for (int64_t i = 0; i < g.r; ++i) {
+        const int64_t ti = t / g.tile_cols, tj = t - ti * g.tile_cols;
+        const int64_t rt = (g.m - ti * g.r < g.r) ? g.m - ti * g.r : g.r;
+        const int64_t ct = (g.n - tj * g.c < g.c) ? g.n - tj * g.c : g.c;
+        const int kt = hTileRank ? hTileRank[t] : g.k;
+        for (int64_t i = 0; i < rt; ++i) {
             const uint8_t *src = hIp01 + (t * g.r + i) * g.k;
             uint8_t *dst = ip + (t * g.r + i) * ip_row;
-            for (int l = 0; l < g.k; ++l)
+            for (int l = 0; l < kt; ++l)
                 if (src[l]) dst[l >> 3] |= (uint8_t)(1u << (l & 7));
         }
-        for (int64_t l = 0; l < g.k; ++l) {
+        for (int64_t l = 0; l < kt; ++l) {
             const uint8_t *src = hIz01 + (t * g.k + l) * g.c;
             uint8_t *dst = iz + (t * g.k + l) * iz_row;
-            for (int j = 0; j < g.c; ++j)
+            for (int j = 0; j < ct; ++j)
                 if (src[j]) dst[j >> 3] |= (uint8_t)(1u << (j & 7));
         }
     }
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_pack_factors(const lrbi_desc *desc, const uint8_t *hIp01, const uint8_t *hIz01,
+                                 void *hIp_packed, void *hIz_packed)
+{
+    return pack_impl(desc, nullptr, hIp01, hIz01, hIp_packed, hIz_packed);
+}
+
+extern "C" int lrbi_pack_factors_ranked(const lrbi_desc *desc, const int32_t *hTileRank, const uint8_t *hIp01,
+                                        const uint8_t *hIz01, void *hIp_packed, void *hIz_packed)
+{
+    if (!hTileRank) return LRBI_ERR_NULL;
+    return pack_impl(desc, hTileRank, hIp01, hIz01, hIp_packed, hIz_packed);
+}
+
+extern "C" int lrbi_index_bits_ranked(const lrbi_desc *desc, const int32_t *hTileRank, uint64_t *lrbi_bits)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!hTileRank || !lrbi_bits) return LRBI_ERR_NULL;
+    const Geom g = make_geom(desc);
+    uint64_t bits = 0;
+    for (int64_t ti = 0; ti < g.tile_rows; ++ti) {
+        const uint64_t rt = (uint64_t)((g.m - ti * g.r < g.r) ? g.m - ti * g.r : g.r);
+        for (int64_t tj = 0; tj < g.tile_cols; ++tj) {
+            const uint64_t ct = (uint64_t)((g.n - tj * g.c < g.c) ? g.n - tj * g.c : g.c);
+            const int32_t kt = hTileRank[ti * g.tile_cols + tj];
+            if (kt < 0 || kt > g.k) return LRBI_ERR_RANK;
+            bits += (uint64_t)kt * (rt + ct);
+        }
+    }
+    *lrbi_bits = bits;
     return LRBI_OK;
 }
 

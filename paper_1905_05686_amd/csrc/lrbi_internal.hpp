@@ -13,8 +13,9 @@ namespace lrbi {
 struct Geom {
     int64_t m, n;      // rows / columns of W
     int32_t r, c, k;   // tile rows, tile columns, rank
-    int32_t tile_cols; // n / c
-    int32_t tile_rows; // m / r
+    int32_t tile_cols; // ceil(n / c)
+    int32_t tile_rows; // ceil(m / r)
+    int32_t ragged;    // r does not divide m or c does not divide n: the last tile row / column is cut off
     int32_t ipw;       // 32-bit words per packed I_p row  = ceil(k / 32)
     int32_t izw;       // 32-bit words per packed I_z row  = 2 * ceil(c / 64)
 };
@@ -133,6 +134,8 @@ __device__ __forceinline__ uint32_t decode_word(const Geom &g, const uint32_t *_
         }
         acc |= v & valid;
     }
+    // a tile cut off at the right edge: whatever its I_z holds beyond column n stays out
+    if (j1 - j0 < 32) acc &= bit_range(0, (int)(j1 - j0));
     return acc;
 }
 #endif // __HIPCC__

@@ -49,7 +49,7 @@ def test_index_bits_matches_oracle(name):
 
 def test_desc_validation():
     bad = [
-        (lrbi.Desc(0, 8, 1, 1, 1), -2), (lrbi.Desc(8, 8, 3, 4, 1), -2), (lrbi.Desc(8, 8, 4, 3, 1), -2),
+        (lrbi.Desc(0, 8, 1, 1, 1), -2), (lrbi.Desc(8, 8, 0, 4, 1), -2), (lrbi.Desc(8, 8, 4, -3, 1), -2),
         (lrbi.Desc(8, 8, 4, 4, 0), -3), (lrbi.Desc(8, 8, 4, 4, 257), -3), (lrbi.Desc(8, 8, 4, 4, 1, 1 << 30), -9),
         (lrbi.Desc(8, 8, 4, 4, 1, 3), -9),
     ]
@@ -57,6 +57,46 @@ def test_desc_validation():
         with pytest.raises(lrbi.LrbiError) as e:
             lrbi.index_bits(d)
         assert e.value.status == code
+    # tiles need not divide the matrix: the last tile row / column is cut off at the edge
+    assert lrbi.Desc(8, 8, 3, 4, 1).tiles == 6 and lrbi.index_bits(lrbi.Desc(8, 8, 3, 4, 1))["lrbi_bits"] == 2 * 8 + 3 * 8
+
+
+def test_edge_tiles_and_ranks_host_side():
+    """Sizes and packing for cut-off edge tiles and per-tile ranks against the oracle / numpy."""
+    rng = np.random.default_rng(5)
+    for (m, n, r, c, k) in [(70, 90, 32, 40, 5), (577, 1000, 576, 512, 145), (7, 9, 3, 4, 2)]:
+        d = lrbi.Desc(m, n, r, c, k)
+        T = d.tiles
+        assert T == orc.num_tiles(m, n, r, c)
+        got = lrbi.index_bits(d)
+        assert got["lrbi_bits"] == orc.index_bits(m, n, r, c, k)
+        assert got["packed_ip_bytes"] == T * r * 4 * ((k + 31) // 32)
+        rank = rng.integers(0, k + 1, size=T).astype(np.int32)
+        assert lrbi.index_bits_ranked(d, rank) == orc.index_bits(m, n, r, c, k, tile_rank=rank)
+        Ip = (rng.random((T, r, k)) < 0.5).astype(np.uint8)
+        Iz = (rng.random((T, k, c)) < 0.5).astype(np.uint8)
+        ip, iz = lrbi.pack_factors(d, Ip, Iz, tile_rank=rank)
+        # expected: the same arrays with everything unused cleared, packed by numpy
+        Ipc, Izc = Ip.copy(), Iz.copy()
+        tile_cols = -(-n // c)
+        for t in range(T):
+            ti, tj = divmod(t, tile_cols)
+            Ipc[t, :, rank[t]:] = 0
+            Izc[t, rank[t]:, :] = 0
+            Ipc[t, max(0, min(r, m - ti * r)):, :] = 0
+            Izc[t, :, max(0, min(c, n - tj * c)):] = 0
+        ref_p = np.packbits(Ipc.reshape(T * r, k), axis=1, bitorder="little")
+        ref_z = np.packbits(Izc.reshape(T * k, c), axis=1, bitorder="little")
+        ipb, izb = ip.view(np.uint8).reshape(T * r, -1), iz.view(np.uint8).reshape(T * k, -1)
+        assert np.array_equal(ipb[:, :ref_p.shape[1]], ref_p) and not ipb[:, ref_p.shape[1]:].any()
+        assert np.array_equal(izb[:, :ref_z.shape[1]], ref_z) and not izb[:, ref_z.shape[1]:].any()
+    d = lrbi.Desc(8, 8, 4, 4, 3)
+    with pytest.raises(lrbi.LrbiError) as e:
+        lrbi.index_bits_ranked(d, np.array([1, 2, 3, 4], np.int32))
+    assert e.value.status == -3
+    with pytest.raises(lrbi.LrbiError) as e:
+        lrbi.pack_factors(d, np.zeros((4, 4, 3), np.uint8), np.zeros((4, 3, 4), np.uint8), tile_rank=[0, -1, 0, 0])
+    assert e.value.status == -3
 
 
 @pytest.mark.parametrize("r,c,k", [(5, 5, 2), (100, 100, 4), (3, 70, 33), (2, 130, 64), (4, 9, 100)])

@@ -102,3 +102,22 @@ def test_brute_force_over_all_thresholds_on_a_tiny_tile():
     assert cands[(float(Tp[0]), float(Tz[0]))] == (int(kept[0]), float(cost[0]))
     best_diff = min(abs(v[0] - target) for v in cands.values())
     assert abs(int(kept[0]) - target) >= best_diff   # cannot be closer than the best reachable
+
+
+def test_cut_off_tiles_are_searched_as_the_smaller_tiles_they_are():
+    """A matrix whose last tile row and column stick out: every tile's result equals the search on that tile alone,
+    as a one-tile matrix of its cut-off shape with the matching part of the factors (a case the pins above cover)."""
+    rng = np.random.default_rng(21)
+    m, n, r, c, k = 11, 14, 4, 5, 3
+    T = 3 * 3
+    W = rng.normal(size=(m, n))
+    Mp = rng.random((T, r, k)).astype(np.float32)
+    Mz = rng.random((T, k, c)).astype(np.float32)
+    sweep, steps, tol, S = [0.3, 0.6, 0.8], 6, 1, 0.6
+    tp, tz, kept, cost = alg1.search_thresholds(W, 0.8, Mp, Mz, r, c, S, sweep, steps, tol)
+    for t in range(T):
+        ti, tj = divmod(t, 3)
+        Wt = W[ti * r:(ti + 1) * r, tj * c:(tj + 1) * c]
+        rt, ct = Wt.shape
+        one = alg1.search_thresholds(Wt, 0.8, Mp[t:t + 1, :rt, :], Mz[t:t + 1, :, :ct], rt, ct, S, sweep, steps, tol)
+        assert (tp[t], tz[t], kept[t]) == (one[0][0], one[1][0], one[2][0]) and cost[t] == one[3][0]

@@ -40,7 +40,7 @@ class Config:
 
     @property
     def tiles(self) -> int:
-        return (self.m // self.r) * (self.n // self.c)
+        return (-(-self.m // self.r)) * (-(-self.n // self.c))  # edge tiles are cut off at the matrix edge
 
 
 CONFIGS = {
@@ -118,8 +118,6 @@ def make_factors(rng, tiles: int, r: int, c: int, k: int, p: float):
 def make(cfg: Config, want_w: bool = True, want_x: bool = True) -> dict:
     """Inputs of one configuration.  Returns storage-dtype arrays:
     W [m, n], X [n, N], Ip01 [T, r, k], Iz01 [T, k, c]."""
-    if cfg.m % cfg.r or cfg.n % cfg.c:
-        raise ValueError("tiles must divide the matrix")
     rng = np.random.default_rng(cfg.seed)
     out = {"cfg": cfg}
     W = rng.standard_normal((cfg.m, cfg.n), dtype=np.float32) * np.float32(cfg.sigma_w)
