@@ -56,7 +56,8 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, C1, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, ceilings); used to profile one workload at a time")
+                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, "
+                         "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: run a plain 1 GiB device copy "
@@ -273,11 +274,18 @@ def main():
             except Exception as e:  # keep the headline line even if an extra fails
                 others[key] = {"error": repr(e)}
 
-        for name in ("C3a", "C3b", "C4", "C5", "C1"):
+        # generality of the format: the paper's own 576 x 512 tiles at rank 145 (tiles divide: tuned decode, general
+        # product kernel), and the C2 layer grown by a few rows and columns so that its edge tiles are cut off
+        # (general kernels throughout)
+        general = {
+            "general_resnet_tiles": workloads.Config("general_resnet_tiles", 2304, 2048, 576, 512, 145, 0.02, 128, "bf16", 0.02),
+            "general_edge_tiles": workloads.Config("general_edge_tiles", 4100, 9224, 256, 256, 16, 0.08, 128, "f16", 0.01),
+        }
+        for name in ("C3a", "C3b", "C4", "C5", "C1", "general_resnet_tiles", "general_edge_tiles"):
             if wanted is not None and name not in wanted:
                 continue
             try:
-                c = workloads.CONFIGS[name]
+                c = workloads.CONFIGS.get(name) or general[name]
                 d = workloads.make(c)
                 de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
                 ip_, iz_ = factors_to_dev(de, d["Ip01"], d["Iz01"])
@@ -299,6 +307,12 @@ def main():
                     seq = [fns[i % 2] for i in range(70)]
                     ms_seq, _ = event_times(seq, 70, 4)
                     extra = {"sequence_70_products_ms": round(ms_seq * 70, 4)}
+                if name in general:
+                    gmask = torch.empty((c.m, ((c.n + 127) // 128) * 16), dtype=torch.uint8, device=dev)
+                    ms_dec, _ = event_times([lambda: lrbi.decode_mask(de, ip_, iz_, out=gmask)], 20, 3)
+                    extra = {"shape": "W %dx%d, tiles %dx%d, rank %d" % (c.m, c.n, c.r, c.c, c.k),
+                             "decode_ms": round(ms_dec, 5), "decode_gbit_s": round(c.m * c.n / (ms_dec * 1e-3) / 1e9, 1)}
+                    del gmask
                 others[name] = {"N": c.N, "dtype": c.dtype, "avg_launch_ms_cold": round(ms, 5), **extra,
                                 "avg_launch_ms_warm": round(ms_warm, 5),
                                 "tflops_dense_equiv": round(fl / (ms * 1e-3) / 1e12, 2),
