@@ -28,6 +28,9 @@
  * Edge tiles and per-tile ranks (tests/test_oracle_general.py): brute force from the set
  * definition, the crop of the zero-padded matrix's decode, tile-by-tile decodes at each
  * tile's own rank, and the closed form k (ceil(n/c) m + ceil(m/r) n) of the size.
+ * Backward pass of the masking layer (tests/test_oracle_backward.py): the adjoint identity
+ * <dY, (W o M) X> = <(W o M)^T dY, X> against the pinned forward product, exact differences of
+ * the (linear) loss in single weights, and numpy's dense products on the masked matrix.
  * Candidate evaluation of Algorithm 1 (threshold, decode, S_a, Cost): pinned by the
  * printed example (Eq. 4 with T_p = 0.5, T_z = 0.6 gives Eq. 5 and Eq. 6; its two
  * mismatches are kept weights, so Cost = 0), by an independent array formulation, by
@@ -93,6 +96,43 @@ int lrbi_oracle_masked_gemm(int64_t m, int64_t n, int64_t N,
             const double w = W[i * n + j];
             const double *x = X + j * N;
             for (int64_t q = 0; q < N; ++q) y[q] += w * x[q];
+        }
+    }
+    return 0;
+}
+
+/* Backward pass of the masked layer (Sec. 2: the mask is a masking layer on W, so retraining sends
+ * gradients through the kept weights only).  With Y = (W o M) X and dY the gradient of a loss with
+ * respect to Y:
+ *   dX[j,q] = sum over i with M[i,j] = 1 of W[i,j] * dY[i,q]      (the transposed masked product),
+ *   dW[i,j] = M[i,j] * sum over q of dY[i,q] * X[j,q]             (pruned weights get exactly 0).
+ * Both in double; sums in ascending i resp. q. */
+int lrbi_oracle_masked_gemm_t(int64_t m, int64_t n, int64_t N, const double *W, const uint8_t *M,
+                              const double *dY, double *dX)
+{
+    if (m <= 0 || n <= 0 || N <= 0) return -1;
+    for (int64_t j = 0; j < n; ++j)
+        for (int64_t q = 0; q < N; ++q) dX[j * N + q] = 0.0;
+    for (int64_t i = 0; i < m; ++i) {
+        for (int64_t j = 0; j < n; ++j) {
+            if (M[i * n + j] == 0) continue;
+            const double w = W[i * n + j];
+            for (int64_t q = 0; q < N; ++q) dX[j * N + q] += w * dY[i * N + q];
+        }
+    }
+    return 0;
+}
+
+int lrbi_oracle_masked_grad(int64_t m, int64_t n, int64_t N, const double *dY, const double *X,
+                            const uint8_t *M, double *dW)
+{
+    if (m <= 0 || n <= 0 || N <= 0) return -1;
+    for (int64_t i = 0; i < m; ++i) {
+        for (int64_t j = 0; j < n; ++j) {
+            double s = 0.0;
+            if (M[i * n + j] != 0)
+                for (int64_t q = 0; q < N; ++q) s += dY[i * N + q] * X[j * N + q];
+            dW[i * n + j] = s;
         }
     }
     return 0;

@@ -48,6 +48,10 @@ def _load():
         lib.lrbi_oracle_index_bits_ranked.restype = u64
         lib.lrbi_oracle_masked_gemm.argtypes = [i64] * 3 + [p, p, p, p, ctypes.c_int]
         lib.lrbi_oracle_masked_gemm.restype = ctypes.c_int
+        lib.lrbi_oracle_masked_gemm_t.argtypes = [i64] * 3 + [p, p, p, p]
+        lib.lrbi_oracle_masked_gemm_t.restype = ctypes.c_int
+        lib.lrbi_oracle_masked_grad.argtypes = [i64] * 3 + [p, p, p, p]
+        lib.lrbi_oracle_masked_grad.restype = ctypes.c_int
         lib.lrbi_oracle_index_bits.argtypes = [i64] * 5
         lib.lrbi_oracle_index_bits.restype = u64
         lib.lrbi_oracle_dense_bits.argtypes = [i64] * 2
@@ -151,6 +155,44 @@ def masked_gemm(W, M, X, threads: int = 1) -> np.ndarray:
     if rc != 0:
         raise ValueError("lrbi_oracle_masked_gemm failed: %d" % rc)
     return Y
+
+
+def masked_gemm_t(W, M, dY) -> np.ndarray:
+    """dX = (W o M)^T dY in float64 (Sec. 2: backward pass through the masking layer); pruned weights are skipped."""
+    W = _c(W, np.float64)
+    M = _c(M, np.uint8)
+    dY = _c(dY, np.float64)
+    if dY.ndim == 1:
+        dY = dY[:, None]
+    m, n = W.shape
+    if M.shape != (m, n) or dY.shape[0] != m:
+        raise ValueError("shape mismatch")
+    N = dY.shape[1]
+    dX = np.empty((n, N), dtype=np.float64)
+    rc = _load().lrbi_oracle_masked_gemm_t(m, n, N, W.ctypes.data, M.ctypes.data, dY.ctypes.data, dX.ctypes.data)
+    if rc != 0:
+        raise ValueError("lrbi_oracle_masked_gemm_t failed: %d" % rc)
+    return dX
+
+
+def masked_grad(dY, X, M) -> np.ndarray:
+    """dW = (dY X^T) o M in float64: the weight gradient of Y = (W o M) X; pruned weights get exactly 0."""
+    dY = _c(dY, np.float64)
+    X = _c(X, np.float64)
+    M = _c(M, np.uint8)
+    if dY.ndim == 1:
+        dY = dY[:, None]
+    if X.ndim == 1:
+        X = X[:, None]
+    m, n = M.shape
+    N = dY.shape[1]
+    if dY.shape != (m, N) or X.shape != (n, N):
+        raise ValueError("shape mismatch")
+    dW = np.empty((m, n), dtype=np.float64)
+    rc = _load().lrbi_oracle_masked_grad(m, n, N, dY.ctypes.data, X.ctypes.data, M.ctypes.data, dW.ctypes.data)
+    if rc != 0:
+        raise ValueError("lrbi_oracle_masked_grad failed: %d" % rc)
+    return dW
 
 
 def index_bits(m: int, n: int, r: int, c: int, k: int, tile_rank=None) -> int:
