@@ -268,6 +268,41 @@ int lrbi_search_thresholds(const lrbi_desc *desc, lrbi_dtype dtype, const void *
 /* Scratch lrbi_search_thresholds needs for this geometry.  Host only. */
 int lrbi_search_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
 
+/*
+ * Backward pass through the masking layer (Sec. 2: the decoded index is a binary masking layer
+ * on W, so retraining with it sends gradients through the kept weights only).  With
+ * Y = (W o I_a) X (lrbi_masked_gemm) and dY the gradient with respect to Y, m x N:
+ *
+ * lrbi_masked_gemm_t: dX = (W o I_a)^T dY, n x N, the gradient with respect to X.  The mask is
+ *   rebuilt from the factors inside the kernel and applied as a select (a pruned weight's stored
+ *   value, NaN and Inf included, never reaches dX).
+ *   dW: m x n row-major, ldw >= n.  dDY: m x N row-major, lddy >= N.  dDX: n x N row-major,
+ *   lddx >= N; overwritten.  All of `dtype`; fp32 accumulation in a fixed order (identical bits
+ *   from call to call), rounded to nearest-even on store.  Pointers aligned to the element size;
+ *   f16 / bf16 with 16-byte aligned W, ldw % 8 == 0, n % 8 == 0 and N > 4 run on the matrix
+ *   cores, everything else on a plain vector-ALU kernel with the same results.
+ *   dWorkspace / workspace_bytes: optional scratch (16-byte aligned) of at least
+ *   lrbi_masked_gemm_t_workspace_bytes bytes: partial sums when the reduction over m is split
+ *   across workgroups; with NULL or too few bytes it is not split (slower for small n * N).
+ *   One or two kernel launches on `stream`.
+ *
+ * lrbi_masked_grad: dW = (dY X^T) o I_a, m x n, the gradient with respect to W: entry (i, j) is
+ *   sum_q dY[i, q] X[j, q] where I_a keeps the weight and exactly 0 where it prunes it.
+ *   dDY: m x N, lddy >= N.  dX: n x N, ldx >= N.  dDW: m x n, lddw >= n; overwritten (every
+ *   entry is written).  Same dtype, accumulation and rounding rules as above; f16 / bf16 with
+ *   N >= 8 run on the matrix cores (16-byte aligned dY, X with lddy, ldx, N multiples of 8, and
+ *   16-byte aligned dW rows, take the vector paths inside it).  One kernel launch on `stream`.
+ */
+int lrbi_masked_gemm_t_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t N,
+                                       uint64_t *bytes);
+int lrbi_masked_gemm_t(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                       const void *dIp_packed, const void *dIz_packed, const void *dDY,
+                       int64_t lddy, int64_t N, void *dDX, int64_t lddx, void *dWorkspace,
+                       uint64_t workspace_bytes, void *stream);
+int lrbi_masked_grad(const lrbi_desc *desc, lrbi_dtype dtype, const void *dDY, int64_t lddy,
+                     const void *dX, int64_t ldx, int64_t N, const void *dIp_packed,
+                     const void *dIz_packed, void *dDW, int64_t lddw, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -82,10 +82,14 @@ def load_library():
                                            ctypes.POINTER(ctypes.c_double), i32, i32, i64, vp, vp, vp, vp, vp, vp, vp, u64,
                                            vp]
     lib.lrbi_search_workspace_bytes.argtypes = [pd, pu64]
+    lib.lrbi_masked_gemm_t_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
+    lib.lrbi_masked_gemm_t.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, u64, vp]
+    lib.lrbi_masked_grad.argtypes = [pd, ctypes.c_int, vp, i64, vp, i64, i64, vp, vp, vp, i64, vp]
     for name in ("lrbi_index_bits", "lrbi_index_bits_ranked", "lrbi_pack_factors_ranked", "lrbi_csr_bits",
                  "lrbi_pack_factors", "lrbi_unpack_mask", "lrbi_decode_mask",
                  "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm", "lrbi_threshold_eval",
-                 "lrbi_threshold_eval_workspace_bytes", "lrbi_search_thresholds", "lrbi_search_workspace_bytes"):
+                 "lrbi_threshold_eval_workspace_bytes", "lrbi_search_thresholds", "lrbi_search_workspace_bytes",
+                 "lrbi_masked_gemm_t_workspace_bytes", "lrbi_masked_gemm_t", "lrbi_masked_grad"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -312,3 +316,53 @@ def search_thresholds(desc: Desc, W, w_threshold: float, Mp, Mz, target_sparsity
         _dev_ptr(iz, "Iz") if want_factors else None, _dev_ptr(workspace, "workspace"),
         workspace.numel() * workspace.element_size(), _stream_ptr(stream)), "lrbi_search_thresholds")
     return (Tp, Tz, kept, cost, ip, iz) if want_factors else (Tp, Tz, kept, cost)
+
+
+def masked_gemm_t_workspace_bytes(desc: Desc, dtype_code: int, N: int) -> int:
+    out = ctypes.c_uint64()
+    _check(load_library().lrbi_masked_gemm_t_workspace_bytes(ctypes.byref(desc), int(dtype_code), int(N),
+                                                             ctypes.byref(out)), "lrbi_masked_gemm_t_workspace_bytes")
+    return out.value
+
+
+def masked_gemm_t(desc: Desc, W, dIp, dIz, dY, out=None, workspace=None, stream=None):
+    """lrbi_masked_gemm_t: dX = (W o decode(Ip, Iz))^T dY.  W [m, n], dY [m, N] row-major device tensors of one
+    dtype (rows may be padded); returns dX [n, N]."""
+    import torch
+    if W.dim() != 2 or dY.dim() != 2 or W.shape != (desc.m, desc.n) or dY.shape[0] != desc.m:
+        raise ValueError("shape mismatch")
+    if W.stride(1) != 1 or (dY.shape[1] > 1 and dY.stride(1) != 1) or W.dtype != dY.dtype:
+        raise ValueError("W and dY must be row-major tensors of the same dtype")
+    N = dY.shape[1]
+    if out is None:
+        out = torch.empty((desc.n, N), dtype=W.dtype, device=W.device)
+    if out.shape != (desc.n, N) or out.dtype != W.dtype or (N > 1 and out.stride(1) != 1):
+        raise ValueError("bad out tensor")
+    ws_ptr, ws_bytes = ctypes.c_void_p(0), 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    _check(load_library().lrbi_masked_gemm_t(
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), _dev_ptr(dIp, "Ip"), _dev_ptr(dIz, "Iz"),
+        _dev_ptr(dY, "dY"), dY.stride(0), N, _dev_ptr(out, "dX"), out.stride(0), ws_ptr, ws_bytes,
+        _stream_ptr(stream)), "lrbi_masked_gemm_t")
+    return out
+
+
+def masked_grad(desc: Desc, dY, X, dIp, dIz, out=None, stream=None):
+    """lrbi_masked_grad: dW = (dY X^T) o decode(Ip, Iz).  dY [m, N], X [n, N] row-major device tensors of one
+    dtype (rows may be padded); returns dW [m, n] with exact zeros at pruned weights."""
+    import torch
+    if dY.dim() != 2 or X.dim() != 2 or dY.shape[0] != desc.m or X.shape[0] != desc.n or dY.shape[1] != X.shape[1]:
+        raise ValueError("shape mismatch")
+    N = dY.shape[1]
+    if (N > 1 and (dY.stride(1) != 1 or X.stride(1) != 1)) or dY.dtype != X.dtype:
+        raise ValueError("dY and X must be row-major tensors of the same dtype")
+    if out is None:
+        out = torch.empty((desc.m, desc.n), dtype=dY.dtype, device=dY.device)
+    if out.shape != (desc.m, desc.n) or out.dtype != dY.dtype or out.stride(1) != 1:
+        raise ValueError("bad out tensor")
+    _check(load_library().lrbi_masked_grad(
+        ctypes.byref(desc), _dtype_code(dY), _dev_ptr(dY, "dY"), dY.stride(0), _dev_ptr(X, "X"), X.stride(0), N,
+        _dev_ptr(dIp, "Ip"), _dev_ptr(dIz, "Iz"), _dev_ptr(out, "dW"), out.stride(0), _stream_ptr(stream)),
+        "lrbi_masked_grad")
+    return out

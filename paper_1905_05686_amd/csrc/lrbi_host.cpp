@@ -337,3 +337,70 @@ extern "C" int lrbi_search_workspace_bytes(const lrbi_desc *desc, uint64_t *byte
     *bytes = plan_search(make_geom(desc)).bytes;
     return LRBI_OK;
 }
+
+// the matrix-core backward kernels load W (and write dW) in 16-byte pieces
+static bool w_pieces_ok(const lrbi_desc *desc, const void *dW, int64_t ldw)
+{
+    return aligned_to(dW, 16) && (ldw % 8 == 0) && (desc->n % 8 == 0);
+}
+
+extern "C" int lrbi_masked_gemm_t_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t N, uint64_t *bytes)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!bytes) return LRBI_ERR_NULL;
+    if (elem_size(dtype) == 0) return LRBI_ERR_DTYPE;
+    if (N <= 0) return LRBI_ERR_SHAPE;
+    *bytes = plan_gemm_t(make_geom(desc), dtype, N, desc->n % 8 == 0).workspace_bytes;
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_masked_gemm_t(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                                  const void *dIp_packed, const void *dIz_packed, const void *dDY, int64_t lddy,
+                                  int64_t N, void *dDX, int64_t lddx, void *dWorkspace, uint64_t workspace_bytes,
+                                  void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dW || !dIp_packed || !dIz_packed || !dDY || !dDX) return LRBI_ERR_NULL;
+    const int es = elem_size(dtype);
+    if (es == 0) return LRBI_ERR_DTYPE;
+    if (N <= 0 || N > (int64_t)0x7FFFFF00) return LRBI_ERR_SHAPE;
+    if (ldw < desc->n || lddy < N || lddx < N) return LRBI_ERR_PITCH;
+    if (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8)) return LRBI_ERR_ALIGN;
+    if (!aligned_to(dW, (uintptr_t)es) || !aligned_to(dDY, (uintptr_t)es) || !aligned_to(dDX, (uintptr_t)es))
+        return LRBI_ERR_ALIGN;
+    const Geom g = make_geom(desc);
+    BwdPlan plan = plan_gemm_t(g, dtype, N, w_pieces_ok(desc, dW, ldw));
+    if (plan.slices > 1) {
+        const bool ws_ok = dWorkspace && aligned_to(dWorkspace, 16) && workspace_bytes >= plan.workspace_bytes;
+        if (!ws_ok) { // no scratch: one slice over all rows of W
+            plan.slices = 1;
+            plan.iper = g.m;
+        }
+    }
+    return launch_gemm_t(g, plan, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed, dDY, lddy,
+                         N, dDX, lddx, dWorkspace, (hipStream_t)stream);
+}
+
+extern "C" int lrbi_masked_grad(const lrbi_desc *desc, lrbi_dtype dtype, const void *dDY, int64_t lddy, const void *dX,
+                                int64_t ldx, int64_t N, const void *dIp_packed, const void *dIz_packed, void *dDW,
+                                int64_t lddw, void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dDY || !dX || !dIp_packed || !dIz_packed || !dDW) return LRBI_ERR_NULL;
+    const int es = elem_size(dtype);
+    if (es == 0) return LRBI_ERR_DTYPE;
+    if (N <= 0 || N > (int64_t)0x7FFFFF00) return LRBI_ERR_SHAPE;
+    if (lddw < desc->n || lddy < N || ldx < N) return LRBI_ERR_PITCH;
+    if (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8)) return LRBI_ERR_ALIGN;
+    if (!aligned_to(dDW, (uintptr_t)es) || !aligned_to(dDY, (uintptr_t)es) || !aligned_to(dX, (uintptr_t)es))
+        return LRBI_ERR_ALIGN;
+    const Geom g = make_geom(desc);
+    // matrix cores for the 16-bit types once the batch gives them something to do; dW rows need not be
+    // 16-byte aligned (the kernel then writes element by element)
+    const bool mfma = dtype != LRBI_F32 && N >= 8;
+    return launch_grad(g, dtype, mfma, dDY, lddy, dX, ldx, N, (const uint32_t *)dIp_packed,
+                       (const uint32_t *)dIz_packed, dDW, lddw, (hipStream_t)stream);
+}

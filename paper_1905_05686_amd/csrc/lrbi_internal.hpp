@@ -54,6 +54,21 @@ int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, flo
                   int64_t tolerance, float *dTpBest, float *dTzBest, uint64_t *dKeptBest, double *dCostBest, void *dIp,
                   void *dIz, void *dWorkspace, hipStream_t stream);
 
+// backward pass through the masking layer (lrbi_backward.hip)
+struct BwdPlan {
+    bool mfma;     // matrix-core kernel (f16 / bf16, aligned operands, N > 4); otherwise the vector-ALU kernel
+    int bq;        // batch columns per workgroup
+    int slices;    // slices over the rows of W (partial planes through the workspace when > 1)
+    int64_t iper;  // rows of W per slice
+    uint64_t workspace_bytes;
+};
+BwdPlan plan_gemm_t(const Geom &g, lrbi_dtype dt, int64_t N, bool aligned);
+int launch_gemm_t(const Geom &g, const BwdPlan &plan, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
+                  const uint32_t *dIz, const void *dDY, int64_t lddy, int64_t N, void *dDX, int64_t lddx,
+                  void *dWorkspace, hipStream_t stream);
+int launch_grad(const Geom &g, lrbi_dtype dt, bool mfma, const void *dDY, int64_t lddy, const void *dX, int64_t ldx,
+                int64_t N, const uint32_t *dIp, const uint32_t *dIz, void *dDW, int64_t lddw, hipStream_t stream);
+
 struct MfmaPlan {
     int tile;     // tile variant id (1-based, see lrbi_gemm_mfma.hip)
     int bm, bn;   // workgroup tile

@@ -225,3 +225,40 @@ def test_search_thresholds_rejects_bad_arguments_before_any_launch():
     # factors of more than 16384 entries take 2^j slots per tile
     d3 = lrbi.Desc(576, 1024, 576, 512, 145)
     assert lrbi.search_workspace_bytes(d3) >= 2 * (131072 + 131072) * 4
+
+
+def test_backward_entry_points_reject_bad_arguments_before_any_launch():
+    lib = lrbi.load_library()
+    d = lrbi.Desc(8, 128, 4, 64, 2)
+    buf = (ctypes.c_uint8 * 4096)()
+    base = (ctypes.addressof(buf) + 63) // 64 * 64
+    p = ctypes.c_void_p(base)
+    t = lib.lrbi_masked_gemm_t
+    targs = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128), p, p,
+                          kw.get("dY", p), kw.get("lddy", 16), kw.get("N", 16), kw.get("dX", p), kw.get("lddx", 16), None,
+                          0, None]
+    assert t(*targs(W=None)) == -1
+    assert t(*targs(dX=None)) == -1
+    assert t(*targs(dt=7)) == -4
+    assert t(*targs(N=0)) == -2
+    assert t(*targs(ldw=127)) == -5
+    assert t(*targs(lddy=15)) == -5
+    assert t(*targs(lddx=8)) == -5
+    assert t(*targs(dY=ctypes.c_void_p(base + 1))) == -6
+    g = lib.lrbi_masked_grad
+    gargs = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("dY", p), kw.get("lddy", 16),
+                          kw.get("X", p), kw.get("ldx", 16), kw.get("N", 16), p, p, kw.get("dW", p), kw.get("lddw", 128),
+                          None]
+    assert g(*gargs(dY=None)) == -1
+    assert g(*gargs(dW=None)) == -1
+    assert g(*gargs(dt=7)) == -4
+    assert g(*gargs(N=-3)) == -2
+    assert g(*gargs(lddw=127)) == -5
+    assert g(*gargs(ldx=15)) == -5
+    assert g(*gargs(X=ctypes.c_void_p(base + 1))) == -6
+    # workspace of the transposed product: slices over m x n x N fp32; none for fp32 or a batch of one
+    big = lrbi.Desc(4096, 9216, 256, 256, 16)
+    nb = lrbi.masked_gemm_t_workspace_bytes(big, lrbi.F16, 128)
+    assert nb > 0 and nb % (9216 * 128 * 4) == 0
+    assert lrbi.masked_gemm_t_workspace_bytes(big, lrbi.F32, 128) == 0
+    assert lrbi.masked_gemm_t_workspace_bytes(big, lrbi.F16, 1) == 0
