@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, "
+                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -347,6 +347,39 @@ def main():
                                "hbm_frac": round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                                "candidates_per_s": round(1.0 / (ms * 1e-3), 1)}
                 del Wl, tens
+            except Exception as e:
+                others[key] = {"error": repr(e)}
+        # backward pass through the masking layer: dX = (W o I_a)^T dY and dW = (dY X^T) o I_a
+        for name in ("C2", "C3b"):
+            key = "backward_" + name
+            if wanted is not None and key not in wanted:
+                continue
+            try:
+                c = workloads.CONFIGS[name]
+                d = workloads.make(c)
+                de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
+                ip_, iz_ = factors_to_dev(de, d["Ip01"], d["Iz01"])
+                Wl = rotated_weights(to_dev(d["W"], c.dtype))
+                X_ = to_dev(d["X"], c.dtype)
+                dY_ = torch.randn((c.m, c.N), device=dev, dtype=torch.float32).to(TD[c.dtype])
+                dX_ = torch.empty((c.n, c.N), dtype=TD[c.dtype], device=dev)
+                dWl = [torch.empty_like(Wi) for Wi in Wl]   # rotating outputs: every launch writes HBM-cold lines
+                wb = lrbi.masked_gemm_t_workspace_bytes(de, DC[c.dtype], c.N)
+                w_ = torch.empty(max(1, wb // 4), dtype=torch.float32, device=dev) if wb else None
+                fns = [(lambda Wi=Wi: lrbi.masked_gemm_t(de, Wi, ip_, iz_, dY_, out=dX_, workspace=w_)) for Wi in Wl]
+                ms_t, _ = event_times(fns, 6 * len(fns), len(fns))
+                fns = [(lambda Gi=Gi: lrbi.masked_grad(de, dY_, X_, ip_, iz_, out=Gi)) for Gi in dWl]
+                ms_g, _ = event_times(fns, 6 * len(fns), len(fns))
+                fl = 2.0 * c.m * c.n * c.N
+                byt_t = (c.m * c.n + c.m * c.N + c.n * c.N) * 2 + lrbi.index_bits(de)["lrbi_bits"] / 8
+                others[key] = {
+                    "N": c.N, "dtype": c.dtype,
+                    "gemm_t_ms_cold": round(ms_t, 5), "gemm_t_tflops_dense_equiv": round(fl / (ms_t * 1e-3) / 1e12, 2),
+                    "gemm_t_GBs": round(byt_t / (ms_t * 1e-3) / 1e9, 1),
+                    "grad_ms": round(ms_g, 5), "grad_tflops_dense_equiv": round(fl / (ms_g * 1e-3) / 1e12, 2),
+                    "grad_GBs": round(byt_t / (ms_g * 1e-3) / 1e9, 1),
+                    "grad_hbm_frac": round(byt_t / (ms_g * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                del Wl, dWl, X_, dY_, dX_
             except Exception as e:
                 others[key] = {"error": repr(e)}
         # the whole threshold search of Algorithm 1 for a layer: sort, then n_sp x steps candidates (W stays in the

@@ -33,20 +33,28 @@ static constexpr int BJ = 128; // columns of W per workgroup (both kernels)
 // dX = (W o I_a)^T dY on the matrix cores
 // ---------------------------------------------------------------------------
 template <int BQ> struct SmemT {
-    static constexpr int WS_STRIDE = BJ + 8; // halfs; rows stay 16-byte aligned, banks staggered
-    static constexpr int XS_STRIDE = BQ + 8;
+    // halfs; rows stay 16-byte aligned, and the four rows a 16-lane group of the transposing read touches fall
+    // into different banks (measured: 6 % faster than a pad of 8)
+    static constexpr int WS_STRIDE = BJ + 16;
+    static constexpr int XS_STRIDE = BQ + 16;
     static constexpr int ws_halfs = BK * WS_STRIDE;
     static constexpr int xs_halfs = BK * XS_STRIDE;
     static constexpr int ms_words = BK * (BJ / 32);
-    static constexpr size_t bytes = 2 * (size_t)(ws_halfs + xs_halfs) * 2 + 2 * (size_t)ms_words * 4;
+    static constexpr int fz_words = FAST_MAX_K * (BJ / 32); // one tile's I_z rows over the workgroup's 128 columns
+    static constexpr size_t bytes =
+        2 * (size_t)(ws_halfs + xs_halfs) * 2 + 2 * (size_t)ms_words * 4 + 2 * (size_t)fz_words * 4;
 };
 
-template <typename Tag, int BQ, int WAVES_J, int WAVES_Q, bool XVEC, bool SPLIT>
+// FAST: c % 128 == 0 (the workgroup's 128 columns lie in one tile column), r % 64 == 0 and r >= 128 (a slab lies in
+// one tile row, three consecutive slabs in at most two), k <= 64, no cut-off tiles.  Then the I_z rows of the current
+// tile row (k x 4 words) are kept in LDS, fetched three slabs ahead, and the I_p words of a slab's rows are requested
+// one iteration before they are used: no dependent global load sits in the loop.
+template <typename Tag, int BQ, int WAVES_J, int WAVES_Q, bool XVEC, bool SPLIT, bool FAST>
 __global__ __launch_bounds__(kBwdThreads) void mfma_gemm_t_kernel(
     Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
     const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ DY, int64_t lddy, int N,
     uint16_t *__restrict__ DX, int64_t lddx, float *__restrict__ P, int64_t ldp, int jblocks, int qblocks,
-    int64_t iper, int y_vec_ok)
+    int64_t iper, int xcd_remap, int y_vec_ok)
 {
     static_assert(WAVES_J * WAVES_Q == 4, "four wavefronts per workgroup");
     constexpr int WJ = BJ / WAVES_J, WQ = BQ / WAVES_Q;
@@ -65,8 +73,16 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_gemm_t_kernel(
     uint16_t *Ws = (uint16_t *)lrbi_dyn_smem;            // [2][BK][WS_STRIDE]
     uint16_t *Xs = Ws + 2 * S::ws_halfs;                 // [2][BK][XS_STRIDE]
     uint32_t *Ms = (uint32_t *)(Xs + 2 * S::xs_halfs);   // [2][BK][BJ / 32]
+    uint32_t *Fz = Ms + 2 * S::ms_words;                 // [2][k][BJ / 32], by parity of the tile row
 
-    const int64_t bid = blockIdx.x;
+    // workgroup -> (slice, column block of W, batch block), batch block fastest: the workgroups that share a strip
+    // of W are neighbours.  With xcd_remap the hardware's round-robin of consecutive workgroup ids over the 8 XCDs
+    // is undone, so that those neighbours land on one XCD and the strip goes through one L2, not eight.
+    int64_t bid = blockIdx.x;
+    if (xcd_remap) {
+        const int64_t per = gridDim.x / 8;
+        bid = (bid % 8) * per + bid / 8;
+    }
     const int qi = (int)(bid % qblocks);
     const int ji = (int)((bid / qblocks) % jblocks);
     const int slice = (int)(bid / ((int64_t)qblocks * jblocks));
@@ -86,49 +102,123 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_gemm_t_kernel(
     uint4 wreg[W_CHUNKS];
     uint4 xreg[X_CHUNKS];
 
-    auto load_slab = [&](int slab) {
-        const int64_t i0 = ibeg + (int64_t)slab * BK;
+    // Addresses: a base that is uniform over the workgroup (advanced per slab with scalar arithmetic) plus a
+    // per-lane byte offset that never changes, so that no 64-bit multiply sits in the loop.  Offsets stay below
+    // 2^31 (64 rows of at most 2^24 elements).  Every load is unconditional: a lane whose piece lies outside the
+    // slice or the matrix reads the piece at the top of the slab / the left of the row instead (always valid) and
+    // what it read is discarded (W: its mask word is zero; dY: zeroed when staged).  A load under a branch would
+    // need its destination cleared first, and that write had the compiler wait for every load in flight.
+    uint32_t woff[W_CHUNKS], woff_top[W_CHUNKS], xoff[X_CHUNKS], xoff_top[X_CHUNKS];
+    int wrow[W_CHUNKS], xrow[X_CHUNKS];
+    bool xcol_ok[X_CHUNKS];
 #pragma unroll
-        for (int c = 0; c < W_CHUNKS; ++c) {
-            const int id = tid + kBwdThreads * c;
-            const int row = id / W_CPR, pc = id % W_CPR;
-            const int64_t gi = i0 + row;
-            const int jj = j0 + pc * 8;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (gi < iend && jj < n) v = *reinterpret_cast<const uint4 *>(W + gi * ldw + jj); // n % 8 == 0
-            wreg[c] = v;
-        }
+    for (int c = 0; c < W_CHUNKS; ++c) {
+        const int id = tid + kBwdThreads * c;
+        wrow[c] = id / W_CPR;
+        int pc = id % W_CPR;
+        if (j0 + pc * 8 >= n) pc = 0; // n % 8 == 0: a piece is inside or outside as a whole; outside -> mask bits are 0
+        woff[c] = (uint32_t)(((int64_t)wrow[c] * ldw + pc * 8) * 2);
+        woff_top[c] = (uint32_t)(pc * 8 * 2);
+    }
+#pragma unroll
+    for (int c = 0; c < X_CHUNKS; ++c) {
+        const int id = (tid + kBwdThreads * c) % (BK * X_CPR); // lanes beyond the slab repeat earlier pieces
+        xrow[c] = id / X_CPR;
+        int nc = id % X_CPR;
+        xcol_ok[c] = q0 + nc * 8 < N;
+        if (!xcol_ok[c]) nc = 0;
+        xoff[c] = (uint32_t)(((int64_t)xrow[c] * lddy + nc * 8) * 2);
+        xoff_top[c] = (uint32_t)(nc * 8 * 2);
+    }
+    const char *wbase0 = (const char *)(W + ibeg * ldw + j0);
+    const char *xbase0 = (const char *)(DY + ibeg * lddy + q0);
+    int x_rows_left = 0; // rows of the slab whose dY pieces sit in xreg (for the zeroing at stage time)
+
+    auto load_slab = [&](int slab) {
+        const int rows_left = (int)(iend - ibeg) - slab * BK; // rows of this slab and beyond (>= 1)
+        const char *wbase = wbase0 + (int64_t)slab * BK * ldw * 2;
+        const char *xbase = xbase0 + (int64_t)slab * BK * lddy * 2;
+#pragma unroll
+        for (int c = 0; c < W_CHUNKS; ++c)
+            wreg[c] = *reinterpret_cast<const uint4 *>(wbase + (wrow[c] < rows_left ? woff[c] : woff_top[c]));
 #pragma unroll
         for (int c = 0; c < X_CHUNKS; ++c) {
-            const int id = tid + kBwdThreads * c;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (id < BK * X_CPR) {
-                const int row = id / X_CPR, nc = id % X_CPR;
-                const int64_t gi = i0 + row;
-                const int qq = q0 + nc * 8;
-                if (gi < iend) {
-                    if (XVEC) {
-                        if (qq < N) v = *reinterpret_cast<const uint4 *>(DY + gi * lddy + qq);
-                    } else {
-                        uint16_t tmp[8];
+            const char *src = xbase + (xrow[c] < rows_left ? xoff[c] : xoff_top[c]);
+            if (XVEC) {
+                xreg[c] = *reinterpret_cast<const uint4 *>(src); // N % 8 == 0
+            } else {
+                const uint16_t *h = reinterpret_cast<const uint16_t *>(src);
+                const int room = N - q0 - ((tid + kBwdThreads * c) % X_CPR) * 8; // valid elements from this piece on
+                uint16_t tmp[8];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) tmp[e] = (qq + e < N) ? DY[gi * lddy + qq + e] : (uint16_t)0;
-                        v = *reinterpret_cast<uint4 *>(tmp);
-                    }
-                }
+                for (int e = 0; e < 8; ++e) tmp[e] = h[(xcol_ok[c] && e < room) ? e : 0];
+                xreg[c] = *reinterpret_cast<uint4 *>(tmp);
             }
-            xreg[c] = v;
         }
+        x_rows_left = rows_left;
     };
 
+    // FAST: tile column of the workgroup and the word offset of its 128 columns inside that tile's I_z rows
+    const int tj = FAST ? j0 / g.c : 0;
+    const int zw0 = FAST ? (j0 - tj * g.c) >> 5 : 0;
+    // FAST: position of a slab's first row as (tile row, row inside the tile), advanced slab by slab without a
+    // division (r % 64 == 0: a slab never straddles two tile rows)
+    struct Cursor {
+        int ti, o;
+    };
+    auto advance = [&](Cursor &c) {
+        c.o += BK;
+        if (c.o >= g.r) {
+            c.o -= g.r;
+            c.ti += 1;
+        }
+    };
+    const uint32_t fz_off = (uint32_t)((((tid >> 2) * g.izw) + (tid & 3)) * 4); // lane's word of the I_z slice
+    const uint32_t ip_off = (uint32_t)((tid >> 2) * g.ipw * 4);                 // lane's row of the slab's I_p rows
+    // I_z rows of the tile row that slab `slab` (at cursor c) starts, when it starts one (or unconditionally):
+    // global -> LDS
+    auto fetch_fz = [&](int slab, const Cursor &c, bool always) {
+        if (slab >= nslabs || !(always || c.o == 0)) return; // uniform over the workgroup
+        const int64_t t = (int64_t)c.ti * g.tile_cols + tj;
+        const char *base = (const char *)(Iz + t * g.k * (int64_t)g.izw + zw0);
+        uint32_t *fz = Fz + (c.ti & 1) * S::fz_words;
+        if (tid < g.k * 4) fz[tid] = *reinterpret_cast<const uint32_t *>(base + fz_off);
+    };
+    // I_p words (k <= 64: at most two) of this lane's row of slab `slab` (at cursor c).  Unconditional loads: a row
+    // beyond the slice reads the slab's first row (its mask word is forced to zero in decode_slab); with one word
+    // per row the second register repeats the first and is not looked at.
+    auto load_ip = [&](int slab, const Cursor &c, uint32_t (&ipw)[2]) {
+        if (slab >= nslabs) return; // uniform; the registers are not used for such a slab
+        const int rows_left = (int)(iend - ibeg) - slab * BK;
+        const int64_t t = (int64_t)c.ti * g.tile_cols + tj;
+        const char *base = (const char *)(Ip + (t * g.r + c.o) * g.ipw);
+        const uint32_t *ip = reinterpret_cast<const uint32_t *>(base + ((tid >> 2) < rows_left ? ip_off : 0u));
+        ipw[0] = ip[0];
+        ipw[1] = ip[g.ipw > 1 ? 1 : 0];
+    };
     // one mask word per lane: (row of the slab, 32-column group of the workgroup's 128 columns)
-    auto decode_slab = [&](int slab, int buf) {
-        const int64_t gi = ibeg + (int64_t)slab * BK + (tid >> 2);
+    auto decode_slab = [&](int slab, int buf, int ti_fast, const uint32_t (&ipw)[2]) {
         uint32_t word = 0u;
-        if (gi < iend) {
-            const int ti = (int)(gi / g.r);
-            const int il = (int)(gi - (int64_t)ti * g.r);
-            word = decode_word(g, Ip, Iz, ti, il, (j0 >> 5) + (tid & 3));
+        if (FAST) {
+            const uint32_t *fz = Fz + (ti_fast & 1) * S::fz_words + (tid & 3);
+            const int rows_left = (int)(iend - ibeg) - slab * BK;
+            const bool live = (tid >> 2) < rows_left; // a row beyond the slice: its W piece is a stand-in, mask it out
+#pragma unroll
+            for (int iw = 0; iw < 2; ++iw) {
+                uint32_t sel = (live && iw < g.ipw) ? ipw[iw] : 0u;
+                while (sel) {
+                    const int l = __builtin_ctz(sel) + 32 * iw;
+                    sel &= sel - 1u;
+                    word |= fz[l * 4];
+                }
+            }
+        } else {
+            const int64_t gi = ibeg + (int64_t)slab * BK + (tid >> 2);
+            if (gi < iend) {
+                const int ti = (int)(gi / g.r);
+                const int il = (int)(gi - (int64_t)ti * g.r);
+                word = decode_word(g, Ip, Iz, ti, il, (j0 >> 5) + (tid & 3));
+            }
         }
         Ms[buf * S::ms_words + tid] = word;
     };
@@ -149,7 +239,16 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_gemm_t_kernel(
             const int id = tid + kBwdThreads * c;
             if (id < BK * X_CPR) {
                 const int row = id / X_CPR, nc = id % X_CPR;
-                *reinterpret_cast<uint4 *>(xs + row * XS_STRIDE + nc * 8) = xreg[c];
+                uint4 v = xreg[c];
+                if (!(row < x_rows_left && xcol_ok[c])) v = make_uint4(0u, 0u, 0u, 0u);
+                if (!XVEC) { // a piece that straddles N: zero its tail
+                    const int room = N - q0 - nc * 8;
+                    uint16_t *h = reinterpret_cast<uint16_t *>(&v);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e >= room) h[e] = 0;
+                }
+                *reinterpret_cast<uint4 *>(xs + row * XS_STRIDE + nc * 8) = v;
             }
         }
     };
@@ -170,19 +269,50 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_gemm_t_kernel(
     const uint32_t wfrag_off = (uint32_t)(frag_row * WS_STRIDE + wj * WJ + frag_col);
     const uint32_t xfrag_off = (uint32_t)(frag_row * XS_STRIDE + wq * WQ + frag_col);
 
+    // FAST: I_p words of the slabs in flight.  The words of slab x live in ip_even / ip_odd by the parity of x; the loop
+    // is unrolled by two so that no register copy (which would wait for a load just requested) is needed.
+    uint32_t ip_even[2] = {0u, 0u}, ip_odd[2] = {0u, 0u};
+    Cursor c2{0, 0}, c3{0, 0}, c4{0, 0}; // slabs s + 2, s + 3, s + 4 of loop iteration s
     if (nslabs > 0) {
-        load_slab(0);
-        decode_slab(0, 0);
+        uint32_t ip0[2] = {0u, 0u};
+        Cursor c0{0, 0}, c1{0, 0};
+        if (FAST) {
+            c0.ti = (int)(ibeg / g.r);
+            c0.o = (int)(ibeg - (int64_t)c0.ti * g.r);
+            c1 = c0;
+            advance(c1);
+            c2 = c1;
+            advance(c2);
+            c3 = c2;
+            advance(c3);
+            c4 = c3;
+            advance(c4);
+            fetch_fz(0, c0, true);
+            fetch_fz(1, c1, false);
+            fetch_fz(2, c2, false);
+            load_ip(0, c0, ip0);
+            load_slab(0);
+            __syncthreads();
+            decode_slab(0, 0, c0.ti, ip0);
+            load_ip(1, c1, ip_odd);
+            load_ip(2, c2, ip_even);
+        } else {
+            load_slab(0);
+            decode_slab(0, 0, 0, ip0);
+        }
         __syncthreads();
         stage_slab(0);
         if (nslabs > 1) {
             load_slab(1);
-            decode_slab(1, 1);
+            decode_slab(1, 1, c1.ti, ip_odd);
         }
+        if (FAST) fetch_fz(3, c3, false);
         __syncthreads();
     }
 
-    for (int s = 0; s < nslabs; ++s) {
+    // one slab: multiply slab s, stage slab s + 1, request slab s + 2 and decode its mask words
+    // (`use` holds its I_p words), request the I_p words of slab s + 3 into `next`
+    auto iteration = [&](int s, const uint32_t (&use)[2], uint32_t (&next)[2]) __attribute__((always_inline)) {
         const int buf = s & 1;
         const uint16_t *ws = Ws + buf * S::ws_halfs + wfrag_off;
         const uint16_t *xs = Xs + buf * S::xs_halfs + xfrag_off;
@@ -209,11 +339,22 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_gemm_t_kernel(
                 for (int b = 0; b < FJ; ++b) acc[a][b] = mfma_32x32x16(Tag{}, xf[a], wf[b], acc[a][b]);
         }
         if (s + 1 < nslabs) stage_slab(buf ^ 1);
+        if (FAST) load_ip(s + 3, c3, next); // requested before the slab's own loads, used one iteration later
         if (s + 2 < nslabs) {
             load_slab(s + 2);
-            decode_slab(s + 2, buf);
+            decode_slab(s + 2, buf, c2.ti, use);
+        }
+        if (FAST) {
+            fetch_fz(s + 4, c4, false);
+            advance(c2);
+            advance(c3);
+            advance(c4);
         }
         __syncthreads();
+    };
+    for (int s = 0; s < nslabs; s += 2) {
+        iteration(s, ip_even, ip_odd);     // slab s + 2 is even, slab s + 3 odd
+        if (s + 1 < nslabs) iteration(s + 1, ip_odd, ip_even);
     }
 
     // epilogue: per 32x32 block the lane holds row (of dX) l32 and columns 8 * (v / 4) + 4 * lg + (v % 4)
@@ -285,8 +426,10 @@ struct SmemG {
     static constexpr int CS_STRIDE = BJ + 8;  // halfs, output tile [row][column]
     static constexpr int op_halfs = 128 * OP_STRIDE;
     static constexpr int ms_words = BI * (BJ / 32);
-    // operands double buffered (the output tile reuses their space after the last slab) + mask words
-    static constexpr size_t op_bytes = 2 * 2 * (size_t)op_halfs * 2;
+    // one stage of both operands (the output tile reuses their space after the last slab) + mask words: 39 KB,
+    // so that four workgroups share a compute unit.  Measured against two stages (75 KB, two workgroups, one
+    // barrier per slab less): 36 us against 48 us on a batch of 128, 56 us against 60 us on a batch of 1024.
+    static constexpr size_t op_bytes = 2 * (size_t)op_halfs * 2;
     static constexpr size_t cs_bytes = (size_t)BI * CS_STRIDE * 2;
     static constexpr size_t bytes = (op_bytes > cs_bytes ? op_bytes : cs_bytes) + (size_t)ms_words * 4;
 };
@@ -306,8 +449,8 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
     constexpr int WI = 64, WJ = 64, FI = 2, FJ = 2;      // 2 x 2 wavefronts, 64 x 64 each
 
     extern __shared__ uint4 lrbi_dyn_smem[];
-    uint16_t *As = (uint16_t *)lrbi_dyn_smem;            // [2][128][OP_STRIDE]  rows of dY
-    uint16_t *Bs = As + 2 * S::op_halfs;                 // [2][128][OP_STRIDE]  rows of X
+    uint16_t *As = (uint16_t *)lrbi_dyn_smem;            // [128][OP_STRIDE]  rows of dY
+    uint16_t *Bs = As + S::op_halfs;                     // [128][OP_STRIDE]  rows of X
     uint16_t *Cs = (uint16_t *)lrbi_dyn_smem;            // [128][CS_STRIDE], after the last slab
     uint32_t *Ms = (uint32_t *)((char *)lrbi_dyn_smem + (S::op_bytes > S::cs_bytes ? S::op_bytes : S::cs_bytes));
 
@@ -351,9 +494,9 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
             breg[c] = load_piece(X, ldx, (int64_t)j0 + row, g.n, k0 + kc * 8);
         }
     };
-    auto stage_slab = [&](int buf) {
-        uint16_t *as = As + buf * S::op_halfs;
-        uint16_t *bs = Bs + buf * S::op_halfs;
+    auto stage_slab = [&]() {
+        uint16_t *as = As;
+        uint16_t *bs = Bs;
 #pragma unroll
         for (int c = 0; c < CHUNKS; ++c) {
             const int id = tid + kBwdThreads * c;
@@ -363,8 +506,16 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
         }
     };
 
-    // mask words of the tile: 128 rows x 4 words, two per lane; needed only in the epilogue, so
-    // their (dependent) factor loads overlap the whole reduction
+    f32x16 acc[FJ][FI];
+#pragma unroll
+    for (int a = 0; a < FJ; ++a)
+#pragma unroll
+        for (int b = 0; b < FI; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    load_slab(0); // requested first: the factor loads below queue up behind it
+    // mask words of the tile: 128 rows x 4 words, two per lane; needed only in the epilogue
 #pragma unroll
     for (int c = 0; c < S::ms_words / kBwdThreads; ++c) {
         const int idx = tid + kBwdThreads * c;
@@ -378,23 +529,13 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
         Ms[idx] = word;
     }
 
-    f32x16 acc[FJ][FI];
-#pragma unroll
-    for (int a = 0; a < FJ; ++a)
-#pragma unroll
-        for (int b = 0; b < FI; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
-    load_slab(0);
-    stage_slab(0);
+    stage_slab();
     if (nslabs > 1) load_slab(1);
     __syncthreads();
 
     for (int s = 0; s < nslabs; ++s) {
-        const int buf = s & 1;
-        const uint16_t *as = As + buf * S::op_halfs + (wi * WI + l32) * OP_STRIDE + 8 * lg;
-        const uint16_t *bs = Bs + buf * S::op_halfs + (wj * WJ + l32) * OP_STRIDE + 8 * lg;
+        const uint16_t *as = As + (wi * WI + l32) * OP_STRIDE + 8 * lg;
+        const uint16_t *bs = Bs + (wj * WJ + l32) * OP_STRIDE + 8 * lg;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             uint4 af[FI], bf[FJ];
@@ -407,7 +548,8 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
 #pragma unroll
                 for (int b = 0; b < FI; ++b) acc[a][b] = mfma_32x32x16(Tag{}, bf[a], af[b], acc[a][b]);
         }
-        if (s + 1 < nslabs) stage_slab(buf ^ 1);
+        __syncthreads(); // everyone has read the stage before it is overwritten
+        if (s + 1 < nslabs) stage_slab();
         if (s + 2 < nslabs) load_slab(s + 2);
         __syncthreads();
     }
@@ -534,7 +676,8 @@ BwdPlan plan_gemm_t(const Geom &g, lrbi_dtype dt, int64_t N, bool aligned)
     const int64_t jblocks = (g.n + BJ - 1) / BJ, qblocks = (N + p.bq - 1) / p.bq;
     const int64_t tiles = jblocks * qblocks;
     const int64_t islabs = (g.m + BK - 1) / BK;
-    int64_t want = (512 + tiles - 1) / tiles;          // enough workgroups for 256 compute units
+    // two workgroups fit a compute unit: at most 512 run at once, and one more than that costs a second round
+    int64_t want = 512 / tiles;
     const int64_t cap = islabs / 4 > 1 ? islabs / 4 : 1; // at least four slabs per slice
     if (want > cap) want = cap;
     if (want > 64) want = 64;
@@ -560,15 +703,18 @@ static int launch_gemm_t_tile(const Geom &g, const BwdPlan &plan, const void *dW
     const int y_vec_ok = (((uintptr_t)dDX & 7) == 0) && (lddx % 4 == 0);
     const int64_t ldp = (N + 3) / 4 * 4;
     const size_t smem = SmemT<BQ>::bytes;
+    const int xcd_remap = (blocks % 8 == 0) ? 1 : 0;
+    const bool fast = (g.c % 128 == 0) && (g.r % BK == 0) && (g.r >= 2 * BK) && (g.k <= FAST_MAX_K) && !g.ragged;
 #define LRBI_LAUNCH_T(XV, SP)                                                                                      \
     do {                                                                                                           \
-        auto kern = mfma_gemm_t_kernel<Tag, BQ, WAVES_J, WAVES_Q, XV, SP>;                                          \
+        auto kern = fast ? mfma_gemm_t_kernel<Tag, BQ, WAVES_J, WAVES_Q, XV, SP, true>                              \
+                         : mfma_gemm_t_kernel<Tag, BQ, WAVES_J, WAVES_Q, XV, SP, false>;                            \
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) !=      \
             hipSuccess)                                                                                            \
             return LRBI_ERR_LAUNCH;                                                                                \
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kBwdThreads), smem, stream, g, (const uint16_t *)dW, \
                            ldw, dIp, dIz, (const uint16_t *)dDY, lddy, (int)N, (uint16_t *)dDX, lddx,              \
-                           (float *)dWorkspace, ldp, (int)jblocks, (int)qblocks, plan.iper, y_vec_ok);             \
+                           (float *)dWorkspace, ldp, (int)jblocks, (int)qblocks, plan.iper, xcd_remap, y_vec_ok);  \
     } while (0)
     if (xvec) {
         if (split) LRBI_LAUNCH_T(true, true);
@@ -648,7 +794,7 @@ int launch_grad(const Geom &g, lrbi_dtype dt, bool mfma, const void *dDY, int64_
         default: return LRBI_ERR_DTYPE;
         }
     }
-    const int64_t iblocks = (g.m + SmemG::BI - 1) / SmemG::BI, jblocks = (g.n + BJ - 1) / BJ;
+    const int64_t iblocks = (g.m + 127) / 128, jblocks = (g.n + BJ - 1) / BJ;
     const int64_t blocks = iblocks * jblocks;
     if (blocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
     const bool vec = (((uintptr_t)dDY & 15) == 0) && (lddy % 8 == 0) && (((uintptr_t)dX & 15) == 0) && (ldx % 8 == 0) &&

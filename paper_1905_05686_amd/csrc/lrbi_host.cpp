@@ -371,7 +371,9 @@ extern "C" int lrbi_masked_gemm_t(const lrbi_desc *desc, lrbi_dtype dtype, const
     if (!aligned_to(dW, (uintptr_t)es) || !aligned_to(dDY, (uintptr_t)es) || !aligned_to(dDX, (uintptr_t)es))
         return LRBI_ERR_ALIGN;
     const Geom g = make_geom(desc);
-    BwdPlan plan = plan_gemm_t(g, dtype, N, w_pieces_ok(desc, dW, ldw));
+    // the matrix-core kernel addresses a slab of 64 rows with 32-bit byte offsets
+    const bool small_pitch = ldw < ((int64_t)1 << 24) && lddy < ((int64_t)1 << 24);
+    BwdPlan plan = plan_gemm_t(g, dtype, N, w_pieces_ok(desc, dW, ldw) && small_pitch);
     if (plan.slices > 1) {
         const bool ws_ok = dWorkspace && aligned_to(dWorkspace, 16) && workspace_bytes >= plan.workspace_bytes;
         if (!ws_ok) { // no scratch: one slice over all rows of W

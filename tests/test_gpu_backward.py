@@ -80,6 +80,9 @@ EDGE = [
     (_small(130, 200, 65, 100, 40, 0.05, 136, "bf16"), 8),      # padded leading dimensions, rank above 32
     (_small(200, 136, 100, 136, 4, 0.3, 20, "f16"), 0),         # N not a multiple of 8
     (_small(1152, 1024, 576, 512, 145, 0.02, 128, "bf16"), 0),  # the paper's tile shape and a rank it uses
+    (_small(768, 256, 384, 128, 40, 0.05, 16, "bf16"), 0),      # slices that start inside a tile, two I_p words
+    (_small(1024, 384, 256, 384, 16, 0.1, 40, "f16"), 0),       # workgroups at three offsets inside a tile column
+    (_small(512, 128, 128, 128, 64, 0.03, 8, "f16"), 0),        # smallest tile rows of the tuned mask path, rank 64
     (_small(2048, 512, 512, 512, 32, 0.06, 4, "bf16"), 0),      # batch of 4: vector-ALU kernels at a large shape
 ]
 
