@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, "
+                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, lstm_sequence_C4, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -349,6 +349,55 @@ def main():
                 del Wl, tens
             except Exception as e:
                 others[key] = {"error": repr(e)}
+        # the LSTM configuration as a sequence: 2 layers x 35 fused steps (gate product + cell equations, h written
+        # straight into the next inputs), one graph replay; against the same sequence with separate product,
+        # reduction and (torch) gate kernels
+        if wanted is None or "lstm_sequence_C4" in wanted:
+            try:
+                Ld = workloads.make_lstm()
+                c = Ld["cfg"]
+                Hh, Bb, steps_, layers_ = Ld["hidden"], Ld["batch"], Ld["steps"], Ld["layers"]
+                de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
+                Wd = [to_dev(w, c.dtype) for w in Ld["W"]]
+                fac = [factors_to_dev(de, Ld["Ip01"][l], Ld["Iz01"][l]) for l in range(layers_)]
+                xs_ = to_dev(Ld["x"], c.dtype)
+                lws = torch.empty(lrbi.lstm_step_workspace_bytes(de, DC[c.dtype], Bb), dtype=torch.uint8, device=dev)
+                xh = [torch.zeros((2 * Hh, Bb), dtype=TD[c.dtype], device=dev) for _ in range(layers_)]
+                cs = [torch.zeros((Hh, Bb), dtype=torch.float32, device=dev) for _ in range(layers_)]
+
+                def fused_sequence():
+                    for t in range(steps_):
+                        xh[0][:Hh].copy_(xs_[t])
+                        for l in range(layers_):
+                            nxt = xh[l + 1][:Hh] if l + 1 < layers_ else None
+                            lrbi.lstm_step(de, Wd[l], fac[l][0], fac[l][1], xh[l], cs[l], xh[l][Hh:], nxt, workspace=lws)
+
+                gwb = lrbi.masked_gemm_workspace_bytes(de, DC[c.dtype], Bb)
+                gws = torch.empty(max(1, (gwb + 3) // 4), dtype=torch.float32, device=dev) if gwb else None
+                zbuf = torch.empty((c.m, Bb), dtype=TD[c.dtype], device=dev)
+
+                def unfused_sequence():
+                    for t in range(steps_):
+                        xh[0][:Hh].copy_(xs_[t])
+                        for l in range(layers_):
+                            z = lrbi.masked_gemm(de, Wd[l], fac[l][0], fac[l][1], xh[l], out=zbuf, workspace=gws).float()
+                            cs[l].copy_(torch.sigmoid(z[Hh:2 * Hh]) * cs[l] + torch.sigmoid(z[0:Hh]) * torch.tanh(z[2 * Hh:3 * Hh]))
+                            hcur = (torch.sigmoid(z[3 * Hh:]) * torch.tanh(cs[l])).to(TD[c.dtype])
+                            xh[l][Hh:].copy_(hcur)
+                            if l + 1 < layers_:
+                                xh[l + 1][:Hh].copy_(hcur)
+
+                ms_f, _ = event_times([fused_sequence], 3, 1)
+                ms_u, _ = event_times([unfused_sequence], 3, 1)
+                others["lstm_sequence_C4"] = {
+                    "workload": "LSTM, %d layers x %d steps, hidden %d, batch %d, gate matrix %dx%d %s, tiles %dx%d rank %d"
+                                % (layers_, steps_, Hh, Bb, c.m, c.n, c.dtype, c.r, c.c, c.k),
+                    "fused_sequence_ms": round(ms_f, 4), "fused_us_per_step": round(ms_f * 1e3 / (steps_ * layers_), 2),
+                    "unfused_sequence_ms": round(ms_u, 4),
+                    "dense_equiv_tflops_fused": round(2.0 * c.m * c.n * Bb * steps_ * layers_ / (ms_f * 1e-3) / 1e12, 2)}
+                del Wd, xs_, lws, xh, cs
+            except Exception as e:
+                others["lstm_sequence_C4"] = {"error": repr(e)}
         # backward pass through the masking layer: dX = (W o I_a)^T dY and dW = (dY X^T) o I_a
         for name in ("C2", "C3b"):
             key = "backward_" + name

@@ -303,6 +303,30 @@ int lrbi_masked_grad(const lrbi_desc *desc, lrbi_dtype dtype, const void *dDY, i
                      const void *dX, int64_t ldx, int64_t N, const void *dIp_packed,
                      const void *dIz_packed, void *dDW, int64_t lddw, void *stream);
 
+/*
+ * One LSTM step on a masked gate matrix (the paper's LSTM model, Sec. 4; it prints no cell
+ * equations, the usual ones are used).  desc: W is m x n with m = 4 H (row blocks i, f, g, o of
+ * H rows each) and n = the length of the stacked input [x_t; h_{t-1}].  Per call:
+ *   z = (W o I_a) XH                         (as lrbi_masked_gemm, kept in fp32)
+ *   c = sigm(z_f) c + sigm(z_i) tanh(z_g)    (dC, H x B fp32, updated in place)
+ *   h = sigm(z_o) tanh(c)                    (rounded to `dtype`, written to dH1 and, when not
+ *                                             NULL, dH2: e.g. the h rows of this layer's next
+ *                                             input and the x rows of the next layer's input)
+ * The gate product leaves the fp32 partial sums of its slices in the workspace and one more
+ * kernel adds them and applies the cell equations; z is never rounded to `dtype`.
+ *   dtype: LRBI_F16 or LRBI_BF16 (LRBI_ERR_DTYPE otherwise).  dW 16-byte aligned, ldw % 8 == 0,
+ *   n % 8 == 0 (LRBI_ERR_ALIGN otherwise).  dXH: n x B, ldxh >= B.  dC: ldc >= B.  dH1 / dH2: H x B,
+ *   ldh1 / ldh2 >= B; they may point into the buffer dXH points into (the product has finished
+ *   reading it when they are written).  dWorkspace: required, 16-byte aligned, at least
+ *   lrbi_lstm_step_workspace_bytes bytes (LRBI_ERR_WORKSPACE otherwise).  m % 4 != 0 is
+ *   LRBI_ERR_SHAPE.  Two kernel launches on `stream`.
+ */
+int lrbi_lstm_step_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t B, uint64_t *bytes);
+int lrbi_lstm_step(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                   const void *dIp_packed, const void *dIz_packed, const void *dXH, int64_t ldxh,
+                   int64_t B, float *dC, int64_t ldc, void *dH1, int64_t ldh1, void *dH2,
+                   int64_t ldh2, void *dWorkspace, uint64_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -85,11 +85,14 @@ def load_library():
     lib.lrbi_masked_gemm_t_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
     lib.lrbi_masked_gemm_t.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, u64, vp]
     lib.lrbi_masked_grad.argtypes = [pd, ctypes.c_int, vp, i64, vp, i64, i64, vp, vp, vp, i64, vp]
+    lib.lrbi_lstm_step_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
+    lib.lrbi_lstm_step.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, i64, vp, i64, vp, u64, vp]
     for name in ("lrbi_index_bits", "lrbi_index_bits_ranked", "lrbi_pack_factors_ranked", "lrbi_csr_bits",
                  "lrbi_pack_factors", "lrbi_unpack_mask", "lrbi_decode_mask",
                  "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm", "lrbi_threshold_eval",
                  "lrbi_threshold_eval_workspace_bytes", "lrbi_search_thresholds", "lrbi_search_workspace_bytes",
-                 "lrbi_masked_gemm_t_workspace_bytes", "lrbi_masked_gemm_t", "lrbi_masked_grad"):
+                 "lrbi_masked_gemm_t_workspace_bytes", "lrbi_masked_gemm_t", "lrbi_masked_grad",
+                 "lrbi_lstm_step_workspace_bytes", "lrbi_lstm_step"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -366,3 +369,35 @@ def masked_grad(desc: Desc, dY, X, dIp, dIz, out=None, stream=None):
         _dev_ptr(dIp, "Ip"), _dev_ptr(dIz, "Iz"), _dev_ptr(out, "dW"), out.stride(0), _stream_ptr(stream)),
         "lrbi_masked_grad")
     return out
+
+
+def lstm_step_workspace_bytes(desc: Desc, dtype_code: int, B: int) -> int:
+    out = ctypes.c_uint64()
+    _check(load_library().lrbi_lstm_step_workspace_bytes(ctypes.byref(desc), int(dtype_code), int(B), ctypes.byref(out)),
+           "lrbi_lstm_step_workspace_bytes")
+    return out.value
+
+
+def lstm_step(desc: Desc, W, dIp, dIz, XH, C, H1, H2=None, workspace=None, stream=None):
+    """lrbi_lstm_step: one LSTM step on the masked gate matrix W [4H, n].  XH [n, B] (f16 / bf16), C [H, B] float32
+    (updated in place), H1 (and H2, optional) [H, B] of W's dtype receive h; they may be row slices of the buffer XH
+    lives in.  `workspace`: device scratch of at least lstm_step_workspace_bytes bytes (allocated here when None)."""
+    import torch
+    Hh = desc.m // 4
+    B = XH.shape[1]
+    if W.shape != (desc.m, desc.n) or XH.shape[0] != desc.n or C.shape != (Hh, B) or C.dtype != torch.float32:
+        raise ValueError("shape mismatch")
+    for t in (H1, H2):
+        if t is not None and (t.shape != (Hh, B) or t.dtype != W.dtype or (B > 1 and t.stride(1) != 1)):
+            raise ValueError("bad h output tensor")
+    if W.stride(1) != 1 or (B > 1 and (XH.stride(1) != 1 or C.stride(1) != 1)) or XH.dtype != W.dtype:
+        raise ValueError("row-major tensors of one dtype expected")
+    if workspace is None:
+        workspace = torch.empty(lstm_step_workspace_bytes(desc, _dtype_code(W), B), dtype=torch.uint8, device=W.device)
+    _check(load_library().lrbi_lstm_step(
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), _dev_ptr(dIp, "Ip"), _dev_ptr(dIz, "Iz"),
+        _dev_ptr(XH, "XH"), XH.stride(0), B, _dev_ptr(C, "C"), C.stride(0), _dev_ptr(H1, "H1"), H1.stride(0),
+        _dev_ptr(H2, "H2") if H2 is not None else None, H2.stride(0) if H2 is not None else 0,
+        _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+        "lrbi_lstm_step")
+    return H1

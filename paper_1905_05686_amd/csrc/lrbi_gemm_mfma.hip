@@ -785,7 +785,7 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
     if (blocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
     const bool aligned = (g.c % BK) == 0;
     const bool xvec = (((uintptr_t)dX & 15) == 0) && (ldx % 8 == 0) && (N % 8 == 0);
-    const bool split = plan.splitk > 1;
+    const bool split = plan.splitk > 1 || plan.planes_only;
     const int y_vec_ok = (((uintptr_t)dY & 7) == 0) && (ldy % 4 == 0);
     const int xcd_remap = (blocks % 8 == 0) ? 1 : 0;
     const int64_t ldp = (N + 3) / 4 * 4;
@@ -834,7 +834,7 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
 #undef LRBI_LAUNCH
     LRBI_CHECK_LAUNCH();
 
-    if (split) return launch_reduce<Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
+    if (split && !plan.planes_only) return launch_reduce<Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
     return LRBI_OK;
 }
 

@@ -406,3 +406,50 @@ extern "C" int lrbi_masked_grad(const lrbi_desc *desc, lrbi_dtype dtype, const v
     return launch_grad(g, dtype, mfma, dDY, lddy, dX, ldx, N, (const uint32_t *)dIp_packed,
                        (const uint32_t *)dIz_packed, dDW, lddw, (hipStream_t)stream);
 }
+
+// plan of the gate product of an LSTM step: always the matrix-core kernels, planes left in the workspace
+static MfmaPlan plan_lstm(const lrbi_desc *desc, int64_t B)
+{
+    MfmaPlan plan = plan_mfma(make_geom(desc), desc->flags, B);
+    plan.planes_only = true;
+    const uint64_t ldp = (uint64_t)((B + 3) / 4 * 4);
+    plan.workspace_bytes = (uint64_t)plan.splitk * (uint64_t)desc->m * ldp * 4u;
+    return plan;
+}
+
+extern "C" int lrbi_lstm_step_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t B, uint64_t *bytes)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!bytes) return LRBI_ERR_NULL;
+    if (dtype != LRBI_F16 && dtype != LRBI_BF16) return LRBI_ERR_DTYPE;
+    if (B <= 0 || desc->m % 4 != 0) return LRBI_ERR_SHAPE;
+    *bytes = plan_lstm(desc, B).workspace_bytes;
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_lstm_step(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                              const void *dIp_packed, const void *dIz_packed, const void *dXH, int64_t ldxh, int64_t B,
+                              float *dC, int64_t ldc, void *dH1, int64_t ldh1, void *dH2, int64_t ldh2,
+                              void *dWorkspace, uint64_t workspace_bytes, void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dW || !dIp_packed || !dIz_packed || !dXH || !dC || !dH1 || !dWorkspace) return LRBI_ERR_NULL;
+    if (dtype != LRBI_F16 && dtype != LRBI_BF16) return LRBI_ERR_DTYPE;
+    if (B <= 0 || B > (int64_t)0x7FFFFF00 || desc->m % 4 != 0) return LRBI_ERR_SHAPE;
+    if (ldw < desc->n || ldxh < B || ldc < B || ldh1 < B || (dH2 && ldh2 < B)) return LRBI_ERR_PITCH;
+    if (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8)) return LRBI_ERR_ALIGN;
+    if (!aligned_to(dW, 16) || ldw % 8 != 0 || desc->n % 8 != 0) return LRBI_ERR_ALIGN; // the matrix-core kernels' W loads
+    if (!aligned_to(dXH, 2) || !aligned_to(dC, 4) || !aligned_to(dH1, 2) || !aligned_to(dH2, 2) ||
+        !aligned_to(dWorkspace, 16))
+        return LRBI_ERR_ALIGN;
+    const Geom g = make_geom(desc);
+    const MfmaPlan plan = plan_lstm(desc, B);
+    if (workspace_bytes < plan.workspace_bytes) return LRBI_ERR_WORKSPACE;
+    const int rc2 = launch_mfma_gemm(g, plan, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
+                                     dXH, ldxh, B, nullptr, 0, dWorkspace, (hipStream_t)stream);
+    if (rc2 != LRBI_OK) return rc2;
+    return launch_lstm_cell(dtype, (const float *)dWorkspace, plan.splitk, desc->m, (B + 3) / 4 * 4, B, dC, ldc, dH1, ldh1,
+                            dH2, ldh2, (hipStream_t)stream);
+}

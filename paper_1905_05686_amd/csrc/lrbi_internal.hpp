@@ -75,11 +75,18 @@ struct MfmaPlan {
     int splitk;   // number of slices of the n range
     int64_t kper; // columns of W per slice (multiple of the kernel's BK)
     uint64_t workspace_bytes;
+    // leave the fp32 planes of the slices in the workspace ([slice][m][ldp], ldp = N rounded up to 4) and skip the
+    // reduction into Y: a fused consumer (the LSTM cell kernel) adds and uses them
+    bool planes_only = false;
 };
 MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N);
 int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const void *dW, int64_t ldw,
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N,
                      void *dY, int64_t ldy, void *dWorkspace, hipStream_t stream);
+
+// LSTM cell on the fp32 planes of a gate product (lrbi_lstm.hip)
+int launch_lstm_cell(lrbi_dtype dt, const float *dPlanes, int slices, int64_t m, int64_t ldp, int64_t B, float *dC,
+                     int64_t ldc, void *dH1, int64_t ldh1, void *dH2, int64_t ldh2, hipStream_t stream);
 
 // register budget of a kernel, as resident wavefronts per SIMD (a host-only build ignores it)
 #if defined(__HIP__)

@@ -262,3 +262,32 @@ def test_backward_entry_points_reject_bad_arguments_before_any_launch():
     assert nb > 0 and nb % (9216 * 128 * 4) == 0
     assert lrbi.masked_gemm_t_workspace_bytes(big, lrbi.F32, 128) == 0
     assert lrbi.masked_gemm_t_workspace_bytes(big, lrbi.F16, 1) == 0
+
+
+def test_lstm_step_rejects_bad_arguments_before_any_launch():
+    lib = lrbi.load_library()
+    d = lrbi.Desc(8, 128, 4, 64, 2)
+    buf = (ctypes.c_uint8 * 4096)()
+    base = (ctypes.addressof(buf) + 63) // 64 * 64
+    p = ctypes.c_void_p(base)
+    f = lib.lrbi_lstm_step
+    args = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128), p, p,
+                         kw.get("XH", p), kw.get("ldxh", 16), kw.get("B", 16), kw.get("C", p), kw.get("ldc", 16),
+                         kw.get("H1", p), kw.get("ldh1", 16), kw.get("H2", None), kw.get("ldh2", 0), kw.get("ws", p),
+                         kw.get("wsb", 1 << 30), None]
+    assert f(*args(W=None)) == -1
+    assert f(*args(C=None)) == -1
+    assert f(*args(H1=None)) == -1
+    assert f(*args(ws=None)) == -1
+    assert f(*args(dt=lrbi.F32)) == -4
+    assert f(*args(B=0)) == -2
+    assert f(*args(d=lrbi.Desc(6, 128, 3, 64, 2))) == -2          # m must be 4 H
+    assert f(*args(ldw=120)) == -5
+    assert f(*args(ldc=8)) == -5
+    assert f(*args(H2=p, ldh2=8)) == -5
+    assert f(*args(ldw=132)) == -6                                 # W rows must be 16-byte pieces
+    assert f(*args(C=ctypes.c_void_p(base + 2))) == -6
+    assert f(*args(wsb=16)) == -8
+    # one fp32 plane of the whole gate matrix per slice
+    nb = lrbi.lstm_step_workspace_bytes(lrbi.Desc(6000, 3000, 300, 300, 8), lrbi.F16, 20)
+    assert nb > 0 and nb % (6000 * 20 * 4) == 0

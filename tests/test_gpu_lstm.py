@@ -64,3 +64,58 @@ def test_lstm_teacher_forced_and_free_running():
         ec = orc.rel_err(to_float64(c[l]), ref["c"][l])
         print("lstm free-running layer %d: h err %.3e, c err %.3e" % (l, eh, ec), flush=True)
         assert eh <= 1e-2 and ec <= 1e-2
+
+
+def test_fused_lstm_step_against_the_oracle():
+    """lrbi_lstm_step: gate product + cell equations in two launches, h written straight into the next inputs.
+    Teacher-forced single steps (oracle's inputs and cell state in, c_t and h_t compared), then the whole
+    free-running 2 x 35 sequence through the entry point alone."""
+    L = workloads.make_lstm()
+    cfg = L["cfg"]
+    H, B, steps, layers = L["hidden"], L["batch"], L["steps"], L["layers"]
+    Ws64 = [workloads.to_float64(w, cfg.dtype) for w in L["W"]]
+    Ms = [orc.decode_mask(L["Ip01"][l], L["Iz01"][l], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k) for l in range(layers)]
+    xs64 = workloads.to_float64(L["x"], cfg.dtype)
+    ref = lstm_oracle.lstm_sequence(Ws64, Ms, xs64, round_input=_round_f16, threads=ORACLE_THREADS)
+    desc = desc_of(cfg)
+    dW = [to_device(w, cfg.dtype) for w in L["W"]]
+    fac = [device_factors(desc, L["Ip01"][l], L["Iz01"][l]) for l in range(layers)]
+    ws = torch.empty(lrbi.lstm_step_workspace_bytes(desc, lrbi.F16, B), dtype=torch.uint8, device="cuda")
+
+    def sigm(z):
+        return 1.0 / (1.0 + np.exp(-z))
+
+    # teacher-forced: a few (step, layer) pairs; the expected c_t, h_t follow from the oracle's z and a c_{t-1} of our own
+    rng = np.random.default_rng(3)
+    for (t, l) in [(0, 0), (1, 1), (17, 0), (34, 1)]:
+        xh = torch.from_numpy(ref["xh"][t][l].astype(np.float16)).cuda()
+        c_prev = rng.standard_normal((H, B)).astype(np.float32)
+        C = torch.from_numpy(c_prev.copy()).cuda()
+        h1 = torch.empty((H, B), dtype=torch.float16, device="cuda")
+        h2 = torch.empty((H, B), dtype=torch.float16, device="cuda")
+        lrbi.lstm_step(desc, dW[l], fac[l][0], fac[l][1], xh, C, h1, h2, workspace=ws)
+        torch.cuda.synchronize()
+        z = ref["z"][t][l]
+        c_ref = sigm(z[H:2 * H]) * c_prev.astype(np.float64) + sigm(z[0:H]) * np.tanh(z[2 * H:3 * H])
+        h_ref = sigm(z[3 * H:4 * H]) * np.tanh(c_ref)
+        ec, eh = orc.rel_err(to_float64(C), c_ref), orc.rel_err(to_float64(h1), h_ref)
+        print("fused step (t=%d, layer %d): c err %.3e, h err %.3e" % (t, l, ec, eh), flush=True)
+        assert ec <= 1e-2 and eh <= 1e-2 and torch.equal(h1, h2)
+
+    # free-running: per layer one [2H, B] input buffer; a step reads it and writes h_t into its lower half and into
+    # the next layer's upper half
+    xs = to_device(L["x"], cfg.dtype)
+    xh = [torch.zeros((2 * H, B), dtype=torch.float16, device="cuda") for _ in range(layers)]
+    c = [torch.zeros((H, B), dtype=torch.float32, device="cuda") for _ in range(layers)]
+    last = torch.empty((H, B), dtype=torch.float16, device="cuda")
+    for t in range(steps):
+        xh[0][:H].copy_(xs[t])
+        for l in range(layers):
+            nxt = xh[l + 1][:H] if l + 1 < layers else None
+            lrbi.lstm_step(desc, dW[l], fac[l][0], fac[l][1], xh[l], c[l], xh[l][H:], nxt, workspace=ws)
+    torch.cuda.synchronize()
+    for l in range(layers):
+        eh = orc.rel_err(to_float64(xh[l][H:]), ref["h"][l])
+        ec = orc.rel_err(to_float64(c[l]), ref["c"][l])
+        print("fused free-running layer %d: h err %.3e, c err %.3e" % (l, eh, ec), flush=True)
+        assert eh <= 1e-2 and ec <= 1e-2
