@@ -327,6 +327,28 @@ int lrbi_lstm_step(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int6
                    int64_t B, float *dC, int64_t ldc, void *dH1, int64_t ldh1, void *dH2,
                    int64_t ldh2, void *dWorkspace, uint64_t workspace_bytes, void *stream);
 
+/*
+ * Non-negative factorisation of the magnitude matrix, every tile on its own (Algorithm 1's first
+ * step, Sec. 2.2: M = |W| ~ M_p M_z with M_p (r x k), M_z (k x c) >= 0, minimising the Frobenius
+ * distance).  The paper uses an off-the-shelf library and names no algorithm; this entry point
+ * runs `iters` multiplicative updates of Lee and Seung for that objective from the caller's
+ * starting point, M_z first, then M_p:
+ *     M_z <- M_z * (M_p^T M) / (M_p^T M_p M_z + eps),   M_p <- M_p * (M M_z^T) / (M_p M_z M_z^T + eps)
+ * Its result feeds lrbi_search_thresholds.
+ *   method (Sec. 3.2, weight-magnitude manipulation, applied to |W| on the fly): 1 none, 2 squared,
+ *   3 multiplied by `amplify` (the paper's 1 / (1 - S)) where |W| >= w_threshold.  W must be finite.
+ *   dW: m x n of `dtype`, ldw >= n.  dMp [T][r][k], dMz [T][k][c] float: on entry the (positive,
+ *   e.g. uniform random) starting point, on return the factors; the rows / columns a cut-off edge
+ *   tile does not use are left as given.  eps > 0.  fp32 arithmetic, fixed summation order.
+ *   dWorkspace: required, 16-byte aligned, at least lrbi_nmf_workspace_bytes bytes (a second copy of
+ *   both factors).  Limits: k <= 64 (LRBI_ERR_RANK otherwise); method outside 1 .. 3, iters < 0 or
+ *   eps <= 0 are LRBI_ERR_SHAPE.  2 + 2 iters (+ 2) kernel launches on `stream`.
+ */
+int lrbi_nmf_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
+int lrbi_nmf(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw, int32_t method,
+             float w_threshold, float amplify, float *dMp, float *dMz, int32_t iters, float eps,
+             void *dWorkspace, uint64_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

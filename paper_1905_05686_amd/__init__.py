@@ -8,7 +8,7 @@ from .binding import (  # noqa: F401
     BF16, F16, F32, FLAG_DECODE_GENERIC, FLAG_PATH_MFMA, FLAG_PATH_VALU, Desc, LrbiError, csr_bits, decode_mask,
     flag_splitk, flag_tile, index_bits, index_bits_ranked, library_path, load_library, lstm_step,
     lstm_step_workspace_bytes, masked_gemm, masked_gemm_t,
-    masked_gemm_t_workspace_bytes, masked_gemm_workspace_bytes, masked_grad,
+    masked_gemm_t_workspace_bytes, masked_gemm_workspace_bytes, masked_grad, nmf, nmf_workspace_bytes,
     pack_factors, search_thresholds, search_workspace_bytes, strerror, threshold_eval, threshold_eval_workspace_bytes,
     unpack_mask,
 )

@@ -86,13 +86,16 @@ def load_library():
     lib.lrbi_masked_gemm_t.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, u64, vp]
     lib.lrbi_masked_grad.argtypes = [pd, ctypes.c_int, vp, i64, vp, i64, i64, vp, vp, vp, i64, vp]
     lib.lrbi_lstm_step_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
+    lib.lrbi_nmf_workspace_bytes.argtypes = [pd, pu64]
+    lib.lrbi_nmf.argtypes = [pd, ctypes.c_int, vp, i64, i32, ctypes.c_float, ctypes.c_float, vp, vp, i32, ctypes.c_float,
+                             vp, u64, vp]
     lib.lrbi_lstm_step.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, i64, vp, i64, vp, u64, vp]
     for name in ("lrbi_index_bits", "lrbi_index_bits_ranked", "lrbi_pack_factors_ranked", "lrbi_csr_bits",
                  "lrbi_pack_factors", "lrbi_unpack_mask", "lrbi_decode_mask",
                  "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm", "lrbi_threshold_eval",
                  "lrbi_threshold_eval_workspace_bytes", "lrbi_search_thresholds", "lrbi_search_workspace_bytes",
                  "lrbi_masked_gemm_t_workspace_bytes", "lrbi_masked_gemm_t", "lrbi_masked_grad",
-                 "lrbi_lstm_step_workspace_bytes", "lrbi_lstm_step"):
+                 "lrbi_lstm_step_workspace_bytes", "lrbi_lstm_step", "lrbi_nmf_workspace_bytes", "lrbi_nmf"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -401,3 +404,29 @@ def lstm_step(desc: Desc, W, dIp, dIz, XH, C, H1, H2=None, workspace=None, strea
         _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
         "lrbi_lstm_step")
     return H1
+
+
+def nmf_workspace_bytes(desc: Desc) -> int:
+    out = ctypes.c_uint64()
+    _check(load_library().lrbi_nmf_workspace_bytes(ctypes.byref(desc), ctypes.byref(out)), "lrbi_nmf_workspace_bytes")
+    return out.value
+
+
+def nmf(desc: Desc, W, Mp, Mz, iters: int, eps: float = 1e-9, method: int = 1, w_threshold: float = 0.0,
+        amplify: float = 1.0, workspace=None, stream=None):
+    """lrbi_nmf: multiplicative updates of |W| ~ Mp Mz per tile, in place.  W [m, n] (f32 / f16 / bf16), Mp [T, r, k],
+    Mz [T, k, c] contiguous float32 device tensors holding the starting point.  Returns (Mp, Mz)."""
+    import torch
+    T = desc.tiles
+    if W.dim() != 2 or W.shape != (desc.m, desc.n) or W.stride(1) != 1:
+        raise ValueError("W must be a row-major [m, n] tensor")
+    for t, shape in ((Mp, (T, desc.r, desc.k)), (Mz, (T, desc.k, desc.c))):
+        if t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError("factor tensors must be contiguous float32 of shape %s" % (shape,))
+    if workspace is None:
+        workspace = torch.empty(nmf_workspace_bytes(desc), dtype=torch.uint8, device=W.device)
+    _check(load_library().lrbi_nmf(
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), int(method), float(w_threshold), float(amplify),
+        _dev_ptr(Mp, "Mp"), _dev_ptr(Mz, "Mz"), int(iters), float(eps), _dev_ptr(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), _stream_ptr(stream)), "lrbi_nmf")
+    return Mp, Mz

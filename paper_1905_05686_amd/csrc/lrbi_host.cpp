@@ -453,3 +453,33 @@ extern "C" int lrbi_lstm_step(const lrbi_desc *desc, lrbi_dtype dtype, const voi
     return launch_lstm_cell(dtype, (const float *)dWorkspace, plan.splitk, desc->m, (B + 3) / 4 * 4, B, dC, ldc, dH1, ldh1,
                             dH2, ldh2, (hipStream_t)stream);
 }
+
+extern "C" int lrbi_nmf_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!bytes) return LRBI_ERR_NULL;
+    *bytes = nmf_workspace_bytes(make_geom(desc));
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_nmf(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw, int32_t method,
+                        float w_threshold, float amplify, float *dMp, float *dMz, int32_t iters, float eps,
+                        void *dWorkspace, uint64_t workspace_bytes, void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dW || !dMp || !dMz || !dWorkspace) return LRBI_ERR_NULL;
+    const int es = elem_size(dtype);
+    if (es == 0) return LRBI_ERR_DTYPE;
+    if (desc->k > 64) return LRBI_ERR_RANK;
+    if (method < 1 || method > 3 || iters < 0 || !(eps > 0.f)) return LRBI_ERR_SHAPE;
+    if (ldw < desc->n) return LRBI_ERR_PITCH;
+    if (!aligned_to(dW, (uintptr_t)es) || !aligned_to(dMp, 4) || !aligned_to(dMz, 4) || !aligned_to(dWorkspace, 16))
+        return LRBI_ERR_ALIGN;
+    const Geom g = make_geom(desc);
+    if (workspace_bytes < nmf_workspace_bytes(g)) return LRBI_ERR_WORKSPACE;
+    if (iters == 0) return LRBI_OK;
+    return launch_nmf(g, dtype, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, dWorkspace,
+                      (hipStream_t)stream);
+}

@@ -84,6 +84,11 @@ int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const v
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N,
                      void *dY, int64_t ldy, void *dWorkspace, hipStream_t stream);
 
+// non-negative factorisation of the magnitude matrix (lrbi_nmf.hip)
+uint64_t nmf_workspace_bytes(const Geom &g);
+int launch_nmf(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, int method, float w_threshold, float amplify,
+               float *dMp, float *dMz, int iters, float eps, void *dWorkspace, hipStream_t stream);
+
 // LSTM cell on the fp32 planes of a gate product (lrbi_lstm.hip)
 int launch_lstm_cell(lrbi_dtype dt, const float *dPlanes, int slices, int64_t m, int64_t ldp, int64_t B, float *dC,
                      int64_t ldc, void *dH1, int64_t ldh1, void *dH2, int64_t ldh2, hipStream_t stream);

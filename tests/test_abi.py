@@ -291,3 +291,29 @@ def test_lstm_step_rejects_bad_arguments_before_any_launch():
     # one fp32 plane of the whole gate matrix per slice
     nb = lrbi.lstm_step_workspace_bytes(lrbi.Desc(6000, 3000, 300, 300, 8), lrbi.F16, 20)
     assert nb > 0 and nb % (6000 * 20 * 4) == 0
+
+
+def test_nmf_rejects_bad_arguments_before_any_launch():
+    lib = lrbi.load_library()
+    d = lrbi.Desc(8, 128, 4, 64, 2)
+    buf = (ctypes.c_uint8 * 4096)()
+    base = (ctypes.addressof(buf) + 63) // 64 * 64
+    p = ctypes.c_void_p(base)
+    f = lib.lrbi_nmf
+    args = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128),
+                         kw.get("method", 1), 0.5, 2.0, kw.get("Mp", p), p, kw.get("iters", 3), kw.get("eps", 1e-9),
+                         kw.get("ws", p), kw.get("wsb", 1 << 30), None]
+    assert f(*args(W=None)) == -1
+    assert f(*args(Mp=None)) == -1
+    assert f(*args(ws=None)) == -1
+    assert f(*args(dt=9)) == -4
+    assert f(*args(d=lrbi.Desc(8, 128, 4, 64, 65))) == -3           # ranks above 64 are not served
+    assert f(*args(method=0)) == -2
+    assert f(*args(method=4)) == -2
+    assert f(*args(iters=-1)) == -2
+    assert f(*args(eps=0.0)) == -2
+    assert f(*args(ldw=100)) == -5
+    assert f(*args(Mp=ctypes.c_void_p(base + 2))) == -6
+    assert f(*args(wsb=8)) == -8
+    # a second copy of both factors
+    assert lrbi.nmf_workspace_bytes(lrbi.Desc(4096, 9216, 256, 256, 16)) == 2 * 576 * 256 * 16 * 4
