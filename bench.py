@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, lstm_sequence_C4, "
+                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, lstm_sequence_C4, nmf_C2, nmf_C3, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -429,6 +429,42 @@ def main():
                     "grad_GBs": round(byt_t / (ms_g * 1e-3) / 1e9, 1),
                     "grad_hbm_frac": round(byt_t / (ms_g * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
                 del Wl, dWl, X_, dY_, dX_
+            except Exception as e:
+                others[key] = {"error": repr(e)}
+        # non-negative factorisation of |W| per tile (Algorithm 1's first step): multiplicative updates on C2 and C3
+        for name in ("C2", "C3a"):
+            key = "nmf_" + name[:2]
+            if wanted is not None and key not in wanted:
+                continue
+            try:
+                c = workloads.CONFIGS[name]
+                d = workloads.make(c, want_x=False)
+                de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
+                W_ = to_dev(d["W"], c.dtype)
+                f = workloads.make_real_factors(c)
+                Mp_, Mz_ = torch.from_numpy(f["Mp"]).to(dev) + 0.05, torch.from_numpy(f["Mz"]).to(dev) + 0.05
+                nws = torch.empty(lrbi.nmf_workspace_bytes(de), dtype=torch.uint8, device=dev)
+                iters_ = 20
+                run = lambda: lrbi.nmf(de, W_, Mp_, Mz_, iters_, workspace=nws)
+                run()
+                torch.cuda.synchronize()
+                ts = []
+                for _ in range(3):
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    run()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ts.append(e0.elapsed_time(e1))
+                ms = float(sorted(ts)[1])
+                fl = iters_ * 4.0 * c.m * c.n * c.k  # two products with the magnitude matrix per iteration
+                others[key] = {"workload": "%s: |W| %dx%d %s, tiles %dx%d, rank %d, %d multiplicative updates"
+                                           % (name[:2], c.m, c.n, c.dtype, c.r, c.c, c.k, iters_),
+                               "ms": round(ms, 4), "us_per_iteration": round(ms * 1e3 / iters_, 2),
+                               "tflops_fp32": round(fl / (ms * 1e-3) / 1e12, 2),
+                               "alu_frac_of_157_tflops": round(fl / (ms * 1e-3) / 1e12 / 157.3, 4)}
+                del W_, Mp_, Mz_, nws
             except Exception as e:
                 others[key] = {"error": repr(e)}
         # the whole threshold search of Algorithm 1 for a layer: sort, then n_sp x steps candidates (W stays in the

@@ -21,6 +21,7 @@ namespace lrbi {
 static constexpr int kNmfThreads = 256;
 static constexpr int kNmfStageFloats = 8192; // 32 KiB of staged factor rows
 static constexpr int kNmfMaxK = 64;
+static constexpr int ZB = 16; // rows of W requested together in the M_z update
 
 template <typename T> struct NmfElem;
 template <> struct NmfElem<float> {
@@ -36,10 +37,11 @@ template <> struct NmfElem<__hip_bfloat16> {
 // magnitude with the manipulation of Sec. 3.2: 1 none, 2 squared, 3 amplified where magnitude pruning keeps the weight
 template <typename T> __device__ __forceinline__ float nmf_mag(T w, int method, float w_threshold, float amplify)
 {
+    // selects, not branches: a branch per element kept the compiler from requesting a batch of loads together
     const float a = fabsf(NmfElem<T>::to_f32(w));
-    if (method == 2) return a * a;
-    if (method == 3) return (a >= w_threshold) ? a * amplify : a;
-    return a;
+    const float squared = a * a;
+    const float amplified = (a >= w_threshold) ? a * amplify : a;
+    return (method == 2) ? squared : ((method == 3) ? amplified : a);
 }
 
 __device__ __forceinline__ void nmf_tile_extent(const Geom &g, int64_t t, int &ti, int &tj, int &rt, int &ct)
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const
                                                                   const float *__restrict__ MzCur,
                                                                   float *__restrict__ MzNew, float eps, int cblocks)
 {
-    static __shared__ float stage[kNmfStageFloats];       // [rows of the chunk][k]
+    __align__(16) static __shared__ float stage[kNmfStageFloats];       // [rows of the chunk][k]
     static __shared__ float gram[kNmfMaxK * kNmfMaxK];    // M_p^T M_p
     const int64_t t = blockIdx.x / cblocks;
     const int cb = (int)(blockIdx.x - t * cblocks);
@@ -68,6 +70,7 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const
     const int j = cb * kNmfThreads + tid;
     const bool live = j < ct;
     const int k = g.k;
+    const bool k4 = (k % 4) == 0;
     const int rows_per_chunk = kNmfStageFloats / k;
     const float *mp = Mp + t * (int64_t)g.r * k;
     const float *mzc = MzCur + t * (int64_t)k * g.c;
@@ -77,6 +80,8 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const
     for (int e = tid; e < k * k; e += kNmfThreads) gram[e] = 0.f;
 
     for (int l0 = 0; l0 < k; l0 += KC) {
+        const bool full = l0 + KC <= k;             // every rank of this pass exists
+        const int kt = full ? KC : k - l0;          // ranks of this pass
         float acc[KC];
 #pragma unroll
         for (int l = 0; l < KC; ++l) acc[l] = 0.f;
@@ -94,12 +99,40 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const
                 }
             }
             if (live) {
-                for (int i = 0; i < rows; ++i) {
-                    const float m = nmf_mag<T>(wcol[(int64_t)(i0 + i) * ldw], method, w_threshold, amplify);
-                    const float *row = stage + i * k + l0;
+                // sixteen rows at a time: their W loads are requested together; the rows of M_p come out of the staged
+                // chunk as broadcast reads (reading them from global memory at lane-uniform addresses, i.e. as scalar
+                // loads, was measured slower: 165 us against 100 us per launch on the 256 x 256, rank 16 layer)
+                for (int i = 0; i < rows; i += ZB) {
+                    T raw[ZB];
+                    float mv[ZB];
 #pragma unroll
-                    for (int l = 0; l < KC; ++l)
-                        if (l0 + l < k) acc[l] = fmaf(row[l], m, acc[l]);
+                    for (int u = 0; u < ZB; ++u) {
+                        const int iu = (i + u < rows) ? i + u : rows - 1; // clamped: always a valid row
+                        raw[u] = wcol[(int64_t)(i0 + iu) * ldw];
+                    }
+#pragma unroll
+                    for (int u = 0; u < ZB; ++u) {
+                        const float m = nmf_mag<T>(raw[u], method, w_threshold, amplify);
+                        mv[u] = (i + u < rows) ? m : 0.f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < ZB; ++u) {
+                        const int iu = (i + u < rows) ? i + u : rows - 1;
+                        const float *row = stage + iu * k + l0;
+                        if (full && k4) { // rows of the staged chunk are 16-byte aligned: four ranks per LDS read
+#pragma unroll
+                            for (int l = 0; l < KC; l += 4) {
+                                const float4 v = *reinterpret_cast<const float4 *>(row + l);
+                                acc[l + 0] = fmaf(v.x, mv[u], acc[l + 0]);
+                                acc[l + 1] = fmaf(v.y, mv[u], acc[l + 1]);
+                                acc[l + 2] = fmaf(v.z, mv[u], acc[l + 2]);
+                                acc[l + 3] = fmaf(v.w, mv[u], acc[l + 3]);
+                            }
+                        } else { // ranks beyond k repeat the last one; their sums are never stored
+#pragma unroll
+                            for (int l = 0; l < KC; ++l) acc[l] = fmaf(row[l < kt ? l : kt - 1], mv[u], acc[l]);
+                        }
+                    }
                 }
             }
         }
@@ -130,9 +163,10 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
                                                                   float w_threshold, float amplify,
                                                                   const float *__restrict__ MpCur,
                                                                   const float *__restrict__ Mz,
-                                                                  float *__restrict__ MpNew, float eps, int rblocks)
+                                                                  float *__restrict__ MpNew, float eps, int rblocks,
+                                                                  int w_vec_ok)
 {
-    static __shared__ float stage[kNmfStageFloats];       // [columns of the chunk][k]: M_z transposed
+    __align__(16) static __shared__ float stage[kNmfStageFloats];       // [columns of the chunk][k]: M_z transposed
     static __shared__ float gram[kNmfMaxK * kNmfMaxK];    // M_z M_z^T
     const int64_t t = blockIdx.x / rblocks;
     const int rb = (int)(blockIdx.x - t * rblocks);
@@ -142,7 +176,8 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
     const int i = rb * kNmfThreads + tid;
     const bool live = i < rt;
     const int k = g.k;
-    const int cols_per_chunk = kNmfStageFloats / k;
+    const bool k4 = (k % 4) == 0;
+    const int cols_per_chunk = (kNmfStageFloats / k) & ~7; // a multiple of 8 keeps later chunks aligned
     const float *mz = Mz + t * (int64_t)k * g.c;
     const float *mpc = MpCur + (t * (int64_t)g.r + (live ? i : 0)) * k;
     float *mpn = MpNew + (t * (int64_t)g.r + (live ? i : 0)) * k;
@@ -151,6 +186,8 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
     for (int e = tid; e < k * k; e += kNmfThreads) gram[e] = 0.f;
 
     for (int l0 = 0; l0 < k; l0 += KC) {
+        const bool full = l0 + KC <= k;             // every rank of this pass exists
+        const int kt = full ? KC : k - l0;          // ranks of this pass
         float acc[KC];
 #pragma unroll
         for (int l = 0; l < KC; ++l) acc[l] = 0.f;
@@ -172,12 +209,49 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
                 }
             }
             if (live) {
-                for (int jj = 0; jj < cols; ++jj) {
-                    const float m = nmf_mag<T>(wrow[j0 + jj], method, w_threshold, amplify);
-                    const float *col = stage + jj * k + l0;
+                // eight columns at a time: one 16-byte load of the lane's row of W where the alignment allows it
+                constexpr int VEC = 16 / (int)sizeof(T);
+                const bool vec = w_vec_ok && (((int64_t)tj * g.c + j0) % VEC == 0);
+                for (int jj = 0; jj < cols; jj += 8) {
+                    float mv[8];
+                    if (vec && jj + 8 <= cols) {
+                        T tmp[8];
 #pragma unroll
-                    for (int l = 0; l < KC; ++l)
-                        if (l0 + l < k) acc[l] = fmaf(col[l], m, acc[l]);
+                        for (int q = 0; q < 8 / VEC; ++q)
+                            *reinterpret_cast<uint4 *>(tmp + q * VEC) = *reinterpret_cast<const uint4 *>(wrow + j0 + jj + q * VEC);
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) mv[u] = nmf_mag<T>(tmp[u], method, w_threshold, amplify);
+                    } else {
+                        T raw[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const int ju = (jj + u < cols) ? jj + u : cols - 1;
+                            raw[u] = wrow[j0 + ju];
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const float m = nmf_mag<T>(raw[u], method, w_threshold, amplify);
+                            mv[u] = (jj + u < cols) ? m : 0.f;
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int ju = (jj + u < cols) ? jj + u : cols - 1;
+                        const float *col = stage + ju * k + l0;
+                        if (full && k4) { // rows of the staged chunk are 16-byte aligned: four ranks per LDS read
+#pragma unroll
+                            for (int l = 0; l < KC; l += 4) {
+                                const float4 v = *reinterpret_cast<const float4 *>(col + l);
+                                acc[l + 0] = fmaf(v.x, mv[u], acc[l + 0]);
+                                acc[l + 1] = fmaf(v.y, mv[u], acc[l + 1]);
+                                acc[l + 2] = fmaf(v.z, mv[u], acc[l + 2]);
+                                acc[l + 3] = fmaf(v.w, mv[u], acc[l + 3]);
+                            }
+                        } else { // ranks beyond k repeat the last one; their sums are never stored
+#pragma unroll
+                            for (int l = 0; l < KC; ++l) acc[l] = fmaf(col[l < kt ? l : kt - 1], mv[u], acc[l]);
+                        }
+                    }
                 }
             }
         }
@@ -221,12 +295,13 @@ static int nmf_iterate(const Geom &g, const void *dW, int64_t ldw, int method, f
     const int cblocks = (g.c + kNmfThreads - 1) / kNmfThreads, rblocks = (g.r + kNmfThreads - 1) / kNmfThreads;
     if (tiles * cblocks > 0x7FFFFFFF || tiles * rblocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
     float *mp_cur = dMp, *mp_new = wsMp, *mz_cur = dMz, *mz_new = wsMz;
+    const int w_vec_ok = (((uintptr_t)dW & 15) == 0) && ((ldw * (int64_t)sizeof(T)) % 16 == 0);
     for (int it = 0; it < iters; ++it) {
         hipLaunchKernelGGL((nmf_update_z_kernel<T, KC>), dim3((unsigned)(tiles * cblocks)), dim3(kNmfThreads), 0, stream, g,
                            (const T *)dW, ldw, method, w_threshold, amplify, mp_cur, mz_cur, mz_new, eps, cblocks);
         LRBI_CHECK_LAUNCH();
         hipLaunchKernelGGL((nmf_update_p_kernel<T, KC>), dim3((unsigned)(tiles * rblocks)), dim3(kNmfThreads), 0, stream, g,
-                           (const T *)dW, ldw, method, w_threshold, amplify, mp_cur, mz_new, mp_new, eps, rblocks);
+                           (const T *)dW, ldw, method, w_threshold, amplify, mp_cur, mz_new, mp_new, eps, rblocks, w_vec_ok);
         LRBI_CHECK_LAUNCH();
         float *tmp = mp_cur;
         mp_cur = mp_new;
