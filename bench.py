@@ -9,7 +9,7 @@ kernel.  Inputs are resident in HBM before the timed region.  Weights rotate
 over several buffers so that W streams from HBM and not from the 256 MB
 last-level cache, as it would inside a network whose layers do not fit there.
 
-Prints ONE JSON line (see README for the fields).  `value` is the
+Prints ONE JSON line.  `value` is the
 dense-equivalent TFLOP/s of the step; the decode part of the metric (Gbit/s on a
 mask larger than 1 GiB) and the other configurations ride along as extra keys.
 """
@@ -29,7 +29,7 @@ MFMA_PEAK_TFLOPS = 2500.0   # dense bf16 / fp16
 
 def _die_multi_gpu(n):
     print("bench.py measures one GPU: this build has no multi-GPU path (the kernels shard by tile "
-          "rows without any exchange step, see DESIGN.md); --gpus %d is not supported." % n, file=sys.stderr)
+          "rows without any exchange step); --gpus %d is not supported." % n, file=sys.stderr)
     sys.exit(2)
 
 
