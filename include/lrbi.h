@@ -255,8 +255,8 @@ int lrbi_threshold_eval_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
  * on-chip memory, a larger one in the workspace, more slowly); LRBI_ERR_SHAPE otherwise, and
  * for n_sp < 1, steps < 1, tolerance < 0, S outside (0, 1) or an S_p outside [0, 1].
  * Costs of candidates that differ by less than the rounding of a double-precision sum may
- * rank either way.  2 + n_sp (1 + 2 steps .. 3 steps) + (0 .. 2) launches on `stream`; the
- * host does not wait for the device.
+ * rank either way.  2 + n_sp (1 + steps .. 2 steps) + (0 .. 2) launches on `stream` (a tile's
+ * search state is advanced inside the evaluation launches); the host does not wait for the device.
  */
 int lrbi_search_thresholds(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
                            float w_threshold, const float *dMp, const float *dMz,

@@ -56,6 +56,92 @@ template <> __device__ __forceinline__ float piece_abs<__hip_bfloat16>(const uin
     return fabsf(__builtin_bit_cast(float, h));
 }
 
+// per-tile state of the threshold search
+struct SearchState {
+    double lo, hi, sz;     // bisection interval and current probe of S_z
+    double rep_cost;       // representative of the current S_p: the probe closest to the target
+    long long rep_diff;    // |ones - target| of the representative, -1 = none yet
+    unsigned long long rep_kept;
+    float rep_tz;
+    float tp;              // threshold of I_p for the current S_p
+    long long best_diff;   // winner so far, -1 = none
+    int best_eligible;
+    int pad;
+};
+
+// rows x columns of tile t's part inside the matrix
+__device__ __forceinline__ void tile_extent(const Geom &g, int64_t t, int &rt, int &ct)
+{
+    const int64_t ti = t / g.tile_cols, tj = t - ti * g.tile_cols;
+    rt = (int)((g.m - ti * g.r < g.r) ? g.m - ti * g.r : g.r);
+    ct = (int)((g.n - tj * g.c < g.c) ? g.n - tj * g.c : g.c);
+}
+
+// entry of the sorted factor at index round(sparsity * count): entries below it become 0
+__device__ __forceinline__ float threshold_at(const float *sorted, int count, double sparsity)
+{
+    // separate multiply and add (no fused operation): the index must be the same as in plain double arithmetic
+    long long idx = (long long)floor(__dadd_rn(__dmul_rn(sparsity, (double)count), 0.5));
+    if (idx < 0) idx = 0;
+    return (idx >= count) ? __builtin_inff() : sorted[idx];
+}
+
+// What the threshold search (further down) does with a tile's result after every probe.  It runs in the evaluation
+// itself: by the lane that has just written the tile's ones and cost (one workgroup per tile), or by the lane that
+// adds the bands of the tile, so a probe costs no launch of its own for this.  st == nullptr: plain evaluation.
+struct SearchStepArgs {
+    SearchState *st;
+    const float *sortedMz;
+    int64_t stride_z;
+    double keep_fraction;  // 1 - S
+    long long tolerance;
+    int last_step;
+    float *Tz;             // the thresholds being probed: read, then replaced by the next probe's
+    float *TpBest, *TzBest;
+    unsigned long long *KeptBest;
+    double *CostBest;
+};
+
+__device__ __forceinline__ void search_step_tile(const Geom &g, const SearchStepArgs &a, int64_t t, unsigned long long kept,
+                                                 double cost)
+{
+    int rt, ct;
+    tile_extent(g, t, rt, ct);
+    // target number of ones of this tile, round((1 - S) rt ct), in plain double arithmetic
+    const long long target =
+        (long long)floor(__dadd_rn(__dmul_rn(__dmul_rn(a.keep_fraction, (double)rt), (double)ct), 0.5));
+    SearchState s = a.st[t];
+    const long long k = (long long)kept;
+    const long long diff = (k > target) ? k - target : target - k;
+    if (s.rep_diff < 0 || diff < s.rep_diff) {
+        s.rep_diff = diff;
+        s.rep_tz = a.Tz[t];
+        s.rep_kept = kept;
+        s.rep_cost = cost;
+    }
+    if (k > target) s.lo = s.sz; // too many ones: I_z must get sparser
+    else s.hi = s.sz;
+    s.sz = 0.5 * (s.lo + s.hi);
+    a.Tz[t] = threshold_at(a.sortedMz + t * a.stride_z, g.k * ct, s.sz);
+    if (a.last_step) {
+        const int eligible = s.rep_diff <= a.tolerance;
+        bool better;
+        if (s.best_diff < 0) better = true;
+        else if (eligible != s.best_eligible) better = eligible != 0;
+        else if (eligible) better = s.rep_cost < a.CostBest[t];
+        else better = s.rep_diff < s.best_diff;
+        if (better) {
+            s.best_diff = s.rep_diff;
+            s.best_eligible = eligible;
+            a.TpBest[t] = s.tp;
+            a.TzBest[t] = s.rep_tz;
+            a.KeptBest[t] = s.rep_kept;
+            a.CostBest[t] = s.rep_cost;
+        }
+    }
+    a.st[t] = s;
+}
+
 template <typename T>
 __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, const T *__restrict__ W, int64_t ldw,
                                                                       float w_threshold,
@@ -67,7 +153,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
                                                                       uint32_t *__restrict__ IzOut,
                                                                       unsigned long long *__restrict__ Kept,
                                                                       double *__restrict__ Cost, int w_vec_ok,
-                                                                      int bands, int rows_per_band)
+                                                                      int bands, int rows_per_band, SearchStepArgs step)
 {
     constexpr int VEC = Mag<T>::VEC;
     extern __shared__ uint4 lrbi_dyn_smem[];
@@ -235,6 +321,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
         }
         Cost[blockIdx.x] = c;
         Kept[blockIdx.x] = kk;
+        if (step.st && bands == 1) search_step_tile(g, step, t, kk, c);
     }
 }
 
@@ -242,7 +329,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
 __global__ __launch_bounds__(256) void threshold_eval_reduce_kernel(const unsigned long long *__restrict__ pk,
                                                                     const double *__restrict__ pc, int64_t tiles,
                                                                     int bands, unsigned long long *__restrict__ Kept,
-                                                                    double *__restrict__ Cost)
+                                                                    double *__restrict__ Cost, Geom g, SearchStepArgs step)
 {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= tiles) return;
@@ -254,6 +341,7 @@ __global__ __launch_bounds__(256) void threshold_eval_reduce_kernel(const unsign
     }
     Kept[t] = kk;
     Cost[t] = c;
+    if (step.st) search_step_tile(g, step, t, kk, c);
 }
 
 size_t threshold_eval_lds_bytes(const Geom &g)
@@ -281,7 +369,7 @@ EvalPlan plan_threshold_eval(const Geom &g)
 template <typename T>
 static int launch_eval_t(const Geom &g, const void *dW, int64_t ldw, float w_threshold, const float *dMp,
                          const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz, uint64_t *dKept,
-                         double *dCost, void *dWorkspace, hipStream_t stream)
+                         double *dCost, void *dWorkspace, hipStream_t stream, const SearchStepArgs &step)
 {
     const int64_t tiles = (int64_t)g.tile_rows * g.tile_cols;
     EvalPlan plan = plan_threshold_eval(g);
@@ -303,41 +391,49 @@ static int launch_eval_t(const Geom &g, const void *dW, int64_t ldw, float w_thr
         return LRBI_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles * plan.bands)), dim3(kEvalThreads), smem, stream, g, (const T *)dW,
                        ldw, w_threshold, dMp, dMz, dTp, dTz, (uint32_t *)dIp, (uint32_t *)dIz, pk, pc, w_vec_ok,
-                       plan.bands, plan.rows_per_band);
+                       plan.bands, plan.rows_per_band, step);
     LRBI_CHECK_LAUNCH();
     if (plan.bands > 1) {
         hipLaunchKernelGGL(threshold_eval_reduce_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, stream, pk,
-                           pc, tiles, plan.bands, (unsigned long long *)dKept, dCost);
+                           pc, tiles, plan.bands, (unsigned long long *)dKept, dCost, g, step);
         LRBI_CHECK_LAUNCH();
     }
     return LRBI_OK;
+}
+
+static int launch_eval_step(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, const float *dMp,
+                            const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz, uint64_t *dKept,
+                            double *dCost, void *dWorkspace, hipStream_t stream, const SearchStepArgs &step)
+{
+    switch (dt) {
+    case LRBI_F32:
+        return launch_eval_t<float>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream,
+                                    step);
+    case LRBI_F16:
+        return launch_eval_t<__half>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream,
+                                     step);
+    case LRBI_BF16:
+        return launch_eval_t<__hip_bfloat16>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace,
+                                             stream, step);
+    default: return LRBI_ERR_DTYPE;
+    }
+}
+
+int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold,
+                          const float *dMp, const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz,
+                          uint64_t *dKept, double *dCost, void *dWorkspace, hipStream_t stream)
+{
+    SearchStepArgs none{};
+    none.st = nullptr;
+    return launch_eval_step(g, dt, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream, none);
 }
 
 // ---------------------------------------------------------------------------
 // Threshold search of Algorithm 1 (Sec. 2.2), all tiles in lockstep: for every S_p of the
 // caller's list, a bisection on S_z whose probes are evaluated by the kernel above (one launch
 // per probe for all tiles); the per-tile search state lives in the caller's workspace and is
-// advanced by two small kernels, so the host never waits for the device.
+// advanced inside those launches (search_step_tile), so the host never waits for the device.
 // ---------------------------------------------------------------------------
-struct SearchState {
-    double lo, hi, sz;     // bisection interval and current probe of S_z
-    double rep_cost;       // representative of the current S_p: the probe closest to the target
-    long long rep_diff;    // |ones - target| of the representative, -1 = none yet
-    unsigned long long rep_kept;
-    float rep_tz;
-    float tp;              // threshold of I_p for the current S_p
-    long long best_diff;   // winner so far, -1 = none
-    int best_eligible;
-    int pad;
-};
-
-// rows x columns of tile t's part inside the matrix
-__device__ __forceinline__ void tile_extent(const Geom &g, int64_t t, int &rt, int &ct)
-{
-    const int64_t ti = t / g.tile_cols, tj = t - ti * g.tile_cols;
-    rt = (int)((g.m - ti * g.r < g.r) ? g.m - ti * g.r : g.r);
-    ct = (int)((g.n - tj * g.c < g.c) ? g.n - tj * g.c : g.c);
-}
 
 // Sorts the used entries of one tile's factor (ascending, bitonic network over `padded` = 2^j slots, the
 // tail filled with +inf).  which = 0: M_p, the first rt rows of k entries; which = 1: M_z, the first ct
@@ -385,15 +481,6 @@ __global__ __launch_bounds__(512) void tile_sort_kernel(Geom g, int which, const
         for (int i = threadIdx.x; i < n; i += 512) dst[i] = v[i];
 }
 
-// entry of the sorted factor at index round(sparsity * count): entries below it become 0
-__device__ __forceinline__ float threshold_at(const float *sorted, int count, double sparsity)
-{
-    // separate multiply and add (no fused operation): the index must be the same as in plain double arithmetic
-    long long idx = (long long)floor(__dadd_rn(__dmul_rn(sparsity, (double)count), 0.5));
-    if (idx < 0) idx = 0;
-    return (idx >= count) ? __builtin_inff() : sorted[idx];
-}
-
 __global__ __launch_bounds__(256) void search_begin_kernel(Geom g, SearchState *__restrict__ st,
                                                            const float *__restrict__ sortedMp,
                                                            const float *__restrict__ sortedMz, int64_t stride_p,
@@ -417,54 +504,6 @@ __global__ __launch_bounds__(256) void search_begin_kernel(Geom g, SearchState *
     st[t] = s;
     Tp[t] = s.tp;
     Tz[t] = threshold_at(sortedMz + t * stride_z, g.k * ct, sz0);
-}
-
-__global__ __launch_bounds__(256) void search_step_kernel(Geom g, SearchState *__restrict__ st,
-                                                          const float *__restrict__ sortedMz, int64_t stride_z,
-                                                          int64_t tiles, double keep_fraction, long long tolerance,
-                                                          int last_step, const unsigned long long *__restrict__ kept,
-                                                          const double *__restrict__ cost, float *__restrict__ Tz,
-                                                          float *__restrict__ TpBest, float *__restrict__ TzBest,
-                                                          unsigned long long *__restrict__ KeptBest,
-                                                          double *__restrict__ CostBest)
-{
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= tiles) return;
-    int rt, ct;
-    tile_extent(g, t, rt, ct);
-    // target number of ones of this tile, round((1 - S) rt ct), in plain double arithmetic
-    const long long target =
-        (long long)floor(__dadd_rn(__dmul_rn(__dmul_rn(keep_fraction, (double)rt), (double)ct), 0.5));
-    SearchState s = st[t];
-    const long long k = (long long)kept[t];
-    const long long diff = (k > target) ? k - target : target - k;
-    if (s.rep_diff < 0 || diff < s.rep_diff) {
-        s.rep_diff = diff;
-        s.rep_tz = Tz[t];
-        s.rep_kept = kept[t];
-        s.rep_cost = cost[t];
-    }
-    if (k > target) s.lo = s.sz; // too many ones: I_z must get sparser
-    else s.hi = s.sz;
-    s.sz = 0.5 * (s.lo + s.hi);
-    Tz[t] = threshold_at(sortedMz + t * stride_z, g.k * ct, s.sz);
-    if (last_step) {
-        const int eligible = s.rep_diff <= tolerance;
-        bool better;
-        if (s.best_diff < 0) better = true;
-        else if (eligible != s.best_eligible) better = eligible != 0;
-        else if (eligible) better = s.rep_cost < CostBest[t];
-        else better = s.rep_diff < s.best_diff;
-        if (better) {
-            s.best_diff = s.rep_diff;
-            s.best_eligible = eligible;
-            TpBest[t] = s.tp;
-            TzBest[t] = s.rep_tz;
-            KeptBest[t] = s.rep_kept;
-            CostBest[t] = s.rep_cost;
-        }
-    }
-    st[t] = s;
 }
 
 constexpr int kSortOnChip = 16384; // floats: 64 KiB of on-chip memory
@@ -542,14 +581,22 @@ int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, flo
                            p.stride_p, p.stride_z, tiles, sp, sz0, a == 0 ? 1 : 0, Tp, Tz);
         LRBI_CHECK_LAUNCH();
         for (int step = 0; step < steps; ++step) {
-            const int rc = launch_threshold_eval(g, dt, dW, ldw, w_threshold, dMp, dMz, Tp, Tz, nullptr, nullptr, kept,
-                                                 cost, eval_ws, stream);
+            // one launch per probe (two with row bands): the tile's search state is advanced where its result is formed
+            SearchStepArgs sa;
+            sa.st = state;
+            sa.sortedMz = sortedMz;
+            sa.stride_z = p.stride_z;
+            sa.keep_fraction = 1.0 - target_sparsity;
+            sa.tolerance = (long long)tolerance;
+            sa.last_step = step == steps - 1 ? 1 : 0;
+            sa.Tz = Tz;
+            sa.TpBest = dTpBest;
+            sa.TzBest = dTzBest;
+            sa.KeptBest = (unsigned long long *)dKeptBest;
+            sa.CostBest = dCostBest;
+            const int rc = launch_eval_step(g, dt, dW, ldw, w_threshold, dMp, dMz, Tp, Tz, nullptr, nullptr, kept, cost,
+                                            eval_ws, stream, sa);
             if (rc != LRBI_OK) return rc;
-            hipLaunchKernelGGL(search_step_kernel, dim3(sblocks), dim3(256), 0, stream, g, state, sortedMz, p.stride_z,
-                               tiles, 1.0 - target_sparsity, (long long)tolerance, step == steps - 1 ? 1 : 0,
-                               (const unsigned long long *)kept, cost, Tz, dTpBest, dTzBest,
-                               (unsigned long long *)dKeptBest, dCostBest);
-            LRBI_CHECK_LAUNCH();
         }
     }
     // 3. the winning thresholds once more, now writing the packed binary factors
@@ -559,20 +606,5 @@ int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, flo
     return LRBI_OK;
 }
 
-int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold,
-                          const float *dMp, const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz,
-                          uint64_t *dKept, double *dCost, void *dWorkspace, hipStream_t stream)
-{
-    switch (dt) {
-    case LRBI_F32:
-        return launch_eval_t<float>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream);
-    case LRBI_F16:
-        return launch_eval_t<__half>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream);
-    case LRBI_BF16:
-        return launch_eval_t<__hip_bfloat16>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace,
-                                             stream);
-    default: return LRBI_ERR_DTYPE;
-    }
-}
 
 } // namespace lrbi
