@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
                                                                       const float *__restrict__ Mp,
                                                                       const float *__restrict__ Mz,
                                                                       const float *__restrict__ Tp,
-                                                                      const float *__restrict__ Tz,
+                                                                      const float *Tz, // may be step.Tz
                                                                       uint32_t *__restrict__ IpOut,
                                                                       uint32_t *__restrict__ IzOut,
                                                                       unsigned long long *__restrict__ Kept,
