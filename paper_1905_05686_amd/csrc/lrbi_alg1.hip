@@ -240,11 +240,15 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
     // ---- 2. the tile as a list of 16-byte pieces (row-major): ones of I_a, and magnitudes kept by
     // pruning but cleared by I_a.  Four pieces per lane are in flight: their W loads are issued
     // before the first is consumed (the loads do not depend on the mask).
-    double cost = 0.0;
+    // four partial sums per lane (element e of a piece goes to sum e mod 4): the double-precision additions of a
+    // piece then form four short dependency chains instead of one long one
+    double cost4[4] = {0.0, 0.0, 0.0, 0.0};
     unsigned long long kept = 0ull;
     const int64_t col0 = (int64_t)tj * g.c;
     const int P = (ct + VEC - 1) / VEC;    // pieces per row of the tile's part inside the matrix
     const int items = nrows * P;
+    const bool p_pow2 = (P & (P - 1)) == 0;
+    const int p_shift = 31 - __builtin_clz(P);
     const T *wtile = W + ((int64_t)ti * g.r + row_lo) * ldw + col0;
     constexpr int U = 4;
     for (int base = tid; base < items; base += U * kEvalThreads) {
@@ -258,7 +262,8 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
 #pragma unroll
             for (int e = 0; e < 4; ++e) w4[u][e] = 0u;
             if (id < items) {
-                const int i = id / P, j = (id - i * P) * VEC;
+                const int i = p_pow2 ? (id >> p_shift) : id / P; // no emulated division for the usual tile widths
+                const int j = (id - i * P) * VEC;
                 const T *wrow = wtile + (int64_t)i * ldw;
                 const int nvalid = (ct - j < VEC) ? ct - j : VEC;
                 const bool vec = w_vec_ok && (nvalid == VEC) && (((col0 + j) % VEC) == 0);
@@ -297,10 +302,13 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 const float a = piece_abs<T>(w4[u], e);
-                if (((lost >> e) & 1u) && a >= w_threshold) cost += (double)a;
+                // the addend is selected (0 when the weight is kept by I_a, pruned by magnitude, or NaN), the sum is not
+                const float add = (((lost >> e) & 1u) && a >= w_threshold) ? a : 0.f;
+                cost4[e & 3] += (double)add;
             }
         }
     }
+    double cost = (cost4[0] + cost4[1]) + (cost4[2] + cost4[3]);
     // lanes in a fixed order, then wavefronts in a fixed order
 #pragma unroll
     for (int s = 32; s >= 1; s >>= 1) {
