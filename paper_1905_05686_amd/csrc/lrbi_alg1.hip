@@ -251,7 +251,57 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
     const int p_shift = 31 - __builtin_clz(P);
     const T *wtile = W + ((int64_t)ti * g.r + row_lo) * ldw + col0;
     constexpr int U = 4;
-    for (int base = tid; base < items; base += U * kEvalThreads) {
+    // Usual tile widths (a power of two of whole, 16-byte aligned pieces per row, at most one row of pieces per
+    // sweep of the workgroup): a lane keeps its piece column and walks down the rows, so its column offset, its
+    // word of the I_z rows and its shift never change and addresses advance by a constant; no index arithmetic,
+    // no test in front of a load (a row beyond the band reads the lane's first row and counts nothing).
+    const bool walk = p_pow2 && P <= kEvalThreads && (ct % VEC == 0) && w_vec_ok && (col0 % VEC == 0);
+    if (walk) {
+        const int pc = tid & (P - 1);
+        const int r0 = tid >> p_shift;
+        const int rstep = kEvalThreads >> p_shift;
+        const int j = pc * VEC;
+        const uint32_t *izc = iz + (j >> 5);
+        const int sh = j & 31;
+        const T *wp = wtile + (int64_t)r0 * ldw + j;
+        const int64_t wstride = (int64_t)rstep * ldw;
+        for (int i = r0; i < nrows; i += U * rstep) {
+            uint32_t w4[U][4];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool live = i + u * rstep < nrows;
+                const uint4 v = *reinterpret_cast<const uint4 *>(live ? wp + u * wstride : wp);
+                w4[u][0] = v.x; w4[u][1] = v.y; w4[u][2] = v.z; w4[u][3] = v.w;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = i + u * rstep;
+                const bool live = row < nrows;
+                const uint32_t *ipr = ip + (live ? row : i) * g.ipw;
+                uint32_t word = 0u;
+                for (int q = 0; q < g.ipw; ++q) {
+                    uint32_t sel = ipr[q];
+                    while (sel) {
+                        const int l = __builtin_ctz(sel) + 32 * q;
+                        sel &= sel - 1u;
+                        word |= izc[l * g.izw];
+                    }
+                }
+                const uint32_t valid = live ? ((1u << VEC) - 1u) : 0u;
+                const uint32_t bits = (word >> sh) & valid;
+                kept += (unsigned long long)__builtin_popcount(bits);
+                const uint32_t lost = valid & ~bits;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const float a = piece_abs<T>(w4[u], e);
+                    const float add = (((lost >> e) & 1u) && a >= w_threshold) ? a : 0.f;
+                    cost4[e & 3] += (double)add;
+                }
+            }
+            wp += U * wstride;
+        }
+    }
+    for (int base = tid; !walk && base < items; base += U * kEvalThreads) {
         uint32_t w4[U][4];
         uint32_t bits_u[U], valid_u[U];
 #pragma unroll
