@@ -484,15 +484,49 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
         }
         return v;
     };
+    // VEC: uniform base per slab + constant per-lane byte offsets (below 2^31: 128 rows of at most 2^22 elements),
+    // every load unconditional: a lane whose row or batch column lies outside reads a valid stand-in (its row clamped
+    // to the last one, batch column 0 of the slab) and the piece is cleared when it is staged
+    uint32_t aoff[CHUNKS], aoff0[CHUNKS], boff[CHUNKS], boff0[CHUNKS];
+    bool arow_ok[CHUNKS], brow_ok[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+        const int id = tid + kBwdThreads * c;
+        const int row = id >> 3, kc = id & 7;
+        arow_ok[c] = i0 + row < g.m;
+        brow_ok[c] = (int64_t)j0 + row < g.n;
+        const int64_t ar = arow_ok[c] ? row : g.m - 1 - i0;
+        const int64_t br = brow_ok[c] ? row : g.n - 1 - j0;
+        aoff0[c] = (uint32_t)(ar * lddy * 2);
+        boff0[c] = (uint32_t)(br * ldx * 2);
+        aoff[c] = aoff0[c] + (uint32_t)(kc * 16);
+        boff[c] = boff0[c] + (uint32_t)(kc * 16);
+    }
+    const char *abase0 = (const char *)(DY + i0 * lddy);
+    const char *bbase0 = (const char *)(X + (int64_t)j0 * ldx);
+    int cols_left = 0; // batch columns from the first one of the slab whose pieces sit in areg / breg
     auto load_slab = [&](int slab) {
         const int k0 = slab * BK;
+        if (VEC) {
+            const char *abase = abase0 + (int64_t)k0 * 2;
+            const char *bbase = bbase0 + (int64_t)k0 * 2;
 #pragma unroll
-        for (int c = 0; c < CHUNKS; ++c) {
-            const int id = tid + kBwdThreads * c;
-            const int row = id >> 3, kc = id & 7;
-            areg[c] = load_piece(DY, lddy, i0 + row, g.m, k0 + kc * 8);
-            breg[c] = load_piece(X, ldx, (int64_t)j0 + row, g.n, k0 + kc * 8);
+            for (int c = 0; c < CHUNKS; ++c) {
+                const int kc = (tid + kBwdThreads * c) & 7;
+                const bool col_ok = kc * 8 < N - k0; // N % 8 == 0
+                areg[c] = *reinterpret_cast<const uint4 *>(abase + (col_ok ? aoff[c] : aoff0[c]));
+                breg[c] = *reinterpret_cast<const uint4 *>(bbase + (col_ok ? boff[c] : boff0[c]));
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < CHUNKS; ++c) {
+                const int id = tid + kBwdThreads * c;
+                const int row = id >> 3, kc = id & 7;
+                areg[c] = load_piece(DY, lddy, i0 + row, g.m, k0 + kc * 8);
+                breg[c] = load_piece(X, ldx, (int64_t)j0 + row, g.n, k0 + kc * 8);
+            }
         }
+        cols_left = N - k0;
     };
     auto stage_slab = [&]() {
         uint16_t *as = As;
@@ -501,8 +535,14 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
         for (int c = 0; c < CHUNKS; ++c) {
             const int id = tid + kBwdThreads * c;
             const int row = id >> 3, kc = id & 7;
-            *reinterpret_cast<uint4 *>(as + row * OP_STRIDE + kc * 8) = areg[c];
-            *reinterpret_cast<uint4 *>(bs + row * OP_STRIDE + kc * 8) = breg[c];
+            uint4 av = areg[c], bv = breg[c];
+            if (VEC) {
+                const bool col_ok = kc * 8 < cols_left;
+                if (!(arow_ok[c] && col_ok)) av = make_uint4(0u, 0u, 0u, 0u);
+                if (!(brow_ok[c] && col_ok)) bv = make_uint4(0u, 0u, 0u, 0u);
+            }
+            *reinterpret_cast<uint4 *>(as + row * OP_STRIDE + kc * 8) = av;
+            *reinterpret_cast<uint4 *>(bs + row * OP_STRIDE + kc * 8) = bv;
         }
     };
 
@@ -798,7 +838,7 @@ int launch_grad(const Geom &g, lrbi_dtype dt, bool mfma, const void *dDY, int64_
     const int64_t blocks = iblocks * jblocks;
     if (blocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
     const bool vec = (((uintptr_t)dDY & 15) == 0) && (lddy % 8 == 0) && (((uintptr_t)dX & 15) == 0) && (ldx % 8 == 0) &&
-                     (N % 8 == 0);
+                     (N % 8 == 0) && lddy < ((int64_t)1 << 22) && ldx < ((int64_t)1 << 22);
     const int w_vec_ok = (((uintptr_t)dDW & 15) == 0) && (lddw % 8 == 0);
     const size_t smem = SmemG::bytes;
 #define LRBI_LAUNCH_G(TAG, V)                                                                                      \
