@@ -22,6 +22,7 @@
 #include <math.h>
 
 #include "lrbi_internal.hpp"
+#include "lrbi_mfma_common.hpp"
 
 namespace lrbi {
 
@@ -291,11 +292,23 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
                 const uint32_t bits = (word >> sh) & valid;
                 kept += (unsigned long long)__builtin_popcount(bits);
                 const uint32_t lost = valid & ~bits;
+                if (sizeof(T) == 2) {
+                    // 16-bit types: the weights I_a keeps are cleared four packed multiplies at a time (an exact
+                    // select on the bit pattern); what is left only needs the magnitude test
+                    const uint4 z = apply_mask8(make_uint4(w4[u][0], w4[u][1], w4[u][2], w4[u][3]), lost);
+                    const uint32_t zz[4] = {z.x, z.y, z.z, z.w};
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    const float a = piece_abs<T>(w4[u], e);
-                    const float add = (((lost >> e) & 1u) && a >= w_threshold) ? a : 0.f;
-                    cost4[e & 3] += (double)add;
+                    for (int e = 0; e < VEC; ++e) {
+                        const float a = piece_abs<T>(zz, e);
+                        cost4[e & 3] += (double)((a >= w_threshold) ? a : 0.f);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const float a = piece_abs<T>(w4[u], e);
+                        const float add = (((lost >> e) & 1u) && a >= w_threshold) ? a : 0.f;
+                        cost4[e & 3] += (double)add;
+                    }
                 }
             }
             wp += U * wstride;
