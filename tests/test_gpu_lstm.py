@@ -119,3 +119,29 @@ def test_fused_lstm_step_against_the_oracle():
         ec = orc.rel_err(to_float64(c[l]), ref["c"][l])
         print("fused free-running layer %d: h err %.3e, c err %.3e" % (l, eh, ec), flush=True)
         assert eh <= 1e-2 and ec <= 1e-2
+
+
+@pytest.mark.parametrize("H,n,r,c,k,B,dtype", [
+    (64, 128, 64, 64, 4, 20, "f16"),       # one slice: a single plane in the workspace
+    (75, 152, 100, 76, 8, 3, "bf16"),      # tiles that fit no tuned kernel, tiny batch, cut-off edge tiles
+    (128, 512, 128, 128, 8, 36, "f16"),    # tuned product kernel, several slices
+    (256, 1024, 256, 256, 16, 128, "bf16"),
+])
+def test_fused_lstm_step_small_shapes(H, n, r, c, k, B, dtype):
+    cfg = workloads.Config("t", 4 * H, n, r, c, k, 0.2, B, dtype, 0.1, 5)
+    data = workloads.make(cfg)
+    desc = desc_of(cfg)
+    dIp, dIz = device_factors(desc, data["Ip01"], data["Iz01"])
+    rng = np.random.default_rng(9)
+    c_prev = rng.standard_normal((H, B)).astype(np.float32)
+    C = torch.from_numpy(c_prev.copy()).cuda()
+    tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+    h1 = torch.empty((H, B), dtype=tdt, device="cuda")
+    lrbi.lstm_step(desc, to_device(data["W"], dtype), dIp, dIz, to_device(data["X"], dtype), C, h1)
+    torch.cuda.synchronize()
+    M = orc.decode_mask(data["Ip01"], data["Iz01"], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    z = orc.masked_gemm(workloads.to_float64(data["W"], dtype), M, workloads.to_float64(data["X"], dtype))
+    sg = lambda v: 1.0 / (1.0 + np.exp(-v))
+    c_ref = sg(z[H:2 * H]) * c_prev.astype(np.float64) + sg(z[0:H]) * np.tanh(z[2 * H:3 * H])
+    h_ref = sg(z[3 * H:]) * np.tanh(c_ref)
+    assert orc.rel_err(to_float64(C), c_ref) <= 1e-2 and orc.rel_err(to_float64(h1), h_ref) <= 1e-2
