@@ -13,9 +13,14 @@
 //      32-bit mask word over it (OR of the I_z words selected by the set bits of the row's I_p
 //      words, all from LDS), counts the ones, and adds |w| for every column with w kept by
 //      magnitude and pruned by the mask.  Per-lane sums are kept in double; lanes, then
-//      wavefronts, are added in a fixed order.
-// The kernel is bound by the single sweep over W (HBM); the factor reads are k (r + c) floats
-// per tile against r c weights.
+//      wavefronts, are added in a fixed order.  For the usual tile widths (a power of two of
+//      whole aligned pieces per row) a lane keeps its piece column and walks down the rows
+//      instead, so that its offsets are constants, and for the 16-bit types the weights the
+//      mask keeps are cleared with a packed 16-bit multiply before the magnitude test.
+// The roofline is the single sweep over W (HBM); measured, the kernel is bound by vector-ALU
+// issue (about five instructions per weight plus the mask look-up per piece).
+//
+// The same file holds the threshold search of Algorithm 1 that drives this kernel (further down).
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 

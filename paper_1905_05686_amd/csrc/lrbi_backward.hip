@@ -9,7 +9,7 @@
 // Matrix-core kernels (f16 / bf16, 16-byte aligned operands), 256 lanes = 4 wavefronts:
 //   * mfma_gemm_t_kernel: output tile 128 columns of W (rows of dX) x BQ batch columns, reduction
 //     over the rows of W in slabs of 64, optionally split into slices over m (partial planes
-//     added in slice order by splitk_reduce).  A slab of W (64 rows x 128 columns) is loaded
+//     added in slice order by bwd_reduce_kernel).  A slab of W (64 rows x 128 columns) is loaded
 //     row-major (coalesced), masked in registers and staged in LDS as [row][column]; dY's slab
 //     likewise as [row][batch column].  Both MFMA operands therefore need 8 consecutive
 //     reduction steps of one column: the gfx950 transposing LDS read delivers exactly that.
