@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const
                                                                   float *__restrict__ MzNew, float eps, int cblocks)
 {
     __align__(16) static __shared__ float stage[kNmfStageFloats];       // [rows of the chunk][k]
-    static __shared__ float gram[kNmfMaxK * kNmfMaxK];    // M_p^T M_p
+    __align__(16) static __shared__ float gram[kNmfMaxK * kNmfMaxK];    // M_p^T M_p
     const int64_t t = blockIdx.x / cblocks;
     const int cb = (int)(blockIdx.x - t * cblocks);
     int ti, tj, rt, ct;
@@ -91,11 +91,27 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const
             for (int e = tid; e < rows * k; e += kNmfThreads) stage[e] = mp[(int64_t)i0 * k + e];
             __syncthreads();
             if (l0 == 0) { // M_p^T M_p, every lane its own entries, rows in ascending order
-                for (int e = tid; e < k * k; e += kNmfThreads) {
-                    const int a = e / k, b = e - a * k;
-                    float s = gram[e];
-                    for (int i = 0; i < rows; ++i) s = fmaf(stage[i * k + a], stage[i * k + b], s);
-                    gram[e] = s;
+                if (k4) { // four neighbouring entries per lane: one broadcast read and one 16-byte read per row
+                    for (int e4 = tid; e4 < k * k / 4; e4 += kNmfThreads) {
+                        const int a = e4 / (k / 4), b = (e4 - a * (k / 4)) * 4;
+                        float4 s = *reinterpret_cast<const float4 *>(gram + a * k + b);
+                        for (int i = 0; i < rows; ++i) {
+                            const float pa = stage[i * k + a];
+                            const float4 pb = *reinterpret_cast<const float4 *>(stage + i * k + b);
+                            s.x = fmaf(pa, pb.x, s.x);
+                            s.y = fmaf(pa, pb.y, s.y);
+                            s.z = fmaf(pa, pb.z, s.z);
+                            s.w = fmaf(pa, pb.w, s.w);
+                        }
+                        *reinterpret_cast<float4 *>(gram + a * k + b) = s;
+                    }
+                } else {
+                    for (int e = tid; e < k * k; e += kNmfThreads) {
+                        const int a = e / k, b = e - a * k;
+                        float s = gram[e];
+                        for (int i = 0; i < rows; ++i) s = fmaf(stage[i * k + a], stage[i * k + b], s);
+                        gram[e] = s;
+                    }
                 }
             }
             if (live) {
@@ -167,7 +183,7 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
                                                                   int w_vec_ok)
 {
     __align__(16) static __shared__ float stage[kNmfStageFloats];       // [columns of the chunk][k]: M_z transposed
-    static __shared__ float gram[kNmfMaxK * kNmfMaxK];    // M_z M_z^T
+    __align__(16) static __shared__ float gram[kNmfMaxK * kNmfMaxK];    // M_z M_z^T
     const int64_t t = blockIdx.x / rblocks;
     const int rb = (int)(blockIdx.x - t * rblocks);
     int ti, tj, rt, ct;
@@ -201,11 +217,27 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
             }
             __syncthreads();
             if (l0 == 0) {
-                for (int e = tid; e < k * k; e += kNmfThreads) {
-                    const int a = e / k, b = e - a * k;
-                    float s = gram[e];
-                    for (int jj = 0; jj < cols; ++jj) s = fmaf(stage[jj * k + a], stage[jj * k + b], s);
-                    gram[e] = s;
+                if (k4) {
+                    for (int e4 = tid; e4 < k * k / 4; e4 += kNmfThreads) {
+                        const int a = e4 / (k / 4), b = (e4 - a * (k / 4)) * 4;
+                        float4 s = *reinterpret_cast<const float4 *>(gram + a * k + b);
+                        for (int jj = 0; jj < cols; ++jj) {
+                            const float za = stage[jj * k + a];
+                            const float4 zb = *reinterpret_cast<const float4 *>(stage + jj * k + b);
+                            s.x = fmaf(za, zb.x, s.x);
+                            s.y = fmaf(za, zb.y, s.y);
+                            s.z = fmaf(za, zb.z, s.z);
+                            s.w = fmaf(za, zb.w, s.w);
+                        }
+                        *reinterpret_cast<float4 *>(gram + a * k + b) = s;
+                    }
+                } else {
+                    for (int e = tid; e < k * k; e += kNmfThreads) {
+                        const int a = e / k, b = e - a * k;
+                        float s = gram[e];
+                        for (int jj = 0; jj < cols; ++jj) s = fmaf(stage[jj * k + a], stage[jj * k + b], s);
+                        gram[e] = s;
+                    }
                 }
             }
             if (live) {
