@@ -14,9 +14,9 @@
 //      words, all from LDS), counts the ones, and adds |w| for every column with w kept by
 //      magnitude and pruned by the mask.  Per-lane sums are kept in double; lanes, then
 //      wavefronts, are added in a fixed order.  For the usual tile widths (a power of two of
-//      whole aligned pieces per row) a lane keeps its piece column and walks down the rows
-//      instead, so that its offsets are constants, and for the 16-bit types the weights the
-//      mask keeps are cleared with a packed 16-bit multiply before the magnitude test.
+//      whole 32-column words per row) a lane keeps its word column and walks down the rows
+//      instead: one mask look-up per 32 columns, constant offsets; for the 16-bit types the
+//      weights the mask keeps are cleared with a packed 16-bit multiply before the magnitude test.
 // The roofline is the single sweep over W (HBM); measured, the kernel is bound by vector-ALU
 // issue (about five instructions per weight plus the mask look-up per piece).
 //
@@ -257,50 +257,45 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
     const int p_shift = 31 - __builtin_clz(P);
     const T *wtile = W + ((int64_t)ti * g.r + row_lo) * ldw + col0;
     constexpr int U = 4;
-    // Usual tile widths (a power of two of whole, 16-byte aligned pieces per row, at most one row of pieces per
-    // sweep of the workgroup): a lane keeps its piece column and walks down the rows, so its column offset, its
-    // word of the I_z rows and its shift never change and addresses advance by a constant; no index arithmetic,
-    // no test in front of a load (a row beyond the band reads the lane's first row and counts nothing).
-    const bool walk = p_pow2 && P <= kEvalThreads && (ct % VEC == 0) && w_vec_ok && (col0 % VEC == 0);
+    // Usual tile widths (a power of two of whole 32-column words per row, rows 16-byte aligned): a lane keeps its word
+    // column and walks down the rows.  Per row it requests the word's pieces of W (no test in front of a load: every
+    // row it visits is inside the band), rebuilds the mask word ONCE for all of them, and its offsets, its word of
+    // the I_z rows and its addresses' increment are constants: no index arithmetic in the loop.
+    constexpr int PW = 32 / VEC; // 16-byte pieces per mask word
+    const int words = ct >> 5;
+    const bool w_pow2 = words > 0 && (words & (words - 1)) == 0;
+    const bool walk = (ct % 32 == 0) && w_pow2 && words <= kEvalThreads && w_vec_ok && (col0 % VEC == 0);
     if (walk) {
-        const int pc = tid & (P - 1);
-        const int r0 = tid >> p_shift;
-        const int rstep = kEvalThreads >> p_shift;
-        const int j = pc * VEC;
-        const uint32_t *izc = iz + (j >> 5);
-        const int sh = j & 31;
-        const T *wp = wtile + (int64_t)r0 * ldw + j;
+        const int w_shift = 31 - __builtin_clz(words);
+        const int wc = tid & (words - 1);
+        const int r0 = tid >> w_shift;
+        const int rstep = kEvalThreads >> w_shift;
+        const uint32_t *izc = iz + wc;
+        const T *wp = wtile + (int64_t)r0 * ldw + 32 * wc;
         const int64_t wstride = (int64_t)rstep * ldw;
-        for (int i = r0; i < nrows; i += U * rstep) {
-            uint32_t w4[U][4];
+        for (int i = r0; i < nrows; i += rstep) {
+            uint4 v[PW];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const bool live = i + u * rstep < nrows;
-                const uint4 v = *reinterpret_cast<const uint4 *>(live ? wp + u * wstride : wp);
-                w4[u][0] = v.x; w4[u][1] = v.y; w4[u][2] = v.z; w4[u][3] = v.w;
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int row = i + u * rstep;
-                const bool live = row < nrows;
-                const uint32_t *ipr = ip + (live ? row : i) * g.ipw;
-                uint32_t word = 0u;
-                for (int q = 0; q < g.ipw; ++q) {
-                    uint32_t sel = ipr[q];
-                    while (sel) {
-                        const int l = __builtin_ctz(sel) + 32 * q;
-                        sel &= sel - 1u;
-                        word |= izc[l * g.izw];
-                    }
+            for (int q = 0; q < PW; ++q) v[q] = *reinterpret_cast<const uint4 *>(wp + q * VEC);
+            const uint32_t *ipr = ip + i * g.ipw;
+            uint32_t word = 0u;
+            for (int q = 0; q < g.ipw; ++q) {
+                uint32_t sel = ipr[q];
+                while (sel) {
+                    const int l = __builtin_ctz(sel) + 32 * q;
+                    sel &= sel - 1u;
+                    word |= izc[l * g.izw];
                 }
-                const uint32_t valid = live ? ((1u << VEC) - 1u) : 0u;
-                const uint32_t bits = (word >> sh) & valid;
-                kept += (unsigned long long)__builtin_popcount(bits);
-                const uint32_t lost = valid & ~bits;
+            }
+            kept += (unsigned long long)__builtin_popcount(word);
+            const uint32_t lost_word = ~word;
+#pragma unroll
+            for (int q = 0; q < PW; ++q) {
+                const uint32_t lost = (lost_word >> (q * VEC)) & ((1u << VEC) - 1u);
                 if (sizeof(T) == 2) {
                     // 16-bit types: the weights I_a keeps are cleared four packed multiplies at a time (an exact
                     // select on the bit pattern); what is left only needs the magnitude test
-                    const uint4 z = apply_mask8(make_uint4(w4[u][0], w4[u][1], w4[u][2], w4[u][3]), lost);
+                    const uint4 z = apply_mask8(v[q], lost);
                     const uint32_t zz[4] = {z.x, z.y, z.z, z.w};
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
@@ -308,15 +303,16 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
                         cost4[e & 3] += (double)((a >= w_threshold) ? a : 0.f);
                     }
                 } else {
+                    const uint32_t ww[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
-                        const float a = piece_abs<T>(w4[u], e);
+                        const float a = piece_abs<T>(ww, e);
                         const float add = (((lost >> e) & 1u) && a >= w_threshold) ? a : 0.f;
                         cost4[e & 3] += (double)add;
                     }
                 }
             }
-            wp += U * wstride;
+            wp += wstride;
         }
     }
     for (int base = tid; !walk && base < items; base += U * kEvalThreads) {
