@@ -36,7 +36,7 @@
  *   zero.  (The paper's tilings all divide; this is the library's reading.)  The
  *   tuned kernels need dividing tiles: shapes with edge tiles run on the general
  *   kernels, with the same results.
- *   Per-tile rank (Sec. 3.2: every submatrix may choose its own rank): tile t of rank
+ *   Per-tile rank (end of Sec. 3.1: every submatrix may choose its own rank): tile t of rank
  *   k_t <= k has zero columns l >= k_t in I_p and zero rows l >= k_t in I_z;
  *   lrbi_pack_factors_ranked writes them so, lrbi_index_bits_ranked counts only k_t.
  *
@@ -63,7 +63,7 @@ extern "C" {
 
 typedef struct lrbi_desc {
     int64_t m, n;   /* rows and columns of W                                   */
-    int32_t r, c;   /* tile rows and columns; r | m and c | n                  */
+    int32_t r, c;   /* tile rows and columns; edge tiles are cut off at m, n    */
     int32_t k;      /* rank of every tile, 1 <= k <= LRBI_MAX_RANK             */
     uint32_t flags; /* 0, or LRBI_FLAG_* bits (kernel choice overrides)        */
 } lrbi_desc;
@@ -135,7 +135,7 @@ int lrbi_pack_factors(const lrbi_desc *desc, const uint8_t *hIp01, const uint8_t
                       void *hIp_packed, void *hIz_packed);
 
 /*
- * The same for tiles of different ranks (Sec. 3.2): hTileRank [T], 0 <= k_t <= k.  The inputs
+ * The same for tiles of different ranks (end of Sec. 3.1): hTileRank [T], 0 <= k_t <= k.  The inputs
  * keep the uniform shapes [T][r][k] and [T][k][c]; ranks l >= k_t of tile t are not read and
  * are packed as zero, so every entry point sees a tile of rank k_t.
  */
@@ -196,16 +196,21 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
                      void *stream);
 
 /*
- * One candidate of Algorithm 1 (Sec. 2.2), evaluated for every tile in one launch:
+ * One candidate of Algorithm 1 (Sec. 2.1), evaluated for every tile in one launch:
  * the real-valued non-negative factors M_p (r x k) and M_z (k x c) of a tile are turned
  * into binary factors with the tile's thresholds, (I_p)_{i,l} = 1 iff (M_p)_{i,l} >= T_p
  * and (I_z)_{l,j} = 1 iff (M_z)_{l,j} >= T_z; the mask I_a = I_p (x) I_z of Eq. 3 is
  * formed on chip; and the two quantities the search needs come back per tile:
  *   dKept[t]  number of ones of I_a in tile t (its sparsity is S_a = 1 - kept / (r c)),
- *   dCost[t]  sum of |W_{i,j}| over the tile's entries that magnitude pruning keeps
+ *   dCost[t]  sum of M_{i,j} over the tile's entries that magnitude pruning keeps
  *             (I_{i,j} = 1 iff |W_{i,j}| >= w_threshold, Eq. 1 -> Eq. 2) but I_a prunes,
- *             the cost function of Sec. 2.2.
- * The caller drives the sweep over S_p and the binary search on S_z with repeated calls.
+ *             the cost function of Sec. 2.1.  M is the magnitude matrix the factorisation saw
+ *             (Sec. 3.2 manipulates the magnitudes and keeps this definition of the cost):
+ *             method 1: |W|; 2: |W|^2; 3: `amplify` * |W| where |W| >= w_threshold (which holds
+ *             for every entry the cost counts).  Pass the method and amplification given to
+ *             lrbi_nmf.  method outside 1 .. 3, or method 3 with amplify not positive and
+ *             finite: LRBI_ERR_SHAPE.  amplify is ignored for methods 1 and 2.
+ * (lrbi_search_thresholds below runs the sweep over S_p and the bisection on S_z around it.)
  *   dW: m x n row-major, ldw >= n elements, of `dtype`; magnitudes are taken exactly.
  *   dMp: [T][r][k] float, dMz: [T][k][c] float, dTp, dTz: [T] float (T = tiles, row-major
  *   tile order); comparisons are made in single precision.
@@ -224,7 +229,7 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
  * One or two kernel launches on `stream`.
  */
 int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
-                        float w_threshold, const float *dMp, const float *dMz, const float *dTp,
+                        float w_threshold, int32_t method, float amplify, const float *dMp, const float *dMz, const float *dTp,
                         const float *dTz, void *dIp_packed, void *dIz_packed, uint64_t *dKept,
                         double *dCost, void *dWorkspace, uint64_t workspace_bytes, void *stream);
 
@@ -232,7 +237,7 @@ int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW,
 int lrbi_threshold_eval_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
 
 /*
- * The threshold search of Algorithm 1 (Sec. 2.2) for every tile of a layer, entirely on
+ * The threshold search of Algorithm 1 (Sec. 2.1) for every tile of a layer, entirely on
  * the device: for each S_p of the caller's list (the sweep of the outer loop), T_p is the
  * entry of the tile's ascending-sorted M_p at index round(S_p r k) (+inf at r k: I_p all
  * zero), and S_z is found by bisection on [0, 1], starting from Eq. 7 solved for S_z,
@@ -244,7 +249,7 @@ int lrbi_threshold_eval_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
  * stands for its S_p; it is eligible when it is within `tolerance` ones of the target.
  * Per tile the result is the eligible candidate of least cost (the first in list order on
  * ties); when no S_p has an eligible candidate, the one closest to the target.
- *   dW, ldw, w_threshold, dMp, dMz: as for lrbi_threshold_eval.  M_p, M_z must hold no NaN.
+ *   dW, ldw, w_threshold, method, amplify, dMp, dMz: as for lrbi_threshold_eval.  M_p, M_z must hold no NaN.
  *   target_sparsity: S, in (0, 1).  sp_values: HOST array of n_sp values in [0, 1].
  *   dTp, dTz [T] float, dKept [T] uint64, dCost [T] double: the winning thresholds of every
  *   tile with their number of ones and cost.  dIp_packed, dIz_packed: when not NULL, the
@@ -259,8 +264,8 @@ int lrbi_threshold_eval_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
  * search state is advanced inside the evaluation launches); the host does not wait for the device.
  */
 int lrbi_search_thresholds(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
-                           float w_threshold, const float *dMp, const float *dMz,
-                           double target_sparsity, const double *sp_values, int32_t n_sp,
+                           float w_threshold, int32_t method, float amplify, const float *dMp,
+                           const float *dMz, double target_sparsity, const double *sp_values, int32_t n_sp,
                            int32_t steps, int64_t tolerance, float *dTp, float *dTz,
                            uint64_t *dKept, double *dCost, void *dIp_packed, void *dIz_packed,
                            void *dWorkspace, uint64_t workspace_bytes, void *stream);
@@ -329,7 +334,7 @@ int lrbi_lstm_step(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int6
 
 /*
  * Non-negative factorisation of the magnitude matrix, every tile on its own (Algorithm 1's first
- * step, Sec. 2.2: M = |W| ~ M_p M_z with M_p (r x k), M_z (k x c) >= 0, minimising the Frobenius
+ * step, Sec. 2.1: M = |W| ~ M_p M_z with M_p (r x k), M_z (k x c) >= 0, minimising the Frobenius
  * distance).  The paper uses an off-the-shelf library and names no algorithm; this entry point
  * runs `iters` multiplicative updates of Lee and Seung for that objective from the caller's
  * starting point, M_z first, then M_p:

@@ -1,4 +1,4 @@
-"""CPU oracle for the threshold search of Algorithm 1 (arXiv 1905.05686, Sec. 2.2), tile by tile.
+"""CPU oracle for the threshold search of Algorithm 1 (arXiv 1905.05686, Sec. 2.1), tile by tile.
 
 TEST INFRASTRUCTURE ONLY: plain loops over tiles, S_p values and bisection steps, in the order
 of the printed algorithm; every candidate is evaluated with the plain C oracle (threshold,
@@ -24,6 +24,8 @@ Readings where the paper is silent (the same ones as the library's header states
     candidate beats an ineligible one; two eligible ones compare by cost (first wins ties); two
     ineligible ones by distance to the target (first wins ties).
   * target ones = round((1 - S) r c); all sparsity comparisons are made on these integers.
+  * the cost is summed over the magnitudes the factorisation saw (Sec. 3.2 manipulates the magnitudes "to keep
+    the definition of Cost"): `method`, `amplify` as in oracle/nmf.py (1 none, 2 squared, 3 amplified kept set).
   * a tile cut off at the matrix edge is searched as the smaller tile it is: its target, its quantiles and
     its cost use only the part inside the matrix.
 Pins: tests/test_oracle_search.py (the printed example is recovered: S_p = 0.5 finds Eq. 5 and
@@ -54,7 +56,7 @@ def initial_sz(S: float, k: int, sp: float) -> float:
     return min(max(v, 0.0), 1.0)
 
 
-def search_thresholds(W, w_threshold, Mp, Mz, r, c, S, sp_values, steps, tolerance):
+def search_thresholds(W, w_threshold, Mp, Mz, r, c, S, sp_values, steps, tolerance, method=1, amplify=1.0):
     """Returns per tile: Tp, Tz (float32), kept (uint64), cost (float64) of the winning candidate."""
     W = np.asarray(W, dtype=np.float64)
     Mp = np.asarray(Mp, dtype=np.float32)
@@ -89,7 +91,7 @@ def search_thresholds(W, w_threshold, Mp, Mz, r, c, S, sp_values, steps, toleran
                 tz = threshold_at(sz_sorted, quantile_index(sz, sz_sorted.size))
                 Ip, Iz = orc.threshold_factors(Mp_t, Mz_t, np.array([tp], np.float32), np.array([tz], np.float32))
                 Ia = orc.decode_mask(Ip, Iz, rt, ct, rt, ct, k)
-                kept, cost = orc.candidate_cost(Wt, w_threshold, Ia, rt, ct)
+                kept, cost = orc.candidate_cost(Wt, w_threshold, Ia, rt, ct, method, amplify)
                 kept, cost = int(kept[0]), float(cost[0])
                 diff = abs(kept - target)
                 if rep is None or diff < rep[0]:

@@ -16,7 +16,7 @@
  *   n - tj*c columns (of I_z).  The paper's tilings all divide (Sec. 3.1); this is the
  *   builder's reading for the ones that do not.
  *   tile_rank [T] (optional): tile t uses only the first tile_rank[t] <= k columns of its
- *   I_p and rows of its I_z ("each submatrix can choose a different rank", Sec. 3.2).
+ *   I_p and rows of its I_z ("each submatrix can choose a different rank", end of Sec. 3.1).
  *   M     m x n      decoded mask, 1 = weight kept, 0 = weight pruned (Sec. 2, Eq. 2)
  *   X     n x N,  Y  m x N
  *
@@ -24,7 +24,9 @@
  * brute force against the set definition on tiny tiles, the integer-product
  * formulation, closed forms of Table 1 / Table 3, the density law of Eq. 7.
  * The LSTM recurrence and the CSR size formula (oracle/lstm.py, csr_bits) are
- * the builder's own definitions: parity unpinned.
+ * the builder's own definitions: parity unpinned by the paper (the LSTM cell is pinned to a
+ * handwritten case of exact-rational gate activations, tests/test_oracle_lstm.py; the CSR
+ * formula has no pin beyond its own statement).
  * Edge tiles and per-tile ranks (tests/test_oracle_general.py): brute force from the set
  * definition, the crop of the zero-padded matrix's decode, tile-by-tile decodes at each
  * tile's own rank, and the closed form k (ceil(n/c) m + ceil(m/r) n) of the size.
@@ -186,7 +188,7 @@ uint64_t lrbi_oracle_csr_bits(uint64_t nnz, int64_t m, int idx_bits, int ptr_bit
     return nnz * (uint64_t)idx_bits + (uint64_t)(m + 1) * (uint64_t)ptr_bits;
 }
 
-/* Algorithm 1, the step "convert (M_p, M_z) into (I_p, I_z)" (Sec. 2.2): a factor entry
+/* Algorithm 1, the step "convert (M_p, M_z) into (I_p, I_z)" (Sec. 2.1): a factor entry
  * becomes 1 when it reaches the threshold, (I_p)_{i,l} = 1 iff (M_p)_{i,l} >= T_p, and the
  * same for I_z with T_z.  Every tile has its own pair of thresholds (the algorithm runs per
  * matrix, and a tiled layer is factorised tile by tile, Sec. 3.1).
@@ -206,16 +208,19 @@ int lrbi_oracle_threshold(int64_t T, int64_t r, int64_t c, int64_t k, const floa
     return 0;
 }
 
-/* Algorithm 1, what is measured for one candidate pair of thresholds (Sec. 2.2), per tile:
+/* Algorithm 1, what is measured for one candidate pair of thresholds (Sec. 2.1), per tile:
  *   kept[t] = number of ones of I_a in the tile (S_a = 1 - kept / (r c)),
- *   cost[t] = sum of |W_{i,j}| over the tile's entries with I_{i,j} = 1 and (I_a)_{i,j} = 0
+ *   cost[t] = sum of M_{i,j} over the tile's entries with I_{i,j} = 1 and (I_a)_{i,j} = 0
  *   (the part of an edge tile inside the matrix),
- * where I is the magnitude-pruning mask I_{i,j} = 1 iff |W_{i,j}| >= w_threshold (Eq. 1 -> Eq. 2)
- * and I_a (M here) the decoded mask of the candidate factors.  Sums in double, row-major order. */
+ * where I is the magnitude-pruning mask I_{i,j} = 1 iff |W_{i,j}| >= w_threshold (Eq. 1 -> Eq. 2),
+ * I_a (the argument M here) the decoded mask of the candidate factors, and M_{i,j} the magnitude as the
+ * factorisation saw it: Sec. 3.2 pre-processes the magnitudes and keeps this definition of the cost, so
+ * method 1: |W|, method 2: |W|^2, method 3: amplify |W| where |W| >= w_threshold and |W| elsewhere.
+ * Sums in double, row-major order. */
 int lrbi_oracle_candidate_cost(int64_t m, int64_t n, int64_t r, int64_t c, const double *W, double w_threshold,
-                               const uint8_t *M, uint64_t *kept, double *cost)
+                               int method, double amplify, const uint8_t *M, uint64_t *kept, double *cost)
 {
-    if (m <= 0 || n <= 0 || r <= 0 || c <= 0) return -1;
+    if (m <= 0 || n <= 0 || r <= 0 || c <= 0 || method < 1 || method > 3) return -1;
     const int64_t tile_cols = (n + c - 1) / c;
     for (int64_t ti = 0; ti < (m + r - 1) / r; ++ti) {
         for (int64_t tj = 0; tj < tile_cols; ++tj) {
@@ -226,7 +231,10 @@ int lrbi_oracle_candidate_cost(int64_t m, int64_t n, int64_t r, int64_t c, const
                     const int64_t at = (ti * r + i) * n + (tj * c + j);
                     const double mag = W[at] < 0.0 ? -W[at] : W[at];
                     if (M[at]) ones += 1;
-                    if (mag >= w_threshold && !M[at]) sum += mag;
+                    double manipulated = mag;
+                    if (method == 2) manipulated = mag * mag;
+                    if (method == 3 && mag >= w_threshold) manipulated = mag * amplify;
+                    if (mag >= w_threshold && !M[at]) sum += manipulated;
                 }
             }
             kept[ti * tile_cols + tj] = ones;

@@ -62,7 +62,7 @@ def _load():
         lib.lrbi_oracle_csr_bits.restype = u64
         lib.lrbi_oracle_threshold.argtypes = [i64] * 4 + [p] * 6
         lib.lrbi_oracle_threshold.restype = ctypes.c_int
-        lib.lrbi_oracle_candidate_cost.argtypes = [i64] * 4 + [p, ctypes.c_double, p, p, p]
+        lib.lrbi_oracle_candidate_cost.argtypes = [i64] * 4 + [p, ctypes.c_double, ctypes.c_int, ctypes.c_double, p, p, p]
         lib.lrbi_oracle_candidate_cost.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -100,7 +100,7 @@ def decode_mask(Ip01, Iz01, m: int, n: int, r: int, c: int, k: int, tile_rank=No
 
 
 def threshold_factors(Mp, Mz, Tp, Tz):
-    """Algorithm 1, "convert (M_p, M_z) into (I_p, I_z)" (Sec. 2.2): entry >= threshold -> 1, per tile.
+    """Algorithm 1, "convert (M_p, M_z) into (I_p, I_z)" (Sec. 2.1): entry >= threshold -> 1, per tile.
     Mp [T][r][k], Mz [T][k][c] float32; Tp, Tz [T] float32.  Returns (Ip01, Iz01)."""
     Mp = _c(Mp, np.float32)
     Mz = _c(Mz, np.float32)
@@ -119,9 +119,10 @@ def threshold_factors(Mp, Mz, Tp, Tz):
     return Ip01, Iz01
 
 
-def candidate_cost(W, w_threshold: float, M, r: int, c: int):
-    """Algorithm 1, the quantities measured for one candidate (Sec. 2.2), per tile: number of ones of
-    I_a, and Cost = sum of |W| over entries with |W| >= w_threshold (I = 1) that I_a prunes.
+def candidate_cost(W, w_threshold: float, M, r: int, c: int, method: int = 1, amplify: float = 1.0):
+    """Algorithm 1, the quantities measured for one candidate (Sec. 2.1), per tile: number of ones of
+    I_a, and Cost = sum of the magnitudes of the entries with |W| >= w_threshold (I = 1) that I_a prunes; the
+    magnitudes are the manipulated ones of Sec. 3.2 (method 1 |W|, 2 |W|^2, 3 amplify |W| on the kept set).
     W float64 m x n (storage-rounded values), M the decoded 0/1 mask.  Returns (kept uint64 [T], cost float64 [T])."""
     W = _c(W, np.float64)
     M = _c(M, np.uint8)
@@ -131,8 +132,8 @@ def candidate_cost(W, w_threshold: float, M, r: int, c: int):
     T = num_tiles(m, n, r, c)
     kept = np.empty(T, dtype=np.uint64)
     cost = np.empty(T, dtype=np.float64)
-    rc = _load().lrbi_oracle_candidate_cost(m, n, r, c, W.ctypes.data, float(w_threshold), M.ctypes.data,
-                                            kept.ctypes.data, cost.ctypes.data)
+    rc = _load().lrbi_oracle_candidate_cost(m, n, r, c, W.ctypes.data, float(w_threshold), int(method),
+                                            float(amplify), M.ctypes.data, kept.ctypes.data, cost.ctypes.data)
     if rc != 0:
         raise ValueError("lrbi_oracle_candidate_cost failed: %d" % rc)
     return kept, cost

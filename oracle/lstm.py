@@ -1,9 +1,13 @@
 """fp64 LSTM recurrence around the masked product (test infrastructure only).
 
-The paper names an LSTM as one of its models (Sec. 4) but prints no cell
-equations, so this is the builder's own definition: PARITY UNPINNED by the
-paper.  It exists to give the 2 x 35 sequential masked products of the LSTM
-configuration realistic inputs and to check a free-running GPU sequence.
+TEST INFRASTRUCTURE ONLY.  The paper names an LSTM as one of its models
+(Sec. 4) but prints no cell equations, so this is the builder's own
+definition (the usual cell): PARITY UNPINNED by the paper.  The definition
+itself is pinned to a handwritten two-layer, two-step case whose gate
+activations are exact rationals (tests/golden/lstm_cell.txt, checked in
+tests/test_oracle_lstm.py).  It exists to give the 2 x 35 sequential masked
+products of the LSTM configuration realistic inputs and to check a
+free-running GPU sequence.
 
 Gate matrix rows are [i; f; g; o] blocks of `hidden` rows; columns are
 [x_t | h_{t-1}].  z = (W o M) [x_t; h_{t-1}], no bias;
@@ -21,8 +25,10 @@ def _sigm(z):
     return 1.0 / (1.0 + np.exp(-z))
 
 
-def lstm_sequence(Ws, Ms, xs, round_input=None, threads: int = 1):
+def lstm_sequence(Ws, Ms, xs, round_input=None, threads: int = 1, h0=None, c0=None, record_states=False):
     """Ws[l] float64 [4H, 2H], Ms[l] uint8 mask, xs float64 [steps, H, B].
+    h0, c0: optional per-layer starting states [H, B] (default zero, the configuration's h_0 = c_0 = 0).
+    record_states: also return `hs`, `cs`: [steps][layers] copies of h_t, c_t.
 
     `round_input`, if given, maps the float64 [x; h] block to the values the
     storage dtype can hold (the GPU's product sees its inputs in that dtype);
@@ -31,8 +37,10 @@ def lstm_sequence(Ws, Ms, xs, round_input=None, threads: int = 1):
     and final `h`, `c` per layer."""
     layers = len(Ws)
     steps, H, B = xs.shape
-    h = [np.zeros((H, B)) for _ in range(layers)]
-    c = [np.zeros((H, B)) for _ in range(layers)]
+    h = [np.zeros((H, B)) if h0 is None else np.array(h0[l], dtype=np.float64) for l in range(layers)]
+    c = [np.zeros((H, B)) if c0 is None else np.array(c0[l], dtype=np.float64) for l in range(layers)]
+    rec_h = [[None] * layers for _ in range(steps)]
+    rec_c = [[None] * layers for _ in range(steps)]
     rec_xh = [[None] * layers for _ in range(steps)]
     rec_z = [[None] * layers for _ in range(steps)]
     for t in range(steps):
@@ -47,5 +55,9 @@ def lstm_sequence(Ws, Ms, xs, round_input=None, threads: int = 1):
             h[l] = _sigm(zo) * np.tanh(c[l])
             rec_xh[t][l] = xh
             rec_z[t][l] = z
+            rec_h[t][l], rec_c[t][l] = h[l].copy(), c[l].copy()
             x = h[l]
-    return {"xh": rec_xh, "z": rec_z, "h": h, "c": c}
+    out = {"xh": rec_xh, "z": rec_z, "h": h, "c": c}
+    if record_states:
+        out["hs"], out["cs"] = rec_h, rec_c
+    return out

@@ -1,4 +1,4 @@
-"""CPU oracle for the non-negative factorisation step of Algorithm 1 (arXiv 1905.05686, Sec. 2.2), tile by tile.
+"""CPU oracle for the non-negative factorisation step of Algorithm 1 (arXiv 1905.05686, Sec. 2.1), tile by tile.
 
 TEST INFRASTRUCTURE ONLY: plain numpy in float64, one tile at a time.  Shares no code with the GPU library.
 

@@ -75,10 +75,10 @@ def load_library():
     lib.lrbi_decode_mask.argtypes = [pd, vp, vp, vp, i64, vp]
     lib.lrbi_masked_gemm_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
     lib.lrbi_masked_gemm.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, u64, vp]
-    lib.lrbi_threshold_eval.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64,
+    lib.lrbi_threshold_eval.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, ctypes.c_int32, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64,
                                         vp]
     lib.lrbi_threshold_eval_workspace_bytes.argtypes = [pd, pu64]
-    lib.lrbi_search_thresholds.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, vp, vp, ctypes.c_double,
+    lib.lrbi_search_thresholds.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, ctypes.c_int32, ctypes.c_float, vp, vp, ctypes.c_double,
                                            ctypes.POINTER(ctypes.c_double), i32, i32, i64, vp, vp, vp, vp, vp, vp, vp, u64,
                                            vp]
     lib.lrbi_search_workspace_bytes.argtypes = [pd, pu64]
@@ -249,12 +249,13 @@ def threshold_eval_workspace_bytes(desc: Desc) -> int:
 
 
 def threshold_eval(desc: Desc, W, w_threshold: float, Mp, Mz, Tp, Tz, want_factors: bool = False, out=None,
-                   workspace=None, stream=None):
+                   workspace=None, stream=None, method: int = 1, amplify: float = 1.0):
     """lrbi_threshold_eval: one candidate of Algorithm 1 for every tile.  W [m, n] (f32 / f16 / bf16),
     Mp [T, r, k], Mz [T, k, c], Tp, Tz [T] float32 device tensors.  Returns (kept int64 [T], cost float64 [T])
     and, with want_factors, also the packed factors (Ip int32 [T*r, ipw], Iz int32 [T*k, izw]).
     `out` = (kept, cost) reuses existing result tensors; `workspace` = device scratch of at least
-    threshold_eval_workspace_bytes(desc) bytes (optional)."""
+    threshold_eval_workspace_bytes(desc) bytes (optional).  method / amplify: the magnitude manipulation the
+    cost is summed over (1 none, 2 squared, 3 amplified), as given to nmf()."""
     import torch
     T = desc.tiles
     if W.dim() != 2 or W.shape != (desc.m, desc.n) or W.stride(1) != 1:
@@ -274,8 +275,8 @@ def threshold_eval(desc: Desc, W, w_threshold: float, Mp, Mz, Tp, Tz, want_facto
         ip = torch.empty((T * desc.r, (desc.k + 31) // 32), dtype=torch.int32, device=W.device)
         iz = torch.empty((T * desc.k, 2 * ((desc.c + 63) // 64)), dtype=torch.int32, device=W.device)
     _check(load_library().lrbi_threshold_eval(
-        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), float(w_threshold), _dev_ptr(Mp, "Mp"),
-        _dev_ptr(Mz, "Mz"), _dev_ptr(Tp, "Tp"), _dev_ptr(Tz, "Tz"), _dev_ptr(ip, "Ip") if want_factors else None,
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), float(w_threshold), int(method),
+        float(amplify), _dev_ptr(Mp, "Mp"), _dev_ptr(Mz, "Mz"), _dev_ptr(Tp, "Tp"), _dev_ptr(Tz, "Tz"), _dev_ptr(ip, "Ip") if want_factors else None,
         _dev_ptr(iz, "Iz") if want_factors else None, _dev_ptr(kept, "kept"), _dev_ptr(cost, "cost"),
         _dev_ptr(workspace, "workspace") if workspace is not None else None,
         workspace.numel() * workspace.element_size() if workspace is not None else 0,
@@ -291,7 +292,8 @@ def search_workspace_bytes(desc: Desc) -> int:
 
 
 def search_thresholds(desc: Desc, W, w_threshold: float, Mp, Mz, target_sparsity: float, sp_values, steps: int,
-                      tolerance: int, want_factors: bool = False, workspace=None, stream=None):
+                      tolerance: int, want_factors: bool = False, workspace=None, stream=None, method: int = 1,
+                      amplify: float = 1.0):
     """lrbi_search_thresholds: the threshold search of Algorithm 1 for every tile.  W [m, n] (f32 / f16 / bf16),
     Mp [T, r, k], Mz [T, k, c] float32 device tensors; sp_values a host sequence of floats.  Returns
     (Tp float32 [T], Tz float32 [T], kept int64 [T], cost float64 [T]) and, with want_factors, also the packed
@@ -316,8 +318,8 @@ def search_thresholds(desc: Desc, W, w_threshold: float, Mp, Mz, target_sparsity
         ip = torch.empty((T * desc.r, (desc.k + 31) // 32), dtype=torch.int32, device=W.device)
         iz = torch.empty((T * desc.k, 2 * ((desc.c + 63) // 64)), dtype=torch.int32, device=W.device)
     _check(load_library().lrbi_search_thresholds(
-        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), float(w_threshold), _dev_ptr(Mp, "Mp"),
-        _dev_ptr(Mz, "Mz"), float(target_sparsity), sp, len(sp_values), int(steps), int(tolerance), _dev_ptr(Tp, "Tp"),
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), float(w_threshold), int(method),
+        float(amplify), _dev_ptr(Mp, "Mp"), _dev_ptr(Mz, "Mz"), float(target_sparsity), sp, len(sp_values), int(steps), int(tolerance), _dev_ptr(Tp, "Tp"),
         _dev_ptr(Tz, "Tz"), _dev_ptr(kept, "kept"), _dev_ptr(cost, "cost"), _dev_ptr(ip, "Ip") if want_factors else None,
         _dev_ptr(iz, "Iz") if want_factors else None, _dev_ptr(workspace, "workspace"),
         workspace.numel() * workspace.element_size(), _stream_ptr(stream)), "lrbi_search_thresholds")

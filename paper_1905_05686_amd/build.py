@@ -42,11 +42,25 @@ def _private_memory_users(remarks: str):
     return bad
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
+def _up_to_date(obj: str, src: str) -> bool:
+    """True when `obj` is newer than its source and every header it can include."""
+    if not os.path.exists(obj):
+        return False
+    deps = [os.path.join(CSRC, src), os.path.abspath(__file__)]
+    deps += [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    deps += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
+    return all(os.path.getmtime(d) < os.path.getmtime(obj) for d in deps)
+
+
+def build(verbose: bool = False, extra_flags=(), incremental: bool = False) -> str:
+    """Compiles every source (always, unless `incremental`: then only what changed) and links liblrbi.so."""
     objs = []
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
+        if incremental and not extra_flags and _up_to_date(obj, src):
+            objs.append(obj)
+            continue
         cmd = [HIPCC] + FLAGS + list(extra_flags) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -77,4 +91,4 @@ def build(verbose: bool = False, extra_flags=()) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, incremental="--incremental" in sys.argv))

@@ -1,4 +1,4 @@
-// Candidate evaluation of Algorithm 1 (Sec. 2.2): threshold the real-valued factors of every
+// Candidate evaluation of Algorithm 1 (Sec. 2.1): threshold the real-valued factors of every
 // tile, form I_a = I_p (x) I_z (Eq. 3) on chip, and return per tile the number of ones of I_a
 // and the cost (sum of the magnitudes that magnitude pruning keeps and I_a prunes).
 //
@@ -148,9 +148,19 @@ __device__ __forceinline__ void search_step_tile(const Geom &g, const SearchStep
     a.st[t] = s;
 }
 
-template <typename T>
+// one addend of the cost, in double (a magnitude and its square are exact there)
+template <bool SQ> __device__ __forceinline__ void cost_add(double &acc, float a)
+{
+    const double d = (double)a;
+    if (SQ) acc = __fma_rn(d, d, acc);
+    else acc += d;
+}
+
+// SQ: the cost sums squared magnitudes (manipulation method 2); cost_scale multiplies a workgroup's sum (method 3:
+// every counted weight is one that magnitude pruning keeps, i.e. an amplified one, so the factor is common)
+template <typename T, bool SQ>
 __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, const T *__restrict__ W, int64_t ldw,
-                                                                      float w_threshold,
+                                                                      float w_threshold, double cost_scale,
                                                                       const float *__restrict__ Mp,
                                                                       const float *__restrict__ Mz,
                                                                       const float *__restrict__ Tp,
@@ -300,7 +310,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
                         const float a = piece_abs<T>(zz, e);
-                        cost4[e & 3] += (double)((a >= w_threshold) ? a : 0.f);
+                        cost_add<SQ>(cost4[e & 3], (a >= w_threshold) ? a : 0.f);
                     }
                 } else {
                     const uint32_t ww[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
@@ -308,7 +318,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
                     for (int e = 0; e < VEC; ++e) {
                         const float a = piece_abs<T>(ww, e);
                         const float add = (((lost >> e) & 1u) && a >= w_threshold) ? a : 0.f;
-                        cost4[e & 3] += (double)add;
+                        cost_add<SQ>(cost4[e & 3], add);
                     }
                 }
             }
@@ -368,7 +378,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
                 const float a = piece_abs<T>(w4[u], e);
                 // the addend is selected (0 when the weight is kept by I_a, pruned by magnitude, or NaN), the sum is not
                 const float add = (((lost >> e) & 1u) && a >= w_threshold) ? a : 0.f;
-                cost4[e & 3] += (double)add;
+                cost_add<SQ>(cost4[e & 3], add);
             }
         }
     }
@@ -391,6 +401,7 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
             c += wave_cost[w];
             kk += wave_kept[w];
         }
+        c *= cost_scale;
         Cost[blockIdx.x] = c;
         Kept[blockIdx.x] = kk;
         if (step.st && bands == 1) search_step_tile(g, step, t, kk, c);
@@ -439,7 +450,7 @@ EvalPlan plan_threshold_eval(const Geom &g)
 }
 
 template <typename T>
-static int launch_eval_t(const Geom &g, const void *dW, int64_t ldw, float w_threshold, const float *dMp,
+static int launch_eval_t(const Geom &g, const void *dW, int64_t ldw, float w_threshold, CostManip manip, const float *dMp,
                          const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz, uint64_t *dKept,
                          double *dCost, void *dWorkspace, hipStream_t stream, const SearchStepArgs &step)
 {
@@ -458,50 +469,49 @@ static int launch_eval_t(const Geom &g, const void *dW, int64_t ldw, float w_thr
     }
     const size_t smem = (threshold_eval_lds_bytes(g) + 15) / 16 * 16;
     const int w_vec_ok = (((uintptr_t)dW & 15) == 0) && (ldw % Mag<T>::VEC == 0);
-    auto kern = threshold_eval_kernel<T>;
-    if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-        return LRBI_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles * plan.bands)), dim3(kEvalThreads), smem, stream, g, (const T *)dW,
-                       ldw, w_threshold, dMp, dMz, dTp, dTz, (uint32_t *)dIp, (uint32_t *)dIz, pk, pc, w_vec_ok,
+    auto kern = manip.squared ? threshold_eval_kernel<T, true> : threshold_eval_kernel<T, false>;
+    LRBI_SET_MAX_LDS(kern, smem);
+    LRBI_LAUNCH(kern, dim3((unsigned)(tiles * plan.bands)), dim3(kEvalThreads), smem, stream, g, (const T *)dW,
+                       ldw, w_threshold, manip.scale, dMp, dMz, dTp, dTz, (uint32_t *)dIp, (uint32_t *)dIz, pk, pc, w_vec_ok,
                        plan.bands, plan.rows_per_band, step);
-    LRBI_CHECK_LAUNCH();
     if (plan.bands > 1) {
-        hipLaunchKernelGGL(threshold_eval_reduce_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, stream, pk,
+        LRBI_LAUNCH(threshold_eval_reduce_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, stream, pk,
                            pc, tiles, plan.bands, (unsigned long long *)dKept, dCost, g, step);
-        LRBI_CHECK_LAUNCH();
     }
     return LRBI_OK;
 }
 
-static int launch_eval_step(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, const float *dMp,
+static int launch_eval_step(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, CostManip manip,
+                            const float *dMp,
                             const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz, uint64_t *dKept,
                             double *dCost, void *dWorkspace, hipStream_t stream, const SearchStepArgs &step)
 {
     switch (dt) {
     case LRBI_F32:
-        return launch_eval_t<float>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream,
+        return launch_eval_t<float>(g, dW, ldw, w_threshold, manip, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream,
                                     step);
     case LRBI_F16:
-        return launch_eval_t<__half>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream,
+        return launch_eval_t<__half>(g, dW, ldw, w_threshold, manip, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream,
                                      step);
     case LRBI_BF16:
-        return launch_eval_t<__hip_bfloat16>(g, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace,
+        return launch_eval_t<__hip_bfloat16>(g, dW, ldw, w_threshold, manip, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace,
                                              stream, step);
     default: return LRBI_ERR_DTYPE;
     }
 }
 
-int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold,
+int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, CostManip manip,
                           const float *dMp, const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz,
                           uint64_t *dKept, double *dCost, void *dWorkspace, hipStream_t stream)
 {
     SearchStepArgs none{};
     none.st = nullptr;
-    return launch_eval_step(g, dt, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream, none);
+    return launch_eval_step(g, dt, dW, ldw, w_threshold, manip, dMp, dMz, dTp, dTz, dIp, dIz, dKept, dCost, dWorkspace, stream,
+                            none);
 }
 
 // ---------------------------------------------------------------------------
-// Threshold search of Algorithm 1 (Sec. 2.2), all tiles in lockstep: for every S_p of the
+// Threshold search of Algorithm 1 (Sec. 2.1), all tiles in lockstep: for every S_p of the
 // caller's list, a bisection on S_z whose probes are evaluated by the kernel above (one launch
 // per probe for all tiles); the per-tile search state lives in the caller's workspace and is
 // advanced inside those launches (search_step_tile), so the host never waits for the device.
@@ -609,7 +619,8 @@ SearchPlan plan_search(const Geom &g)
     return p;
 }
 
-int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, const float *dMp,
+int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, CostManip manip,
+                  const float *dMp,
                   const float *dMz, double target_sparsity, int n_sp, const double *sp_values, int steps,
                   int64_t tolerance, float *dTpBest, float *dTzBest, uint64_t *dKeptBest, double *dCostBest, void *dIp,
                   void *dIz, void *dWorkspace, hipStream_t stream)
@@ -632,12 +643,9 @@ int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, flo
         const int padded = (int)pow2_at_least(n);
         const int on_chip = n <= kSortOnChip;
         const size_t smem = on_chip ? (size_t)padded * 4 : 0;
-        if (hipFuncSetAttribute((const void *)tile_sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kSortOnChip * 4) != hipSuccess)
-            return LRBI_ERR_LAUNCH;
-        hipLaunchKernelGGL(tile_sort_kernel, dim3((unsigned)tiles), dim3(512), smem, stream, g, which, which ? dMz : dMp,
+        LRBI_SET_MAX_LDS(tile_sort_kernel, kSortOnChip * 4);
+        LRBI_LAUNCH(tile_sort_kernel, dim3((unsigned)tiles), dim3(512), smem, stream, g, which, which ? dMz : dMp,
                            which ? sortedMz : sortedMp, padded, which ? p.stride_z : p.stride_p, on_chip);
-        LRBI_CHECK_LAUNCH();
     }
     // 2. sweep over S_p, bisection on S_z
     const unsigned sblocks = (unsigned)((tiles + 255) / 256);
@@ -649,9 +657,8 @@ int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, flo
             if (sz0 < 0.0) sz0 = 0.0;
             if (sz0 > 1.0) sz0 = 1.0;
         }
-        hipLaunchKernelGGL(search_begin_kernel, dim3(sblocks), dim3(256), 0, stream, g, state, sortedMp, sortedMz,
+        LRBI_LAUNCH(search_begin_kernel, dim3(sblocks), dim3(256), 0, stream, g, state, sortedMp, sortedMz,
                            p.stride_p, p.stride_z, tiles, sp, sz0, a == 0 ? 1 : 0, Tp, Tz);
-        LRBI_CHECK_LAUNCH();
         for (int step = 0; step < steps; ++step) {
             // one launch per probe (two with row bands): the tile's search state is advanced where its result is formed
             SearchStepArgs sa;
@@ -666,14 +673,14 @@ int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, flo
             sa.TzBest = dTzBest;
             sa.KeptBest = (unsigned long long *)dKeptBest;
             sa.CostBest = dCostBest;
-            const int rc = launch_eval_step(g, dt, dW, ldw, w_threshold, dMp, dMz, Tp, Tz, nullptr, nullptr, kept, cost,
+            const int rc = launch_eval_step(g, dt, dW, ldw, w_threshold, manip, dMp, dMz, Tp, Tz, nullptr, nullptr, kept, cost,
                                             eval_ws, stream, sa);
             if (rc != LRBI_OK) return rc;
         }
     }
     // 3. the winning thresholds once more, now writing the packed binary factors
     if (dIp)
-        return launch_threshold_eval(g, dt, dW, ldw, w_threshold, dMp, dMz, dTpBest, dTzBest, dIp, dIz, dKeptBest,
+        return launch_threshold_eval(g, dt, dW, ldw, w_threshold, manip, dMp, dMz, dTpBest, dTzBest, dIp, dIz, dKeptBest,
                                      dCostBest, eval_ws, stream);
     return LRBI_OK;
 }

@@ -749,10 +749,8 @@ static int launch_gemm_t_tile(const Geom &g, const BwdPlan &plan, const void *dW
     do {                                                                                                           \
         auto kern = fast ? mfma_gemm_t_kernel<Tag, BQ, WAVES_J, WAVES_Q, XV, SP, true>                              \
                          : mfma_gemm_t_kernel<Tag, BQ, WAVES_J, WAVES_Q, XV, SP, false>;                            \
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) !=      \
-            hipSuccess)                                                                                            \
-            return LRBI_ERR_LAUNCH;                                                                                \
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kBwdThreads), smem, stream, g, (const uint16_t *)dW, \
+        LRBI_SET_MAX_LDS(kern, smem);                                                                              \
+        LRBI_LAUNCH(kern, dim3((unsigned)blocks), dim3(kBwdThreads), smem, stream, g, (const uint16_t *)dW, \
                            ldw, dIp, dIz, (const uint16_t *)dDY, lddy, (int)N, (uint16_t *)dDX, lddx,              \
                            (float *)dWorkspace, ldp, (int)jblocks, (int)qblocks, plan.iper, xcd_remap, y_vec_ok);  \
     } while (0)
@@ -764,14 +762,12 @@ static int launch_gemm_t_tile(const Geom &g, const BwdPlan &plan, const void *dW
         else LRBI_LAUNCH_T(false, false);
     }
 #undef LRBI_LAUNCH_T
-    LRBI_CHECK_LAUNCH();
     if (split) {
         const int64_t items = g.n * (ldp / 4);
         const int64_t rblocks = (items + 255) / 256;
         if (rblocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
-        hipLaunchKernelGGL(bwd_reduce_kernel<Tag>, dim3((unsigned)rblocks), dim3(256), 0, stream,
+        LRBI_LAUNCH(bwd_reduce_kernel<Tag>, dim3((unsigned)rblocks), dim3(256), 0, stream,
                            (const float *)dWorkspace, ldp, g.n, (int)N, plan.slices, (uint16_t *)dDX, lddx, y_vec_ok);
-        LRBI_CHECK_LAUNCH();
     }
     return LRBI_OK;
 }
@@ -782,9 +778,8 @@ static int launch_valu_t(const Geom &g, const void *dW, int64_t ldw, const uint3
 {
     const int64_t bx = (g.n + 63) / 64, by = (N + 3) / 4;
     if (bx > 0x7FFFFFFF || by > 65535) return LRBI_ERR_SHAPE;
-    hipLaunchKernelGGL(valu_gemm_t_kernel<T>, dim3((unsigned)bx, (unsigned)by), dim3(64), 0, stream, g, (const T *)dW, ldw,
+    LRBI_LAUNCH(valu_gemm_t_kernel<T>, dim3((unsigned)bx, (unsigned)by), dim3(64), 0, stream, g, (const T *)dW, ldw,
                        dIp, dIz, (const T *)dDY, lddy, (int)N, (T *)dDX, lddx);
-    LRBI_CHECK_LAUNCH();
     return LRBI_OK;
 }
 
@@ -817,9 +812,8 @@ static int launch_valu_grad(const Geom &g, const void *dDY, int64_t lddy, const 
     const int64_t bx = (g.n + 63) / 64;
     if (bx > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
     const unsigned by = (unsigned)(g.m < 65535 ? g.m : 65535);
-    hipLaunchKernelGGL(valu_grad_kernel<T>, dim3((unsigned)bx, by), dim3(64), 0, stream, g, (const T *)dDY, lddy,
+    LRBI_LAUNCH(valu_grad_kernel<T>, dim3((unsigned)bx, by), dim3(64), 0, stream, g, (const T *)dDY, lddy,
                        (const T *)dX, ldx, (int)N, dIp, dIz, (T *)dDW, lddw);
-    LRBI_CHECK_LAUNCH();
     return LRBI_OK;
 }
 
@@ -844,10 +838,8 @@ int launch_grad(const Geom &g, lrbi_dtype dt, bool mfma, const void *dDY, int64_
 #define LRBI_LAUNCH_G(TAG, V)                                                                                      \
     do {                                                                                                           \
         auto kern = mfma_grad_kernel<TAG, V>;                                                                      \
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) !=      \
-            hipSuccess)                                                                                            \
-            return LRBI_ERR_LAUNCH;                                                                                \
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kBwdThreads), smem, stream, g, (const uint16_t *)dDY, \
+        LRBI_SET_MAX_LDS(kern, smem);                                                                              \
+        LRBI_LAUNCH(kern, dim3((unsigned)blocks), dim3(kBwdThreads), smem, stream, g, (const uint16_t *)dDY, \
                            lddy, (const uint16_t *)dX, ldx, (int)N, dIp, dIz, (uint16_t *)dDW, lddw, (int)jblocks,  \
                            w_vec_ok);                                                                              \
     } while (0)
@@ -859,7 +851,6 @@ int launch_grad(const Geom &g, lrbi_dtype dt, bool mfma, const void *dDY, int64_
         else LRBI_LAUNCH_G(BF16Tag, false);
     }
 #undef LRBI_LAUNCH_G
-    LRBI_CHECK_LAUNCH();
     return LRBI_OK;
 }
 

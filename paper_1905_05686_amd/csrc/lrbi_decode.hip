@@ -628,19 +628,14 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
         const int64_t items = g.m * chunks64;
         const int64_t blocks = (items + kDecodeThreads - 1) / kDecodeThreads;
         if (blocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
-        hipLaunchKernelGGL(decode_generic_kernel, dim3((unsigned)blocks), dim3(kDecodeThreads), 0, stream, g, dIp,
+        LRBI_LAUNCH(decode_generic_kernel, dim3((unsigned)blocks), dim3(kDecodeThreads), 0, stream, g, dIp,
                            dIz, (uint4 *)dMask, p.pitch16, p.chunks);
-        LRBI_CHECK_LAUNCH();
         return LRBI_OK;
     };
     // cut-off edge tiles: only the generic kernel bounds its rows and columns by the matrix
     if ((flags & LRBI_FLAG_DECODE_GENERIC) || g.ragged) return launch_generic();
 
-    int device = 0, cus = 256;
-    if (hipGetDevice(&device) == hipSuccess) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && v > 0) cus = v;
-    }
+    const int cus = compute_units_of(stream);
     {
         NibblePlan np;
         if (plan_nibble(g, np, pitch_bytes, dIz, cus)) {
@@ -653,13 +648,11 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
             case 8: kern = decode_nibble_kernel<8>; break;
             default: break;
             }
-            if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-                return LRBI_ERR_LAUNCH;
+            LRBI_SET_MAX_LDS(kern, lds);
             const int64_t want = (int64_t)np.wgs_per_cu * cus;
             const int64_t grid = (np.items < want) ? np.items : want;
-            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kStreamThreads), lds, stream, g, np, dIp, dIz,
+            LRBI_LAUNCH(kern, dim3((unsigned)grid), dim3(kStreamThreads), lds, stream, g, np, dIp, dIz,
                                (uint4 *)dMask);
-            LRBI_CHECK_LAUNCH();
             return LRBI_OK;
         }
     }
@@ -697,16 +690,14 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
     if (p.items >= 4 * (int64_t)cus) {
         const size_t lds = 2 * (z_bytes + ip_bytes);
         auto kern = aligned ? decode_stream_kernel<true> : decode_stream_kernel<false>;
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return LRBI_ERR_LAUNCH;
-        hipLaunchKernelGGL(kern, dim3((unsigned)cus), dim3(kStreamThreads), lds, stream, g, p, dIp, dIz, (uint4 *)dMask);
+        LRBI_SET_MAX_LDS(kern, lds);
+        LRBI_LAUNCH(kern, dim3((unsigned)cus), dim3(kStreamThreads), lds, stream, g, p, dIp, dIz, (uint4 *)dMask);
     } else {
         const size_t lds = z_bytes + ip_bytes;
         auto kern = aligned ? decode_ztable_kernel<true> : decode_ztable_kernel<false>;
-        hipLaunchKernelGGL(kern, dim3((unsigned)p.items), dim3(kDecodeThreads), lds, stream, g, p, dIp, dIz,
+        LRBI_LAUNCH(kern, dim3((unsigned)p.items), dim3(kDecodeThreads), lds, stream, g, p, dIp, dIz,
                            (uint4 *)dMask);
     }
-    LRBI_CHECK_LAUNCH();
     return LRBI_OK;
 }
 

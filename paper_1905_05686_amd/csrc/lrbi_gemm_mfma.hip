@@ -768,9 +768,8 @@ static int launch_reduce(const Geom &g, const MfmaPlan &plan, int64_t N, void *d
     const int64_t items = g.m * (ldp / 4);
     const int64_t rblocks = (items + 255) / 256;
     if (rblocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
-    hipLaunchKernelGGL(splitk_reduce_kernel<Tag>, dim3((unsigned)rblocks), dim3(256), 0, stream,
+    LRBI_LAUNCH(splitk_reduce_kernel<Tag>, dim3((unsigned)rblocks), dim3(256), 0, stream,
                        (const float *)dWorkspace, ldp, g.m, (int)N, plan.splitk, (uint16_t *)dY, ldy, y_vec_ok);
-    LRBI_CHECK_LAUNCH();
     return LRBI_OK;
 }
 
@@ -791,13 +790,11 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
     const int64_t ldp = (N + 3) / 4 * 4;
     const dim3 grid((unsigned)blocks), block(RS > 0 ? 256 * KGROUPS : kThreads);
 
-#define LRBI_LAUNCH(KERN, SMEM)                                                                                   \
+#define LRBI_LAUNCH_TILE(KERN, SMEM)                                                                                   \
     do {                                                                                                          \
         auto kern = KERN;                                                                                         \
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(SMEM)) !=   \
-            hipSuccess)                                                                                           \
-            return LRBI_ERR_LAUNCH;                                                                               \
-        hipLaunchKernelGGL(kern, grid, block, (SMEM), stream, g, (const uint16_t *)dW, ldw, dIp, dIz,             \
+        LRBI_SET_MAX_LDS(kern, (SMEM));                                                                           \
+        LRBI_LAUNCH(kern, grid, block, (SMEM), stream, g, (const uint16_t *)dW, ldw, dIp, dIz,             \
                            (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp,      \
                            (int)mblocks, (int)nblocks, plan.kper, xcd_remap, y_vec_ok);                           \
     } while (0)
@@ -805,34 +802,33 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
     if constexpr (RS > 0) {
         const size_t smem = SmemPanel<BM, BN>::bytes;
         if (xvec) {
-            if (split) LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, true>), smem);
-            else LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, false>), smem);
+            if (split) LRBI_LAUNCH_TILE((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, true>), smem);
+            else LRBI_LAUNCH_TILE((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, true, false>), smem);
         } else {
-            if (split) LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, true>), smem);
-            else LRBI_LAUNCH((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, false>), smem);
+            if (split) LRBI_LAUNCH_TILE((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, true>), smem);
+            else LRBI_LAUNCH_TILE((mfma_gemm_panel_kernel<Tag, BM, BN, WAVES_M, WAVES_N, KGROUPS, RS, false, false>), smem);
         }
     } else {
         const size_t smem = Smem<BM, BN>::bytes;
         if (aligned) {
             if (xvec) {
-                if (split) LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, true>), smem);
-                else LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, false>), smem);
+                if (split) LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, true>), smem);
+                else LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, false>), smem);
             } else {
-                if (split) LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, true>), smem);
-                else LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, false>), smem);
+                if (split) LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, true>), smem);
+                else LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, false>), smem);
             }
         } else {
             if (xvec) {
-                if (split) LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, true>), smem);
-                else LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, false>), smem);
+                if (split) LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, true>), smem);
+                else LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, false>), smem);
             } else {
-                if (split) LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, true>), smem);
-                else LRBI_LAUNCH((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, false>), smem);
+                if (split) LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, true>), smem);
+                else LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, false>), smem);
             }
         }
     }
-#undef LRBI_LAUNCH
-    LRBI_CHECK_LAUNCH();
+#undef LRBI_LAUNCH_TILE
 
     if (split && !plan.planes_only) return launch_reduce<Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
     return LRBI_OK;

@@ -128,12 +128,11 @@ static int launch_valu_t(const Geom &g, const void *dW, int64_t ldw, const uint3
     const int x_vec_ok = (N == 1) && (ldx == 1) && (((uintptr_t)dX & 15) == 0);
     const dim3 grid((unsigned)blocks), block(kGemvThreads);
     if (N == 1)
-        hipLaunchKernelGGL((valu_gemm_kernel<T, 1>), grid, block, 0, stream, g, (const T *)dW, ldw, dIp, dIz,
+        LRBI_LAUNCH((valu_gemm_kernel<T, 1>), grid, block, 0, stream, g, (const T *)dW, ldw, dIp, dIz,
                            (const T *)dX, ldx, (int)N, (T *)dY, ldy, w_vec_ok, x_vec_ok);
     else
-        hipLaunchKernelGGL((valu_gemm_kernel<T, 4>), grid, block, 0, stream, g, (const T *)dW, ldw, dIp, dIz,
+        LRBI_LAUNCH((valu_gemm_kernel<T, 4>), grid, block, 0, stream, g, (const T *)dW, ldw, dIp, dIz,
                            (const T *)dX, ldx, (int)N, (T *)dY, ldy, w_vec_ok, x_vec_ok);
-    LRBI_CHECK_LAUNCH();
     return LRBI_OK;
 }
 

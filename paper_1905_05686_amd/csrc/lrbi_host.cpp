@@ -1,5 +1,5 @@
 // Host side of the LRBI library: descriptor validation, index-size accounting,
-// factor packing, and the dispatch of the two GPU entry points.
+// factor packing, workspace queries, and argument checks + dispatch of every GPU entry point.
 #include <string.h>
 
 #include "lrbi_internal.hpp"
@@ -267,8 +267,18 @@ extern "C" int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const v
                             dX, ldx, N, dY, ldy, dWorkspace, s);
 }
 
+// Sec. 3.2: methods 1 .. 3; the amplification must be a positive finite number for method 3
+static bool cost_manip_of(int32_t method, float amplify, CostManip *out)
+{
+    if (method < 1 || method > 3) return false;
+    if (method == 3 && !(amplify > 0.f && amplify <= 3.0e38f)) return false;
+    out->squared = method == 2;
+    out->scale = method == 3 ? (double)amplify : 1.0;
+    return true;
+}
+
 extern "C" int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
-                                   float w_threshold, const float *dMp, const float *dMz, const float *dTp,
+                                   float w_threshold, int32_t method, float amplify, const float *dMp, const float *dMz, const float *dTp,
                                    const float *dTz, void *dIp_packed, void *dIz_packed, uint64_t *dKept,
                                    double *dCost, void *dWorkspace, uint64_t workspace_bytes, void *stream)
 {
@@ -283,11 +293,13 @@ extern "C" int lrbi_threshold_eval(const lrbi_desc *desc, lrbi_dtype dtype, cons
         !aligned_to(dTz, 4) || !aligned_to(dKept, 8) || !aligned_to(dCost, 8))
         return LRBI_ERR_ALIGN;
     if (dIp_packed && (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8))) return LRBI_ERR_ALIGN;
+    CostManip manip;
+    if (!cost_manip_of(method, amplify, &manip)) return LRBI_ERR_SHAPE;
     const Geom g = make_geom(desc);
     if (threshold_eval_lds_bytes(g) > 64 * 1024) return LRBI_ERR_SHAPE;
     const EvalPlan plan = plan_threshold_eval(g);
     const bool ws_ok = dWorkspace && aligned_to(dWorkspace, 8) && workspace_bytes >= plan.workspace_bytes;
-    return launch_threshold_eval(g, dtype, dW, ldw, w_threshold, dMp, dMz, dTp, dTz, dIp_packed, dIz_packed, dKept,
+    return launch_threshold_eval(g, dtype, dW, ldw, w_threshold, manip, dMp, dMz, dTp, dTz, dIp_packed, dIz_packed, dKept,
                                  dCost, (plan.bands > 1 && ws_ok) ? dWorkspace : nullptr, (hipStream_t)stream);
 }
 
@@ -301,7 +313,8 @@ extern "C" int lrbi_threshold_eval_workspace_bytes(const lrbi_desc *desc, uint64
 }
 
 extern "C" int lrbi_search_thresholds(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
-                                      float w_threshold, const float *dMp, const float *dMz, double target_sparsity,
+                                      float w_threshold, int32_t method, float amplify, const float *dMp,
+                                      const float *dMz, double target_sparsity,
                                       const double *sp_values, int32_t n_sp, int32_t steps, int64_t tolerance,
                                       float *dTp, float *dTz, uint64_t *dKept, double *dCost, void *dIp_packed,
                                       void *dIz_packed, void *dWorkspace, uint64_t workspace_bytes, void *stream)
@@ -314,6 +327,8 @@ extern "C" int lrbi_search_thresholds(const lrbi_desc *desc, lrbi_dtype dtype, c
     if (es == 0) return LRBI_ERR_DTYPE;
     if (ldw < desc->n) return LRBI_ERR_PITCH;
     if (n_sp < 1 || steps < 1 || tolerance < 0) return LRBI_ERR_SHAPE;
+    CostManip manip;
+    if (!cost_manip_of(method, amplify, &manip)) return LRBI_ERR_SHAPE;
     if (!(target_sparsity > 0.0 && target_sparsity < 1.0)) return LRBI_ERR_SHAPE;
     for (int32_t a = 0; a < n_sp; ++a)
         if (!(sp_values[a] >= 0.0 && sp_values[a] <= 1.0)) return LRBI_ERR_SHAPE;
@@ -325,7 +340,7 @@ extern "C" int lrbi_search_thresholds(const lrbi_desc *desc, lrbi_dtype dtype, c
     if (threshold_eval_lds_bytes(g) > 64 * 1024) return LRBI_ERR_SHAPE;
     const SearchPlan plan = plan_search(g);
     if (workspace_bytes < plan.bytes) return LRBI_ERR_WORKSPACE;
-    return launch_search(g, dtype, dW, ldw, w_threshold, dMp, dMz, target_sparsity, n_sp, sp_values, steps, tolerance,
+    return launch_search(g, dtype, dW, ldw, w_threshold, manip, dMp, dMz, target_sparsity, n_sp, sp_values, steps, tolerance,
                          dTp, dTz, dKept, dCost, dIp_packed, dIz_packed, dWorkspace, (hipStream_t)stream);
 }
 

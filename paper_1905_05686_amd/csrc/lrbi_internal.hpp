@@ -5,6 +5,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <map>
+#include <mutex>
+#include <tuple>
+#include <utility>
+
 #include "lrbi.h"
 
 namespace lrbi {
@@ -36,9 +41,14 @@ struct EvalPlan {
     int rows_per_band;
     uint64_t workspace_bytes;
 };
+// how the cost of a candidate sees the magnitudes (Sec. 3.2: the cost keeps its definition, on manipulated magnitudes)
+struct CostManip {
+    bool squared;  // method 2: sum of squared magnitudes
+    double scale;  // method 3: the amplification, common to every counted weight; 1 otherwise
+};
 EvalPlan plan_threshold_eval(const Geom &g);
 size_t threshold_eval_lds_bytes(const Geom &g);
-int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold,
+int launch_threshold_eval(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, CostManip manip,
                           const float *dMp, const float *dMz, const float *dTp, const float *dTz, void *dIp, void *dIz,
                           uint64_t *dKept, double *dCost, void *dWorkspace, hipStream_t stream);
 
@@ -49,7 +59,8 @@ struct SearchPlan {
     uint64_t off_sorted_mp, off_sorted_mz, off_state, off_tp, off_tz, off_kept, off_cost, off_eval, bytes;
 };
 SearchPlan plan_search(const Geom &g);
-int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, const float *dMp,
+int launch_search(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, float w_threshold, CostManip manip,
+                  const float *dMp,
                   const float *dMz, double target_sparsity, int n_sp, const double *sp_values, int steps,
                   int64_t tolerance, float *dTpBest, float *dTzBest, uint64_t *dKeptBest, double *dCostBest, void *dIp,
                   void *dIz, void *dWorkspace, hipStream_t stream);
@@ -100,9 +111,61 @@ int launch_lstm_cell(lrbi_dtype dt, const float *dPlanes, int slices, int64_t m,
 #define LRBI_WAVES_PER_SIMD(n)
 #endif
 
-#define LRBI_CHECK_LAUNCH()                                   \
-    do {                                                      \
-        if (hipGetLastError() != hipSuccess) return LRBI_ERR_LAUNCH; \
+// Kernel launch with its own status: hipLaunchKernel returns the error of this launch, so an error that an
+// earlier HIP call of the caller left behind on this thread is neither reported as ours nor cleared.
+template <typename... P, size_t... I>
+inline hipError_t launch_kernel_impl(void (*kern)(P...), dim3 grid, dim3 block, size_t smem, hipStream_t stream,
+                                     std::tuple<P...> &vals, std::index_sequence<I...>)
+{
+    void *ptrs[sizeof...(P) ? sizeof...(P) : 1] = {(void *)&std::get<I>(vals)...};
+    return hipLaunchKernel((const void *)kern, grid, block, ptrs, smem, stream);
+}
+template <typename... P, typename... A>
+inline hipError_t launch_kernel(void (*kern)(P...), dim3 grid, dim3 block, size_t smem, hipStream_t stream, A &&...args)
+{
+    static_assert(sizeof...(P) == sizeof...(A), "kernel argument count");
+    std::tuple<P...> vals(static_cast<P>(args)...); // converted to the kernel's parameter types, by value
+    return launch_kernel_impl(kern, grid, block, smem, stream, vals, std::index_sequence_for<P...>{});
+}
+#define LRBI_LAUNCH(kern, grid, block, smem, stream, ...)                                                   \
+    do {                                                                                                    \
+        if (::lrbi::launch_kernel(kern, grid, block, smem, stream, __VA_ARGS__) != hipSuccess)              \
+            return LRBI_ERR_LAUNCH;                                                                         \
+    } while (0)
+
+// Raises a kernel's dynamic LDS limit; asked of the runtime once per (device, kernel, size reached), not per call.
+inline hipError_t set_max_lds(const void *kern, int bytes)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, const void *>, int> granted;
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) device = 0;
+    std::lock_guard<std::mutex> lock(mu);
+    int &have = granted[std::make_pair(device, kern)];
+    if (have >= bytes) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) have = bytes;
+    return e;
+}
+// Compute units of the device `stream` belongs to (the persistent kernels size their grids by it); looked up once
+// per device.
+inline int compute_units_of(hipStream_t stream)
+{
+    static std::mutex mu;
+    static std::map<int, int> known;
+    int device = 0;
+    if (hipStreamGetDevice(stream, &device) != hipSuccess && hipGetDevice(&device) != hipSuccess) device = 0;
+    std::lock_guard<std::mutex> lock(mu);
+    int &cus = known[device];
+    if (cus <= 0) {
+        int v = 0;
+        cus = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && v > 0) ? v : 256;
+    }
+    return cus;
+}
+#define LRBI_SET_MAX_LDS(kern, bytes)                                                                       \
+    do {                                                                                                    \
+        if (::lrbi::set_max_lds((const void *)(kern), (int)(bytes)) != hipSuccess) return LRBI_ERR_LAUNCH;  \
     } while (0)
 
 #if defined(__HIPCC__)

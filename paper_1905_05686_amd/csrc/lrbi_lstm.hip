@@ -50,14 +50,13 @@ int launch_lstm_cell(lrbi_dtype dt, const float *dPlanes, int slices, int64_t m,
     const int64_t blocks = (items + 255) / 256;
     if (blocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
     if (dt == LRBI_F16)
-        hipLaunchKernelGGL(lstm_cell_kernel<F16Tag>, dim3((unsigned)blocks), dim3(256), 0, stream, dPlanes, slices, m, ldp,
+        LRBI_LAUNCH(lstm_cell_kernel<F16Tag>, dim3((unsigned)blocks), dim3(256), 0, stream, dPlanes, slices, m, ldp,
                            (int)B, dC, ldc, (uint16_t *)dH1, ldh1, (uint16_t *)dH2, ldh2);
     else if (dt == LRBI_BF16)
-        hipLaunchKernelGGL(lstm_cell_kernel<BF16Tag>, dim3((unsigned)blocks), dim3(256), 0, stream, dPlanes, slices, m, ldp,
+        LRBI_LAUNCH(lstm_cell_kernel<BF16Tag>, dim3((unsigned)blocks), dim3(256), 0, stream, dPlanes, slices, m, ldp,
                            (int)B, dC, ldc, (uint16_t *)dH1, ldh1, (uint16_t *)dH2, ldh2);
     else
         return LRBI_ERR_DTYPE;
-    LRBI_CHECK_LAUNCH();
     return LRBI_OK;
 }
 

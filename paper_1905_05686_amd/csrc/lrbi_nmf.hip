@@ -1,4 +1,4 @@
-// Non-negative factorisation of the magnitude matrix, tile by tile (Algorithm 1's first step, Sec. 2.2):
+// Non-negative factorisation of the magnitude matrix, tile by tile (Algorithm 1's first step, Sec. 2.1):
 // M = |W| (optionally manipulated, Sec. 3.2) ~ M_p M_z with M_p (r x k), M_z (k x c) >= 0, minimising the
 // Frobenius distance.  The paper uses an off-the-shelf library and names no algorithm; this is Lee and Seung's
 // multiplicative update for that objective, from the caller's starting point, M_z first and then M_p:
@@ -314,8 +314,7 @@ static int nmf_copy(const float *src, float *dst, int64_t count, hipStream_t str
 {
     int64_t blocks = (count + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(nmf_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count);
-    LRBI_CHECK_LAUNCH();
+    LRBI_LAUNCH(nmf_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count);
     return LRBI_OK;
 }
 
@@ -329,12 +328,10 @@ static int nmf_iterate(const Geom &g, const void *dW, int64_t ldw, int method, f
     float *mp_cur = dMp, *mp_new = wsMp, *mz_cur = dMz, *mz_new = wsMz;
     const int w_vec_ok = (((uintptr_t)dW & 15) == 0) && ((ldw * (int64_t)sizeof(T)) % 16 == 0);
     for (int it = 0; it < iters; ++it) {
-        hipLaunchKernelGGL((nmf_update_z_kernel<T, KC>), dim3((unsigned)(tiles * cblocks)), dim3(kNmfThreads), 0, stream, g,
+        LRBI_LAUNCH((nmf_update_z_kernel<T, KC>), dim3((unsigned)(tiles * cblocks)), dim3(kNmfThreads), 0, stream, g,
                            (const T *)dW, ldw, method, w_threshold, amplify, mp_cur, mz_cur, mz_new, eps, cblocks);
-        LRBI_CHECK_LAUNCH();
-        hipLaunchKernelGGL((nmf_update_p_kernel<T, KC>), dim3((unsigned)(tiles * rblocks)), dim3(kNmfThreads), 0, stream, g,
+        LRBI_LAUNCH((nmf_update_p_kernel<T, KC>), dim3((unsigned)(tiles * rblocks)), dim3(kNmfThreads), 0, stream, g,
                            (const T *)dW, ldw, method, w_threshold, amplify, mp_cur, mz_new, mp_new, eps, rblocks, w_vec_ok);
-        LRBI_CHECK_LAUNCH();
         float *tmp = mp_cur;
         mp_cur = mp_new;
         mp_new = tmp;

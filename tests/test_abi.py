@@ -167,8 +167,8 @@ def test_threshold_eval_rejects_bad_arguments_before_any_launch():
     p = ctypes.c_void_p(base)
     f = lib.lrbi_threshold_eval
     args = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128), 0.5,
-                         kw.get("Mp", p), p, p, p, kw.get("Ip", None), kw.get("Iz", None), kw.get("kept", p), p, None, 0,
-                         None]
+                         kw.get("method", 1), kw.get("amp", 1.0), kw.get("Mp", p), p, p, p, kw.get("Ip", None),
+                         kw.get("Iz", None), kw.get("kept", p), p, None, 0, None]
     assert f(*args(W=None)) == -1
     assert f(*args(Mp=None)) == -1
     assert f(*args(kept=None)) == -1
@@ -178,6 +178,10 @@ def test_threshold_eval_rejects_bad_arguments_before_any_launch():
     assert f(*args(W=ctypes.c_void_p(base + 1))) == -6
     assert f(*args(kept=ctypes.c_void_p(base + 4))) == -6
     assert f(*args(Ip=p, Iz=ctypes.c_void_p(base + 4))) == -6
+    # magnitude manipulation of the cost: methods 1 .. 3, a positive finite amplification for method 3
+    assert f(*args(method=0)) == -2 and f(*args(method=4)) == -2
+    assert f(*args(method=3, amp=0.0)) == -2 and f(*args(method=3, amp=float("inf"))) == -2
+    assert f(*args(method=3, amp=float("nan"))) == -2
     # factor bits of one tile must fit in 64 KiB of on-chip memory
     big = lrbi.Desc(4096, 65536, 4096, 65536, 8)
     assert f(*args(d=big, ldw=65536)) == -2
@@ -197,7 +201,8 @@ def test_search_thresholds_rejects_bad_arguments_before_any_launch():
     f = lib.lrbi_search_thresholds
     big = 1 << 30
     args = lambda **kw: [ctypes.byref(kw.get("d", d)), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128), 0.5,
-                         kw.get("Mp", p), p, kw.get("S", 0.9), kw.get("sweep", sweep), kw.get("n_sp", 3),
+                         kw.get("method", 1), kw.get("amp", 1.0), kw.get("Mp", p), p, kw.get("S", 0.9),
+                         kw.get("sweep", sweep), kw.get("n_sp", 3),
                          kw.get("steps", 4), kw.get("tol", 1), kw.get("Tp", p), p, kw.get("kept", p), p,
                          kw.get("Ip", None), kw.get("Iz", None), kw.get("ws", p), kw.get("wsb", big), None]
     assert f(*args(W=None)) == -1
@@ -211,6 +216,7 @@ def test_search_thresholds_rejects_bad_arguments_before_any_launch():
     assert f(*args(n_sp=0)) == -2
     assert f(*args(steps=0)) == -2
     assert f(*args(tol=-1)) == -2
+    assert f(*args(method=5)) == -2 and f(*args(method=3, amp=-2.0)) == -2
     assert f(*args(S=0.0)) == -2
     assert f(*args(S=1.0)) == -2
     assert f(*args(S=float("nan"))) == -2

@@ -1,4 +1,4 @@
-"""GPU parity for the generality of the format (Sec. 3.1, Sec. 3.2): tiles cut off at the matrix edge and
+"""GPU parity for the generality of the format (Sec. 3.1): tiles cut off at the matrix edge and
 tiles of different ranks, through every entry point, against the oracle."""
 import numpy as np
 import pytest

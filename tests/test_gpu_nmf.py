@@ -1,4 +1,4 @@
-"""GPU parity of lrbi_nmf (Algorithm 1's first step, Sec. 2.2: non-negative factorisation of the magnitude matrix, tile
+"""GPU parity of lrbi_nmf (Algorithm 1's first step, Sec. 2.1: non-negative factorisation of the magnitude matrix, tile
 by tile; Sec. 3.2: weight-magnitude manipulation) against the oracle's float64 multiplicative updates."""
 import numpy as np
 import pytest

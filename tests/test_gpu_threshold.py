@@ -126,3 +126,34 @@ def test_nan_weights_are_never_counted():
     assert np.array_equal(kept.cpu().numpy().astype(np.uint64), kept_ref)
     assert np.all(np.isfinite(cost.cpu().numpy()))
     assert np.allclose(cost.cpu().numpy(), cost_ref, rtol=1e-12)
+
+
+@pytest.mark.parametrize("method,amplify", [(2, 1.0), (3, 10.0), (3, 1.0 / (1.0 - 0.9))])
+@pytest.mark.parametrize("idx", [1, 3, 5, 8])
+def test_cost_over_manipulated_magnitudes(idx, method, amplify):
+    """Sec. 3.2: the cost is summed over the manipulated magnitudes (squared, or amplified on the kept set); counts
+    and packed factors do not see the manipulation.  Squares and amplified values are exact in double on both sides."""
+    cfg, ldpad = EDGE[idx]
+    print("threshold_eval manipulated", idx, method, amplify, flush=True)
+    f = workloads.make_real_factors(cfg)
+    data = workloads.make(cfg, want_x=False)
+    W64 = workloads.to_float64(data["W"], cfg.dtype)
+    Ip, Iz = orc.threshold_factors(f["Mp"], f["Mz"], f["Tp"], f["Tz"])
+    M = orc.decode_mask(Ip, Iz, cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    amp32 = float(np.float32(amplify))
+    kept_ref, cost_ref = orc.candidate_cost(W64, f["w_threshold"], M, cfg.r, cfg.c, method, amp32)
+    d = desc_of(cfg)
+    t = lambda a: torch.from_numpy(a).to(dev())
+    for use_ws in (True, False):
+        ws = None
+        nbytes = lrbi.threshold_eval_workspace_bytes(d)
+        if use_ws and nbytes:
+            ws = torch.empty(nbytes // 8, dtype=torch.int64, device=dev())
+        kept, cost = lrbi.threshold_eval(d, to_device(data["W"], cfg.dtype), f["w_threshold"], t(f["Mp"]), t(f["Mz"]),
+                                         t(f["Tp"]), t(f["Tz"]), workspace=ws, method=method, amplify=amplify)
+        torch.cuda.synchronize()
+        assert np.array_equal(kept.cpu().numpy().astype(np.uint64), kept_ref)
+        c = cost.cpu().numpy()
+        assert np.all(np.abs(c - cost_ref) <= 1e-12 * np.maximum(cost_ref, 1e-30)), float(np.abs(c - cost_ref).max())
+    plain = orc.candidate_cost(W64, f["w_threshold"], M, cfg.r, cfg.c)[1]
+    assert cost_ref.sum() > 0 and not np.allclose(cost_ref, plain)

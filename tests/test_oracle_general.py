@@ -1,4 +1,4 @@
-"""Pins of the oracle for tiles that do not divide the matrix and for per-tile ranks (Sec. 3.1, Sec. 3.2:
+"""Pins of the oracle for tiles that do not divide the matrix and for per-tile ranks (Sec. 3.1:
 every submatrix is factorised on its own and may choose its own rank).  Each check reduces the general case
 to something fixed elsewhere: the set definition written out in plain Python, or the uniform, dividing case
 that the printed example and the brute-force tests already pin."""

@@ -1,4 +1,4 @@
-"""Pins of the oracle's non-negative factorisation (Algorithm 1's first step, Sec. 2.2; the paper uses a library and
+"""Pins of the oracle's non-negative factorisation (Algorithm 1's first step, Sec. 2.1; the paper uses a library and
 names no algorithm, so these pin the algorithm chosen, Lee and Seung's multiplicative updates, to the mathematics)."""
 import numpy as np
 import pytest
@@ -37,8 +37,8 @@ def test_rank_one_update_is_the_least_squares_solution():
     assert np.allclose(Mz, z1) and np.allclose(Mp, p1)
 
 
-def test_printed_example_and_manipulation_methods():
-    # the magnitude matrix of the worked example is |W| of Eq. 1; manipulation acts elementwise before the factorisation
+def test_manipulation_methods_on_a_handwritten_matrix():
+    # Sec. 3.2: manipulation acts elementwise on the magnitudes before the factorisation (values worked out by hand)
     W = np.array([[-0.1, 0.9, -1.2], [1.4, -0.2, 0.8]])
     assert np.array_equal(nmf.magnitude(W, 1), np.abs(W))
     assert np.allclose(nmf.magnitude(W, 2), W * W)

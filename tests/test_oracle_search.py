@@ -1,4 +1,4 @@
-"""Pins for the oracle's threshold search of Algorithm 1 (Sec. 2.2).  CPU only."""
+"""Pins for the oracle's threshold search of Algorithm 1 (Sec. 2.1).  CPU only."""
 import numpy as np
 import pytest
 
@@ -18,7 +18,7 @@ def test_index_and_initial_sz():
 
 
 def test_worked_example_is_recovered():
-    # Sec. 2.2: with S_p = 0.5 the thresholds behind Eq. 5 give S_a = 0.40 (15 ones, Eq. 6) and lose none of
+    # Sec. 2.1: with S_p = 0.5 the thresholds behind Eq. 5 give S_a = 0.40 (15 ones, Eq. 6) and lose none of
     # the weights of Eq. 2.  Searching for S = 0.40 from Eq. 4 must find exactly these factors.
     g = read_sections("worked_example.txt")
     Mp = g["Mp"].astype(np.float32)[None]
@@ -100,8 +100,20 @@ def test_brute_force_over_all_thresholds_on_a_tiny_tile():
             cands[(float(tp), float(tz))] = (int(kk[0]), float(cc[0]))
     assert (float(Tp[0]), float(Tz[0])) in cands
     assert cands[(float(Tp[0]), float(Tz[0]))] == (int(kept[0]), float(cost[0]))
-    best_diff = min(abs(v[0] - target) for v in cands.values())
-    assert abs(int(kept[0]) - target) >= best_diff   # cannot be closer than the best reachable
+    # For a fixed T_p the number of ones falls monotonically as T_z rises, and 8 halvings of [0, 1] resolve the 11
+    # possible T_z of this tile, so the bisection reaches the T_z closest to the target for every swept S_p.  The
+    # result must therefore be exactly as close to the target as brute force over (swept T_p) x (every T_z) gets.
+    sorted_p = np.sort(Mp.reshape(-1))
+    swept_tp = {float(alg1.threshold_at(sorted_p, alg1.quantile_index(sp, sorted_p.size))) for sp in sp_values}
+    assert float(Tp[0]) in swept_tp
+    reach = {tp: min(abs(v[0] - target) for (tp2, _), v in cands.items() if tp2 == tp) for tp in swept_tp}
+    assert abs(int(kept[0]) - target) == min(reach.values())
+    if min(reach.values()) == 0:
+        # eligible winners compare by cost: no swept T_p whose every target-hitting T_z is cheaper can have lost
+        for tp, d in reach.items():
+            if d == 0:
+                worst = max(v[1] for (tp2, _), v in cands.items() if tp2 == tp and v[0] == target)
+                assert float(cost[0]) <= worst
 
 
 def test_cut_off_tiles_are_searched_as_the_smaller_tiles_they_are():

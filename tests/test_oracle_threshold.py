@@ -44,6 +44,70 @@ def test_worked_example_cost_by_hand_at_a_harsher_threshold():
     assert cost[0] == pytest.approx(6.4, abs=1e-12)
 
 
+def test_worked_example_cost_over_manipulated_magnitudes():
+    # Sec. 3.2 pre-processes the magnitudes and keeps the definition of the cost, so the cost sums the manipulated
+    # magnitudes of the same six lost weights as above (1.2, 0.7, 1.6, 0.9, 1.0, 1.0), by hand:
+    #   method 2 (squared):  1.44 + 0.49 + 2.56 + 0.81 + 1 + 1 = 7.30
+    #   method 3 (x 2 where |w| >= 0.7; all six are): 2 * 6.4 = 12.8; with the paper's 1 / (1 - S), S = 0.48: 6.4 / 0.52
+    g = read_sections("worked_example.txt")
+    Mp = g["Mp"].astype(np.float32)[None]
+    Mz = g["Mz"].astype(np.float32)[None]
+    Ip, Iz = orc.threshold_factors(Mp, Mz, np.float32([0.5]), np.float32([1.25]))
+    M = orc.decode_mask(Ip, Iz, 5, 5, 5, 5, 2)
+    k1, c1 = orc.candidate_cost(g["W"], 0.7, M, 5, 5, 1)
+    k2, c2 = orc.candidate_cost(g["W"], 0.7, M, 5, 5, 2)
+    k3, c3 = orc.candidate_cost(g["W"], 0.7, M, 5, 5, 3, 2.0)
+    _, c3b = orc.candidate_cost(g["W"], 0.7, M, 5, 5, 3, 1.0 / (1.0 - 0.48))
+    assert int(k1[0]) == int(k2[0]) == int(k3[0]) == 8           # the count of ones does not see the manipulation
+    assert c1[0] == pytest.approx(6.4, abs=1e-12)
+    assert c2[0] == pytest.approx(7.30, abs=1e-12)
+    assert c3[0] == pytest.approx(12.8, abs=1e-12)
+    assert c3b[0] == pytest.approx(6.4 / 0.52, abs=1e-12)
+    with pytest.raises(ValueError):
+        orc.candidate_cost(g["W"], 0.7, M, 5, 5, 4)
+
+
+def test_search_reports_cost_over_manipulated_magnitudes():
+    # one row, rank 1, I_p = [1]: M_z alone decides which columns are kept.  Target 2 ones of 4 (S = 0.5): the only
+    # such candidate keeps columns {1, 2} and loses column 0 (3.0; column 3 is below the pruning threshold).
+    # Cost by hand: method 1: 3.0; method 2: 9.0; method 3 with amplification 4: 12.0.
+    from oracle import alg1
+    W = np.array([[3.0, 1.5, 1.5, 0.1]])
+    Mp = np.float32([[[1.0]]])
+    Mz = np.float32([[[0.2, 0.9, 0.8, 0.5]]])
+    for method, amp, want in ((1, 1.0, 3.0), (2, 1.0, 9.0), (3, 4.0, 12.0)):
+        tp, tz, kept, cost = alg1.search_thresholds(W, 1.0, Mp, Mz, 1, 4, 0.5, [0.0], steps=6, tolerance=0,
+                                                    method=method, amplify=amp)
+        assert int(kept[0]) == 2 and cost[0] == want
+
+
+def test_joint_sweep_takes_the_cheaper_candidate_under_each_method():
+    # thresholds and counts of each S_p's representative do not depend on the manipulation; the joint sweep returns
+    # the cheaper representative under the method's own cost
+    from oracle import alg1
+    #        col: 0    1    2    3
+    W = np.array([[3.0, 0.1, 0.1, 5.0],
+                  [0.1, 2.0, 2.0, 5.0]])
+    # rank 2: factor column 0 covers row 0, column 1 covers row 1 (M_p), M_z rows choose the columns
+    Mp = np.float32([[[0.9, 0.1], [0.2, 0.8]]])
+    Mz = np.float32([[[0.7, 0.1, 0.1, 0.9], [0.1, 0.6, 0.6, 0.9]]])
+    results = {}
+    for method in (1, 2):
+        cands = []
+        for sp in (0.25, 0.5):
+            tp, tz, kept, cost = alg1.search_thresholds(W, 1.0, Mp, Mz, 2, 4, 0.5, [sp], steps=8, tolerance=8,
+                                                        method=method)
+            cands.append((float(tp[0]), float(tz[0]), int(kept[0]), float(cost[0])))
+        both = alg1.search_thresholds(W, 1.0, Mp, Mz, 2, 4, 0.5, [0.25, 0.5], steps=8, tolerance=8, method=method)
+        winner = (float(both[0][0]), float(both[1][0]), int(both[2][0]), float(both[3][0]))
+        # the joint sweep returns the cheaper of the two single-S_p results (first on ties)
+        assert winner == min(cands, key=lambda v: v[3]) or cands[0][3] == cands[1][3]
+        results[method] = cands
+    # the squared cost of every candidate is the sum of squares of the same lost weights: never below plain^2 / count
+    for (a1, b1, k1, c1), (a2, b2, k2, c2) in zip(results[1], results[2]):
+        assert (a1, b1, k1) == (a2, b2, k2)        # thresholds and counts do not see the manipulation
+
+
 @pytest.mark.parametrize("m,n,r,c,k", [(6, 8, 3, 4, 2), (20, 30, 5, 10, 3), (64, 96, 32, 48, 9)])
 def test_against_array_formulation(m, n, r, c, k):
     # independent statement with whole-array numpy operations (integer product > 0, boolean selection)
