@@ -196,6 +196,25 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
                      void *stream);
 
 /*
+ * lrbi_masked_gemm for callers that cannot allocate device memory and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results
+ * (identical bits) and launches as lrbi_masked_gemm called with a workspace of
+ * lrbi_masked_gemm_workspace_bytes bytes, but the partial sums of a split reduction go to a scratch array
+ * of LRBI_STATIC_SCRATCH_BYTES bytes that is part of the library image on every GPU it runs on (held until
+ * the process ends).  The call allocates and frees nothing, on the host side or the device side of HIP.
+ *   Limit: shapes whose workspace query exceeds LRBI_STATIC_SCRATCH_BYTES return LRBI_ERR_WORKSPACE before
+ *   any launch (all five paper-shaped configurations fit: the largest, 4096 x 9216 at N = 128, needs 16 MiB).
+ *   The device of `stream` must be the current device (the scratch array is looked up per current device).
+ *   All calls on one GPU share that GPU's array: two calls that may overlap in time (different streams, or
+ *   graph branches without an edge between them) race on it; calls ordered by one stream do not.
+ *   Nothing in the array needs to start at zero: every partial sum is written before it is read.
+ */
+#define LRBI_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+int lrbi_masked_gemm_static(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                            const void *dIp_packed, const void *dIz_packed, const void *dX, int64_t ldx,
+                            int64_t N, void *dY, int64_t ldy, void *stream);
+
+/*
  * One candidate of Algorithm 1 (Sec. 2.1), evaluated for every tile in one launch:
  * the real-valued non-negative factors M_p (r x k) and M_z (k x c) of a tile are turned
  * into binary factors with the tile's thresholds, (I_p)_{i,l} = 1 iff (M_p)_{i,l} >= T_p

@@ -75,6 +75,7 @@ def load_library():
     lib.lrbi_decode_mask.argtypes = [pd, vp, vp, vp, i64, vp]
     lib.lrbi_masked_gemm_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
     lib.lrbi_masked_gemm.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, u64, vp]
+    lib.lrbi_masked_gemm_static.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp]
     lib.lrbi_threshold_eval.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, ctypes.c_int32, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64,
                                         vp]
     lib.lrbi_threshold_eval_workspace_bytes.argtypes = [pd, pu64]
@@ -92,7 +93,7 @@ def load_library():
     lib.lrbi_lstm_step.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, i64, vp, i64, vp, u64, vp]
     for name in ("lrbi_index_bits", "lrbi_index_bits_ranked", "lrbi_pack_factors_ranked", "lrbi_csr_bits",
                  "lrbi_pack_factors", "lrbi_unpack_mask", "lrbi_decode_mask",
-                 "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm", "lrbi_threshold_eval",
+                 "lrbi_masked_gemm_workspace_bytes", "lrbi_masked_gemm", "lrbi_masked_gemm_static", "lrbi_threshold_eval",
                  "lrbi_threshold_eval_workspace_bytes", "lrbi_search_thresholds", "lrbi_search_workspace_bytes",
                  "lrbi_masked_gemm_t_workspace_bytes", "lrbi_masked_gemm_t", "lrbi_masked_grad",
                  "lrbi_lstm_step_workspace_bytes", "lrbi_lstm_step", "lrbi_nmf_workspace_bytes", "lrbi_nmf"):
@@ -239,6 +240,26 @@ def masked_gemm(desc: Desc, W, dIp, dIz, X, out=None, workspace=None, stream=Non
         _dev_ptr(X, "X"), X.stride(0), N, _dev_ptr(out, "Y"), out.stride(0), ws_ptr, ws_bytes, _stream_ptr(stream)),
         "lrbi_masked_gemm")
     return out[:, 0] if squeeze else out
+
+
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def masked_gemm_static(desc: Desc, W, dIp, dIz, X, out, stream=None):
+    """lrbi_masked_gemm_static: as masked_gemm, with the library's own static scratch array instead of a workspace.
+    `out` [m, N] must be given: the call itself allocates nothing."""
+    if W.dim() != 2 or X.dim() != 2 or W.shape != (desc.m, desc.n) or X.shape[0] != desc.n:
+        raise ValueError("shape mismatch")
+    if W.stride(1) != 1 or (X.shape[1] > 1 and X.stride(1) != 1) or W.dtype != X.dtype:
+        raise ValueError("W and X must be row-major tensors of the same dtype")
+    N = X.shape[1]
+    if out.shape != (desc.m, N) or out.dtype != W.dtype or (N > 1 and out.stride(1) != 1):
+        raise ValueError("bad out tensor")
+    _check(load_library().lrbi_masked_gemm_static(
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), _dev_ptr(dIp, "Ip"), _dev_ptr(dIz, "Iz"),
+        _dev_ptr(X, "X"), X.stride(0), N, _dev_ptr(out, "Y"), out.stride(0), _stream_ptr(stream)),
+        "lrbi_masked_gemm_static")
+    return out
 
 
 def threshold_eval_workspace_bytes(desc: Desc) -> int:

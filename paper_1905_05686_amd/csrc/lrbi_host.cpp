@@ -267,6 +267,51 @@ extern "C" int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const v
                             dX, ldx, N, dY, ldy, dWorkspace, s);
 }
 
+// ---------------------------------------------------------------------------
+// lrbi_masked_gemm_static: the fused masked product for callers that cannot allocate.  The partial sums of a
+// split reduction live in `scratch`, a device array that is part of the library's code object: every GPU the
+// library runs on holds its own copy from the moment the code object is loaded there until the process ends.
+// In host code the array's name only stands for the symbol; its address on a device is asked of the runtime once
+// per device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[LRBI_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+void *scratch_ptr[kMaxDevices]; // per device: address of that device's copy of `scratch`, nullptr until asked
+
+// address of the current device's scratch array; nullptr when the runtime cannot tell
+void *scratch_of_current_device()
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[device]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        scratch_ptr[device] = p;
+    }
+    return scratch_ptr[device];
+}
+} // namespace
+
+extern "C" int lrbi_masked_gemm_static(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                                       const void *dIp_packed, const void *dIz_packed, const void *dX, int64_t ldx,
+                                       int64_t N, void *dY, int64_t ldy, void *stream)
+{
+    uint64_t need = 0;
+    const int rc = lrbi_masked_gemm_workspace_bytes(desc, dtype, N, &need);
+    if (rc != LRBI_OK) return rc;
+    if (need > (uint64_t)LRBI_STATIC_SCRATCH_BYTES) return LRBI_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (need) {
+        ws = scratch_of_current_device();
+        if (!ws) return LRBI_ERR_LAUNCH;
+    }
+    return lrbi_masked_gemm(desc, dtype, dW, ldw, dIp_packed, dIz_packed, dX, ldx, N, dY, ldy, ws,
+                            ws ? (uint64_t)LRBI_STATIC_SCRATCH_BYTES : 0u, stream);
+}
+
 // Sec. 3.2: methods 1 .. 3; the amplification must be a positive finite number for method 3
 static bool cost_manip_of(int32_t method, float amplify, CostManip *out)
 {
