@@ -706,8 +706,10 @@ struct TileDef {
 // wavefronts, 9-11: panel kernel with 8 wavefronts (two wave groups).
 static const TileDef kTiles[] = {{0, 0, false},    {128, 128, false}, {128, 64, false}, {128, 32, false},
                                  {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
-                                 {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true}};
-static constexpr int kNumTiles = 11;
+                                 {128, 128, true}, {128, 128, true},  {128, 64, true},  {128, 32, true},
+                                 {128, 128, true}, {128, 128, true},  {128, 128, true}};
+static constexpr int kNumTiles = 14;
+static constexpr int kFirstPipeTile = 12; // 12 .. 14: the software-pipelined kernel (lrbi_gemm_pipe.hip), variants 0 .. 2
 
 static bool panel_ok(const Geom &g, int bm)
 {
@@ -721,7 +723,7 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
     if (tile >= 1 && tile <= kNumTiles && kTiles[tile].panel && !panel_ok(g, kTiles[tile].bm)) tile = 0;
     if (tile < 1 || tile > kNumTiles) {
         tile = (N > 64) ? 1 : (N > 32 ? 2 : 3);
-        if (panel_ok(g, 128)) tile = (N > 64) ? 9 : (N > 32 ? 10 : 11);
+        if (panel_ok(g, 128)) tile = (N > 64) ? 14 : (N > 32 ? 10 : 11); // 14: falls back to 9 when X is not 16-byte readable
     }
     p.tile = tile;
     p.bm = kTiles[tile].bm;
@@ -860,12 +862,26 @@ static int launch_dtype(const Geom &g, const MfmaPlan &plan, const void *dW, int
 }
 #undef LRBI_TILE_ARGS
 
-int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const void *dW, int64_t ldw,
+int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan_in, lrbi_dtype dt, const void *dW, int64_t ldw,
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY,
                      int64_t ldy, void *dWorkspace, hipStream_t stream)
 {
     // the W loads are 16 bytes wide
     if (((uintptr_t)dW & 15) != 0 || ldw % 8 != 0 || g.n % 8 != 0) return LRBI_ERR_ALIGN;
+    MfmaPlan plan = plan_in;
+    if (plan.tile >= kFirstPipeTile) {
+        if (pipe_ok(g, dIz, dX, ldw, ldx, N)) {
+            const int pf = plan.tile - kFirstPipeTile;
+            const int rc = launch_pipe_gemm(g, plan, dt, pf, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+            if (rc != LRBI_OK) return rc;
+            if (plan.splitk > 1 && !plan.planes_only) {
+                if (dt == LRBI_F16) return launch_reduce<F16Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
+                return launch_reduce<BF16Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
+            }
+            return LRBI_OK;
+        }
+        plan.tile = 9; // same blocking on the staged panel kernel
+    }
     if (dt == LRBI_F16)
         return launch_dtype<F16Tag>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
     if (dt == LRBI_BF16)
