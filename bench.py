@@ -33,19 +33,27 @@ def _die_multi_gpu(n):
     sys.exit(2)
 
 
+# kernels behind lrbi_masked_gemm on the headline workload; the recorded HBM traffic is only quoted when it was
+# measured on these same kernels
+C2_GEMM_KERNELS = "mfma_gemm_pipe_kernel + splitk_reduce_kernel"
+
+
 def _recorded_traffic():
     """HBM bytes per launch of the C2 fused product (kernel + split-K reduction), from the rocprofv3
     FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (counters cannot be read from inside
-    this process); None when no summary is there."""
+    this process); None when no summary is there or when it was taken on other kernels."""
     path = os.path.join(ROOT, "profiles", "C2_masked_gemm_hbm_traffic.md")
+    kernels, traffic = None, None
     try:
         with open(path) as f:
             for line in f:
+                if line.startswith("kernels:"):
+                    kernels = line.split(":", 1)[1].strip()
                 if line.startswith("traffic_bytes_per_launch:"):
-                    return int(line.split(":")[1].strip())
+                    traffic = int(line.split(":")[1].strip())
     except OSError:
-        pass
-    return None
+        return None
+    return traffic if kernels == C2_GEMM_KERNELS else None
 
 
 def main():
@@ -56,7 +64,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, lstm_sequence_C4, nmf_C2, nmf_C3, "
+                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, lstm_sequence_C4, nmf_C2, nmf_C3, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -203,7 +211,7 @@ def main():
     factor_bytes = lrbi.index_bits(desc)["lrbi_bits"] / 8
     gemm_bytes = cfg.m * cfg.n * es + cfg.n * cfg.N * es + cfg.m * cfg.N * es + factor_bytes
     achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "lrbi_masked_gemm (mfma_gemm_panel_kernel + splitk_reduce_kernel)",
+    roofline = {"bound": "hbm", "kernel": "lrbi_masked_gemm (%s)" % C2_GEMM_KERNELS,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _recorded_traffic(),
                 "avg_launch_ms": round(gemm_ms, 5), "algorithmic_bytes": int(gemm_bytes),
@@ -264,12 +272,15 @@ def main():
                 bmask = torch.empty((big.m, big.n // 8), dtype=torch.uint8, device=dev)
                 ms, med = event_times([lambda: lrbi.decode_mask(bdesc, bIp, bIz, out=bmask)], 10, 3)
                 mask_bytes = big.m * big.n / 8
+                moved = mask_bytes + sizes["lrbi_bits"] / 8  # the mask written once, the packed factors read once
                 others[key] = {
                     "workload": "%s tile shape (%dx%d, rank %d, p=%.2f) on a %dx%d mask (%.2f GiB)" % (
                         base[:2], big.r, big.c, big.k, big.p, big.m, big.n, mask_bytes / 2 ** 30),
                     "avg_launch_ms": round(ms, 4), "gbit_s": round(big.m * big.n / (ms * 1e-3) / 1e9, 1),
                     "write_GBs": round(mask_bytes / (ms * 1e-3) / 1e9, 1),
-                    "hbm_frac_on_mask_bytes_written": round(mask_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                    "hbm_frac_on_mask_bytes_written": round(mask_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "algorithmic_bytes": int(moved), "GBs": round(moved / (ms * 1e-3) / 1e9, 1),
+                    "hbm_frac": round(moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
                 del bIp, bIz, bmask
             except Exception as e:  # keep the headline line even if an extra fails
                 others[key] = {"error": repr(e)}
@@ -281,11 +292,14 @@ def main():
             "general_resnet_tiles": workloads.Config("general_resnet_tiles", 2304, 2048, 576, 512, 145, 0.02, 128, "bf16", 0.02),
             "general_edge_tiles": workloads.Config("general_edge_tiles", 4100, 9224, 256, 256, 16, 0.08, 128, "f16", 0.01),
         }
-        for name in ("C3a", "C3b", "C4", "C5", "C1", "general_resnet_tiles", "general_edge_tiles"):
+        # the C3 tile shape on a product large enough that the prologue and the last partial wave of workgroups do not
+        # count: the matrix-core kernel's steady state
+        steady = {"steady_state_C3_tiles": workloads.Config("steady_state_C3_tiles", 16384, 16384, 512, 512, 32, 0.06, 4096, "bf16", 0.01)}
+        for name in ("C3a", "C3b", "C4", "C5", "C1", "general_resnet_tiles", "general_edge_tiles", "steady_state_C3_tiles"):
             if wanted is not None and name not in wanted:
                 continue
             try:
-                c = workloads.CONFIGS.get(name) or general[name]
+                c = workloads.CONFIGS.get(name) or general.get(name) or steady[name]
                 d = workloads.make(c)
                 de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
                 ip_, iz_ = factors_to_dev(de, d["Ip01"], d["Iz01"])

@@ -71,6 +71,8 @@ def build(verbose: bool = False, extra_flags=(), incremental: bool = False) -> s
         out, _ = p.communicate()
         for name, nbytes in _private_memory_users(out):
             failed = True
+            if os.path.exists(os.path.join(CSRC, os.path.splitext(src)[0] + ".o")):
+                os.remove(os.path.join(CSRC, os.path.splitext(src)[0] + ".o"))  # not to be linked by a later incremental build
             print("FAILED: %s: kernel %s uses %d bytes of private memory per lane" % (src, name, nbytes),
                   file=sys.stderr)
         out = "\n".join(l for l in out.splitlines()

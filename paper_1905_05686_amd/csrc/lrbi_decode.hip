@@ -22,6 +22,7 @@
 #include <stdlib.h>
 
 #include "lrbi_internal.hpp"
+#include "lrbi_lds_dma.hpp"
 
 namespace lrbi {
 
@@ -406,23 +407,59 @@ struct NibblePlan {
     int ip_words;      // words in one IpL buffer (multiple of 4)
     int zs_pieces;     // pieces in Zs
     int wgs_per_cu;    // resident workgroups per compute unit the launch aims at
+    // one grid stride of the item index, split the way an item index splits into (tile row, band, span)
+    int step_span, step_band, step_ti;
+    int ip_sh;         // a band's I_p words per tile fit 1 << ip_sh
+    int ip_pitch;      // words between the I_p runs of neighbouring tiles in LDS
+    int rot_div;       // bands per rotation of the span order
 };
-static constexpr int kNibTableBytes = 32 * 1024; // halved when two workgroups share a compute unit
-static constexpr int kNibIpBytes = 10 * 1024;
-static constexpr int kNibMaxIpPerLane = (kNibIpBytes / 4 + kStreamThreads - 1) / kStreamThreads;
+static constexpr int kNibTableBytes = 32 * 1024; // per workgroup
+static constexpr int kNibTileSkew = 4; // unused 16-byte pieces after every tile's table
+static constexpr int kNibMaxIpPerLane = 2; // I_p words a lane fetches per item (one band of every tile under the span)
 
 struct NibItem {
     int ti, row_lo, nrows, tj_first, ntiles;
 };
-__device__ __forceinline__ NibItem make_nib_item(const Geom &g, const NibblePlan &p, int64_t id)
+// Item index = (tile row * bands_per_tile_row + band) * spans + span.  A workgroup splits its first index once and
+// then advances the three digits by the grid stride (split on the host), so no division runs per item.
+struct NibCursor {
+    int span, band, ti;
+};
+__device__ __forceinline__ NibCursor nib_cursor_at(const NibblePlan &p, uint32_t id)
+{
+    NibCursor cu;
+    const uint32_t row = id / (uint32_t)p.spans;
+    cu.span = (int)(id - row * (uint32_t)p.spans);
+    cu.ti = (int)(row / (uint32_t)p.bands_per_tile_row);
+    cu.band = (int)(row - (uint32_t)cu.ti * (uint32_t)p.bands_per_tile_row);
+    return cu;
+}
+__device__ __forceinline__ void nib_cursor_step(const NibblePlan &p, NibCursor &cu)
+{
+    cu.span += p.step_span;
+    cu.band += p.step_band;
+    cu.ti += p.step_ti;
+    if (cu.span >= p.spans) {
+        cu.span -= p.spans;
+        ++cu.band;
+    }
+    if (cu.band >= p.bands_per_tile_row) {
+        cu.band -= p.bands_per_tile_row;
+        ++cu.ti;
+    }
+}
+__device__ __forceinline__ NibItem make_nib_item(const Geom &g, const NibblePlan &p, const NibCursor &cu)
 {
     NibItem it;
-    const int span = (int)(id % p.spans);
-    const int64_t band = id / p.spans;
-    it.ti = (int)(band / p.bands_per_tile_row);
-    it.row_lo = (int)(band - (int64_t)it.ti * p.bands_per_tile_row) * p.rows_per_band;
+    it.ti = cu.ti;
+    it.row_lo = cu.band * p.rows_per_band;
     const int row_hi = (it.row_lo + p.rows_per_band < g.r) ? it.row_lo + p.rows_per_band : g.r;
     it.nrows = row_hi - it.row_lo;
+    // Workgroups whose grid stride is a whole number of bands would stay on one span for good, and with them every
+    // XCD (workgroup index modulo 8) on the same few 256-byte lanes of its L2: the span is rotated by one for every
+    // rot_div bands, which is a bijection within a band
+    const uint32_t rot = (uint32_t)(cu.ti * p.bands_per_tile_row + cu.band) / (uint32_t)p.rot_div;
+    const int span = (int)(((uint32_t)cu.span + rot) % (uint32_t)p.spans);
     it.tj_first = span * p.span_tiles;
     it.ntiles = (it.tj_first + p.span_tiles <= g.tile_cols) ? p.span_tiles : g.tile_cols - it.tj_first;
     return it;
@@ -433,66 +470,63 @@ __device__ __forceinline__ uint4 or3x4(uint4 a, uint4 b, uint4 c)
     return make_uint4(a.x | b.x | c.x, a.y | b.y | c.y, a.z | b.z | c.z, a.w | b.w | c.w);
 }
 
-template <int GT /* compile-time G, 0 = run-time */>
-__global__ __launch_bounds__(kStreamThreads) LRBI_WAVES_PER_SIMD(GT == 8 ? 4 : 8) void decode_nibble_kernel(Geom g, NibblePlan p,
+template <int GT /* compile-time G, 0 = run-time */, int CPT /* compile-time pieces per tile row, 0 = run-time */>
+__global__ __launch_bounds__(kStreamThreads) LRBI_WAVES_PER_SIMD((GT >= 4 && CPT == 0) ? 4 : 8) void decode_nibble_kernel(Geom g, NibblePlan p,
                                                                        const uint32_t *__restrict__ Ip,
                                                                        const uint32_t *__restrict__ Iz,
                                                                        uint4 *__restrict__ mask)
 {
     extern __shared__ uint4 lrbi_dyn_smem[];
     const int G = GT ? GT : p.G;
-    const int ip_rows = p.rows_per_band + 1;
-    const int buf_pieces = p.t_pieces + p.ip_words / 4;
-#define LRBI_TB(b) (lrbi_dyn_smem + (b) * buf_pieces)
-#define LRBI_IPB(b) ((uint32_t *)(lrbi_dyn_smem + (b) * buf_pieces + p.t_pieces))
-    uint4 *Zs = lrbi_dyn_smem + 2 * buf_pieces;
+    const int cpt = CPT ? CPT : p.cpt;
+    // a tile's table is followed by four unused pieces, so that the tables of neighbouring tiles start 64 bytes
+    // apart modulo the bank width: the entries of the zero nibble (most nibbles) of four tiles then sit in
+    // different banks
+    const int tile_pieces = G * 16 * cpt + kNibTileSkew;
+    // one table (it is rebuilt between two barriers, when nobody reads it), two I_p buffers (the next item's words
+    // are stored while the current item is still being decoded), one buffer of raw I_z rows
+#define LRBI_TB(b) (lrbi_dyn_smem)
+#define LRBI_IPB(b) ((uint32_t *)(lrbi_dyn_smem + p.t_pieces + (b) * (p.ip_words / 4)))
+    uint4 *Zs = lrbi_dyn_smem + p.t_pieces + 2 * (p.ip_words / 4);
 
-    uint4 zreg;                       // at most one I_z piece per lane and item
-    int zdst;
-    uint32_t ipreg[kNibMaxIpPerLane];
-    int ipdst[kNibMaxIpPerLane];
-
-    auto load_item = [&](const NibItem &it) {
-        // I_z rows of the item's tiles: piece index = (tile, l, piece in tile row)
-        const int total = it.ntiles * g.k * p.cpt;
-        zdst = -1;
-        zreg = make_uint4(0u, 0u, 0u, 0u);
-        if ((int)threadIdx.x < total) {
-            const int per_tile = g.k * p.cpt;
-            const int tl = threadIdx.x / per_tile, e = threadIdx.x - tl * per_tile;
-            const uint32_t *src = Iz + ((int64_t)it.ti * g.tile_cols + it.tj_first + tl) * g.k * (int64_t)g.izw + 4 * e;
-            // a tile's k rows are contiguous (izw = 4 * cpt words per row), so e indexes them linearly
-            if (p.iz16) zreg = *reinterpret_cast<const uint4 *>(src);
-            else zreg = make_uint4(src[0], src[1], src[2], src[3]);
-            zdst = threadIdx.x;
+    // The factor words of an item go from global memory straight into LDS (no registers, no second pass): every
+    // wavefront copies runs of 64 consecutive words.  I_z: the k rows of a tile are contiguous (izw = 4 * cpt words
+    // per row) and so are the tiles of a span, so the lane index is the piece index from the span's first tile on.
+    // I_p: linear index = lane + 1024 * slot, split by a shift into (tile of the span, word within the tile's band);
+    // the plan keeps a band within 1 << ip_sh words, and a wavefront's 64 words within one tile's run in LDS.
+    const int z_per_tile = g.k * cpt;
+    const int z_tl = (int)((uint32_t)threadIdx.x / (uint32_t)z_per_tile); // tile of the span this lane's I_z piece is in
+    const uint32_t wave_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x & ~63u)); // uniform in a wavefront
+    auto load_item = [&](const NibItem &it, int b) {
+        const uint32_t *zsrc = Iz + ((int64_t)it.ti * g.tile_cols + it.tj_first) * g.k * (int64_t)g.izw;
+        if (p.iz16) {
+            if (z_tl < it.ntiles) load_to_lds16(lds_address(Zs + wave_first), zsrc, 16u * threadIdx.x);
+        } else {
+            const uint32_t z_words = (uint32_t)(it.ntiles * z_per_tile) * 4u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { // words 256 * wave + 64 * q + lane of the run
+                const uint32_t w = 4u * wave_first + 64u * q + (threadIdx.x & 63u);
+                if (w < z_words) load_to_lds4(lds_address(Zs + wave_first) + 256u * q, zsrc, 4u * w);
+            }
         }
-        const int ip_per_tile = it.nrows * g.ipw;
-        const int ip_total = it.ntiles * ip_per_tile;
+        const uint32_t *isrc = Ip + (((int64_t)it.ti * g.tile_cols + it.tj_first) * g.r + it.row_lo) * g.ipw;
+        const int ip_live = it.nrows * g.ipw; // words of a tile's band that exist (the last band may be short)
+        const int tile_words = g.r * g.ipw;
 #pragma unroll
         for (int j = 0; j < kNibMaxIpPerLane; ++j) {
             const int idx = threadIdx.x + kStreamThreads * j;
-            ipreg[j] = 0u;
-            ipdst[j] = -1;
-            if (idx < ip_total) {
-                const int tl = idx / ip_per_tile, e = idx - tl * ip_per_tile;
-                const int64_t t = (int64_t)it.ti * g.tile_cols + it.tj_first + tl;
-                ipreg[j] = Ip[(t * g.r + it.row_lo) * g.ipw + e];
-                ipdst[j] = (tl * ip_rows) * g.ipw + e;
-            }
+            const int tl = idx >> p.ip_sh, e = idx & ((1 << p.ip_sh) - 1);
+            const int idx0 = (int)wave_first + kStreamThreads * j; // the wavefront's first word
+            const int dst0 = (idx0 >> p.ip_sh) * p.ip_pitch + (idx0 & ((1 << p.ip_sh) - 1));
+            if (tl < it.ntiles && e < ip_live)
+                load_to_lds4(lds_address(LRBI_IPB(b) + dst0), isrc, 4u * (uint32_t)(tl * tile_words + e));
         }
     };
-    auto stash_item = [&](int b) {
-        if (zdst >= 0) Zs[zdst] = zreg;
-#pragma unroll
-        for (int j = 0; j < kNibMaxIpPerLane; ++j)
-            if (ipdst[j] >= 0) LRBI_IPB(b)[ipdst[j]] = ipreg[j];
-    };
-    // T[tile][g][nib][piece] = OR of the I_z rows 4g + bit, bit in nib
     auto build_table = [&](const NibItem &it, int b) {
-        const int total = it.ntiles * G * 16 * p.cpt;
+        const int total = it.ntiles * G * 16 * cpt;
         for (int idx = threadIdx.x; idx < total; idx += kStreamThreads) {
-            const int cq = idx % p.cpt;
-            const int rest = idx / p.cpt;
+            const int cq = idx % cpt;
+            const int rest = idx / cpt;
             const int nib = rest & 15;
             const int tg = rest >> 4; // tile * G + g
             const int tl = tg / G, gg = tg - tl * G;
@@ -500,60 +534,79 @@ __global__ __launch_bounds__(kStreamThreads) LRBI_WAVES_PER_SIMD(GT == 8 ? 4 : 8
 #pragma unroll
             for (int bit = 0; bit < 4; ++bit) {
                 const int l = 4 * gg + bit;
-                if (((nib >> bit) & 1) && l < g.k) acc = or4(acc, Zs[(tl * g.k + l) * p.cpt + cq]);
+                if (((nib >> bit) & 1) && l < g.k) acc = or4(acc, Zs[(tl * g.k + l) * cpt + cq]);
             }
-            LRBI_TB(b)[idx] = acc;
+            LRBI_TB(b)[tl * tile_pieces + (gg * 16 + nib) * cpt + cq] = acc;
         }
     };
-    auto decode_rows = [&](const NibItem &it, int b) {
-        const int TX = 1 << p.tx_log2;
-        const int tx = threadIdx.x & (TX - 1);
-        const int ty = threadIdx.x >> p.tx_log2;
-        const int TY = kStreamThreads >> p.tx_log2;
-        if (tx >= it.ntiles * p.cpt) return;
-        const int tl = tx / p.cpt, cq = tx - tl * p.cpt;
-        const uint4 *Tq = LRBI_TB(b) + (tl * G * 16) * p.cpt + cq;
-        const uint32_t *ipr = LRBI_IPB(b) + (tl * ip_rows + ty) * g.ipw;
-        const int ip_step = TY * g.ipw;
-        uint4 *out = mask + ((int64_t)it.ti * g.r + it.row_lo + ty) * p.pitch16 + (int64_t)(it.tj_first + tl) * p.cpt + cq;
-        const int64_t out_step = (int64_t)TY * p.pitch16;
-        const uint4 *zero_piece = LRBI_TB(b); // entry (tile 0, group 0, nibble 0): all zero
-        const int nstride = p.cpt;       // pieces between nibble values
-        const int gstride = 16 * p.cpt;  // pieces between groups
-        for (int i = ty; i < it.nrows; i += TY, ipr += ip_step, out += out_step) {
-            uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-            if (GT == 1 || GT == 2 || GT == 4 || GT == 8) {
-                // one I_p word holds all nibbles; GT independent table reads, OR tree of 3-input ORs
-                const uint32_t w = ipr[0];
-                uint4 e[GT ? GT : 1];
+    // Row loop of an item.  Lane (tx, ty): tx picks the 16-byte piece of the span, ty the row; a lane past the end of a
+    // short last span repeats the last piece (the same bytes to the same address), so every wavefront issues the same
+    // number of stores and the loop has no per-lane exit.
+    const int TX = 1 << p.tx_log2;
+    const int TY = kStreamThreads >> p.tx_log2;
+    const int ty = threadIdx.x >> p.tx_log2;
+    const int nbytes = 16 * cpt, gbytes = 256 * cpt;
+    const int ip_step = TY * g.ipw;
+    const uint32_t ostep = (uint32_t)((int64_t)TY * p.pitch16 * 16);
+    const unsigned char *Tq; // byte address of this lane's column of table entries: entry (g, nib) at g * gbytes + nib * nbytes
+    const uint32_t *ipr;
+    unsigned char *obase;    // uniform base of the item's first row; a 32-bit byte offset per lane and row is added
+    uint32_t ooff;
+    uint32_t w_ahead;        // the I_p word is read one row ahead (rows past the band are never used)
+    int row;
+    auto begin_rows = [&](const NibItem &it, int b) {
+        int tx = threadIdx.x & (TX - 1);
+        if (tx >= it.ntiles * cpt) tx = it.ntiles * cpt - 1;
+        const int tl = tx / cpt, cq = tx - tl * cpt;
+        Tq = (const unsigned char *)(LRBI_TB(b) + tl * tile_pieces + cq);
+        ipr = LRBI_IPB(b) + tl * p.ip_pitch + ty * g.ipw;
+        obase = (unsigned char *)(mask + ((int64_t)it.ti * g.r + it.row_lo) * p.pitch16 + (int64_t)it.tj_first * cpt);
+        ooff = (uint32_t)(((int64_t)ty * p.pitch16 + tl * cpt + cq) * 16);
+        row = ty;
+        w_ahead = ((GT == 1 || GT == 2 || GT == 4 || GT == 8) && ty < it.nrows) ? ipr[0] : 0u;
+    };
+    auto one_row = [&](const NibItem &it) {
+        uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+        if (GT == 1 || GT == 2 || GT == 4 || GT == 8) {
+            // one I_p word holds all nibbles; GT independent table reads (extract the nibble, scale, add),
+            // OR tree of 3-input ORs
+            const uint32_t w = w_ahead;
+            w_ahead = (row + TY < it.nrows) ? ipr[ip_step] : 0u;
+            constexpr int H = (GT > 4) ? 4 : (GT ? GT : 1); // reads in flight together (registers: 4 per read)
 #pragma unroll
-                for (int gg = 0; gg < GT; ++gg) {
-                    // A zero nibble selects an all-zero entry.  Most nibbles are zero, so those lanes
-                    // all read ONE shared zero piece (a broadcast, no bank pressure) instead of their
-                    // own tile's zero entry; LDS time then goes with the lanes that carry set bits.
-                    const uint32_t nib = (w >> (4 * gg)) & 15u;
-                    const uint4 *src = nib ? (Tq + gg * gstride + nib * nstride) : zero_piece;
-                    e[gg] = *src;
+            for (int h0 = 0; h0 < (GT ? GT : 1); h0 += H) {
+                uint4 e[H];
+#pragma unroll
+                for (int q = 0; q < H; ++q) {
+                    const uint32_t nib = (w >> (4 * (h0 + q))) & 15u;
+                    e[q] = *reinterpret_cast<const uint4 *>(Tq + (h0 + q) * gbytes + nib * nbytes);
                 }
-                if (GT == 1) acc = e[0];
-                if (GT == 2) acc = or4(e[0], e[1]);
-                if (GT == 4) acc = or4(or3x4(e[0], e[1], e[2]), e[3]);
-                if (GT == 8) acc = or3x4(or3x4(e[0], e[1], e[2]), or3x4(e[3], e[4], e[5]), or4(e[6], e[7]));
-            } else {
-                for (int gg = 0; gg < G; ++gg) {
-                    const uint32_t w = ipr[gg >> 3];
-                    acc = or4(acc, Tq[gg * gstride + ((w >> (4 * (gg & 7))) & 15u) * nstride]);
-                }
+                if (H == 1) acc = or4(acc, e[0]);
+                if (H == 2) acc = or3x4(acc, e[0], e[1]);
+                if (H == 4) acc = or3x4(or3x4(acc, e[0], e[1]), e[2], e[3]);
+#if defined(__HIP_DEVICE_COMPILE__)
+                if (GT > 4) __builtin_amdgcn_sched_barrier(0); // the second half's reads start after the first half's ORs
+#endif
             }
-            *out = acc;
+        } else {
+            for (int gg = 0; gg < G; ++gg) {
+                const uint32_t w = ipr[gg >> 3];
+                const uint32_t nib = (w >> (4 * (gg & 7))) & 15u;
+                acc = or4(acc, *reinterpret_cast<const uint4 *>(Tq + gg * gbytes + nib * nbytes));
+            }
         }
+        *reinterpret_cast<uint4 *>(obase + ooff) = acc;
+        row += TY;
+        ipr += ip_step;
+        ooff += ostep;
     };
 
     int64_t id = blockIdx.x;
     if (id >= p.items) return;
-    NibItem cur = make_nib_item(g, p, id);
-    load_item(cur);
-    stash_item(0);
+    NibCursor cu = nib_cursor_at(p, blockIdx.x);
+    NibItem cur = make_nib_item(g, p, cu);
+    load_item(cur, 0);
+    wait_loads<0>();
     __syncthreads();
     build_table(cur, 0);
     __syncthreads();
@@ -563,12 +616,27 @@ __global__ __launch_bounds__(kStreamThreads) LRBI_WAVES_PER_SIMD(GT == 8 ? 4 : 8
         const bool has_next = next_id < p.items;
         NibItem nxt = cur;
         if (has_next) {
-            nxt = make_nib_item(g, p, next_id);
-            load_item(nxt); // in flight while the current item is decoded
+            nib_cursor_step(p, cu);
+            nxt = make_nib_item(g, p, cu);
+            load_item(nxt, b ^ 1); // lands in Zs and buffer b^1 (last read before the previous barrier) during the row loop
         }
-        decode_rows(cur, b);
+        begin_rows(cur, b);
+        int issued = 0;
+        while (row < cur.nrows) {
+            one_row(cur);
+            ++issued;
+        }
         if (!has_next) break;
-        stash_item(b ^ 1);   // Zs and buffer b^1 were last read before the previous barrier
+        // Loads and stores share one in-order completion counter per wavefront.  Waiting until nothing is outstanding
+        // would wait for every store of the row loop and run the store pipeline dry once per item; waiting until no
+        // more accesses are outstanding than stores were issued after the loads waits for the loads alone.  Lane 0 of
+        // a wavefront has its lowest row, hence the most rows: its count is the wavefront's number of stores.
+        const int stores = __builtin_amdgcn_readfirstlane(issued);
+        if (stores >= 8) wait_loads<8>();
+        else if (stores >= 4) wait_loads<4>();
+        else if (stores >= 2) wait_loads<2>();
+        else if (stores >= 1) wait_loads<1>();
+        else wait_loads<0>();
         __syncthreads();
         build_table(nxt, b ^ 1);
         __syncthreads();
@@ -588,11 +656,12 @@ static bool plan_nibble(const Geom &g, NibblePlan &p, int64_t pitch_bytes, const
     if (p.cpt > 64) return false;
     p.G = (g.k + 3) / 4;
     const int per_tile_pieces = p.G * 16 * p.cpt;
-    // Up to four nibble groups the kernel fits in 64 registers per lane, so two 1024-lane
-    // workgroups can share a compute unit (and its LDS): while one waits at its item boundary
-    // (loads of the next item, table build, two barriers) the other keeps the store path busy.
-    p.wgs_per_cu = (p.G <= 4) ? 2 : 1;
-    p.span_tiles = (kNibTableBytes / p.wgs_per_cu / 16) / per_tile_pieces;
+    // Up to four nibble groups (and eight, with the tile width known at compile time) the kernel fits in
+    // 64 registers per lane, so two 1024-lane workgroups can share a compute unit (and its LDS): while one
+    // waits at its item boundary (loads of the next item, table build, two barriers) the other keeps the
+    // store path busy.
+    p.wgs_per_cu = (p.G <= 2 || (p.G == 4 && p.cpt == 2) || (p.G == 8 && p.cpt == 4)) ? 2 : 1; // the variants that fit 64 registers per lane
+    p.span_tiles = (kNibTableBytes / (p.G <= 4 ? 2 : 1) / 16) / per_tile_pieces; // the skew pieces come on top of the budget
     if (p.span_tiles > 64 / p.cpt) p.span_tiles = 64 / p.cpt;
     if (p.span_tiles > g.tile_cols) p.span_tiles = g.tile_cols;
     if (p.span_tiles < 1) return false;
@@ -602,16 +671,27 @@ static bool plan_nibble(const Geom &g, NibblePlan &p, int64_t pitch_bytes, const
     p.tx_log2 = 0;
     while ((1 << p.tx_log2) < p.span_tiles * p.cpt) ++p.tx_log2;
     p.rows_per_band = g.r;
-    const int cap_rows = kNibIpBytes / (4 * g.ipw * p.span_tiles) - 1;
+    const int cap_rows = kNibMaxIpPerLane * kStreamThreads / (g.ipw * p.span_tiles);
     if (p.rows_per_band > cap_rows) p.rows_per_band = cap_rows;
+    if (p.rows_per_band < 1) return false;
+    // a lane finds its I_p words by shifting a linear index: bands padded to a power of two must fit the lanes' slots
+    p.ip_sh = 0;
+    while ((1 << p.ip_sh) < p.rows_per_band * g.ipw) ++p.ip_sh;
+    while (((int64_t)p.span_tiles << p.ip_sh) > (int64_t)kNibMaxIpPerLane * kStreamThreads) {
+        --p.ip_sh;
+        p.rows_per_band = (1 << p.ip_sh) / g.ipw;
+    }
     if (p.rows_per_band < 16 && p.rows_per_band < g.r) return false;
     p.bands_per_tile_row = (g.r + p.rows_per_band - 1) / p.rows_per_band;
     p.items = (int64_t)p.spans * g.tile_rows * p.bands_per_tile_row;
     if (p.items < 4 * (int64_t)cus || p.items > 0x7FFFFFFF) return false;
     p.iz16 = (((uintptr_t)dIz & 15) == 0) ? 1 : 0;
     p.pitch16 = pitch_bytes / 16;
-    p.t_pieces = p.span_tiles * per_tile_pieces;
-    p.ip_words = (p.span_tiles * (p.rows_per_band + 1) * g.ipw + 3) / 4 * 4;
+    p.t_pieces = p.span_tiles * (per_tile_pieces + kNibTileSkew);
+    // one spare row per tile keeps the rows that the tiles of a span read together in different banks; runs shorter
+    // than a wavefront's 64 words are packed at their power-of-two pitch, so that the copy into LDS is linear
+    p.ip_pitch = (p.ip_sh >= 6) ? (p.rows_per_band + 1) * g.ipw : (1 << p.ip_sh);
+    p.ip_words = (p.span_tiles * p.ip_pitch + 3) / 4 * 4;
     p.zs_pieces = p.span_tiles * g.k * p.cpt;
     return true;
 }
@@ -639,18 +719,22 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
     {
         NibblePlan np;
         if (plan_nibble(g, np, pitch_bytes, dIz, cus)) {
-            const size_t lds = ((size_t)2 * (np.t_pieces + np.ip_words / 4) + np.zs_pieces) * 16;
-            auto kern = decode_nibble_kernel<0>;
-            switch (np.G) {
-            case 1: kern = decode_nibble_kernel<1>; break;
-            case 2: kern = decode_nibble_kernel<2>; break;
-            case 4: kern = decode_nibble_kernel<4>; break;
-            case 8: kern = decode_nibble_kernel<8>; break;
-            default: break;
-            }
+            const size_t lds = ((size_t)np.t_pieces + 2 * (np.ip_words / 4) + np.zs_pieces) * 16;
+            auto kern = decode_nibble_kernel<0, 0>;
+            if (np.G == 8 && np.cpt == 4) kern = decode_nibble_kernel<8, 4>;      // 512-column tiles, rank 32
+            else if (np.G == 4 && np.cpt == 2) kern = decode_nibble_kernel<4, 2>; // 256-column tiles, rank 16
+            else if (np.G == 2 && np.cpt == 1) kern = decode_nibble_kernel<2, 1>; // 128-column tiles, rank 8
+            else if (np.G == 8) kern = decode_nibble_kernel<8, 0>;
+            else if (np.G == 4) kern = decode_nibble_kernel<4, 0>;
+            else if (np.G == 2) kern = decode_nibble_kernel<2, 0>;
+            else if (np.G == 1) kern = decode_nibble_kernel<1, 0>;
             LRBI_SET_MAX_LDS(kern, lds);
             const int64_t want = (int64_t)np.wgs_per_cu * cus;
             const int64_t grid = (np.items < want) ? np.items : want;
+            np.step_span = (int)(grid % np.spans);
+            np.step_band = (int)((grid / np.spans) % np.bands_per_tile_row);
+            np.step_ti = (int)((grid / np.spans) / np.bands_per_tile_row);
+            np.rot_div = (grid / np.spans) > 0 ? (int)(grid / np.spans) : 1;
             LRBI_LAUNCH(kern, dim3((unsigned)grid), dim3(kStreamThreads), lds, stream, g, np, dIp, dIz,
                                (uint4 *)dMask);
             return LRBI_OK;

@@ -23,6 +23,7 @@
 //     reads in flight (68 against 160 bytes per clock and compute unit).
 //   * The output tile leaves through LDS as 16-byte pieces of whole rows.
 #include "lrbi_internal.hpp"
+#include "lrbi_lds_dma.hpp"
 #include "lrbi_mfma_common.hpp"
 
 namespace lrbi {
@@ -43,35 +44,6 @@ template <int NS> struct SmemDma {
     static constexpr size_t bytes = fip_off + PIPE_BM * PANEL_UNITS * 2 * 4;
 };
 
-// 16 bytes per lane from global memory (uniform base + per-lane byte offset) straight into LDS at
-// (uniform byte address lds_addr) + 16 * lane.  The compiler does not see the LDS write: the kernel waits for
-// it with wait_loads() before the barrier that hands the stage over.
-__device__ __forceinline__ void load_to_lds16(uint32_t lds_addr, const void *gbase, uint32_t voff)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(gbase)
-                 : "memory");
-#endif
-}
-// the same with 4 bytes per lane: lands at lds_addr + 4 * lane
-__device__ __forceinline__ void load_to_lds4(uint32_t lds_addr, const void *gbase, uint32_t voff)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(gbase)
-                 : "memory");
-#endif
-}
-template <int N> __device__ __forceinline__ void wait_loads()
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-#endif
-}
 
 template <typename Tag, int NS, bool SPREAD, bool SPLIT>
 __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(

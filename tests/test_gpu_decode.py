@@ -114,6 +114,51 @@ def test_scaled_grid_sampled_tiles():
     assert abs(total / (cfg.m * cfg.n) - (1 - (1 - cfg.p ** 2) ** cfg.k)) < 0.002
 
 
+# Shapes with enough work items for the table-lookup kernel (tile width a multiple of 128 columns, at least four
+# items per compute unit), one per compiled variant and per ragged case of its item grid.
+TABLE_SHAPES = [
+    # m, n, r, c, k, p, what
+    (2048, 65536, 32, 128, 8, 0.2, "two nibble groups, one piece per tile row"),
+    (1280, 65536, 40, 256, 16, 0.08, "four groups, two pieces"),
+    (2048, 131584, 128, 512, 32, 0.06, "eight groups, four pieces, short last span"),
+    (2400, 131840, 300, 256, 32, 0.06, "eight groups, two bands per tile row (256 + 44 rows), short last span"),
+    (1600, 49792, 100, 128, 40, 0.05, "ten groups over two I_p words, short last band and span"),
+    (2048, 131072, 32, 128, 4, 0.3, "one group, 64 tiles per span"),
+    (4096, 66048, 64, 128, 12, 0.15, "three groups (run-time count), short last span"),
+]
+
+
+@pytest.mark.parametrize("m,n,r,c,k,p,what", TABLE_SHAPES)
+def test_table_lookup_kernel_variants(m, n, r, c, k, p, what):
+    rng = np.random.default_rng(m + n + k)
+    T = (m // r) * (n // c)
+    Ip = (rng.random((T, r, k)) < p).astype(np.uint8)
+    Iz = (rng.random((T, k, c)) < p).astype(np.uint8)
+    print("decode table shape", (m, n, r, c, k), what, flush=True)
+    _check(m, n, r, c, k, Ip, Iz)
+
+
+def test_table_lookup_kernel_with_factors_at_odd_addresses():
+    """I_z needs 8-byte alignment only: the 16-byte loads of the table kernel must not be taken then."""
+    m, n, r, c, k = 1280, 65536, 40, 256, 16
+    rng = np.random.default_rng(5)
+    T = (m // r) * (n // c)
+    Ip = (rng.random((T, r, k)) < 0.08).astype(np.uint8)
+    Iz = (rng.random((T, k, c)) < 0.08).astype(np.uint8)
+    d = lrbi.Desc(m, n, r, c, k, 0)
+    dIp, dIz = device_factors(d, Ip, Iz)
+    shifted_z = torch.empty(dIz.numel() + 1, dtype=dIz.dtype, device=dIz.device)
+    shifted_z[1:] = dIz.reshape(-1)
+    shifted_p = torch.empty(dIp.numel() + 1, dtype=dIp.dtype, device=dIp.device)
+    shifted_p[1:] = dIp.reshape(-1)
+    assert shifted_z[1:].data_ptr() % 16 == 8 and shifted_p[1:].data_ptr() % 16 == 4
+    print("decode table shape", (m, n, r, c, k), "factors 8 and 4 bytes past a 16-byte boundary", flush=True)
+    out = lrbi.decode_mask(d, shifted_p[1:], shifted_z[1:])
+    torch.cuda.synchronize()
+    ref = orc.decode_mask(Ip, Iz, m, n, r, c, k)
+    assert np.array_equal(unpack_device_mask(out, n)[:, :n], ref)
+
+
 def test_runs_on_a_side_stream():
     cfg = workloads.CONFIGS["C5"]
     d = workloads.make(cfg, want_w=False, want_x=False)
