@@ -15,6 +15,7 @@ _lib = None
 F32, F16, BF16 = 0, 1, 2
 FLAG_PATH_VALU = 0x1
 FLAG_PATH_MFMA = 0x2
+FLAG_PATH_STREAM = 0x3
 FLAG_DECODE_GENERIC = 0x00100000
 
 

@@ -1,0 +1,408 @@
+// Fused masked product for narrow batches (N <= 32 columns of X, f16 / bf16): Y = (W o I_a) X with W streamed from
+// HBM exactly once at the rate the memory delivers it.  Any tile shape: the mask words come from the general
+// decode (Eq. 3), so tiles need not line up with anything.
+//
+// A workgroup of eight wavefronts owns BM (16 or 8) rows of one tile row of W and walks all n columns in slabs of
+// KS (256 or 512) columns; BM * KS * 2 bytes = 8 KB of W per slab either way.
+//   * First the mask of the workgroup's rows, all n columns of it, is rebuilt: the tile row's packed I_z and the
+//     rows' I_p words are copied into LDS, then every lane decodes 32-bit mask words from there (Eq. 3; no dependent
+//     global load per word) into an LDS array.  The first slabs of W are already on their way meanwhile.
+//   * Slab loop: every wavefront copies its share of the slab NS - 1 slabs ahead -- one 1 KB piece of W (a row, or two
+//     half rows) and up to two 1 KB pieces of the slab's 256 x N or 512 x N part of X -- from global memory straight
+//     into an LDS ring of NS stages (load-to-LDS, 16 bytes per lane, no registers).  Many wavefronts with few
+//     loads each is what the memory pipeline wants: measured on the box, a wavefront gets no more than about four
+//     such loads to overlap, however many it has issued.  Every wavefront issues the same number of copy
+//     instructions for every slab (addresses past the matrix are clamped, never skipped), so "my share of slab s has
+//     landed" is a fixed bound on its count of outstanding loads, and one barrier per slab makes that true of the
+//     whole slab and hands the oldest stage back.
+//   * Arithmetic: 16x16x32 MFMAs, A = 16 rows x 32 columns of W read from LDS with the pruned weights zeroed by
+//     select on the bit pattern, B = the matching 32 x 16 piece of X.  Wavefront w takes the slab's 32-column steps
+//     w (and w + 8); the eight partial accumulators are added through LDS at the end, in wavefront order.
+// X stays in its [k][N] order in LDS: for N = 1 an operand is 16 consecutive bytes of it, otherwise the transposing
+// LDS read delivers 8 consecutive k of one column per lane (needs N % 4 == 0 for its 8-byte alignment).
+#include "lrbi_internal.hpp"
+#include "lrbi_lds_dma.hpp"
+#include "lrbi_mfma_common.hpp"
+
+namespace lrbi {
+
+static constexpr int ST_WAVES = 8;
+static constexpr int ST_THREADS = ST_WAVES * 64;
+static constexpr int ST_W_INSTR = 8;              // 1 KB copy instructions per W slab: one per wavefront
+static constexpr int ST_WPIECE = 1024 + 16;       // LDS bytes per such piece (16 bytes of skew against bank conflicts)
+static constexpr int ST_WSTAGE = ST_W_INSTR * ST_WPIECE;
+static constexpr int ST_FP_ROWS = 16;             // I_p rows per tile held in LDS
+static constexpr int ST_FZ_MAX_BYTES = 40 * 1024; // packed I_z of one tile row that the kernel is willing to hold in LDS
+static constexpr int ST_X_PAD = 64;               // the transposing read of the last k rows may run this far past the slab
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+__device__ __forceinline__ f32x4 mfma_16x16x32(F16Tag, u32x4 a, u32x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
+                                                  0);
+}
+__device__ __forceinline__ f32x4 mfma_16x16x32(BF16Tag, u32x4 a, u32x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+}
+
+// wait until at most n of this wavefront's loads are outstanding (n known only at run time; waiting for a few
+// loads more than asked is harmless, so above 15 the count is rounded down to a multiple of four)
+__device__ __forceinline__ void wait_loads_at_most(int n)
+{
+    switch (n < 16 ? n : 12 + (n >> 2)) {
+    case 0: wait_loads<0>(); break;
+    case 1: wait_loads<1>(); break;
+    case 2: wait_loads<2>(); break;
+    case 3: wait_loads<3>(); break;
+    case 4: wait_loads<4>(); break;
+    case 5: wait_loads<5>(); break;
+    case 6: wait_loads<6>(); break;
+    case 7: wait_loads<7>(); break;
+    case 8: wait_loads<8>(); break;
+    case 9: wait_loads<9>(); break;
+    case 10: wait_loads<10>(); break;
+    case 11: wait_loads<11>(); break;
+    case 12: wait_loads<12>(); break;
+    case 13: wait_loads<13>(); break;
+    case 14: wait_loads<14>(); break;
+    case 15: wait_loads<15>(); break;
+    case 16: wait_loads<16>(); break; // 16 .. 19
+    case 17: wait_loads<20>(); break;
+    case 18: wait_loads<24>(); break;
+    case 19: wait_loads<28>(); break;
+    case 20: wait_loads<32>(); break;
+    case 21: wait_loads<36>(); break;
+    case 22: wait_loads<40>(); break;
+    case 23: wait_loads<44>(); break;
+    case 24: wait_loads<48>(); break;
+    case 25: wait_loads<52>(); break;
+    case 26: wait_loads<56>(); break;
+    case 27: wait_loads<60>(); break;
+    default: wait_loads<0>(); break;
+    }
+}
+
+struct StreamArgs {
+    const uint16_t *W;
+    int64_t ldw;
+    const uint32_t *Ip, *Iz;
+    const uint16_t *X;
+    int N;
+    uint16_t *Y;   // storage-dtype output [m][ldy], or null
+    int64_t ldy;
+    float *P;      // fp32 output [m][ldp] (the pre-activations of a fused consumer), or null
+    int64_t ldp;
+    int x_instr;   // copy instructions per X slab
+    int x_stage;   // LDS bytes per X stage
+    uint32_t x_pieces; // 16-byte pieces of X in all
+    int blocks_per_tile_row; // workgroups per tile row (BM rows each, the last one may be short)
+    int fz_words;  // packed I_z words of one tile row
+    int fz_pad;    // the same rounded up to whole copy instructions (64 words)
+    int fp_pitch;  // LDS words per tile for the I_p words of 16 rows: 16 * ipw rounded up to whole copy instructions
+    int ms_pitch;  // mask words per row in LDS (odd, at least 8 per slab)
+};
+
+// One 32-bit word of the decoded mask row, like decode_word(), from factors held in LDS:
+// Fz [tile_cols][k][izw] (the tile row's packed I_z as it lies in memory), Fp [tile_cols][fp_pitch] holding [16][ipw].
+__device__ __forceinline__ uint32_t decode_word_lds(const Geom &g, const uint32_t *Fp, int fp_pitch, const uint32_t *Fz, int rl,
+                                                    int w)
+{
+    const int n = (int)g.n; // below 2^30 here: 32-bit arithmetic throughout
+    const int j0 = w * 32;
+    if (j0 >= n) return 0u;
+    const int j1 = (j0 + 32 < n) ? j0 + 32 : n;
+    int tj = (int)((uint32_t)j0 / (uint32_t)g.c);
+    uint32_t acc = 0u;
+    for (int tbeg = tj * g.c; tbeg < j1; tbeg += g.c, ++tj) {
+        const uint32_t *ip = Fp + tj * fp_pitch + rl * g.ipw;
+        const uint32_t *izt = Fz + tj * g.k * g.izw;
+        const int off = j0 - tbeg; // -32 < off < c
+        const uint32_t valid = bit_range(off < 0 ? -off : 0, (g.c - off < 32) ? g.c - off : 32);
+        uint32_t v = 0u;
+        for (int iw = 0; iw < g.ipw; ++iw) {
+            uint32_t sel = ip[iw];
+            while (sel) {
+                const int l = __builtin_ctz(sel) + 32 * iw;
+                sel &= sel - 1u;
+                v |= iz_window(izt + l * g.izw, g.izw, off);
+            }
+        }
+        acc |= v & valid;
+    }
+    if (j1 - j0 < 32) acc &= bit_range(0, j1 - j0); // a tile cut off at the right edge
+    return acc;
+}
+
+template <typename Tag, int NS, int BM, int KS>
+__global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamArgs a)
+{
+    static_assert(BM * KS * 2 == ST_W_INSTR * 1024, "a W slab is eight 1 KB pieces");
+    constexpr int ROWS_PER_PIECE = 1024 / (KS * 2); // 2 half rows (KS = 256) or 1 row (KS = 512)
+    constexpr int STEPS = KS / 32;                  // MFMA steps per slab: 8 or 16
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    unsigned char *smem = (unsigned char *)lrbi_dyn_smem;
+    unsigned char *Wst = smem;                                  // [NS][ST_WSTAGE]
+    unsigned char *Xst = smem + NS * ST_WSTAGE;                  // [NS][x_stage]
+    uint32_t *Ms = (uint32_t *)(Xst + (size_t)NS * a.x_stage);   // [BM][ms_pitch]: the rows' whole mask
+    uint32_t *Fz = Ms + BM * a.ms_pitch;                         // [tile_cols][k][izw]
+    uint32_t *Fp = Fz + a.fz_pad;                                // [tile_cols][fp_pitch]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ti = blockIdx.x / a.blocks_per_tile_row;           // tile row
+    const int il0 = (blockIdx.x - ti * a.blocks_per_tile_row) * BM; // first row within the tile
+    const int64_t m0 = (int64_t)ti * g.r + il0;
+    // rows of this workgroup: at most BM, cut at the end of the tile and of the matrix
+    int rows_here = BM;
+    if (g.r - il0 < rows_here) rows_here = g.r - il0;
+    if (g.m - m0 < rows_here) rows_here = (int)(g.m - m0);
+    if (rows_here <= 0) return; // a tile row cut off by the end of the matrix: the whole workgroup leaves
+    const int n = (int)g.n;
+    const int N = a.N;
+    const int nslabs = (n + KS - 1) / KS;
+
+    // ---- this wavefront's share of a slab's copies ----
+    const uint16_t *wbase = a.W + m0 * a.ldw; // uniform; lanes add 32-bit byte offsets
+    // piece `wave` of the W slab: KS = 512: row `wave`; KS = 256: rows 2 wave (lanes 0-31) and 2 wave + 1 (lanes 32-63).
+    // Past the last row or column the address is clamped, never skipped: such values meet a zero mask bit or land
+    // in rows that are never stored.
+    int my_row = wave * ROWS_PER_PIECE + (ROWS_PER_PIECE == 2 ? (lane >> 5) : 0);
+    if (my_row >= rows_here) my_row = rows_here - 1;
+    const int my_col = 8 * (ROWS_PER_PIECE == 2 ? (lane & 31) : lane);
+    const int my_x_instr = (a.x_instr > wave ? 1 : 0) + (a.x_instr > wave + ST_WAVES ? 1 : 0);
+    const int my_per_slab = 1 + my_x_instr; // copy instructions of this wavefront per slab
+    auto copy_slab = [&](int slab) {
+        const int stage = slab % NS;
+        const int k0 = slab * KS;
+        int col = k0 + my_col;
+        if (col > n - 8) col = n - 8;
+        load_to_lds16(lds_address(Wst + stage * ST_WSTAGE + wave * ST_WPIECE), wbase,
+                      (uint32_t)(((int64_t)my_row * a.ldw + col) * 2));
+        const uint32_t x_lds = lds_address(Xst + (size_t)stage * a.x_stage);
+        const uint32_t first = (uint32_t)(((int64_t)k0 * N * 2) >> 4); // 16-byte piece of X the slab starts at
+        for (int i = wave; i < a.x_instr; i += ST_WAVES) {
+            uint32_t piece = first + 64u * i + lane;
+            if (piece >= a.x_pieces) piece = a.x_pieces - 1u; // stays inside X; meets zeroed weights only
+            load_to_lds16(x_lds + 1024u * i, a.X, piece * 16u);
+        }
+    };
+
+    // ---- the mask of the workgroup's rows ----
+    auto stage_factors = [&]() { // linear copies, 4 bytes per lane
+        const uint32_t *zsrc = a.Iz + (int64_t)ti * g.tile_cols * g.k * (int64_t)g.izw;
+        for (int w0 = wave * 64; w0 < a.fz_words; w0 += ST_THREADS) {
+            int w = w0 + lane;
+            if (w >= a.fz_words) w = a.fz_words - 1; // the copy instruction's slots past the end are part of the pad
+            load_to_lds4(lds_address(Fz + w0), zsrc, 4u * (uint32_t)w);
+        }
+        // per tile, the I_p rows il0 .. il0 + rows_here - 1 (slots past them are filled with the last row, never used)
+        const int live = rows_here * g.ipw;
+        for (int tj = 0; tj < g.tile_cols; ++tj) {
+            const uint32_t *psrc = a.Ip + (((int64_t)ti * g.tile_cols + tj) * g.r + il0) * g.ipw;
+            for (int e0 = wave * 64; e0 < a.fp_pitch; e0 += ST_THREADS) {
+                int e = e0 + lane;
+                if (e >= live) e = live - 1;
+                load_to_lds4(lds_address(Fp + tj * a.fp_pitch + e0), psrc, 4u * (uint32_t)e);
+            }
+        }
+    };
+    const int nwords = nslabs * STEPS; // words past column n decode to zero
+    auto decode_rows = [&]() { // all mask words of the workgroup's rows, one per lane and turn
+        for (int idx = tid; idx < BM * nwords; idx += ST_THREADS) {
+            const int rl = (int)((uint32_t)idx / (uint32_t)nwords), w = idx - rl * nwords;
+            Ms[rl * a.ms_pitch + w] = (rl < rows_here) ? decode_word_lds(g, Fp, a.fp_pitch, Fz, rl, w) : 0u;
+        }
+    };
+
+    // ---- arithmetic ----
+    const int row16 = lane & 15, kg = lane >> 4; // operand row / column, and which 8 of a step's 32 reduction indices
+    const int arow = row16 & (BM - 1);           // BM = 8: rows 8-15 of the operand repeat rows 0-7 and are dropped
+    f32x4 acc[2];
+    acc[0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int nblocks = (N > 16) ? 2 : 1; // 16-column blocks of Y
+
+    auto multiply_slab = [&](int slab) {
+        const int stage = slab % NS;
+        const unsigned char *ws = Wst + stage * ST_WSTAGE + (arow / ROWS_PER_PIECE) * ST_WPIECE +
+                                  (arow % ROWS_PER_PIECE) * (KS * 2);
+        const unsigned char *xs = Xst + (size_t)stage * a.x_stage;
+        const unsigned char *mb = (const unsigned char *)(Ms + arow * a.ms_pitch + slab * STEPS);
+#pragma unroll
+        for (int h = 0; h < STEPS / ST_WAVES; ++h) {
+            const int step = wave + ST_WAVES * h;    // 32 columns of the slab
+            const int kk = step * 32 + 8 * kg;       // this lane's 8 reduction indices
+            const u32x4 wf = *reinterpret_cast<const u32x4 *>(ws + kk * 2);
+            const u32x4 am = apply_mask8(wf, mb[step * 4 + kg]);
+            if (N == 1) {
+                const u32x4 xf = *reinterpret_cast<const u32x4 *>(xs + kk * 2); // every column of the block sees x
+                acc[0] = mfma_16x16x32(Tag{}, am, xf, acc[0]);
+            } else {
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) { // static indices: the accumulators must stay in registers
+                    if (cb >= nblocks) break;
+                    // lane s of a 16-lane group addresses row s / 4 (then + 4), columns 4 (s % 4) .. + 3 of the block
+                    const unsigned char *p = xs + ((size_t)(kk + (row16 >> 2)) * N + cb * 16 + 4 * (row16 & 3)) * 2;
+                    const u32x2 lo = lds_read_tr16_v((const uint16_t *)p);
+                    const u32x2 hi = lds_read_tr16_v((const uint16_t *)(p + (size_t)4 * N * 2));
+                    const u32x4 xf = {lo.x, lo.y, hi.x, hi.y};
+                    acc[cb] = mfma_16x16x32(Tag{}, am, xf, acc[cb]);
+                }
+            }
+        }
+    };
+
+#define LRBI_BARRIER()                                      \
+    do {                                                    \
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  \
+        __builtin_amdgcn_s_barrier();                       \
+        asm volatile("" ::: "memory");                      \
+    } while (0)
+
+    // The factor copies go first and are waited for by count: the slab copies issued after them stay in flight.
+    stage_factors();
+    for (int s = 0; s < NS - 1; ++s) copy_slab(s); // slabs past the end copy clamped addresses: same count
+    wait_loads_at_most((NS - 1) * my_per_slab);
+    LRBI_BARRIER();
+    decode_rows();
+    for (int s = 0; s < nslabs; ++s) {
+        wait_loads_at_most((NS - 2) * my_per_slab); // my share of slab s is in; slabs s + 1 .. s + NS - 2 may be on their way
+        LRBI_BARRIER(); // the first one also publishes the mask words
+        copy_slab(s + NS - 1); // into the stage of slab s - 1, which every wavefront has left
+        multiply_slab(s);
+    }
+    wait_loads<0>(); // nothing may still be landing when the stages are reused below
+    LRBI_BARRIER();
+
+    // wavefronts' partial accumulators -> LDS; lane holds rows 4 kg + v, column row16 of each 16 x 16 block
+    float *red = (float *)smem; // [8][2][16][16]
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[((wave * 2 + cb) * 16 + 4 * kg + v) * 16 + row16] = acc[cb][v];
+    LRBI_BARRIER();
+#undef LRBI_BARRIER
+    for (int e = tid; e < 16 * 16 * nblocks; e += ST_THREADS) {
+        const int cb = e >> 8, rr = (e >> 4) & 15, cc = e & 15;
+        const int col = cb * 16 + cc;
+        const int64_t row = m0 + rr;
+        if (col >= N || rr >= rows_here) continue;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < ST_WAVES; ++w) v += red[((w * 2 + cb) * 16 + rr) * 16 + cc];
+        if (a.P) a.P[row * a.ldp + col] = v;
+        if (a.Y) a.Y[row * a.ldy + col] = cvt_store(Tag{}, v);
+    }
+}
+
+// The kernel serves: f16 / bf16, N = 1 or a multiple of 4 up to 32, X contiguous ([n][N] with ldx = N) and 16-byte
+// aligned, W rows 16-byte aligned, n a multiple of 8, a tile row's packed I_z small enough for LDS, and enough rows to
+// give every compute unit a workgroup or so.
+struct StreamPlan {
+    int ns;       // ring stages
+    int bm, ks;   // rows per workgroup and columns per slab: (16, 256), or (8, 512) for a single column
+    size_t lds;
+    unsigned grid;
+    StreamArgs a; // the geometry-derived fields only
+};
+
+static bool plan_stream(const Geom &g, int64_t N, int cus, StreamPlan &p)
+{
+    StreamArgs &a = p.a;
+    // one column: eight rows per workgroup, so that twice as many workgroups (and copying wavefronts) share the
+    // chip, and 512-column slabs: a wavefront's piece is 1 KB of one row
+    p.bm = (N == 1) ? 8 : 16;
+    p.ks = (N == 1) ? 512 : 256;
+    const int slab_bytes = p.ks * (int)N * 2;
+    a.x_instr = (slab_bytes + 1023) / 1024;
+    a.x_stage = a.x_instr * 1024 + ST_X_PAD;
+    a.x_pieces = (uint32_t)(((uint64_t)g.n * (uint64_t)N * 2u) >> 4);
+    a.blocks_per_tile_row = (g.r + p.bm - 1) / p.bm;
+    const int64_t fz_words = (int64_t)g.tile_cols * g.k * g.izw;
+    if (fz_words * 4 > ST_FZ_MAX_BYTES) return false;
+    a.fz_words = (int)fz_words;
+    a.fz_pad = (a.fz_words + 63) / 64 * 64;
+    a.fp_pitch = (ST_FP_ROWS * g.ipw + 63) / 64 * 64;
+    const int nslabs = (int)((g.n + p.ks - 1) / p.ks);
+    a.ms_pitch = nslabs * (p.ks / 32) + 1;
+    const int64_t grid = (int64_t)g.tile_rows * a.blocks_per_tile_row;
+    if (grid > 0x7FFFFFFF || grid < cus / 2) return false;
+    p.grid = (unsigned)grid;
+    const size_t fixed = ((size_t)p.bm * a.ms_pitch + a.fz_pad + (size_t)g.tile_cols * a.fp_pitch) * 4;
+    // two workgroups per compute unit when there are more workgroups than compute units, else the deepest ring;
+    // a wavefront issues at most three copies per slab, so its 6-bit load counter never limits the depth
+    const size_t budget = (grid > cus) ? 80 * 1024 : 160 * 1024;
+    for (int ns : {6, 4, 3}) {
+        const size_t lds = (size_t)ns * (ST_WSTAGE + a.x_stage) + fixed;
+        if (lds <= budget) {
+            p.ns = ns;
+            p.lds = lds;
+            return true;
+        }
+    }
+    return false;
+}
+
+bool stream_ok(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const void *dX, int64_t ldx, int64_t N, int cus)
+{
+    if (dt != LRBI_F16 && dt != LRBI_BF16) return false;
+    if (!(N == 1 || (N % 4 == 0 && N <= 32))) return false;
+    if (ldx != N || ((uintptr_t)dX & 15) != 0) return false;
+    if (((uintptr_t)dW & 15) != 0 || ldw % 8 != 0 || g.n % 8 != 0 || g.n < 8) return false;
+    if (ldw >= ((int64_t)1 << 26) || g.n >= ((int64_t)1 << 30)) return false;       // 32-bit byte offsets within 16 rows
+    if ((uint64_t)g.n * (uint64_t)N * 2u >= ((uint64_t)1 << 32)) return false;       // and within X
+    StreamPlan p;
+    return plan_stream(g, N, cus, p);
+}
+
+template <typename Tag, int NS, int BM, int KS>
+static int launch_stream_t(const Geom &g, const StreamPlan &p, hipStream_t stream)
+{
+    auto kern = stream_gemm_kernel<Tag, NS, BM, KS>;
+    LRBI_SET_MAX_LDS(kern, p.lds);
+    LRBI_LAUNCH(kern, dim3(p.grid), dim3(ST_THREADS), p.lds, stream, g, p.a);
+    return LRBI_OK;
+}
+
+template <typename Tag, int BM, int KS> static int launch_stream_ns(const Geom &g, const StreamPlan &p, hipStream_t stream)
+{
+    switch (p.ns) {
+    case 6: return launch_stream_t<Tag, 6, BM, KS>(g, p, stream);
+    case 4: return launch_stream_t<Tag, 4, BM, KS>(g, p, stream);
+    default: return launch_stream_t<Tag, 3, BM, KS>(g, p, stream);
+    }
+}
+
+template <typename Tag> static int launch_stream_shape(const Geom &g, const StreamPlan &p, hipStream_t stream)
+{
+    return (p.bm == 8) ? launch_stream_ns<Tag, 8, 512>(g, p, stream) : launch_stream_ns<Tag, 16, 256>(g, p, stream);
+}
+
+// dY (storage dtype) and / or dP (fp32) receive the product; the caller has checked stream_ok() with the same cus
+int launch_stream_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
+                       const uint32_t *dIz, const void *dX, int64_t N, void *dY, int64_t ldy, float *dP, int64_t ldp,
+                       int cus, hipStream_t stream)
+{
+    StreamPlan p;
+    if (!plan_stream(g, N, cus, p)) return LRBI_ERR_SHAPE;
+    StreamArgs &a = p.a;
+    a.W = (const uint16_t *)dW;
+    a.ldw = ldw;
+    a.Ip = dIp;
+    a.Iz = dIz;
+    a.X = (const uint16_t *)dX;
+    a.N = (int)N;
+    a.Y = (uint16_t *)dY;
+    a.ldy = ldy;
+    a.P = dP;
+    a.ldp = ldp;
+    if (dt == LRBI_F16) return launch_stream_shape<F16Tag>(g, p, stream);
+    if (dt == LRBI_BF16) return launch_stream_shape<BF16Tag>(g, p, stream);
+    return LRBI_ERR_DTYPE;
+}
+
+} // namespace lrbi

@@ -17,7 +17,7 @@ int validate_desc(const lrbi_desc *d)
                            LRBI_FLAG_DECODE_GENERIC;
     if (d->flags & ~known) return LRBI_ERR_FLAGS;
     const uint32_t path = d->flags & LRBI_FLAG_PATH_MASK;
-    if (path > LRBI_FLAG_PATH_MFMA) return LRBI_ERR_FLAGS;
+    if (path > LRBI_FLAG_PATH_STREAM) return LRBI_ERR_FLAGS;
     return LRBI_OK;
 }
 
@@ -242,6 +242,17 @@ extern "C" int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const v
     if ((desc->flags & LRBI_FLAG_PATH_MASK) == LRBI_FLAG_PATH_MFMA && dtype == LRBI_F32) return LRBI_ERR_DTYPE;
     const Geom g = make_geom(desc);
     hipStream_t s = (hipStream_t)stream;
+    {
+        // narrow batches of the 16-bit types: W streamed once, whatever the tile shape
+        const uint32_t path = desc->flags & LRBI_FLAG_PATH_MASK;
+        if (path == LRBI_FLAG_PATH_AUTO || path == LRBI_FLAG_PATH_STREAM) {
+            const int cus = (path == LRBI_FLAG_PATH_STREAM) ? 0 : compute_units_of(s); // forced: any number of rows
+            if (stream_ok(g, dtype, dW, ldw, dX, ldx, N, cus))
+                return launch_stream_gemm(g, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
+                                          dX, N, dY, ldy, nullptr, 0, cus, s);
+            if (path == LRBI_FLAG_PATH_STREAM) return (dtype == LRBI_F32) ? LRBI_ERR_DTYPE : LRBI_ERR_ALIGN;
+        }
+    }
     bool mfma = use_mfma(desc, dtype, N);
     if (mfma) {
         // the matrix-core kernel loads W in 16-byte pieces; anything else goes to the vector-ALU kernel

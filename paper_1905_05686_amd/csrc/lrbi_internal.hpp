@@ -95,6 +95,12 @@ int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const v
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N,
                      void *dY, int64_t ldy, void *dWorkspace, hipStream_t stream);
 
+// row-streaming kernel for narrow batches (lrbi_gemm_stream.hip)
+bool stream_ok(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const void *dX, int64_t ldx, int64_t N, int cus);
+int launch_stream_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
+                       const uint32_t *dIz, const void *dX, int64_t N, void *dY, int64_t ldy, float *dP, int64_t ldp,
+                       int cus, hipStream_t stream);
+
 // software-pipelined tile kernel (lrbi_gemm_pipe.hip)
 bool pipe_ok(const Geom &g, const void *dIz, const void *dX, int64_t ldw, int64_t ldx, int64_t N);
 int launch_pipe_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, int pf, const void *dW, int64_t ldw,

@@ -51,7 +51,7 @@ def test_desc_validation():
     bad = [
         (lrbi.Desc(0, 8, 1, 1, 1), -2), (lrbi.Desc(8, 8, 0, 4, 1), -2), (lrbi.Desc(8, 8, 4, -3, 1), -2),
         (lrbi.Desc(8, 8, 4, 4, 0), -3), (lrbi.Desc(8, 8, 4, 4, 257), -3), (lrbi.Desc(8, 8, 4, 4, 1, 1 << 30), -9),
-        (lrbi.Desc(8, 8, 4, 4, 1, 3), -9),
+        (lrbi.Desc(8, 8, 4, 4, 1, 4), -9),  # path values beyond the three kernels
     ]
     for d, code in bad:
         with pytest.raises(lrbi.LrbiError) as e:

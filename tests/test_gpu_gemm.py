@@ -96,6 +96,60 @@ def test_edge_shapes(idx):
     _assert_close(_run(cfg, data, flags=flags), ref, cfg.dtype, "edge%d" % idx)
 
 
+# The row-streaming kernel (narrow batches), forced so that small matrices take it too; the configurations C3a and
+# C4 above reach it on their own.
+STREAM = [
+    _small(100, 200, 50, 100, 4, 0.2, 1, "bf16"),        # last workgroup has 4 of its 16 rows, one short slab
+    _small(130, 4104, 65, 1368, 9, 0.1, 4, "f16"),       # 16 slabs and 8 columns; tiles cut through slabs and words
+    _small(300, 2400, 300, 300, 8, 0.12, 20, "f16"),     # C4's tiles and batch
+    _small(256, 512, 128, 128, 8, 0.2, 32, "bf16"),      # both 16-column blocks full
+    _small(48, 264, 24, 33, 5, 0.3, 8, "f16"),           # tiles narrower than two mask words
+    _small(1152, 1024, 576, 512, 145, 0.02, 16, "f16"),  # rank 145: five I_p words per row
+    _small(64, 520, 32, 130, 6, 0.25, 12, "bf16"),
+    _small(64, 520, 32, 130, 6, 0.25, 28, "f16"),
+    _small(2048, 8, 512, 8, 2, 0.5, 1, "f16"),           # a single 16-byte piece per row
+]
+
+
+@pytest.mark.parametrize("idx", range(len(STREAM)))
+def test_row_streaming_kernel(idx):
+    cfg = STREAM[idx]
+    print("gemm stream", idx, cfg, flush=True)
+    data = workloads.make(cfg)
+    ref, M = _oracle(cfg, data)
+    Y = _run(cfg, data, flags=lrbi.FLAG_PATH_STREAM)
+    _assert_close(Y, ref, cfg.dtype, "stream%d" % idx)
+    # nothing stored under a pruned bit reaches Y, also not through the clamped loads past the last row and column
+    W = workloads.to_float64(data["W"], cfg.dtype).astype(np.float32)
+    poison = np.where(np.arange(cfg.n)[None, :] % 2 == 0, np.nan, np.inf).astype(np.float32)
+    data["W"] = workloads.to_storage(np.where(M == 1, W, poison), cfg.dtype)
+    Yp = _run(cfg, data, flags=lrbi.FLAG_PATH_STREAM)
+    assert torch.equal(Y.view(torch.int16), Yp.view(torch.int16))
+
+
+def test_row_streaming_kernel_refuses_what_it_cannot_serve():
+    cfg = _small(64, 520, 32, 130, 6, 0.25, 6, "f16")  # N = 6: neither 1 nor a multiple of 4
+    data = workloads.make(cfg)
+    with pytest.raises(lrbi.LrbiError):
+        _run(cfg, data, flags=lrbi.FLAG_PATH_STREAM)
+    cfg = _small(64, 520, 32, 130, 6, 0.25, 1, "f32")
+    with pytest.raises(lrbi.LrbiError):
+        _run(cfg, workloads.make(cfg), flags=lrbi.FLAG_PATH_STREAM)
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 1), ("f16", 20)])
+def test_row_streaming_identity_x_returns_masked_weights_exactly(dtype, N):
+    cfg = _small(256, 256, 128, 128, 8, 0.2, N, dtype)
+    data = workloads.make(cfg)
+    X = np.zeros((cfg.n, N), np.float32)
+    X[np.arange(N), np.arange(N)] = 1.0
+    data["X"] = workloads.to_storage(X, dtype)
+    M = orc.decode_mask(data["Ip01"], data["Iz01"], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    Wm = np.where(M == 1, workloads.to_float64(data["W"], dtype), 0.0)
+    Y = to_float64(_run(cfg, data, flags=lrbi.FLAG_PATH_STREAM))
+    assert np.array_equal(Y, Wm[:, :N])
+
+
 def test_padded_leading_dimensions():
     for cfg in (_small(128, 256, 64, 128, 8, 0.2, 24, "f16"), _small(128, 256, 64, 128, 8, 0.2, 1, "bf16"),
                 _small(50, 120, 25, 60, 4, 0.2, 3, "f32")):
