@@ -105,37 +105,6 @@ struct StreamArgs {
     int ms_pitch;  // mask words per row in LDS (odd, at least 8 per slab)
 };
 
-// One 32-bit word of the decoded mask row, like decode_word(), from factors held in LDS:
-// Fz [tile_cols][k][izw] (the tile row's packed I_z as it lies in memory), Fp [tile_cols][fp_pitch] holding [16][ipw].
-__device__ __forceinline__ uint32_t decode_word_lds(const Geom &g, const uint32_t *Fp, int fp_pitch, const uint32_t *Fz, int rl,
-                                                    int w)
-{
-    const int n = (int)g.n; // below 2^30 here: 32-bit arithmetic throughout
-    const int j0 = w * 32;
-    if (j0 >= n) return 0u;
-    const int j1 = (j0 + 32 < n) ? j0 + 32 : n;
-    int tj = (int)((uint32_t)j0 / (uint32_t)g.c);
-    uint32_t acc = 0u;
-    for (int tbeg = tj * g.c; tbeg < j1; tbeg += g.c, ++tj) {
-        const uint32_t *ip = Fp + tj * fp_pitch + rl * g.ipw;
-        const uint32_t *izt = Fz + tj * g.k * g.izw;
-        const int off = j0 - tbeg; // -32 < off < c
-        const uint32_t valid = bit_range(off < 0 ? -off : 0, (g.c - off < 32) ? g.c - off : 32);
-        uint32_t v = 0u;
-        for (int iw = 0; iw < g.ipw; ++iw) {
-            uint32_t sel = ip[iw];
-            while (sel) {
-                const int l = __builtin_ctz(sel) + 32 * iw;
-                sel &= sel - 1u;
-                v |= iz_window(izt + l * g.izw, g.izw, off);
-            }
-        }
-        acc |= v & valid;
-    }
-    if (j1 - j0 < 32) acc &= bit_range(0, j1 - j0); // a tile cut off at the right edge
-    return acc;
-}
-
 template <typename Tag, int NS, int BM, int KS>
 __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamArgs a)
 {
@@ -210,11 +179,37 @@ __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamA
             }
         }
     };
-    const int nwords = nslabs * STEPS; // words past column n decode to zero
-    auto decode_rows = [&]() { // all mask words of the workgroup's rows, one per lane and turn
-        for (int idx = tid; idx < BM * nwords; idx += ST_THREADS) {
-            const int rl = (int)((uint32_t)idx / (uint32_t)nwords), w = idx - rl * nwords;
-            Ms[rl * a.ms_pitch + w] = (rl < rows_here) ? decode_word_lds(g, Fp, a.fp_pitch, Fz, rl, w) : 0u;
+    // Eq. 3 from the factors in LDS, one work item per (tile, row, 32-bit word of the tile's I_z rows): the item ORs
+    // the word of every I_z row that its I_p row selects and then ORs the result into the row's mask at the tile's
+    // bit position (two words when the tile does not start on a word boundary; neighbouring tiles may share a word,
+    // hence LDS atomics).  No item looks at more than one tile, so tile edges need no special cases.
+    auto decode_rows = [&]() {
+        const uint32_t per_tile = (uint32_t)(BM * g.izw);
+        const uint32_t items = (uint32_t)g.tile_cols * per_tile;
+        for (uint32_t idx = tid; idx < items; idx += ST_THREADS) {
+            const uint32_t tj = idx / per_tile, rem = idx - tj * per_tile;
+            const uint32_t rl = rem / (uint32_t)g.izw, wz = rem - rl * (uint32_t)g.izw;
+            const int in_tile = (int)wz * 32;
+            const int col0 = (int)tj * g.c + in_tile;
+            if ((int)rl >= rows_here || in_tile >= g.c || col0 >= n) continue;
+            uint32_t v = 0u;
+            for (int iw = 0; iw < g.ipw; ++iw) {
+                uint32_t sel = Fp[tj * a.fp_pitch + rl * g.ipw + iw];
+                while (sel) {
+                    const int l = __builtin_ctz(sel) + 32 * iw;
+                    sel &= sel - 1u;
+                    v |= Fz[(tj * g.k + l) * g.izw + wz];
+                }
+            }
+            // columns past the tile's width (pad bits of the packed rows) and past n (a cut-off last tile) stay out
+            const int lim = (g.c - in_tile < n - col0) ? g.c - in_tile : n - col0;
+            if (lim < 32) v &= (1u << lim) - 1u;
+            if (v == 0u) continue;
+            uint32_t *dst = Ms + rl * a.ms_pitch + (col0 >> 5);
+            const int sh = col0 & 31;
+            __hip_atomic_fetch_or(dst, v << sh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (sh && (v >> (32 - sh)))
+                __hip_atomic_fetch_or(dst + 1, v >> (32 - sh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     };
 
@@ -266,6 +261,7 @@ __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamA
     // The factor copies go first and are waited for by count: the slab copies issued after them stay in flight.
     stage_factors();
     for (int s = 0; s < NS - 1; ++s) copy_slab(s); // slabs past the end copy clamped addresses: same count
+    for (int i = tid; i < BM * a.ms_pitch; i += ST_THREADS) Ms[i] = 0u;
     wait_loads_at_most((NS - 1) * my_per_slab);
     LRBI_BARRIER();
     decode_rows();

@@ -518,6 +518,18 @@ extern "C" int lrbi_lstm_step(const lrbi_desc *desc, lrbi_dtype dtype, const voi
     const Geom g = make_geom(desc);
     const MfmaPlan plan = plan_lstm(desc, B);
     if (workspace_bytes < plan.workspace_bytes) return LRBI_ERR_WORKSPACE;
+    if ((desc->flags & LRBI_FLAG_PATH_MASK) == LRBI_FLAG_PATH_AUTO) {
+        // narrow batches: the row-streaming kernel leaves the fp32 pre-activations as a single plane
+        const int cus = compute_units_of((hipStream_t)stream);
+        if (stream_ok(g, dtype, dW, ldw, dXH, ldxh, B, cus)) {
+            const int64_t ldp = (B + 3) / 4 * 4;
+            const int rc1 = launch_stream_gemm(g, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
+                                               dXH, B, nullptr, 0, (float *)dWorkspace, ldp, cus, (hipStream_t)stream);
+            if (rc1 != LRBI_OK) return rc1;
+            return launch_lstm_cell(dtype, (const float *)dWorkspace, 1, desc->m, ldp, B, dC, ldc, dH1, ldh1, dH2, ldh2,
+                                    (hipStream_t)stream);
+        }
+    }
     const int rc2 = launch_mfma_gemm(g, plan, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
                                      dXH, ldxh, B, nullptr, 0, dWorkspace, (hipStream_t)stream);
     if (rc2 != LRBI_OK) return rc2;
