@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, C1, general_resnet_tiles, general_edge_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, lstm_sequence_C4, nmf_C2, nmf_C3, "
+                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, lstm_sequence_C4, nmf_C2, nmf_C3, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -336,6 +336,40 @@ def main():
                 del Wl, X_, Y_
             except Exception as e:
                 others[name] = {"error": repr(e)}
+        # the convolution configuration without its unfolded input: C5's layer (256 filters, 256 channels, 3 x 3,
+        # 14 x 14 images, batch 64) with X gathered from the zero-padded activation inside the product kernel
+        if wanted is None or "conv_C5" in wanted:
+            try:
+                c = workloads.CONFIGS["C5"]
+                cin, Hh, Ww = c.n // 9, 14, 14
+                batch = c.N // (Hh * Ww)
+                d = workloads.make(c, want_x=False)
+                de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
+                ip_, iz_ = factors_to_dev(de, d["Ip01"], d["Iz01"])
+                Wl = rotated_weights(to_dev(d["W"], c.dtype), min_total_bytes=8e6)
+                acts = []
+                for i in range(8):  # rotating activations: each launch reads one that the cache saw 7 launches ago
+                    a_ = torch.zeros((batch, Hh + 2, Ww + 2, cin), dtype=TD[c.dtype], device=dev)
+                    a_[:, 1:Hh + 1, 1:Ww + 1, :] = torch.randn((batch, Hh, Ww, cin), device=dev, dtype=torch.float32).to(TD[c.dtype])
+                    acts.append(a_)
+                Y_ = torch.empty((c.m, c.N), dtype=TD[c.dtype], device=dev)
+                wb = lrbi.masked_conv3x3_workspace_bytes(de, DC[c.dtype], batch, Hh, Ww)
+                w_ = torch.empty(max(1, (wb + 3) // 4), dtype=torch.float32, device=dev) if wb else None
+                fns = [(lambda Wi=Wl[i % len(Wl)], Ai=acts[i]: lrbi.masked_conv3x3(de, Wi, ip_, iz_, Ai, out=Y_, workspace=w_))
+                       for i in range(len(acts))]
+                ms, _ = event_times(fns, 6 * len(fns), len(fns))
+                byts = (c.m * c.n + batch * Hh * Ww * cin + c.m * c.N) * 2 + lrbi.index_bits(de)["lrbi_bits"] / 8
+                fl = 2.0 * c.m * c.n * c.N
+                others["conv_C5"] = {
+                    "workload": "C5 as a convolution: %d filters x %d channels x 3 x 3 (%s), images %d x %d x %d, tiles %dx%d "
+                                "rank %d; X gathered from the padded activation" % (c.m, cin, c.dtype, batch, Hh, Ww, c.r, c.c, c.k),
+                    "avg_launch_ms": round(ms, 5), "tflops_dense_equiv": round(fl / (ms * 1e-3) / 1e12, 2),
+                    "mfma_frac": round(fl / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
+                    "algorithmic_bytes": int(byts), "GBs": round(byts / (ms * 1e-3) / 1e9, 1),
+                    "hbm_frac": round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                del Wl, acts, Y_
+            except Exception as e:
+                others["conv_C5"] = {"error": repr(e)}
         # one candidate of Algorithm 1 per launch (threshold, decode on chip, ones and cost per tile)
         for name in ("C2", "C3a"):
             key = "alg1_eval_" + name[:2]

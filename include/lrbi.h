@@ -198,6 +198,31 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
                      void *stream);
 
 /*
+ * The masked product of a 3 x 3 convolution layer with padding 1 and stride 1 (the convolution layers of Sec. 4's
+ * ResNet32 and AlexNet rows), without the unfolded input matrix: Y = (W o I_a) X where column (b, oh, ow) of X would
+ * hold the 9 * cin input values under the filter at output pixel (oh, ow) of image b.  The kernel gathers them from
+ * the activation itself.  The paper leaves the 2-D view of a 4-D filter bank open ("reshaping the original binary
+ * index matrix can be varied", Sec. 3.1); here
+ *   W is m x (9 * cin) with column index (kh * 3 + kw) * cin + ci (filter tap major, channel minor), desc.n = 9 * cin,
+ *   and the factors describe that matrix;
+ *   dActPadded: the input activation with a zero border of one pixel, [batch][H + 2][Wd + 2][cin], channels
+ *   fastest, same dtype as W, 16-byte aligned; the producer of the activation writes the interior and keeps the
+ *   border zero (the entry point neither checks nor writes it);
+ *   dY: m x (batch * H * Wd) row-major, column index (b * H + oh) * Wd + ow, ldy >= batch * H * Wd.
+ * Same arithmetic contract as lrbi_masked_gemm (fp32 accumulation, fixed order, nearest-even store, pruned weights
+ * contribute nothing).  Served shapes: f16 / bf16, tile sizes that are multiples of 128 dividing m and 9 * cin,
+ * rank <= 64, cin a multiple of 64, 16-byte aligned W rows and I_z; anything else returns LRBI_ERR_SHAPE /
+ * LRBI_ERR_ALIGN (the caller can still unfold X and call lrbi_masked_gemm).  Workspace as for lrbi_masked_gemm.
+ * One or two kernel launches on `stream`.
+ */
+int lrbi_masked_conv3x3_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t batch, int64_t H, int64_t Wd,
+                                        uint64_t *bytes);
+int lrbi_masked_conv3x3(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                        const void *dIp_packed, const void *dIz_packed, const void *dActPadded, int64_t batch,
+                        int64_t H, int64_t Wd, int64_t cin, void *dY, int64_t ldy, void *dWorkspace,
+                        uint64_t workspace_bytes, void *stream);
+
+/*
  * lrbi_masked_gemm for callers that cannot allocate device memory and have no workspace to hand over: code
  * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results
  * (identical bits) and launches as lrbi_masked_gemm called with a workspace of

@@ -76,6 +76,8 @@ def load_library():
     lib.lrbi_decode_mask.argtypes = [pd, vp, vp, vp, i64, vp]
     lib.lrbi_masked_gemm_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
     lib.lrbi_masked_gemm.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, u64, vp]
+    lib.lrbi_masked_conv3x3_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, i64, i64, pu64]
+    lib.lrbi_masked_conv3x3.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, i64, i64, vp, i64, vp, u64, vp]
     lib.lrbi_masked_gemm_static.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp]
     lib.lrbi_threshold_eval.argtypes = [pd, ctypes.c_int, vp, i64, ctypes.c_float, ctypes.c_int32, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64,
                                         vp]
@@ -241,6 +243,39 @@ def masked_gemm(desc: Desc, W, dIp, dIz, X, out=None, workspace=None, stream=Non
         _dev_ptr(X, "X"), X.stride(0), N, _dev_ptr(out, "Y"), out.stride(0), ws_ptr, ws_bytes, _stream_ptr(stream)),
         "lrbi_masked_gemm")
     return out[:, 0] if squeeze else out
+
+
+def masked_conv3x3_workspace_bytes(desc: Desc, dtype_code: int, batch: int, H: int, Wd: int) -> int:
+    out = ctypes.c_uint64()
+    _check(load_library().lrbi_masked_conv3x3_workspace_bytes(ctypes.byref(desc), int(dtype_code), int(batch), int(H),
+                                                              int(Wd), ctypes.byref(out)),
+           "lrbi_masked_conv3x3_workspace_bytes")
+    return out.value
+
+
+def masked_conv3x3(desc: Desc, W, dIp, dIz, act_padded, out=None, workspace=None, stream=None):
+    """lrbi_masked_conv3x3: Y = (W o decode(Ip, Iz)) X for a 3 x 3, padding-1 convolution, X gathered from the
+    activation.  W [m, 9 * cin] with column (kh * 3 + kw) * cin + ci; act_padded [batch, H + 2, Wd + 2, cin]
+    contiguous with a zero border; returns Y [m, batch * H * Wd]."""
+    import torch
+    if act_padded.dim() != 4 or not act_padded.is_contiguous() or act_padded.dtype != W.dtype:
+        raise ValueError("act_padded must be a contiguous [batch, H + 2, Wd + 2, cin] tensor of W's dtype")
+    batch, H, Wd, cin = act_padded.shape[0], act_padded.shape[1] - 2, act_padded.shape[2] - 2, act_padded.shape[3]
+    if W.dim() != 2 or W.shape != (desc.m, desc.n) or W.stride(1) != 1:
+        raise ValueError("shape mismatch")
+    N = batch * H * Wd
+    if out is None:
+        out = torch.empty((desc.m, N), dtype=W.dtype, device=W.device)
+    if out.shape != (desc.m, N) or out.dtype != W.dtype or out.stride(1) != 1:
+        raise ValueError("bad out tensor")
+    ws_ptr, ws_bytes = ctypes.c_void_p(0), 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    _check(load_library().lrbi_masked_conv3x3(
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), _dev_ptr(dIp, "Ip"), _dev_ptr(dIz, "Iz"),
+        _dev_ptr(act_padded, "act"), batch, H, Wd, cin, _dev_ptr(out, "Y"), out.stride(0), ws_ptr, ws_bytes,
+        _stream_ptr(stream)), "lrbi_masked_conv3x3")
+    return out
 
 
 STATIC_SCRATCH_BYTES = 32 * 1024 * 1024

@@ -862,6 +862,23 @@ static int launch_dtype(const Geom &g, const MfmaPlan &plan, const void *dW, int
 }
 #undef LRBI_TILE_ARGS
 
+// The convolution form: plan as for N = batch * H * Wd columns on the pipelined kernel, which gathers its X operand
+// from the padded activation; partial planes of a split reduction are added as for the matrix form.
+int launch_mfma_conv(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const ConvGeom &cg, const void *dW, int64_t ldw,
+                     const uint32_t *dIp, const uint32_t *dIz, const void *dAct, int64_t N, void *dY, int64_t ldy,
+                     void *dWorkspace, hipStream_t stream)
+{
+    if (((uintptr_t)dW & 15) != 0 || ldw % 8 != 0) return LRBI_ERR_ALIGN;
+    if (plan.tile < kFirstPipeTile) return LRBI_ERR_SHAPE;
+    const int rc = launch_pipe_conv(g, plan, dt, cg, dW, ldw, dIp, dIz, dAct, N, dY, ldy, dWorkspace, stream);
+    if (rc != LRBI_OK) return rc;
+    if (plan.splitk > 1 && !plan.planes_only) {
+        if (dt == LRBI_F16) return launch_reduce<F16Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
+        return launch_reduce<BF16Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
+    }
+    return LRBI_OK;
+}
+
 int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan_in, lrbi_dtype dt, const void *dW, int64_t ldw,
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY,
                      int64_t ldy, void *dWorkspace, hipStream_t stream)

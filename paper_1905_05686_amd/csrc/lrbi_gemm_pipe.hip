@@ -45,12 +45,17 @@ template <int NS> struct SmemDma {
 };
 
 
-template <typename Tag, int NS, bool SPREAD, bool SPLIT>
+// CONV: X is not a matrix in memory but a zero-padded activation [B][H + 2][Wd + 2][C] (channels fastest), and column
+// (b, oh, ow) of the product's X holds, at reduction index (kh * 3 + kw) * C + ci, the value act[b][oh + kh][ow + kw][ci]
+// (a 3 x 3 convolution with padding 1 written as a product, the unfolded matrix never materialised).  A slab of 64
+// reduction indices is then 64 consecutive channels of one tap: 128 contiguous bytes per column, which go into the
+// stage in the same swizzled row-major image as W's rows and come out with the same 16-byte operand reads.
+template <typename Tag, int NS, bool SPREAD, bool SPLIT, bool CONV>
 __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
     Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
     const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ X, int64_t ldx, int N,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ P, int64_t ldp, int mblocks, int nblocks,
-    int64_t kper, int xcd_remap, int y_vec_ok)
+    int64_t kper, int xcd_remap, int y_vec_ok, ConvGeom cg)
 {
     static_assert(NS == 4, "LDS stages (an even number: the W operand registers alternate with the slab's parity)");
     static_assert(!SPREAD || NS == 4, "loads spread over the iteration land one iteration later: four stages");
@@ -101,21 +106,41 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
         const int wr = chunk * 8 + (lane >> 3);
         const int wp = (lane & 7) ^ ((wr >> 1) & 7);
         wvo[i] = (uint32_t)((wr * ldw + wp * 8) * 2);
-        const int xr = chunk * 4 + (lane >> 4);
-        const int xp = (lane & 15) ^ (2 * (xr & 3));
-        int nn = xp * 8;
-        if (n0 + nn + 8 > N) nn = N - 8 - n0; // piece beyond N: fetch a valid piece instead, its columns are dropped
-        xvo[i] = (uint32_t)((xr * ldx + nn) * 2);
+        if constexpr (CONV) {
+            // same image as W: 8 columns of X (128 bytes of channels each) per instruction
+            const int xr = chunk * 8 + (lane >> 3);
+            const int xp = (lane & 7) ^ ((xr >> 1) & 7);
+            int col = n0 + xr;
+            if (col >= N) col = N - 1; // column beyond N: a valid column instead, it is dropped at the end
+            const int hw = cg.H * cg.Wd;
+            const int b = col / hw, rem = col - b * hw;
+            const int oh = rem / cg.Wd, ow = rem - oh * cg.Wd;
+            const int64_t pix = ((int64_t)b * (cg.H + 2) + oh) * (cg.Wd + 2) + ow; // tap (0, 0) of the column
+            xvo[i] = (uint32_t)((pix * cg.cin + xp * 8) * 2);
+        } else {
+            const int xr = chunk * 4 + (lane >> 4);
+            const int xp = (lane & 15) ^ (2 * (xr & 3));
+            int nn = xp * 8;
+            if (n0 + nn + 8 > N) nn = N - 8 - n0; // piece beyond N: fetch a valid piece instead, its columns are dropped
+            xvo[i] = (uint32_t)((xr * ldx + nn) * 2);
+        }
     }
     const uint16_t *wbase = W + m0 * ldw + kbeg;
-    const uint16_t *xbase = X + (int64_t)kbeg * ldx + n0;
+    const uint16_t *xbase = CONV ? X : X + (int64_t)kbeg * ldx + n0;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     // piece i (0, 1: W chunks, 2, 3: X chunks) of a slab into a stage
     auto issue_piece = [&](int slab, int stage, auto i_c) {
         constexpr int i = decltype(i_c)::value;
         const uint32_t sb = lds0 + (uint32_t)stage * STAGE_BYTES + (uint32_t)wave * 1024u;
         if constexpr (i < 2) load_to_lds16(sb + i * 8192u, wbase + slab * BK, wvo[i]);
-        else load_to_lds16(sb + STAGE_X + (i - 2) * 8192u, xbase + (int64_t)slab * BK * ldx, xvo[i - 2]);
+        else if constexpr (CONV) {
+            // the slab's 64 reduction indices: channels ci0 .. ci0 + 63 of tap (kh, kw)
+            const int kidx = kbeg + slab * BK;
+            const int tap = kidx / cg.cin, ci0 = kidx - tap * cg.cin;
+            const int kh = tap / 3, kw = tap - 3 * kh;
+            load_to_lds16(sb + STAGE_X + (i - 2) * 8192u, xbase + ((kh * (cg.Wd + 2) + kw) * cg.cin + ci0), xvo[i - 2]);
+        } else
+            load_to_lds16(sb + STAGE_X + (i - 2) * 8192u, xbase + (int64_t)slab * BK * ldx, xvo[i - 2]);
     };
 
     // ---- operand reads: byte addresses inside a stage.  This wavefront's steps are kk = 2 kg + j, j = 0, 1.
@@ -149,8 +174,19 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
         constexpr int par = decltype(par_c)::value, j = decltype(j_c)::value;
         wf[par][j] = *reinterpret_cast<const u32x4 *>(smem + stage * STAGE_BYTES + wfa[j]);
     };
+    // CONV: X operand of step kk, block a: column q = 32 a + (lane % 32), piece 2 kk + (lane / 32), image as W's
+    uint32_t xca[2];
+    {
+        const int c7 = (l32 >> 1) & 7; // (q >> 1) & 7 does not depend on the block
+#pragma unroll
+        for (int j = 0; j < 2; ++j) xca[j] = (uint32_t)(STAGE_X + l32 * 128 + (((2 * (2 * kg + j) + lg) ^ c7) * 16));
+    }
     auto read_x = [&](int stage, auto j_c, auto a_c) {
         constexpr int j = decltype(j_c)::value, a = decltype(a_c)::value;
+        if constexpr (CONV) {
+            xf[j][a] = *reinterpret_cast<const u32x4 *>(smem + stage * STAGE_BYTES + xca[j] + a * 4096);
+            return;
+        }
         const unsigned char *p = smem + stage * STAGE_BYTES + ((a & 1) ? xfo : xfe) + (a >> 1) * 128 + j * 4096;
         const u32x2 lo = lds_read_tr16_v((const uint16_t *)p);
         const u32x2 hi = lds_read_tr16_v((const uint16_t *)(p + 1024));
@@ -461,10 +497,10 @@ bool pipe_ok(const Geom &g, const void *dIz, const void *dX, int64_t ldw, int64_
     return true;
 }
 
-template <typename Tag, int NS, bool SPREAD>
+template <typename Tag, int NS, bool SPREAD, bool CONV>
 static int launch_pipe_t(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
                          const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
-                         void *dWorkspace, hipStream_t stream)
+                         void *dWorkspace, const ConvGeom &cg, hipStream_t stream)
 {
     const int64_t mblocks = g.m / PIPE_BM;
     const int64_t nblocks = (N + PIPE_BN - 1) / PIPE_BN;
@@ -475,11 +511,11 @@ static int launch_pipe_t(const Geom &g, const MfmaPlan &plan, const void *dW, in
     const int xcd_remap = (blocks % 8 == 0) ? 1 : 0;
     const int64_t ldp = (N + 3) / 4 * 4;
     const size_t smem = SmemDma<NS>::bytes;
-    auto kern = split ? mfma_gemm_pipe_kernel<Tag, NS, SPREAD, true> : mfma_gemm_pipe_kernel<Tag, NS, SPREAD, false>;
+    auto kern = split ? mfma_gemm_pipe_kernel<Tag, NS, SPREAD, true, CONV> : mfma_gemm_pipe_kernel<Tag, NS, SPREAD, false, CONV>;
     LRBI_SET_MAX_LDS(kern, smem);
     LRBI_LAUNCH(kern, dim3((unsigned)blocks), dim3(PIPE_THREADS), smem, stream, g, (const uint16_t *)dW, ldw, dIp, dIz,
                 (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp, (int)mblocks,
-                (int)nblocks, plan.kper, xcd_remap, y_vec_ok);
+                (int)nblocks, plan.kper, xcd_remap, y_vec_ok, cg);
     return LRBI_OK;
 }
 
@@ -490,16 +526,45 @@ int launch_pipe_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, int var
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY,
                      int64_t ldy, void *dWorkspace, hipStream_t stream)
 {
-#define LRBI_PIPE_ARGS g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream
+    const ConvGeom none = {0, 0, 0};
+#define LRBI_PIPE_ARGS g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, none, stream
     if (dt == LRBI_F16) {
-        if (variant <= 1) return launch_pipe_t<F16Tag, 4, false>(LRBI_PIPE_ARGS);
-        return launch_pipe_t<F16Tag, 4, true>(LRBI_PIPE_ARGS);
+        if (variant <= 1) return launch_pipe_t<F16Tag, 4, false, false>(LRBI_PIPE_ARGS);
+        return launch_pipe_t<F16Tag, 4, true, false>(LRBI_PIPE_ARGS);
     }
     if (dt == LRBI_BF16) {
-        if (variant <= 1) return launch_pipe_t<BF16Tag, 4, false>(LRBI_PIPE_ARGS);
-        return launch_pipe_t<BF16Tag, 4, true>(LRBI_PIPE_ARGS);
+        if (variant <= 1) return launch_pipe_t<BF16Tag, 4, false, false>(LRBI_PIPE_ARGS);
+        return launch_pipe_t<BF16Tag, 4, true, false>(LRBI_PIPE_ARGS);
     }
 #undef LRBI_PIPE_ARGS
+    return LRBI_ERR_DTYPE;
+}
+
+// true when the pipelined kernel serves the convolution form: aligned tile shapes, 64 channels or a multiple,
+// the weight matrix's 9 * cin columns, offsets that fit the kernel's 32-bit per-lane byte offsets
+bool pipe_conv_ok(const Geom &g, const ConvGeom &cg, int64_t batch, const void *dIz, const void *dAct, int64_t ldw)
+{
+    if ((g.c % 128) != 0 || (g.r % PIPE_BM) != 0 || g.k > FAST_MAX_K || g.ragged) return false;
+    if (cg.cin <= 0 || cg.cin % 64 != 0 || cg.H <= 0 || cg.Wd <= 0 || batch <= 0) return false;
+    if (g.n != (int64_t)9 * cg.cin) return false;
+    if ((((uintptr_t)dAct | (uintptr_t)dIz) & 15) != 0) return false;
+    if (ldw > (1 << 22)) return false;
+    const int64_t act_bytes = batch * (cg.H + 2) * (int64_t)(cg.Wd + 2) * cg.cin * 2;
+    if (act_bytes >= ((int64_t)1 << 32) || batch * cg.H * (int64_t)cg.Wd > 0x7FFFFF00) return false;
+    const int64_t tiles = (int64_t)g.tile_rows * g.tile_cols;
+    if (tiles * g.k * g.izw * 4 >= (int64_t)1 << 31 || tiles * g.r * g.ipw * 4 >= (int64_t)1 << 31) return false;
+    return true;
+}
+
+// the convolution form (operands from L2: loads spread over the iteration); N = batch * H * Wd columns
+int launch_pipe_conv(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const ConvGeom &cg, const void *dW, int64_t ldw,
+                     const uint32_t *dIp, const uint32_t *dIz, const void *dAct, int64_t N, void *dY, int64_t ldy,
+                     void *dWorkspace, hipStream_t stream)
+{
+    if (dt == LRBI_F16)
+        return launch_pipe_t<F16Tag, 4, true, true>(g, plan, dW, ldw, dIp, dIz, dAct, 0, N, dY, ldy, dWorkspace, cg, stream);
+    if (dt == LRBI_BF16)
+        return launch_pipe_t<BF16Tag, 4, true, true>(g, plan, dW, ldw, dIp, dIz, dAct, 0, N, dY, ldy, dWorkspace, cg, stream);
     return LRBI_ERR_DTYPE;
 }
 

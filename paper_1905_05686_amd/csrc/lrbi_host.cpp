@@ -278,6 +278,58 @@ extern "C" int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const v
                             dX, ldx, N, dY, ldy, dWorkspace, s);
 }
 
+// plan of the convolution form: the pipelined tile kernel, whatever the tile flag says
+static MfmaPlan plan_conv(const lrbi_desc *desc, int64_t N)
+{
+    const uint32_t flags = (desc->flags & ~LRBI_FLAG_TILE_MASK) | (14u << LRBI_FLAG_TILE_SHIFT);
+    return plan_mfma(make_geom(desc), flags, N);
+}
+
+extern "C" int lrbi_masked_conv3x3_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t batch, int64_t H,
+                                                   int64_t Wd, uint64_t *bytes)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!bytes) return LRBI_ERR_NULL;
+    if (dtype != LRBI_F16 && dtype != LRBI_BF16) return LRBI_ERR_DTYPE;
+    if (batch <= 0 || H <= 0 || Wd <= 0 || batch * H * Wd > (int64_t)0x7FFFFF00) return LRBI_ERR_SHAPE;
+    *bytes = plan_conv(desc, batch * H * Wd).workspace_bytes;
+    return LRBI_OK;
+}
+
+extern "C" int lrbi_masked_conv3x3(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                                   const void *dIp_packed, const void *dIz_packed, const void *dActPadded, int64_t batch,
+                                   int64_t H, int64_t Wd, int64_t cin, void *dY, int64_t ldy, void *dWorkspace,
+                                   uint64_t workspace_bytes, void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dW || !dIp_packed || !dIz_packed || !dActPadded || !dY) return LRBI_ERR_NULL;
+    if (dtype != LRBI_F16 && dtype != LRBI_BF16) return LRBI_ERR_DTYPE;
+    if (batch <= 0 || H <= 0 || Wd <= 0 || cin <= 0 || H > 32766 || Wd > 32766 || cin > (1 << 20)) return LRBI_ERR_SHAPE;
+    if (batch * H * Wd > (int64_t)0x7FFFFF00 || desc->n != 9 * cin) return LRBI_ERR_SHAPE;
+    const int64_t N = batch * H * Wd;
+    if (ldw < desc->n || ldy < N) return LRBI_ERR_PITCH;
+    if (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 16) || !aligned_to(dW, 16) || ldw % 8 != 0 ||
+        !aligned_to(dActPadded, 16) || !aligned_to(dY, 2))
+        return LRBI_ERR_ALIGN;
+    const Geom g = make_geom(desc);
+    const ConvGeom cg = {(int)cin, (int)H, (int)Wd};
+    if (!pipe_conv_ok(g, cg, batch, dIz_packed, dActPadded, ldw)) return LRBI_ERR_SHAPE;
+    MfmaPlan plan = plan_conv(desc, N);
+    if (plan.splitk > 1) {
+        const bool ws_ok = dWorkspace && aligned_to(dWorkspace, 16) && workspace_bytes >= plan.workspace_bytes;
+        if (!ws_ok) {
+            if (desc->flags & LRBI_FLAG_SPLITK_MASK) return LRBI_ERR_WORKSPACE;
+            lrbi_desc one = *desc; // no scratch: one slice over the whole reduction range
+            one.flags = (desc->flags & ~LRBI_FLAG_SPLITK_MASK) | (1u << LRBI_FLAG_SPLITK_SHIFT);
+            plan = plan_conv(&one, N);
+        }
+    }
+    return launch_mfma_conv(g, plan, dtype, cg, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
+                            dActPadded, N, dY, ldy, dWorkspace, (hipStream_t)stream);
+}
+
 // ---------------------------------------------------------------------------
 // lrbi_masked_gemm_static: the fused masked product for callers that cannot allocate.  The partial sums of a
 // split reduction live in `scratch`, a device array that is part of the library's code object: every GPU the

@@ -101,6 +101,20 @@ int launch_stream_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw
                        const uint32_t *dIz, const void *dX, int64_t N, void *dY, int64_t ldy, float *dP, int64_t ldp,
                        int cus, hipStream_t stream);
 
+// a 3 x 3 convolution with padding 1 read as a product (lrbi_gemm_pipe.hip): the activation is zero-padded,
+// [batch][H + 2][Wd + 2][cin] with channels fastest; reduction index = (kh * 3 + kw) * cin + ci
+struct ConvGeom {
+    int cin, H, Wd; // channels, output height and width
+};
+bool pipe_conv_ok(const Geom &g, const ConvGeom &cg, int64_t batch, const void *dIz, const void *dAct, int64_t ldw);
+int launch_pipe_conv(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const ConvGeom &cg, const void *dW, int64_t ldw,
+                     const uint32_t *dIp, const uint32_t *dIz, const void *dAct, int64_t N, void *dY, int64_t ldy,
+                     void *dWorkspace, hipStream_t stream);
+
+int launch_mfma_conv(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const ConvGeom &cg, const void *dW, int64_t ldw,
+                     const uint32_t *dIp, const uint32_t *dIz, const void *dAct, int64_t N, void *dY, int64_t ldy,
+                     void *dWorkspace, hipStream_t stream);
+
 // software-pipelined tile kernel (lrbi_gemm_pipe.hip)
 bool pipe_ok(const Geom &g, const void *dIz, const void *dX, int64_t ldw, int64_t ldx, int64_t N);
 int launch_pipe_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, int pf, const void *dW, int64_t ldw,
