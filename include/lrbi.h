@@ -392,8 +392,9 @@ int lrbi_lstm_step(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int6
  *   e.g. uniform random) starting point, on return the factors; the rows / columns a cut-off edge
  *   tile does not use are left as given.  eps > 0.  fp32 arithmetic, fixed summation order.
  *   dWorkspace: required, 16-byte aligned, at least lrbi_nmf_workspace_bytes bytes (a second copy of
- *   both factors).  Limits: k <= 64 (LRBI_ERR_RANK otherwise); method outside 1 .. 3, iters < 0 or
- *   eps <= 0 are LRBI_ERR_SHAPE.  2 + 2 iters (+ 2) kernel launches on `stream`.
+ *   both factors and one k x k matrix per tile).  Any rank the descriptor allows (up to LRBI_MAX_RANK);
+ *   method outside 1 .. 3, iters < 0 or eps <= 0 are LRBI_ERR_SHAPE.  2 + 4 iters (+ 2) kernel launches
+ *   on `stream`.
  */
 int lrbi_nmf_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
 int lrbi_nmf(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw, int32_t method,

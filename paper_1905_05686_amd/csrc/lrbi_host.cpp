@@ -607,7 +607,6 @@ extern "C" int lrbi_nmf(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW,
     if (!dW || !dMp || !dMz || !dWorkspace) return LRBI_ERR_NULL;
     const int es = elem_size(dtype);
     if (es == 0) return LRBI_ERR_DTYPE;
-    if (desc->k > 64) return LRBI_ERR_RANK;
     if (method < 1 || method > 3 || iters < 0 || !(eps > 0.f)) return LRBI_ERR_SHAPE;
     if (ldw < desc->n) return LRBI_ERR_PITCH;
     if (!aligned_to(dW, (uintptr_t)es) || !aligned_to(dMp, 4) || !aligned_to(dMz, 4) || !aligned_to(dWorkspace, 16))

@@ -4,13 +4,17 @@
 // multiplicative update for that objective, from the caller's starting point, M_z first and then M_p:
 //     M_z <- M_z * (M_p^T M) / (M_p^T M_p M_z + eps)
 //     M_p <- M_p * (M M_z^T) / (M_p M_z M_z^T + eps)
-// One kernel per half update, all tiles per launch.  In the M_z update a lane owns one column j of a tile: it
-// streams the column of W (coalesced across the lanes), while the rows of M_p, which every lane needs, are staged
-// in LDS chunk by chunk and read as broadcasts; the k x k matrix M_p^T M_p is accumulated in LDS from the same
-// chunks; the lane then forms its k numerators and denominators and writes its column of the new M_z.  The M_p
-// update is the mirror image (a lane owns a row i, M_z is staged transposed, M_z M_z^T in LDS).  New factors go to a
-// second buffer (the other half update still needs the old values), the two buffers swap every iteration.
-// fp32 throughout, every sum in a fixed order.  Limits: k <= 64 (the k x k matrix and the chunks live in LDS).
+// Per half update two kernels, all tiles per launch: the k x k Gram matrix of the factor that stays fixed
+// (M_p^T M_p or M_z M_z^T, one lane per entry), then the update itself.
+// M_z update: a workgroup of four wavefronts owns 64 columns of a tile; lane = column, and each wavefront takes a
+// quarter of the tile's rows.  The rows of M_p, which every lane needs, are staged in LDS chunk by chunk and read as
+// broadcasts while the lane streams its column of W (coalesced across the lanes); the four partial numerators of a
+// column are added through LDS in wavefront order; the denominators come from the Gram rows (staged in LDS) and
+// the lane's column of the old M_z.  Splitting tiles this finely is what fills the chip: 64 tiles of 512 columns
+// give 512 workgroups.  The M_p update is the mirror image (lane = row, M_z staged transposed, a wavefront per
+// quarter of the columns).  New factors go to a second buffer (the other half update still needs the old values),
+// the two buffers swap every iteration.  fp32 throughout, every sum in a fixed order.  The ranks are processed KC
+// (8, 16 or 32) at a time, so any k up to 256 (the paper's largest) is served; each pass streams W again.
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
@@ -20,7 +24,9 @@ namespace lrbi {
 
 static constexpr int kNmfThreads = 256;
 static constexpr int kNmfStageFloats = 8192; // 32 KiB of staged factor rows
-static constexpr int kNmfMaxK = 64;
+static constexpr int kNmfMaxK = 256;
+// A workgroup owns kNmfThreads / PARTS columns (rows) of a tile, one per lane, and PARTS groups of lanes share them, each
+// taking a part of the rows (columns): PARTS = 4 when the tiles alone would not fill the chip, else 1.
 static constexpr int ZB = 16; // rows of W requested together in the M_z update
 
 template <typename T> struct NmfElem;
@@ -52,22 +58,84 @@ __device__ __forceinline__ void nmf_tile_extent(const Geom &g, int64_t t, int &t
     ct = (int)((g.n - (int64_t)tj * g.c < g.c) ? g.n - (int64_t)tj * g.c : g.c);
 }
 
-// M_z update.  Workgroup = (tile, block of 256 columns); lane = column.
-template <typename T, int KC>
+// Gram matrix of a tile's fixed factor: G[a][b] = sum_i Mp[i][a] Mp[i][b] (ZSIDE = false, rows of the tile in
+// ascending order) or sum_j Mz[a][j] Mz[b][j] (ZSIDE = true, columns in ascending order).  The factor is staged in LDS
+// chunk by chunk as [row or column][k] (M_z transposed on the way in); a lane owns four neighbouring entries of G (one
+// when k is not a multiple of 4) and reads one broadcast value and one 16-byte piece per staged row.
+template <bool ZSIDE>
+__global__ __launch_bounds__(kNmfThreads) void nmf_gram_kernel(Geom g, const float *__restrict__ F, float *__restrict__ G,
+                                                              int eblocks)
+{
+    __align__(16) static __shared__ float stage[kNmfStageFloats];
+    const int64_t t = blockIdx.x / eblocks;
+    const int eb = (int)(blockIdx.x - t * eblocks);
+    const int tid = threadIdx.x;
+    const int k = g.k;
+    const bool k4 = (k % 4) == 0;
+    int ti, tj, rt, ct;
+    nmf_tile_extent(g, t, ti, tj, rt, ct);
+    const int count = ZSIDE ? ct : rt;                 // rows (columns) summed over
+    const int per_chunk = kNmfStageFloats / k;
+    const float *f = F + (ZSIDE ? t * (int64_t)k * g.c : t * (int64_t)g.r * k);
+    const int unit = eb * kNmfThreads + tid;           // four entries (k4) or one
+    const int units = k4 ? k * k / 4 : k * k;
+    const bool live = unit < units;
+    const int a = live ? (k4 ? unit / (k / 4) : unit / k) : 0;
+    const int b = live ? (k4 ? (unit - a * (k / 4)) * 4 : unit - a * k) : 0;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i0 = 0; i0 < count; i0 += per_chunk) {
+        const int n = (count - i0 < per_chunk) ? count - i0 : per_chunk;
+        __syncthreads();
+        if (ZSIDE) { // consecutive lanes read consecutive columns of one row of M_z
+            for (int e = tid; e < n * k; e += kNmfThreads) {
+                const int l = e / n, jj = e - l * n;
+                stage[jj * k + l] = f[(int64_t)l * g.c + i0 + jj];
+            }
+        } else {
+            for (int e = tid; e < n * k; e += kNmfThreads) stage[e] = f[(int64_t)i0 * k + e];
+        }
+        __syncthreads();
+        if (!live) continue;
+        if (k4) {
+            for (int i = 0; i < n; ++i) {
+                const float pa = stage[i * k + a];
+                const float4 pb = *reinterpret_cast<const float4 *>(stage + i * k + b);
+                s.x = fmaf(pa, pb.x, s.x);
+                s.y = fmaf(pa, pb.y, s.y);
+                s.z = fmaf(pa, pb.z, s.z);
+                s.w = fmaf(pa, pb.w, s.w);
+            }
+        } else {
+            for (int i = 0; i < n; ++i) s.x = fmaf(stage[i * k + a], stage[i * k + b], s.x);
+        }
+    }
+    if (!live) return;
+    float *gt = G + t * (int64_t)k * k + (int64_t)a * k + b;
+    if (k4) *reinterpret_cast<float4 *>(gt) = s;
+    else *gt = s.x;
+}
+
+// M_z update.  Workgroup = (tile, block of 256 / PARTS columns); lane = column, group of lanes = part of the rows.
+template <typename T, int KC, int PARTS>
 __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const T *__restrict__ W, int64_t ldw, int method,
                                                                   float w_threshold, float amplify,
                                                                   const float *__restrict__ Mp,
                                                                   const float *__restrict__ MzCur,
-                                                                  float *__restrict__ MzNew, float eps, int cblocks)
+                                                                  float *__restrict__ MzNew, const float *__restrict__ G,
+                                                                  float eps, int cblocks)
 {
-    __align__(16) static __shared__ float stage[kNmfStageFloats];       // [rows of the chunk][k]
-    __align__(16) static __shared__ float gram[kNmfMaxK * kNmfMaxK];    // M_p^T M_p
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    float *stage = (float *)lrbi_dyn_smem;   // [rows of the chunk][k]; then the partial sums [part][rank][lane]
+    float *gramL = stage + kNmfStageFloats;  // the pass's rows of M_p^T M_p: [KC][k]
+    constexpr int kNmfParts = PARTS, kNmfOwn = kNmfThreads / PARTS;
+    static_assert(kNmfParts * KC * kNmfOwn <= kNmfStageFloats && KC * kNmfMaxK <= kNmfStageFloats, "LDS reuse");
     const int64_t t = blockIdx.x / cblocks;
     const int cb = (int)(blockIdx.x - t * cblocks);
     int ti, tj, rt, ct;
     nmf_tile_extent(g, t, ti, tj, rt, ct);
     const int tid = threadIdx.x;
-    const int j = cb * kNmfThreads + tid;
+    const int lane = tid & (kNmfOwn - 1), part = tid / kNmfOwn;
+    const int j = cb * kNmfOwn + lane;
     const bool live = j < ct;
     const int k = g.k;
     const bool k4 = (k % 4) == 0;
@@ -75,9 +143,8 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const
     const float *mp = Mp + t * (int64_t)g.r * k;
     const float *mzc = MzCur + t * (int64_t)k * g.c;
     float *mzn = MzNew + t * (int64_t)k * g.c;
+    const float *gt = G + t * (int64_t)k * k;
     const T *wcol = W + (int64_t)ti * g.r * ldw + (int64_t)tj * g.c + (live ? j : 0);
-
-    for (int e = tid; e < k * k; e += kNmfThreads) gram[e] = 0.f;
 
     for (int l0 = 0; l0 < k; l0 += KC) {
         const bool full = l0 + KC <= k;             // every rank of this pass exists
@@ -85,55 +152,35 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const
         float acc[KC];
 #pragma unroll
         for (int l = 0; l < KC; ++l) acc[l] = 0.f;
+        __syncthreads(); // the previous pass has read its Gram rows and partial sums
+        for (int e = tid; e < kt * k; e += kNmfThreads) gramL[e] = gt[(int64_t)l0 * k + e];
         for (int i0 = 0; i0 < rt; i0 += rows_per_chunk) {
             const int rows = (rt - i0 < rows_per_chunk) ? rt - i0 : rows_per_chunk;
             __syncthreads(); // the previous chunk has been consumed
             for (int e = tid; e < rows * k; e += kNmfThreads) stage[e] = mp[(int64_t)i0 * k + e];
             __syncthreads();
-            if (l0 == 0) { // M_p^T M_p, every lane its own entries, rows in ascending order
-                if (k4) { // four neighbouring entries per lane: one broadcast read and one 16-byte read per row
-                    for (int e4 = tid; e4 < k * k / 4; e4 += kNmfThreads) {
-                        const int a = e4 / (k / 4), b = (e4 - a * (k / 4)) * 4;
-                        float4 s = *reinterpret_cast<const float4 *>(gram + a * k + b);
-                        for (int i = 0; i < rows; ++i) {
-                            const float pa = stage[i * k + a];
-                            const float4 pb = *reinterpret_cast<const float4 *>(stage + i * k + b);
-                            s.x = fmaf(pa, pb.x, s.x);
-                            s.y = fmaf(pa, pb.y, s.y);
-                            s.z = fmaf(pa, pb.z, s.z);
-                            s.w = fmaf(pa, pb.w, s.w);
-                        }
-                        *reinterpret_cast<float4 *>(gram + a * k + b) = s;
-                    }
-                } else {
-                    for (int e = tid; e < k * k; e += kNmfThreads) {
-                        const int a = e / k, b = e - a * k;
-                        float s = gram[e];
-                        for (int i = 0; i < rows; ++i) s = fmaf(stage[i * k + a], stage[i * k + b], s);
-                        gram[e] = s;
-                    }
-                }
-            }
+            // this wavefront's rows of the chunk
+            const int per = (rows + kNmfParts - 1) / kNmfParts;
+            const int ibeg = part * per, iend = (ibeg + per < rows) ? ibeg + per : rows;
             if (live) {
                 // sixteen rows at a time: their W loads are requested together; the rows of M_p come out of the staged
-                // chunk as broadcast reads (reading them from global memory at lane-uniform addresses, i.e. as scalar
-                // loads, was measured slower: 165 us against 100 us per launch on the 256 x 256, rank 16 layer)
-                for (int i = 0; i < rows; i += ZB) {
+                // chunk as broadcast reads
+                for (int i = ibeg; i < iend; i += ZB) {
                     T raw[ZB];
                     float mv[ZB];
 #pragma unroll
                     for (int u = 0; u < ZB; ++u) {
-                        const int iu = (i + u < rows) ? i + u : rows - 1; // clamped: always a valid row
+                        const int iu = (i + u < iend) ? i + u : iend - 1; // clamped: always a valid row
                         raw[u] = wcol[(int64_t)(i0 + iu) * ldw];
                     }
 #pragma unroll
                     for (int u = 0; u < ZB; ++u) {
                         const float m = nmf_mag<T>(raw[u], method, w_threshold, amplify);
-                        mv[u] = (i + u < rows) ? m : 0.f;
+                        mv[u] = (i + u < iend) ? m : 0.f;
                     }
 #pragma unroll
                     for (int u = 0; u < ZB; ++u) {
-                        const int iu = (i + u < rows) ? i + u : rows - 1;
+                        const int iu = (i + u < iend) ? i + u : iend - 1;
                         const float *row = stage + iu * k + l0;
                         if (full && k4) { // rows of the staged chunk are 16-byte aligned: four ranks per LDS read
 #pragma unroll
@@ -152,54 +199,68 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_z_kernel(Geom g, const
                 }
             }
         }
-        __syncthreads(); // gram complete
-        if (live) {
-            float den[KC];
+        __syncthreads(); // the last chunk has been consumed: the staging area takes the partial sums
 #pragma unroll
-            for (int l = 0; l < KC; ++l) den[l] = 0.f;
+        for (int l = 0; l < KC; ++l) stage[(part * KC + l) * kNmfOwn + lane] = acc[l];
+        __syncthreads();
+        if (live) {
+            // this lane finishes the ranks part, part + 4, ... of its column: numerator in wavefront order, denominator
+            // from the Gram rows and the column of the old M_z
+            float den[KC / kNmfParts];
+#pragma unroll
+            for (int q = 0; q < KC / kNmfParts; ++q) den[q] = 0.f;
             for (int b = 0; b < k; ++b) {
                 const float z = mzc[(int64_t)b * g.c + j];
 #pragma unroll
-                for (int l = 0; l < KC; ++l)
-                    if (l0 + l < k) den[l] = fmaf(gram[(l0 + l) * k + b], z, den[l]);
+                for (int q = 0; q < KC / kNmfParts; ++q) {
+                    const int l = part + kNmfParts * q;
+                    if (l < kt) den[q] = fmaf(gramL[l * k + b], z, den[q]);
+                }
             }
 #pragma unroll
-            for (int l = 0; l < KC; ++l)
-                if (l0 + l < k) {
+            for (int q = 0; q < KC / kNmfParts; ++q) {
+                const int l = part + kNmfParts * q;
+                if (l < kt) {
+                    float num = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kNmfParts; ++w) num += stage[(w * KC + l) * kNmfOwn + lane];
                     const int64_t at = (int64_t)(l0 + l) * g.c + j;
-                    mzn[at] = mzc[at] * acc[l] / (den[l] + eps);
+                    mzn[at] = mzc[at] * num / (den[q] + eps);
                 }
+            }
         }
     }
 }
 
-// M_p update.  Workgroup = (tile, block of 256 rows); lane = row.
-template <typename T, int KC>
+// M_p update.  Workgroup = (tile, block of 256 / PARTS rows); lane = row, group of lanes = part of the columns.
+template <typename T, int KC, int PARTS>
 __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const T *__restrict__ W, int64_t ldw, int method,
                                                                   float w_threshold, float amplify,
                                                                   const float *__restrict__ MpCur,
                                                                   const float *__restrict__ Mz,
-                                                                  float *__restrict__ MpNew, float eps, int rblocks,
-                                                                  int w_vec_ok)
+                                                                  float *__restrict__ MpNew, const float *__restrict__ G,
+                                                                  float eps, int rblocks, int w_vec_ok)
 {
-    __align__(16) static __shared__ float stage[kNmfStageFloats];       // [columns of the chunk][k]: M_z transposed
-    __align__(16) static __shared__ float gram[kNmfMaxK * kNmfMaxK];    // M_z M_z^T
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    float *stage = (float *)lrbi_dyn_smem;   // [columns of the chunk][k]: M_z transposed; then the partial sums
+    float *gramL = stage + kNmfStageFloats;  // the pass's rows of M_z M_z^T (symmetric): [KC][k]
+    constexpr int kNmfParts = PARTS, kNmfOwn = kNmfThreads / PARTS;
     const int64_t t = blockIdx.x / rblocks;
     const int rb = (int)(blockIdx.x - t * rblocks);
     int ti, tj, rt, ct;
     nmf_tile_extent(g, t, ti, tj, rt, ct);
     const int tid = threadIdx.x;
-    const int i = rb * kNmfThreads + tid;
+    const int lane = tid & (kNmfOwn - 1), part = tid / kNmfOwn;
+    const int i = rb * kNmfOwn + lane;
     const bool live = i < rt;
     const int k = g.k;
     const bool k4 = (k % 4) == 0;
-    const int cols_per_chunk = (kNmfStageFloats / k) & ~7; // a multiple of 8 keeps later chunks aligned
+    const int cols_per_chunk = (kNmfStageFloats / k) & ~31; // a multiple of 32: every part is a multiple of 8 columns
     const float *mz = Mz + t * (int64_t)k * g.c;
     const float *mpc = MpCur + (t * (int64_t)g.r + (live ? i : 0)) * k;
     float *mpn = MpNew + (t * (int64_t)g.r + (live ? i : 0)) * k;
+    const float *gt = G + t * (int64_t)k * k;
     const T *wrow = W + ((int64_t)ti * g.r + (live ? i : 0)) * ldw + (int64_t)tj * g.c;
-
-    for (int e = tid; e < k * k; e += kNmfThreads) gram[e] = 0.f;
 
     for (int l0 = 0; l0 < k; l0 += KC) {
         const bool full = l0 + KC <= k;             // every rank of this pass exists
@@ -207,6 +268,8 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
         float acc[KC];
 #pragma unroll
         for (int l = 0; l < KC; ++l) acc[l] = 0.f;
+        __syncthreads();
+        for (int e = tid; e < kt * k; e += kNmfThreads) gramL[e] = gt[(int64_t)l0 * k + e];
         for (int j0 = 0; j0 < ct; j0 += cols_per_chunk) {
             const int cols = (ct - j0 < cols_per_chunk) ? ct - j0 : cols_per_chunk;
             __syncthreads();
@@ -216,37 +279,16 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
                 stage[jj * k + l] = mz[(int64_t)l * g.c + j0 + jj];
             }
             __syncthreads();
-            if (l0 == 0) {
-                if (k4) {
-                    for (int e4 = tid; e4 < k * k / 4; e4 += kNmfThreads) {
-                        const int a = e4 / (k / 4), b = (e4 - a * (k / 4)) * 4;
-                        float4 s = *reinterpret_cast<const float4 *>(gram + a * k + b);
-                        for (int jj = 0; jj < cols; ++jj) {
-                            const float za = stage[jj * k + a];
-                            const float4 zb = *reinterpret_cast<const float4 *>(stage + jj * k + b);
-                            s.x = fmaf(za, zb.x, s.x);
-                            s.y = fmaf(za, zb.y, s.y);
-                            s.z = fmaf(za, zb.z, s.z);
-                            s.w = fmaf(za, zb.w, s.w);
-                        }
-                        *reinterpret_cast<float4 *>(gram + a * k + b) = s;
-                    }
-                } else {
-                    for (int e = tid; e < k * k; e += kNmfThreads) {
-                        const int a = e / k, b = e - a * k;
-                        float s = gram[e];
-                        for (int jj = 0; jj < cols; ++jj) s = fmaf(stage[jj * k + a], stage[jj * k + b], s);
-                        gram[e] = s;
-                    }
-                }
-            }
+            // this wavefront's columns of the chunk, a multiple of 8 so that the 16-byte loads of W stay aligned
+            const int per = ((cols + kNmfParts - 1) / kNmfParts + 7) & ~7;
+            const int jbeg = (part * per < cols) ? part * per : cols, jend = (jbeg + per < cols) ? jbeg + per : cols;
             if (live) {
                 // eight columns at a time: one 16-byte load of the lane's row of W where the alignment allows it
                 constexpr int VEC = 16 / (int)sizeof(T);
                 const bool vec = w_vec_ok && (((int64_t)tj * g.c + j0) % VEC == 0);
-                for (int jj = 0; jj < cols; jj += 8) {
+                for (int jj = jbeg; jj < jend; jj += 8) {
                     float mv[8];
-                    if (vec && jj + 8 <= cols) {
+                    if (vec && jj + 8 <= jend) {
                         T tmp[8];
 #pragma unroll
                         for (int q = 0; q < 8 / VEC; ++q)
@@ -257,18 +299,18 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
                         T raw[8];
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {
-                            const int ju = (jj + u < cols) ? jj + u : cols - 1;
+                            const int ju = (jj + u < jend) ? jj + u : jend - 1;
                             raw[u] = wrow[j0 + ju];
                         }
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {
                             const float m = nmf_mag<T>(raw[u], method, w_threshold, amplify);
-                            mv[u] = (jj + u < cols) ? m : 0.f;
+                            mv[u] = (jj + u < jend) ? m : 0.f;
                         }
                     }
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
-                        const int ju = (jj + u < cols) ? jj + u : cols - 1;
+                        const int ju = (jj + u < jend) ? jj + u : jend - 1;
                         const float *col = stage + ju * k + l0;
                         if (full && k4) { // rows of the staged chunk are 16-byte aligned: four ranks per LDS read
 #pragma unroll
@@ -288,19 +330,31 @@ __global__ __launch_bounds__(kNmfThreads) void nmf_update_p_kernel(Geom g, const
             }
         }
         __syncthreads();
+#pragma unroll
+        for (int l = 0; l < KC; ++l) stage[(part * KC + l) * kNmfOwn + lane] = acc[l];
+        __syncthreads();
         if (live) {
-            float den[KC];
+            float den[KC / kNmfParts];
 #pragma unroll
-            for (int l = 0; l < KC; ++l) den[l] = 0.f;
+            for (int q = 0; q < KC / kNmfParts; ++q) den[q] = 0.f;
             for (int b = 0; b < k; ++b) {
-                const float p = mpc[b];
+                const float pv = mpc[b];
 #pragma unroll
-                for (int l = 0; l < KC; ++l)
-                    if (l0 + l < k) den[l] = fmaf(p, gram[b * k + l0 + l], den[l]);
+                for (int q = 0; q < KC / kNmfParts; ++q) {
+                    const int l = part + kNmfParts * q;
+                    if (l < kt) den[q] = fmaf(pv, gramL[l * k + b], den[q]);
+                }
             }
 #pragma unroll
-            for (int l = 0; l < KC; ++l)
-                if (l0 + l < k) mpn[l0 + l] = mpc[l0 + l] * acc[l] / (den[l] + eps);
+            for (int q = 0; q < KC / kNmfParts; ++q) {
+                const int l = part + kNmfParts * q;
+                if (l < kt) {
+                    float num = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kNmfParts; ++w) num += stage[(w * KC + l) * kNmfOwn + lane];
+                    mpn[l0 + l] = mpc[l0 + l] * num / (den[q] + eps);
+                }
+            }
         }
     }
 }
@@ -318,20 +372,30 @@ static int nmf_copy(const float *src, float *dst, int64_t count, hipStream_t str
     return LRBI_OK;
 }
 
-template <typename T, int KC>
+template <typename T, int KC, int PARTS>
 static int nmf_iterate(const Geom &g, const void *dW, int64_t ldw, int method, float w_threshold, float amplify, float *dMp,
-                       float *dMz, int iters, float eps, float *wsMp, float *wsMz, hipStream_t stream)
+                       float *dMz, int iters, float eps, float *wsMp, float *wsMz, float *wsG, hipStream_t stream)
 {
+    constexpr int kNmfOwn = kNmfThreads / PARTS;
     const int64_t tiles = (int64_t)g.tile_rows * g.tile_cols;
-    const int cblocks = (g.c + kNmfThreads - 1) / kNmfThreads, rblocks = (g.r + kNmfThreads - 1) / kNmfThreads;
-    if (tiles * cblocks > 0x7FFFFFFF || tiles * rblocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
+    const int cblocks = (g.c + kNmfOwn - 1) / kNmfOwn, rblocks = (g.r + kNmfOwn - 1) / kNmfOwn;
+    const int eunits = (g.k % 4 == 0) ? g.k * g.k / 4 : g.k * g.k; // a lane owns four entries of the Gram matrix, or one
+    const int eblocks = (eunits + kNmfThreads - 1) / kNmfThreads;
+    if (tiles * cblocks > 0x7FFFFFFF || tiles * rblocks > 0x7FFFFFFF || tiles * eblocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
+    const size_t lds = ((size_t)kNmfStageFloats + (size_t)KC * g.k) * 4; // staging area + the pass's Gram rows
+    LRBI_SET_MAX_LDS((nmf_update_z_kernel<T, KC, PARTS>), lds);
+    LRBI_SET_MAX_LDS((nmf_update_p_kernel<T, KC, PARTS>), lds);
     float *mp_cur = dMp, *mp_new = wsMp, *mz_cur = dMz, *mz_new = wsMz;
     const int w_vec_ok = (((uintptr_t)dW & 15) == 0) && ((ldw * (int64_t)sizeof(T)) % 16 == 0);
     for (int it = 0; it < iters; ++it) {
-        LRBI_LAUNCH((nmf_update_z_kernel<T, KC>), dim3((unsigned)(tiles * cblocks)), dim3(kNmfThreads), 0, stream, g,
-                           (const T *)dW, ldw, method, w_threshold, amplify, mp_cur, mz_cur, mz_new, eps, cblocks);
-        LRBI_LAUNCH((nmf_update_p_kernel<T, KC>), dim3((unsigned)(tiles * rblocks)), dim3(kNmfThreads), 0, stream, g,
-                           (const T *)dW, ldw, method, w_threshold, amplify, mp_cur, mz_new, mp_new, eps, rblocks, w_vec_ok);
+        LRBI_LAUNCH((nmf_gram_kernel<false>), dim3((unsigned)(tiles * eblocks)), dim3(kNmfThreads), 0, stream, g, mp_cur, wsG,
+                    eblocks);
+        LRBI_LAUNCH((nmf_update_z_kernel<T, KC, PARTS>), dim3((unsigned)(tiles * cblocks)), dim3(kNmfThreads), lds, stream, g,
+                           (const T *)dW, ldw, method, w_threshold, amplify, mp_cur, mz_cur, mz_new, wsG, eps, cblocks);
+        LRBI_LAUNCH((nmf_gram_kernel<true>), dim3((unsigned)(tiles * eblocks)), dim3(kNmfThreads), 0, stream, g, mz_new, wsG,
+                    eblocks);
+        LRBI_LAUNCH((nmf_update_p_kernel<T, KC, PARTS>), dim3((unsigned)(tiles * rblocks)), dim3(kNmfThreads), lds, stream, g,
+                           (const T *)dW, ldw, method, w_threshold, amplify, mp_cur, mz_new, mp_new, wsG, eps, rblocks, w_vec_ok);
         float *tmp = mp_cur;
         mp_cur = mp_new;
         mp_new = tmp;
@@ -350,12 +414,17 @@ static int nmf_iterate(const Geom &g, const void *dW, int64_t ldw, int method, f
 
 template <typename T>
 static int nmf_dtype(const Geom &g, const void *dW, int64_t ldw, int method, float w_threshold, float amplify, float *dMp,
-                     float *dMz, int iters, float eps, float *wsMp, float *wsMz, hipStream_t stream)
+                     float *dMz, int iters, float eps, float *wsMp, float *wsMz, float *wsG, hipStream_t stream)
 {
-    // ranks held in registers per pass: the smallest of 8 / 16 / 32 that covers k (two passes for 32 < k <= 64)
-    if (g.k <= 8) return nmf_iterate<T, 8>(g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, stream);
-    if (g.k <= 16) return nmf_iterate<T, 16>(g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, stream);
-    return nmf_iterate<T, 32>(g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, stream);
+    // ranks held in registers per pass: the smallest of 8 / 16 / 32 that covers k (several passes above 32); tiles are
+    // split four ways more finely when whole-tile column blocks would leave compute units idle
+    const int64_t coarse = (int64_t)g.tile_rows * g.tile_cols * ((((g.c < g.r) ? g.c : g.r) + kNmfThreads - 1) / kNmfThreads);
+    const bool fine = coarse < 2 * (int64_t)compute_units_of(stream);
+#define LRBI_NMF_ARGS g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, wsG, stream
+    if (g.k <= 8) return fine ? nmf_iterate<T, 8, 4>(LRBI_NMF_ARGS) : nmf_iterate<T, 8, 1>(LRBI_NMF_ARGS);
+    if (g.k <= 16) return fine ? nmf_iterate<T, 16, 4>(LRBI_NMF_ARGS) : nmf_iterate<T, 16, 1>(LRBI_NMF_ARGS);
+    return fine ? nmf_iterate<T, 32, 4>(LRBI_NMF_ARGS) : nmf_iterate<T, 32, 1>(LRBI_NMF_ARGS);
+#undef LRBI_NMF_ARGS
 }
 
 uint64_t nmf_workspace_bytes(const Geom &g)
@@ -363,7 +432,8 @@ uint64_t nmf_workspace_bytes(const Geom &g)
     const uint64_t tiles = (uint64_t)g.tile_rows * g.tile_cols;
     const uint64_t mp = (tiles * g.r * g.k * 4 + 255) / 256 * 256;
     const uint64_t mz = (tiles * g.k * g.c * 4 + 255) / 256 * 256;
-    return mp + mz;
+    const uint64_t gram = (tiles * g.k * g.k * 4 + 255) / 256 * 256;
+    return mp + mz + gram;
 }
 
 int launch_nmf(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, int method, float w_threshold, float amplify,
@@ -373,16 +443,17 @@ int launch_nmf(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, int me
     const uint64_t tiles = (uint64_t)g.tile_rows * g.tile_cols;
     float *wsMp = (float *)dWorkspace;
     float *wsMz = (float *)((char *)dWorkspace + (tiles * g.r * g.k * 4 + 255) / 256 * 256);
+    float *wsG = (float *)((char *)wsMz + (tiles * g.k * g.c * 4 + 255) / 256 * 256);
     // the second buffers start as copies, so that what a cut-off tile does not use is the same in both
     int rc = nmf_copy(dMp, wsMp, (int64_t)(tiles * g.r * g.k), stream);
     if (rc != LRBI_OK) return rc;
     rc = nmf_copy(dMz, wsMz, (int64_t)(tiles * g.k * g.c), stream);
     if (rc != LRBI_OK) return rc;
     switch (dt) {
-    case LRBI_F32: return nmf_dtype<float>(g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, stream);
-    case LRBI_F16: return nmf_dtype<__half>(g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, stream);
+    case LRBI_F32: return nmf_dtype<float>(g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, wsG, stream);
+    case LRBI_F16: return nmf_dtype<__half>(g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, wsG, stream);
     case LRBI_BF16:
-        return nmf_dtype<__hip_bfloat16>(g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, stream);
+        return nmf_dtype<__hip_bfloat16>(g, dW, ldw, method, w_threshold, amplify, dMp, dMz, iters, eps, wsMp, wsMz, wsG, stream);
     default: return LRBI_ERR_DTYPE;
     }
 }

@@ -313,7 +313,7 @@ def test_nmf_rejects_bad_arguments_before_any_launch():
     assert f(*args(Mp=None)) == -1
     assert f(*args(ws=None)) == -1
     assert f(*args(dt=9)) == -4
-    assert f(*args(d=lrbi.Desc(8, 128, 4, 64, 65))) == -3           # ranks above 64 are not served
+    assert f(*args(d=lrbi.Desc(8, 128, 4, 64, 257))) == -3          # ranks above LRBI_MAX_RANK
     assert f(*args(method=0)) == -2
     assert f(*args(method=4)) == -2
     assert f(*args(iters=-1)) == -2
@@ -321,5 +321,5 @@ def test_nmf_rejects_bad_arguments_before_any_launch():
     assert f(*args(ldw=100)) == -5
     assert f(*args(Mp=ctypes.c_void_p(base + 2))) == -6
     assert f(*args(wsb=8)) == -8
-    # a second copy of both factors
-    assert lrbi.nmf_workspace_bytes(lrbi.Desc(4096, 9216, 256, 256, 16)) == 2 * 576 * 256 * 16 * 4
+    # a second copy of both factors and a k x k matrix per tile
+    assert lrbi.nmf_workspace_bytes(lrbi.Desc(4096, 9216, 256, 256, 16)) == 2 * 576 * 256 * 16 * 4 + 576 * 16 * 16 * 4
