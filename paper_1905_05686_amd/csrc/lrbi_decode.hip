@@ -674,6 +674,10 @@ static bool plan_nibble(const Geom &g, NibblePlan &p, int64_t pitch_bytes, const
     const int cap_rows = kNibMaxIpPerLane * kStreamThreads / (g.ipw * p.span_tiles);
     if (p.rows_per_band > cap_rows) p.rows_per_band = cap_rows;
     if (p.rows_per_band < 1) return false;
+    // small masks: shorter bands until every compute unit has a couple of items
+    while (p.rows_per_band > 32 &&
+           (int64_t)p.spans * g.tile_rows * ((g.r + p.rows_per_band - 1) / p.rows_per_band) < 2 * (int64_t)cus)
+        p.rows_per_band = (p.rows_per_band + 1) / 2;
     // a lane finds its I_p words by shifting a linear index: bands padded to a power of two must fit the lanes' slots
     p.ip_sh = 0;
     while ((1 << p.ip_sh) < p.rows_per_band * g.ipw) ++p.ip_sh;
@@ -684,7 +688,7 @@ static bool plan_nibble(const Geom &g, NibblePlan &p, int64_t pitch_bytes, const
     if (p.rows_per_band < 16 && p.rows_per_band < g.r) return false;
     p.bands_per_tile_row = (g.r + p.rows_per_band - 1) / p.rows_per_band;
     p.items = (int64_t)p.spans * g.tile_rows * p.bands_per_tile_row;
-    if (p.items < 4 * (int64_t)cus || p.items > 0x7FFFFFFF) return false;
+    if (p.items < (int64_t)cus || p.items > 0x7FFFFFFF) return false;
     p.iz16 = (((uintptr_t)dIz & 15) == 0) ? 1 : 0;
     p.pitch16 = pitch_bytes / 16;
     p.t_pieces = p.span_tiles * (per_tile_pieces + kNibTileSkew);
