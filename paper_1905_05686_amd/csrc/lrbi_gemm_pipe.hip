@@ -329,7 +329,11 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
         LRBI_SB();                                                 \
     } while (0)
 
-    // ---- prologue: slabs 0 .. NS - 2 on their way, mask of panel 0
+    // ---- prologue: the factor slices of panel 0 first, then slabs 0 .. NS - 2; the panel is decoded as soon as the
+    // factor slices are in (the slabs issued behind them stay in flight), and slab 0 is waited for after that
+    if (tid < PANEL_WORDS) Fz[FAST_MAX_K * PANEL_WORDS + tid] = 0u;
+    load_factors();
+    constexpr int kProloguePieces = SPREAD ? (NS - 2) * 4 + 2 : (NS - 1) * 4; // slab copies of this wavefront behind them
     static_for<NS - 1>([&](auto sc) {
         constexpr int st = decltype(sc)::value;
         const int sl0 = st < last ? st : last;
@@ -340,11 +344,10 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
             issue_piece(sl0, st, I3{});
         }
     });
-    if (tid < PANEL_WORDS) Fz[FAST_MAX_K * PANEL_WORDS + tid] = 0u;
-    load_factors();
-    wait_loads<0>();
+    wait_loads<kProloguePieces>();
     __syncthreads();
     decode_panel(0);
+    wait_loads<kProloguePieces - 4>(); // slab 0
     __syncthreads();
     // entry state of the loop: X operands of this wavefront's first step, its W operand masked, the second read
     uint32_t mcur = my_bytes(fetch_mask(0));

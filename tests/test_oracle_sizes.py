@@ -56,6 +56,17 @@ def test_csr_bits_builder_formula():
     assert orc.popcount(M) == 4 and orc.density(M) == 0.25
 
 
+def test_csr_bits_counts_the_arrays_of_a_library_csr_matrix():
+    # the accounting (one column index per kept weight, m + 1 row pointers) against the arrays scipy actually builds
+    import scipy.sparse
+    rng = np.random.default_rng(3)
+    for (m, n, p) in [(7, 5, 0.3), (50, 80, 0.05), (1, 9, 1.0), (12, 12, 0.0)]:
+        dense = (rng.random((m, n)) < p).astype(np.float32)
+        csr = scipy.sparse.csr_matrix(dense)
+        for idx_bits, ptr_bits in [(16, 32), (8, 16)]:
+            assert orc.csr_bits(int(csr.nnz), m, idx_bits, ptr_bits) == csr.indices.size * idx_bits + csr.indptr.size * ptr_bits
+
+
 def test_invalid_shapes():
     with pytest.raises(ValueError):
         orc.index_bits(10, 10, 0, 5, 2)
