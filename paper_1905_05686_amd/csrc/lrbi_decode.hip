@@ -674,9 +674,9 @@ static bool plan_nibble(const Geom &g, NibblePlan &p, int64_t pitch_bytes, const
     const int cap_rows = kNibMaxIpPerLane * kStreamThreads / (g.ipw * p.span_tiles);
     if (p.rows_per_band > cap_rows) p.rows_per_band = cap_rows;
     if (p.rows_per_band < 1) return false;
-    // small masks: shorter bands until every compute unit has a couple of items
+    // small masks: shorter bands until every compute unit has an item
     while (p.rows_per_band > 32 &&
-           (int64_t)p.spans * g.tile_rows * ((g.r + p.rows_per_band - 1) / p.rows_per_band) < 2 * (int64_t)cus)
+           (int64_t)p.spans * g.tile_rows * ((g.r + p.rows_per_band - 1) / p.rows_per_band) < (int64_t)cus)
         p.rows_per_band = (p.rows_per_band + 1) / 2;
     // a lane finds its I_p words by shifting a linear index: bands padded to a power of two must fit the lanes' slots
     p.ip_sh = 0;

@@ -100,7 +100,8 @@ struct StreamArgs {
     uint32_t x_pieces; // 16-byte pieces of X in all
     int blocks_per_tile_row; // workgroups per tile row (BM rows each, the last one may be short)
     int fz_words;  // packed I_z words of one tile row
-    int fz_pad;    // the same rounded up to whole copy instructions (64 words)
+    int fz_pad;    // the same rounded up to whole copy instructions (64 words, or 64 16-byte pieces)
+    int fz_vec;    // the tile rows' slices of I_z are 16-byte aligned whole numbers of 16-byte pieces
     int fp_pitch;  // LDS words per tile for the I_p words of 16 rows: 16 * ipw rounded up to whole copy instructions
     int ms_pitch;  // mask words per row in LDS (odd, at least 8 per slab)
 };
@@ -161,18 +162,30 @@ __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamA
     };
 
     // ---- the mask of the workgroup's rows ----
-    auto stage_factors = [&]() { // linear copies, 4 bytes per lane
+    // Linear copies, spread evenly over the wavefronts (a wavefront's copies complete in order and only a few of
+    // them overlap, so the wavefront with the most of them sets the time): I_z in 16-byte pieces when its slices
+    // allow, else word by word; the I_p words of tile tj by wavefront tj % 8.
+    auto stage_factors = [&]() {
         const uint32_t *zsrc = a.Iz + (int64_t)ti * g.tile_cols * g.k * (int64_t)g.izw;
-        for (int w0 = wave * 64; w0 < a.fz_words; w0 += ST_THREADS) {
-            int w = w0 + lane;
-            if (w >= a.fz_words) w = a.fz_words - 1; // the copy instruction's slots past the end are part of the pad
-            load_to_lds4(lds_address(Fz + w0), zsrc, 4u * (uint32_t)w);
+        if (a.fz_vec) {
+            const int pieces = a.fz_words >> 2;
+            for (int p0 = wave * 64; p0 < pieces; p0 += ST_THREADS) {
+                int p = p0 + lane;
+                if (p >= pieces) p = pieces - 1; // the copy instruction's slots past the end are part of the pad
+                load_to_lds16(lds_address(Fz + 4 * p0), zsrc, 16u * (uint32_t)p);
+            }
+        } else {
+            for (int w0 = wave * 64; w0 < a.fz_words; w0 += ST_THREADS) {
+                int w = w0 + lane;
+                if (w >= a.fz_words) w = a.fz_words - 1;
+                load_to_lds4(lds_address(Fz + w0), zsrc, 4u * (uint32_t)w);
+            }
         }
         // per tile, the I_p rows il0 .. il0 + rows_here - 1 (slots past them are filled with the last row, never used)
         const int live = rows_here * g.ipw;
-        for (int tj = 0; tj < g.tile_cols; ++tj) {
+        for (int tj = wave; tj < g.tile_cols; tj += ST_WAVES) {
             const uint32_t *psrc = a.Ip + (((int64_t)ti * g.tile_cols + tj) * g.r + il0) * g.ipw;
-            for (int e0 = wave * 64; e0 < a.fp_pitch; e0 += ST_THREADS) {
+            for (int e0 = 0; e0 < a.fp_pitch; e0 += 64) {
                 int e = e0 + lane;
                 if (e >= live) e = live - 1;
                 load_to_lds4(lds_address(Fp + tj * a.fp_pitch + e0), psrc, 4u * (uint32_t)e);
@@ -260,10 +273,15 @@ __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamA
 
     // The factor copies go first and are waited for by count: the slab copies issued after them stay in flight.
     stage_factors();
-    for (int s = 0; s < NS - 1; ++s) copy_slab(s); // slabs past the end copy clamped addresses: same count
+    // Only the first two slabs are asked for behind the factor copies, the rest of the ring once the factors are in:
+    // a compute unit serves its requests in order, and a second workgroup's factor copies would otherwise queue
+    // behind the first one's whole ring.  (Slabs past the end copy clamped addresses: same count.)
+    constexpr int EARLY = NS - 1 < 2 ? NS - 1 : 2;
+    for (int s = 0; s < EARLY; ++s) copy_slab(s);
     for (int i = tid; i < BM * a.ms_pitch; i += ST_THREADS) Ms[i] = 0u;
-    wait_loads_at_most((NS - 1) * my_per_slab);
+    wait_loads_at_most(EARLY * my_per_slab);
     LRBI_BARRIER();
+    for (int s = EARLY; s < NS - 1; ++s) copy_slab(s);
     decode_rows();
     for (int s = 0; s < nslabs; ++s) {
         wait_loads_at_most((NS - 2) * my_per_slab); // my share of slab s is in; slabs s + 1 .. s + NS - 2 may be on their way
@@ -321,7 +339,7 @@ static bool plan_stream(const Geom &g, int64_t N, int cus, StreamPlan &p)
     const int64_t fz_words = (int64_t)g.tile_cols * g.k * g.izw;
     if (fz_words * 4 > ST_FZ_MAX_BYTES) return false;
     a.fz_words = (int)fz_words;
-    a.fz_pad = (a.fz_words + 63) / 64 * 64;
+    a.fz_pad = (a.fz_words + 255) / 256 * 256; // whole copy instructions of either width
     a.fp_pitch = (ST_FP_ROWS * g.ipw + 63) / 64 * 64;
     const int nslabs = (int)((g.n + p.ks - 1) / p.ks);
     a.ms_pitch = nslabs * (p.ks / 32) + 1;
@@ -396,6 +414,7 @@ int launch_stream_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw
     a.ldy = ldy;
     a.P = dP;
     a.ldp = ldp;
+    a.fz_vec = ((((uintptr_t)dIz) & 15) == 0 && (a.fz_words & 3) == 0) ? 1 : 0;
     if (dt == LRBI_F16) return launch_stream_shape<F16Tag>(g, p, stream);
     if (dt == LRBI_BF16) return launch_stream_shape<BF16Tag>(g, p, stream);
     return LRBI_ERR_DTYPE;
