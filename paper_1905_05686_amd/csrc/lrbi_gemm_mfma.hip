@@ -292,8 +292,24 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     const int64_t row = e / groups_per_row;
     const int col = (int)(e - row * groups_per_row) * 4;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int k = 0; k < splitk; ++k) {
-        const float4 p = *reinterpret_cast<const float4 *>(P + ((int64_t)k * m + row) * ldp + col);
+    const float *src = P + row * ldp + col;
+    const int64_t plane = m * ldp;
+    int k = 0;
+    // eight slices at a time: their loads are in flight together, the additions stay in slice order
+    for (; k + 8 <= splitk; k += 8) {
+        float4 p[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) p[q] = *reinterpret_cast<const float4 *>(src + (int64_t)(k + q) * plane);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            s.x += p[q].x;
+            s.y += p[q].y;
+            s.z += p[q].z;
+            s.w += p[q].w;
+        }
+    }
+    for (; k < splitk; ++k) {
+        const float4 p = *reinterpret_cast<const float4 *>(src + (int64_t)k * plane);
         s.x += p.x;
         s.y += p.y;
         s.z += p.z;
