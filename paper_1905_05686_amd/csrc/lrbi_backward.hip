@@ -500,24 +500,15 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
         }
         return v;
     };
-    // VEC: uniform base per slab + constant per-lane byte offsets (below 2^31: 128 rows of at most 2^22 elements),
+    // VEC: uniform base per slab + per-lane byte offsets (below 2^31: 128 rows of at most 2^22 elements) that are
+    // recomputed per load from the lane's first row (registers are what limits the workgroups per compute unit),
     // every load unconditional: a lane whose row or batch column lies outside reads a valid stand-in (its row clamped
     // to the last one, batch column 0 of the slab) and the piece is cleared when it is staged
-    uint32_t aoff[CHUNKS], aoff0[CHUNKS], boff[CHUNKS], boff0[CHUNKS];
-    bool arow_ok[CHUNKS], brow_ok[CHUNKS];
-#pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) {
-        const int id = tid + kBwdThreads * c;
-        const int row = id >> 3, kc = id & 7;
-        arow_ok[c] = i0 + row < g.m;
-        brow_ok[c] = (int64_t)j0 + row < g.n;
-        const int64_t ar = arow_ok[c] ? row : g.m - 1 - i0;
-        const int64_t br = brow_ok[c] ? row : g.n - 1 - j0;
-        aoff0[c] = (uint32_t)(ar * lddy * 2);
-        boff0[c] = (uint32_t)(br * ldx * 2);
-        aoff[c] = aoff0[c] + (uint32_t)(kc * 16);
-        boff[c] = boff0[c] + (uint32_t)(kc * 16);
-    }
+    const int row0 = tid >> 3;             // chunk c of this lane: row row0 + 32 c, 16-byte piece tid % 8
+    const uint32_t kc16 = (uint32_t)((tid & 7) * 16);
+    const int a_last = (int)((g.m - 1 - i0 < BI - 1) ? g.m - 1 - i0 : BI - 1); // last row of the block inside the matrix
+    const int b_last = (int)((g.n - 1 - j0 < BJ - 1) ? g.n - 1 - j0 : BJ - 1);
+    const uint32_t lda2 = (uint32_t)(lddy * 2), ldb2 = (uint32_t)(ldx * 2);
     const char *abase0 = (const char *)(DY + i0 * lddy);
     const char *bbase0 = (const char *)(X + (int64_t)j0 * ldx);
     int cols_left = 0; // batch columns from the first one of the slab whose pieces sit in areg / breg
@@ -526,12 +517,13 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
         if (VEC) {
             const char *abase = abase0 + (int64_t)k0 * 2;
             const char *bbase = bbase0 + (int64_t)k0 * 2;
+            const uint32_t off = ((tid & 7) * 8 < N - k0) ? kc16 : 0u; // N % 8 == 0
 #pragma unroll
             for (int c = 0; c < CHUNKS; ++c) {
-                const int kc = (tid + kBwdThreads * c) & 7;
-                const bool col_ok = kc * 8 < N - k0; // N % 8 == 0
-                areg[c] = *reinterpret_cast<const uint4 *>(abase + (col_ok ? aoff[c] : aoff0[c]));
-                breg[c] = *reinterpret_cast<const uint4 *>(bbase + (col_ok ? boff[c] : boff0[c]));
+                const int row = row0 + 32 * c;
+                const uint32_t ar = (uint32_t)(row < a_last ? row : a_last), br = (uint32_t)(row < b_last ? row : b_last);
+                areg[c] = *reinterpret_cast<const uint4 *>(abase + (ar * lda2 + off));
+                breg[c] = *reinterpret_cast<const uint4 *>(bbase + (br * ldb2 + off));
             }
         } else {
 #pragma unroll
@@ -554,8 +546,8 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
             uint4 av = areg[c], bv = breg[c];
             if (VEC) {
                 const bool col_ok = kc * 8 < cols_left;
-                if (!(arow_ok[c] && col_ok)) av = make_uint4(0u, 0u, 0u, 0u);
-                if (!(brow_ok[c] && col_ok)) bv = make_uint4(0u, 0u, 0u, 0u);
+                if (!(row <= a_last && col_ok)) av = make_uint4(0u, 0u, 0u, 0u);
+                if (!(row <= b_last && col_ok)) bv = make_uint4(0u, 0u, 0u, 0u);
             }
             *reinterpret_cast<uint4 *>(as + row * OP_STRIDE + kc * 8) = av;
             *reinterpret_cast<uint4 *>(bs + row * OP_STRIDE + kc * 8) = bv;
@@ -571,23 +563,62 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
     load_slab(0); // requested first: the factor loads below queue up behind it
-    // mask words of the tile: 128 rows x 4 words, two per lane; needed only in the epilogue
-#pragma unroll
-    for (int c = 0; c < S::ms_words / kBwdThreads; ++c) {
+    // Mask words of the tile: 128 rows x 4 words, two per lane; needed only in the epilogue.
+    // Tile shapes that line up with the block (it lies inside one tile, ranks up to 64): the block's slices of the
+    // factors -- k rows x 4 words of I_z, 128 rows x ipw words of I_p -- are fetched with one independent load per
+    // lane and parked in the mask array's own space; after the barrier below every lane forms its two mask words from
+    // there (Eq. 3) into registers, and stores them behind the slab loop's first barrier, when nobody reads the
+    // parked factors any more.  Other shapes: word by word from global memory (a chain of dependent loads).
+    static_assert(S::ms_words == 2 * kBwdThreads && FAST_MAX_K * 4 <= kBwdThreads && BI * 2 <= kBwdThreads,
+                  "factor slices fit the mask array, one load per lane and factor");
+    const bool lined_up = (g.c % BJ) == 0 && (g.r % BI) == 0 && g.k <= FAST_MAX_K && !g.ragged;
+    if (lined_up) {
+        const int ti = (int)(i0 / g.r), tj = j0 / g.c;
+        const int il0 = (int)(i0 - (int64_t)ti * g.r), coff = j0 - tj * g.c;
+        const int64_t t = (int64_t)ti * g.tile_cols + tj;
+        uint32_t fzv = 0u, fpv = 0u;
+        if (tid < g.k * 4) fzv = Iz[(t * g.k + (tid >> 2)) * g.izw + (coff >> 5) + (tid & 3)];
+        if (tid < BI * g.ipw) fpv = Ip[(t * g.r + il0) * g.ipw + tid];
+        Ms[tid] = fzv;               // [k][4]
+        Ms[kBwdThreads + tid] = fpv; // [128][ipw]
+    }
+    // this lane's two mask words
+    auto mask_word = [&](int c) -> uint32_t {
         const int idx = tid + kBwdThreads * c;
-        const int64_t gi = i0 + (idx >> 2);
         uint32_t word = 0u;
-        if (gi < g.m) {
-            const int ti = (int)(gi / g.r);
-            const int il = (int)(gi - (int64_t)ti * g.r);
-            word = decode_word(g, Ip, Iz, ti, il, (j0 >> 5) + (idx & 3));
+        if (lined_up) {
+            const int row = idx >> 2, w = idx & 3;
+            for (int iw = 0; iw < g.ipw; ++iw) {
+                uint32_t sel = Ms[kBwdThreads + row * g.ipw + iw];
+                while (sel) {
+                    const int l = __builtin_ctz(sel) + 32 * iw;
+                    sel &= sel - 1u;
+                    word |= Ms[l * 4 + w];
+                }
+            }
+        } else {
+            const int64_t gi = i0 + (idx >> 2);
+            if (gi < g.m) {
+                const int ti = (int)(gi / g.r);
+                const int il = (int)(gi - (int64_t)ti * g.r);
+                word = decode_word(g, Ip, Iz, ti, il, (j0 >> 5) + (idx & 3));
+            }
         }
-        Ms[idx] = word;
+        return word;
+    };
+    uint32_t mw0 = 0u, mw1 = 0u;
+    if (!lined_up) { // from global memory: asked for before the wait for the operands
+        mw0 = mask_word(0);
+        mw1 = mask_word(1);
     }
 
     stage_slab();
     if (nslabs > 1) load_slab(1);
     __syncthreads();
+    if (lined_up) { // from the parked factors, visible now
+        mw0 = mask_word(0);
+        mw1 = mask_word(1);
+    }
 
     for (int s = 0; s < nslabs; ++s) {
         const uint16_t *as = As + (wi * WI + l32) * OP_STRIDE + 8 * lg;
@@ -605,6 +636,10 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
                 for (int b = 0; b < FI; ++b) acc[a][b] = mfma_32x32x16(Tag{}, bf[a], af[b], acc[a][b]);
         }
         __syncthreads(); // everyone has read the stage before it is overwritten
+        if (s == 0) { // ... and the parked factors: the mask words take their place
+            Ms[tid] = mw0;
+            Ms[tid + kBwdThreads] = mw1;
+        }
         if (s + 1 < nslabs) stage_slab();
         if (s + 2 < nslabs) load_slab(s + 2);
         __syncthreads();
