@@ -33,13 +33,13 @@ def _die_multi_gpu(n):
     sys.exit(2)
 
 
-# kernels behind lrbi_masked_gemm on the headline workload; the recorded HBM traffic is only quoted when it was
+# kernels behind lrbi_decode_and_gemm on the headline workload; the recorded HBM traffic is only quoted when it was
 # measured on these same kernels
-C2_GEMM_KERNELS = "mfma_gemm_pipe_kernel + splitk_reduce_kernel"
+C2_GEMM_KERNELS = "mfma_gemm_pipe_kernel (mask stored) + splitk_reduce_kernel"
 
 
 def _recorded_traffic():
-    """HBM bytes per launch of the C2 fused product (kernel + split-K reduction), from the rocprofv3
+    """HBM bytes per launch of the C2 decode + fused product (kernel + split-K reduction), from the rocprofv3
     FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (counters cannot be read from inside
     this process); None when no summary is there or when it was taken on other kernels."""
     path = os.path.join(ROOT, "profiles", "C2_masked_gemm_hbm_traffic.md")
@@ -161,21 +161,22 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         for i in range(2 * len(Ws)):
-            lrbi.masked_gemm(desc, Ws[i % len(Ws)], dIp, dIz, X, out=Y, workspace=ws)
+            lrbi.decode_and_gemm(desc, Ws[i % len(Ws)], dIp, dIz, X, out=Y, mask=mask, workspace=ws)
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": 1 << 30, "copies": 3,
                           "gemm_launches": 2 * len(Ws)}))
         return
 
     def gpu_step(i):
-        lrbi.decode_mask(desc, dIp, dIz, out=mask)
-        lrbi.masked_gemm(desc, Ws[i % len(Ws)], dIp, dIz, X, out=Y, workspace=ws)
+        # rows a1-a6 in one call: the mask to HBM and the fused masked product (for this shape one product launch,
+        # which stores the mask bytes it rebuilds, plus the split reduction)
+        lrbi.decode_and_gemm(desc, Ws[i % len(Ws)], dIp, dIz, X, out=Y, mask=mask, workspace=ws)
 
     for i in range(args.warmup):
         lrbi.index_bits(desc)
         gpu_step(i)
     torch.cuda.synchronize()
-    # The GPU part of the K steps is captured once into a HIP graph (decode + fused product per
+    # The GPU part of the K steps is captured once into a HIP graph (decode + fused product of every
     # step, weights rotating) and replayed inside the timed region; the host part of every step
     # (index-size accounting) runs in the timed region as well.
     launch_mode = "hipgraph"
@@ -204,22 +205,25 @@ def main():
     flops = 2.0 * cfg.m * cfg.n * cfg.N
     value = flops / (ms_per_step * 1e-3) / 1e12
 
-    # dominant kernel: the fused masked product alone, same launch configuration, weights rotating
-    gemm_ms, _ = event_times([(lambda Wi=Wi: lrbi.masked_gemm(desc, Wi, dIp, dIz, X, out=Y, workspace=ws)) for Wi in Ws],
-                             10 * len(Ws), 2 * len(Ws))
+    # dominant kernel: the fused product that also leaves the mask, same launch configuration, weights rotating
+    gemm_ms, _ = event_times([(lambda Wi=Wi: lrbi.decode_and_gemm(desc, Wi, dIp, dIz, X, out=Y, mask=mask, workspace=ws))
+                              for Wi in Ws], 10 * len(Ws), 2 * len(Ws))
     es = 2
     factor_bytes = lrbi.index_bits(desc)["lrbi_bits"] / 8
-    gemm_bytes = cfg.m * cfg.n * es + cfg.n * cfg.N * es + cfg.m * cfg.N * es + factor_bytes
+    # W, X, the packed factors read once; Y and the one-bit-per-weight mask written once
+    gemm_bytes = cfg.m * cfg.n * es + cfg.n * cfg.N * es + cfg.m * cfg.N * es + factor_bytes + cfg.m * cfg.n / 8
     achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "lrbi_masked_gemm (%s)" % C2_GEMM_KERNELS,
+    roofline = {"bound": "hbm", "kernel": "lrbi_decode_and_gemm (%s)" % C2_GEMM_KERNELS,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _recorded_traffic(),
                 "avg_launch_ms": round(gemm_ms, 5), "algorithmic_bytes": int(gemm_bytes),
                 "tflops_dense_equiv": round(flops / (gemm_ms * 1e-3) / 1e12, 1),
                 "mfma_frac": round(flops / (gemm_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)}
 
-    # decode kernel inside the same step (4.5 MiB mask: launch-latency bound)
+    # for comparison: the two entry points on their own (the step above no longer launches the decode kernel)
     dec_ms, _ = event_times([lambda: lrbi.decode_mask(desc, dIp, dIz, out=mask)], 100, 10)
+    plain_ms, _ = event_times([(lambda Wi=Wi: lrbi.masked_gemm(desc, Wi, dIp, dIz, X, out=Y, workspace=ws)) for Wi in Ws],
+                              10 * len(Ws), 2 * len(Ws))
 
     out = {
         "metric": "mask decode Gbit/s + fused masked-GEMM TFLOP/s (dense-equiv), % of roofline",
@@ -227,12 +231,13 @@ def main():
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic", "launch": launch_mode,
         "config": {"workload": "C2: W 4096x9216 fp16 N(0,0.01), tiles 256x256, rank 16, factors Bernoulli(0.08), "
-                               "X 9216x128; step = index_bits + decode_mask to HBM + fused masked_gemm; "
+                               "X 9216x128; step = index_bits + decode_and_gemm (mask to HBM and fused masked product); "
                                "W rotated over %d buffers (HBM-cold)" % len(Ws)},
-        "value_note": "dense-equivalent 2*m*n*N flops over the whole step (decode + fused product)",
+        "value_note": "dense-equivalent 2*m*n*N flops over the whole step (mask decoded to HBM + fused product)",
         "roofline": roofline,
-        "decode_in_step": {"mask_bits": cfg.m * cfg.n, "avg_launch_ms": round(dec_ms, 5),
-                           "gbit_s": round(cfg.m * cfg.n / (dec_ms * 1e-3) / 1e9, 1)},
+        "separate_calls": {"mask_bits": cfg.m * cfg.n, "decode_mask_avg_launch_ms": round(dec_ms, 5),
+                           "decode_mask_gbit_s": round(cfg.m * cfg.n / (dec_ms * 1e-3) / 1e9, 1),
+                           "masked_gemm_avg_launch_ms": round(plain_ms, 5)},
     }
 
     # ------------------------------------------------------------------ extras

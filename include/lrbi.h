@@ -198,6 +198,21 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
                      void *stream);
 
 /*
+ * Rows a1-a6 of the hot path in one call: the decoded mask (Eq. 3, layout and pitch rules of lrbi_decode_mask)
+ * AND the fused masked product Y = (W o I_a) X (arguments of lrbi_masked_gemm, workspace as sized by
+ * lrbi_masked_gemm_workspace_bytes).  For f16 / bf16 layers whose tile shape lines up with the tile kernel
+ * (c % 128 == 0, r % 128 == 0, k <= 64, no cut-off tiles, N > 64, X and W readable in 16-byte pieces) this is one
+ * product launch (plus the split reduction when the plan splits): the kernel rebuilds every mask byte for its own
+ * use and stores it on the way, so the stand-alone decode kernel and its launch drop out.  Every other case runs
+ * lrbi_decode_mask and then lrbi_masked_gemm on `stream`.  Results are bit-identical to those two calls.
+ * Errors: those of the two entry points.
+ */
+int lrbi_decode_and_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                         const void *dIp_packed, const void *dIz_packed, const void *dX, int64_t ldx, int64_t N,
+                         void *dY, int64_t ldy, void *dMask, int64_t mask_pitch_bytes, void *dWorkspace,
+                         uint64_t workspace_bytes, void *stream);
+
+/*
  * The masked product of a 3 x 3 convolution layer with padding 1 and stride 1 (the convolution layers of Sec. 4's
  * ResNet32 and AlexNet rows), without the unfolded input matrix: Y = (W o I_a) X where column (b, oh, ow) of X would
  * hold the 9 * cin input values under the filter at output pixel (oh, ow) of image b.  The kernel gathers them from

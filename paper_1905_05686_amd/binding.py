@@ -76,6 +76,7 @@ def load_library():
     lib.lrbi_decode_mask.argtypes = [pd, vp, vp, vp, i64, vp]
     lib.lrbi_masked_gemm_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, pu64]
     lib.lrbi_masked_gemm.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, u64, vp]
+    lib.lrbi_decode_and_gemm.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp, i64, vp, u64, vp]
     lib.lrbi_masked_conv3x3_workspace_bytes.argtypes = [pd, ctypes.c_int, i64, i64, i64, pu64]
     lib.lrbi_masked_conv3x3.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, i64, i64, vp, i64, vp, u64, vp]
     lib.lrbi_masked_gemm_static.argtypes = [pd, ctypes.c_int, vp, i64, vp, vp, vp, i64, i64, vp, i64, vp]
@@ -243,6 +244,35 @@ def masked_gemm(desc: Desc, W, dIp, dIz, X, out=None, workspace=None, stream=Non
         _dev_ptr(X, "X"), X.stride(0), N, _dev_ptr(out, "Y"), out.stride(0), ws_ptr, ws_bytes, _stream_ptr(stream)),
         "lrbi_masked_gemm")
     return out[:, 0] if squeeze else out
+
+
+def decode_and_gemm(desc: Desc, W, dIp, dIz, X, out=None, mask=None, pitch_bytes=None, workspace=None, stream=None):
+    """lrbi_decode_and_gemm: the packed mask [m, pitch] (uint8) and Y = (W o mask) X from one call; arguments as
+    for decode_mask and masked_gemm.  Returns (mask, Y)."""
+    import torch
+    if W.dim() != 2 or X.dim() != 2 or W.shape != (desc.m, desc.n) or X.shape[0] != desc.n:
+        raise ValueError("shape mismatch")
+    if W.stride(1) != 1 or (X.shape[1] > 1 and X.stride(1) != 1) or W.dtype != X.dtype:
+        raise ValueError("W and X must be row-major tensors of the same dtype")
+    N = X.shape[1]
+    if out is None:
+        out = torch.empty((desc.m, N), dtype=W.dtype, device=W.device)
+    if out.shape != (desc.m, N) or out.dtype != W.dtype or (N > 1 and out.stride(1) != 1):
+        raise ValueError("bad out tensor")
+    if pitch_bytes is None:
+        pitch_bytes = mask.shape[1] if mask is not None else default_pitch(desc.n)
+    if mask is None:
+        mask = torch.empty((desc.m, pitch_bytes), dtype=torch.uint8, device=W.device)
+    if mask.dtype != torch.uint8 or not mask.is_contiguous() or mask.shape != (desc.m, pitch_bytes):
+        raise ValueError("mask must be a contiguous uint8 [m, pitch_bytes] tensor")
+    ws_ptr, ws_bytes = ctypes.c_void_p(0), 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    _check(load_library().lrbi_decode_and_gemm(
+        ctypes.byref(desc), _dtype_code(W), _dev_ptr(W, "W"), W.stride(0), _dev_ptr(dIp, "Ip"), _dev_ptr(dIz, "Iz"),
+        _dev_ptr(X, "X"), X.stride(0), N, _dev_ptr(out, "Y"), out.stride(0), _dev_ptr(mask, "mask"), int(pitch_bytes),
+        ws_ptr, ws_bytes, _stream_ptr(stream)), "lrbi_decode_and_gemm")
+    return mask, out
 
 
 def masked_conv3x3_workspace_bytes(desc: Desc, dtype_code: int, batch: int, H: int, Wd: int) -> int:

@@ -895,9 +895,16 @@ int launch_mfma_conv(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const C
     return LRBI_OK;
 }
 
+bool mfma_gemm_emits_mask(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const void *dIz,
+                          const void *dX, int64_t ldx, int64_t N)
+{
+    if (((uintptr_t)dW & 15) != 0 || ldw % 8 != 0 || g.n % 8 != 0) return false;
+    return plan.tile >= kFirstPipeTile && pipe_ok(g, dIz, dX, ldw, ldx, N);
+}
+
 int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan_in, lrbi_dtype dt, const void *dW, int64_t ldw,
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY,
-                     int64_t ldy, void *dWorkspace, hipStream_t stream)
+                     int64_t ldy, void *dWorkspace, hipStream_t stream, MaskOut mo)
 {
     // the W loads are 16 bytes wide
     if (((uintptr_t)dW & 15) != 0 || ldw % 8 != 0 || g.n % 8 != 0) return LRBI_ERR_ALIGN;
@@ -905,7 +912,7 @@ int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan_in, lrbi_dtype dt, cons
     if (plan.tile >= kFirstPipeTile) {
         if (pipe_ok(g, dIz, dX, ldw, ldx, N)) {
             const int pf = plan.tile - kFirstPipeTile;
-            const int rc = launch_pipe_gemm(g, plan, dt, pf, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+            const int rc = launch_pipe_gemm(g, plan, dt, pf, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream, mo);
             if (rc != LRBI_OK) return rc;
             if (plan.splitk > 1 && !plan.planes_only) {
                 if (dt == LRBI_F16) return launch_reduce<F16Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
@@ -915,6 +922,7 @@ int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan_in, lrbi_dtype dt, cons
         }
         plan.tile = 9; // same blocking on the staged panel kernel
     }
+    if (mo.ptr) return LRBI_ERR_SHAPE; // the caller asks mfma_gemm_emits_mask() first
     if (dt == LRBI_F16)
         return launch_dtype<F16Tag>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
     if (dt == LRBI_BF16)

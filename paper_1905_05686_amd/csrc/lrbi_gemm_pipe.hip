@@ -50,12 +50,16 @@ template <int NS> struct SmemDma {
 // (a 3 x 3 convolution with padding 1 written as a product, the unfolded matrix never materialised).  A slab of 64
 // reduction indices is then 64 consecutive channels of one tap: 128 contiguous bytes per column, which go into the
 // stage in the same swizzled row-major image as W's rows and come out with the same 16-byte operand reads.
-template <typename Tag, int NS, bool SPREAD, bool SPLIT, bool CONV>
+// EMIT: the mask bytes that the kernel rebuilds anyway also go to global memory, in the layout of the stand-alone
+// decode (one bit per weight, rows of `mask_pitch16` 16-byte pieces): every (row, 128-column unit) of the mask is
+// formed by exactly one workgroup of the first column block, so the decode costs one 16-byte store per lane and
+// panel instead of a kernel of its own.
+template <typename Tag, int NS, bool SPREAD, bool SPLIT, bool CONV, bool EMIT = false>
 __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
     Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
     const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ X, int64_t ldx, int N,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ P, int64_t ldp, int mblocks, int nblocks,
-    int64_t kper, int xcd_remap, int y_vec_ok, ConvGeom cg)
+    int64_t kper, int xcd_remap, int y_vec_ok, ConvGeom cg, uint4 *__restrict__ mask_out, int64_t mask_pitch16)
 {
     static_assert(NS == 4, "LDS stages (an even number: the W operand registers alternate with the slab's parity)");
     static_assert(!SPREAD || NS == 4, "loads spread over the iteration land one iteration later: four stages");
@@ -311,6 +315,11 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
         }
         *reinterpret_cast<uint2 *>(out) = make_uint2(a.x, a.y);
         *reinterpret_cast<uint2 *>(out + 8) = make_uint2(a.z, a.w);
+        if constexpr (EMIT) {
+            // units past the end of this workgroup's reduction range were formed from stand-in factors: not stored
+            const int unit = kbeg / 128 + panel * PANEL_UNITS + u;
+            if (ni == 0 && unit * 128 < kend) mask_out[(m0 + row) * mask_pitch16 + unit] = a;
+        }
     };
 
     using I0 = std::integral_constant<int, 0>;
@@ -347,7 +356,8 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
     wait_loads<kProloguePieces>();
     __syncthreads();
     decode_panel(0);
-    wait_loads<kProloguePieces - 4>(); // slab 0
+    // slab 0 (EMIT: the panel's mask store is one more, younger, entry of the same in-order count)
+    wait_loads<kProloguePieces - 4 + (EMIT ? 1 : 0)>();
     __syncthreads();
     // entry state of the loop: X operands of this wavefront's first step, its W operand masked, the second read
     uint32_t mcur = my_bytes(fetch_mask(0));
@@ -394,8 +404,10 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
                 const int ps = s % PANEL_SLABS;
                 const int np = s / PANEL_SLABS + 1;
                 if (ps == 0 && np < npanels) load_factors();
-                // slab s + 1 has landed (four younger loads may still be in flight with four stages)
-                wait_loads<(NS - 3) * 4>();
+                // slab s + 1 has landed (four younger loads may still be in flight with four stages; EMIT: and the mask
+                // store of the panel that the previous iteration turned into mask bytes)
+                if (EMIT && ps == 3 && np < npanels) wait_loads<(NS - 3) * 4 + 1>();
+                else wait_loads<(NS - 3) * 4>();
                 LRBI_BARRIER();
                 // second step
                 mma(Par{}, I1{}, I0{}); read_x(st1, I0{}, I0{}); read_w(st1, Nxt{}, I0{}); read_w(st1, Nxt{}, I1{});
@@ -500,10 +512,10 @@ bool pipe_ok(const Geom &g, const void *dIz, const void *dX, int64_t ldw, int64_
     return true;
 }
 
-template <typename Tag, int NS, bool SPREAD, bool CONV>
+template <typename Tag, int NS, bool SPREAD, bool CONV, bool EMIT = false>
 static int launch_pipe_t(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
                          const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
-                         void *dWorkspace, const ConvGeom &cg, hipStream_t stream)
+                         void *dWorkspace, const ConvGeom &cg, hipStream_t stream, MaskOut mo = {nullptr, 0})
 {
     const int64_t mblocks = g.m / PIPE_BM;
     const int64_t nblocks = (N + PIPE_BN - 1) / PIPE_BN;
@@ -514,11 +526,12 @@ static int launch_pipe_t(const Geom &g, const MfmaPlan &plan, const void *dW, in
     const int xcd_remap = (blocks % 8 == 0) ? 1 : 0;
     const int64_t ldp = (N + 3) / 4 * 4;
     const size_t smem = SmemDma<NS>::bytes;
-    auto kern = split ? mfma_gemm_pipe_kernel<Tag, NS, SPREAD, true, CONV> : mfma_gemm_pipe_kernel<Tag, NS, SPREAD, false, CONV>;
+    auto kern = split ? mfma_gemm_pipe_kernel<Tag, NS, SPREAD, true, CONV, EMIT>
+                      : mfma_gemm_pipe_kernel<Tag, NS, SPREAD, false, CONV, EMIT>;
     LRBI_SET_MAX_LDS(kern, smem);
     LRBI_LAUNCH(kern, dim3((unsigned)blocks), dim3(PIPE_THREADS), smem, stream, g, (const uint16_t *)dW, ldw, dIp, dIz,
                 (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp, (int)mblocks,
-                (int)nblocks, plan.kper, xcd_remap, y_vec_ok, cg);
+                (int)nblocks, plan.kper, xcd_remap, y_vec_ok, cg, (uint4 *)mo.ptr, mo.pitch16);
     return LRBI_OK;
 }
 
@@ -527,9 +540,18 @@ static int launch_pipe_t(const Geom &g, const MfmaPlan &plan, const void *dW, in
 // The caller adds the partial planes when the plan is split.
 int launch_pipe_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, int variant, const void *dW, int64_t ldw,
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY,
-                     int64_t ldy, void *dWorkspace, hipStream_t stream)
+                     int64_t ldy, void *dWorkspace, hipStream_t stream, MaskOut mo)
 {
     const ConvGeom none = {0, 0, 0};
+    if (mo.ptr) { // the mask as a by-product: one variant per dtype (loads spread over the iteration)
+        if (dt == LRBI_F16)
+            return launch_pipe_t<F16Tag, 4, true, false, true>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace,
+                                                               none, stream, mo);
+        if (dt == LRBI_BF16)
+            return launch_pipe_t<BF16Tag, 4, true, false, true>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace,
+                                                                none, stream, mo);
+        return LRBI_ERR_DTYPE;
+    }
 #define LRBI_PIPE_ARGS g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, none, stream
     if (dt == LRBI_F16) {
         if (variant <= 1) return launch_pipe_t<F16Tag, 4, false, false>(LRBI_PIPE_ARGS);

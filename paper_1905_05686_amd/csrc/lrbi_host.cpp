@@ -278,6 +278,46 @@ extern "C" int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const v
                             dX, ldx, N, dY, ldy, dWorkspace, s);
 }
 
+extern "C" int lrbi_decode_and_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,
+                                    const void *dIp_packed, const void *dIz_packed, const void *dX, int64_t ldx,
+                                    int64_t N, void *dY, int64_t ldy, void *dMask, int64_t mask_pitch_bytes,
+                                    void *dWorkspace, uint64_t workspace_bytes, void *stream)
+{
+    const int rc = validate_desc(desc);
+    if (rc != LRBI_OK) return rc;
+    if (!dW || !dIp_packed || !dIz_packed || !dX || !dY || !dMask) return LRBI_ERR_NULL;
+    const int es = elem_size(dtype);
+    if (es == 0) return LRBI_ERR_DTYPE;
+    if (N <= 0 || N > (int64_t)0x7FFFFF00) return LRBI_ERR_SHAPE;
+    if (ldw < desc->n || ldx < N || ldy < N) return LRBI_ERR_PITCH;
+    if (mask_pitch_bytes % 16 != 0 || mask_pitch_bytes < (desc->n + 7) / 8) return LRBI_ERR_PITCH;
+    if (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8) || !aligned_to(dMask, 16)) return LRBI_ERR_ALIGN;
+    if (!aligned_to(dW, (uintptr_t)es) || !aligned_to(dX, (uintptr_t)es) || !aligned_to(dY, (uintptr_t)es))
+        return LRBI_ERR_ALIGN;
+    // One launch when the pipelined tile kernel serves the product: it rebuilds every mask byte anyway and stores
+    // it on the way.  Batches of up to 32 columns belong to the row-streaming kernel, which is tried first there.
+    if (N > 32 && use_mfma(desc, dtype, N)) {
+        const Geom g = make_geom(desc);
+        MfmaPlan plan = plan_mfma(g, desc->flags, N);
+        if (plan.splitk > 1) {
+            const bool ws_ok = dWorkspace && aligned_to(dWorkspace, 16) && workspace_bytes >= plan.workspace_bytes;
+            if (!ws_ok) {
+                if (desc->flags & LRBI_FLAG_SPLITK_MASK) return LRBI_ERR_WORKSPACE;
+                plan = plan_mfma(g, (desc->flags & ~LRBI_FLAG_SPLITK_MASK) | (1u << LRBI_FLAG_SPLITK_SHIFT), N);
+            }
+        }
+        if (mfma_gemm_emits_mask(g, plan, dW, ldw, dIz_packed, dX, ldx, N))
+            return launch_mfma_gemm(g, plan, dtype, dW, ldw, (const uint32_t *)dIp_packed,
+                                    (const uint32_t *)dIz_packed, dX, ldx, N, dY, ldy, dWorkspace, (hipStream_t)stream,
+                                    MaskOut{dMask, mask_pitch_bytes / 16});
+    }
+    // every other shape: the two entry points one after the other on the same stream
+    const int rc1 = lrbi_decode_mask(desc, dIp_packed, dIz_packed, dMask, mask_pitch_bytes, stream);
+    if (rc1 != LRBI_OK) return rc1;
+    return lrbi_masked_gemm(desc, dtype, dW, ldw, dIp_packed, dIz_packed, dX, ldx, N, dY, ldy, dWorkspace,
+                            workspace_bytes, stream);
+}
+
 // plan of the convolution form: the pipelined tile kernel, whatever the tile flag says
 static MfmaPlan plan_conv(const lrbi_desc *desc, int64_t N)
 {

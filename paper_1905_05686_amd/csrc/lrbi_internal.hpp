@@ -91,9 +91,17 @@ struct MfmaPlan {
     bool planes_only = false;
 };
 MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N);
+// Where the tile kernel leaves the decoded mask as a by-product (rows of 16-byte pieces, one bit per weight), or {nullptr, 0}.
+struct MaskOut {
+    void *ptr;
+    int64_t pitch16; // 16-byte pieces per mask row
+};
 int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const void *dW, int64_t ldw,
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N,
-                     void *dY, int64_t ldy, void *dWorkspace, hipStream_t stream);
+                     void *dY, int64_t ldy, void *dWorkspace, hipStream_t stream, MaskOut mo = {nullptr, 0});
+// true when launch_mfma_gemm would run the kernel that can leave the mask behind (and so honours MaskOut)
+bool mfma_gemm_emits_mask(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const void *dIz,
+                          const void *dX, int64_t ldx, int64_t N);
 
 // row-streaming kernel for narrow batches (lrbi_gemm_stream.hip)
 bool stream_ok(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const void *dX, int64_t ldx, int64_t N, int cus);
@@ -119,7 +127,7 @@ int launch_mfma_conv(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const C
 bool pipe_ok(const Geom &g, const void *dIz, const void *dX, int64_t ldw, int64_t ldx, int64_t N);
 int launch_pipe_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, int pf, const void *dW, int64_t ldw,
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY,
-                     int64_t ldy, void *dWorkspace, hipStream_t stream);
+                     int64_t ldy, void *dWorkspace, hipStream_t stream, MaskOut mo = {nullptr, 0});
 
 // non-negative factorisation of the magnitude matrix (lrbi_nmf.hip)
 uint64_t nmf_workspace_bytes(const Geom &g);

@@ -157,6 +157,20 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
     assert lrbi.masked_gemm_workspace_bytes(d2, lrbi.F16, 16) == 2 * 8 * 16 * 4
     assert lrbi.masked_gemm_workspace_bytes(lrbi.Desc(4096, 4096, 512, 512, 32), lrbi.BF16, 1024) == 0
     assert lrbi.masked_gemm_workspace_bytes(lrbi.Desc(4096, 4096, 512, 512, 32), lrbi.BF16, 1) == 0
+    # the fused decode + product entry point: the checks of both
+    h = lib.lrbi_decode_and_gemm
+    hargs = lambda **kw: [ctypes.byref(d), kw.get("dt", lrbi.F16), kw.get("W", p), kw.get("ldw", 128), p, p, p,
+                          kw.get("ldx", 16), kw.get("N", 16), p, kw.get("ldy", 16), kw.get("M", p), kw.get("pitch", 16),
+                          None, 0, None]
+    assert h(*hargs(W=None)) == -1
+    assert h(*hargs(M=None)) == -1
+    assert h(*hargs(dt=7)) == -4
+    assert h(*hargs(N=0)) == -2
+    assert h(*hargs(ldw=127)) == -5
+    assert h(*hargs(pitch=8)) == -5
+    assert h(*hargs(pitch=24)) == -5
+    assert h(*hargs(M=ctypes.c_void_p(base + 8))) == -6
+    assert h(*hargs(W=ctypes.c_void_p(base + 1))) == -6
 
 
 def test_threshold_eval_rejects_bad_arguments_before_any_launch():

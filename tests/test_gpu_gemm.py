@@ -7,7 +7,7 @@ import paper_1905_05686_amd as lrbi
 import workloads
 from oracle import lrbi_oracle as orc
 from gpu_util import (ORACLE_THREADS, TOL, TORCH_DTYPE, desc_of, dev, device_factors, to_device, to_float64,
-                      workspace_for)
+                      unpack_device_mask, workspace_for)
 
 pytestmark = pytest.mark.gpu
 
@@ -246,3 +246,40 @@ def test_full_size_sampled_rows_in_bench_configuration():
             row += orc.masked_gemm(Wd[i:i + 1, tj * cfg.c:(tj + 1) * cfg.c], bits, Xd[tj * cfg.c:(tj + 1) * cfg.c])[0]
         err = np.max(np.abs(Y[i] - row) / np.maximum(np.abs(row), rms))
         assert err <= TOL[cfg.dtype], (i, err)
+
+
+# ---- mask and product from one call (rows a1-a6 fused)
+FUSED = [
+    _small(256, 1152, 128, 128, 8, 0.2, 128, "f16"),     # the tile kernel leaves the mask: one column block, unsplit
+    _small(256, 1024, 256, 256, 16, 0.1, 256, "bf16"),   # two column blocks: only the first one stores the mask
+    _small(128, 9216, 128, 256, 16, 0.08, 128, "f16"),   # split over n: every slice stores its own units, last panel short
+    _small(300, 2400, 300, 300, 8, 0.12, 20, "f16"),     # no fused kernel for this shape: the two entry points in a row
+    _small(130, 264, 65, 33, 5, 0.3, 70, "bf16"),        # general tile kernel
+    _small(50, 120, 25, 60, 4, 0.2, 3, "f32"),
+    workloads.CONFIGS["C2"],                             # the benchmark's workload at full size
+]
+
+
+@pytest.mark.parametrize("idx", range(len(FUSED)))
+def test_decode_and_gemm_equals_the_two_calls(idx):
+    cfg = FUSED[idx]
+    print("decode_and_gemm", idx, cfg, flush=True)
+    data = workloads.make(cfg)
+    desc = desc_of(cfg)
+    dIp, dIz = device_factors(desc, data["Ip01"], data["Iz01"])
+    W, X = to_device(data["W"], cfg.dtype), to_device(data["X"], cfg.dtype)
+    ws = workspace_for(desc, DT_CODE[cfg.dtype], cfg.N)
+    pitch = ((cfg.n + 127) // 128) * 16 + 32
+    mask = torch.full((cfg.m, pitch), 0xA5, dtype=torch.uint8, device=dev())
+    mask2 = torch.full((cfg.m, pitch), 0xA5, dtype=torch.uint8, device=dev())
+    m1, Y1 = lrbi.decode_and_gemm(desc, W, dIp, dIz, X, mask=mask, workspace=ws)
+    lrbi.decode_mask(desc, dIp, dIz, out=mask2)
+    Y2 = lrbi.masked_gemm(desc, W, dIp, dIz, X, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(m1, mask2)  # the bytes beyond the written part of a row are left alone by both
+    assert torch.equal(Y1.view(torch.uint8), Y2.view(torch.uint8))
+    # and against the oracle
+    M = orc.decode_mask(data["Ip01"], data["Iz01"], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
+    assert np.array_equal(unpack_device_mask(m1, cfg.n)[:, :cfg.n], M)
+    ref, _ = _oracle(cfg, data)
+    _assert_close(Y1, ref, cfg.dtype, "fused%d" % idx)
