@@ -108,6 +108,7 @@ STREAM = [
     _small(64, 520, 32, 130, 6, 0.25, 12, "bf16"),
     _small(64, 520, 32, 130, 6, 0.25, 28, "f16"),
     _small(2048, 8, 512, 8, 2, 0.5, 1, "f16"),           # a single 16-byte piece per row
+    _small(64, 96, 32, 32, 3, 0.3, 8, "bf16"),           # a tile row's I_z is no whole number of 16-byte pieces
 ]
 
 
