@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblrbi.so")
-SOURCES = ["lrbi_host.cpp", "lrbi_decode.hip", "lrbi_gemv.hip", "lrbi_gemm_mfma.hip", "lrbi_gemm_pipe.hip", "lrbi_gemm_stream.hip", "lrbi_alg1.hip", "lrbi_backward.hip", "lrbi_lstm.hip", "lrbi_nmf.hip"]
+SOURCES = ["lrbi_host.cpp", "lrbi_decode.hip", "lrbi_gemv.hip", "lrbi_gemm_mfma.hip", "lrbi_gemm_pipe.hip", "lrbi_gemm_stream.hip", "lrbi_gemm_pipe_t.hip", "lrbi_alg1.hip", "lrbi_backward.hip", "lrbi_lstm.hip", "lrbi_nmf.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -846,6 +846,25 @@ int launch_gemm_t(const Geom &g, const BwdPlan &plan, lrbi_dtype dt, const void 
         default: return LRBI_ERR_DTYPE;
         }
     }
+    // tile shapes that line up with its blocking: the pipelined kernel (both operands straight into LDS)
+    if (plan.bq == 128 && pipe_t_ok(g, dW, ldw, dIz, dDY, lddy, N)) {
+        int64_t iper = g.m;
+        const int slices = pipe_t_slices(g, N, plan.slices, &iper);
+        const int rc = launch_pipe_t_gemm(g, slices, iper, dt, dW, ldw, dIp, dIz, dDY, lddy, N, dDX, lddx, dWorkspace,
+                                          stream);
+        if (rc != LRBI_OK || slices == 1) return rc;
+        const int64_t ldp = (N + 3) / 4 * 4;
+        const int y_vec_ok = (((uintptr_t)dDX & 7) == 0) && (lddx % 4 == 0);
+        const int64_t rblocks = (g.n * (ldp / 4) + 255) / 256;
+        if (rblocks > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
+        if (dt == LRBI_F16)
+            LRBI_LAUNCH(bwd_reduce_kernel<F16Tag>, dim3((unsigned)rblocks), dim3(256), 0, stream,
+                        (const float *)dWorkspace, ldp, g.n, (int)N, slices, (uint16_t *)dDX, lddx, y_vec_ok);
+        else
+            LRBI_LAUNCH(bwd_reduce_kernel<BF16Tag>, dim3((unsigned)rblocks), dim3(256), 0, stream,
+                        (const float *)dWorkspace, ldp, g.n, (int)N, slices, (uint16_t *)dDX, lddx, y_vec_ok);
+        return LRBI_OK;
+    }
 #define LRBI_T_ARGS g, plan, dW, ldw, dIp, dIz, dDY, lddy, N, dDX, lddx, dWorkspace, stream
     if (dt == LRBI_F16) {
         if (plan.bq == 128) return launch_gemm_t_tile<F16Tag, 128, 2, 2>(LRBI_T_ARGS);

@@ -77,6 +77,12 @@ BwdPlan plan_gemm_t(const Geom &g, lrbi_dtype dt, int64_t N, bool aligned);
 int launch_gemm_t(const Geom &g, const BwdPlan &plan, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
                   const uint32_t *dIz, const void *dDY, int64_t lddy, int64_t N, void *dDX, int64_t lddx,
                   void *dWorkspace, hipStream_t stream);
+// the pipelined transposed product (lrbi_gemm_pipe_t.hip)
+bool pipe_t_ok(const Geom &g, const void *dW, int64_t ldw, const void *dIz, const void *dDY, int64_t lddy, int64_t N);
+int pipe_t_slices(const Geom &g, int64_t N, int max_slices, int64_t *iper);
+int launch_pipe_t_gemm(const Geom &g, int slices, int64_t iper, lrbi_dtype dt, const void *dW, int64_t ldw,
+                       const uint32_t *dIp, const uint32_t *dIz, const void *dDY, int64_t lddy, int64_t N, void *dDX,
+                       int64_t lddx, void *dWorkspace, hipStream_t stream);
 int launch_grad(const Geom &g, lrbi_dtype dt, bool mfma, const void *dDY, int64_t lddy, const void *dX, int64_t ldx,
                 int64_t N, const uint32_t *dIp, const uint32_t *dIz, void *dDW, int64_t lddw, hipStream_t stream);
 

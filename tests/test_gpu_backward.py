@@ -84,6 +84,12 @@ EDGE = [
     (_small(1024, 384, 256, 384, 16, 0.1, 40, "f16"), 0),       # workgroups at three offsets inside a tile column
     (_small(512, 128, 128, 128, 64, 0.03, 8, "f16"), 0),        # smallest tile rows of the tuned mask path, rank 64
     (_small(2048, 512, 512, 512, 32, 0.06, 4, "bf16"), 0),      # batch of 4: vector-ALU kernels at a large shape
+    # the pipelined transposed kernel (aligned tiles, batch above 64 columns)
+    (_small(256, 256, 128, 128, 8, 0.2, 128, "f16"), 0),        # one panel of four slabs, one 128-row unit per tile row
+    (_small(1536, 384, 256, 384, 16, 0.1, 136, "bf16"), 0),     # three panels, three slices, a short second batch block
+    (_small(1024, 128, 128, 128, 64, 0.03, 72, "f16"), 0),      # rank 64: two I_p words per row, a batch block of 72
+    (_small(768, 256, 384, 128, 40, 0.05, 80, "bf16"), 8),      # rank 40, three units per tile row, padded leading dimensions
+    (_small(2048, 256, 512, 256, 5, 0.3, 256, "f16"), 0),       # rank 5 (a short round of ranks), four panels
 ]
 
 
@@ -101,8 +107,9 @@ def test_without_workspace_the_reduction_is_not_split():
     assert orc.rel_err(to_float64(a), to_float64(b)) <= 1e-2
 
 
-def test_nonfinite_values_under_pruned_weights_never_reach_dx():
-    cfg = _small(256, 512, 128, 256, 8, 0.15, 16, "f16")
+@pytest.mark.parametrize("N", [16, 128])
+def test_nonfinite_values_under_pruned_weights_never_reach_dx(N):
+    cfg = _small(256, 512, 128, 256, 8, 0.15, N, "f16")
     data, dYs = _inputs(cfg)
     desc = desc_of(cfg)
     M = orc.decode_mask(data["Ip01"], data["Iz01"], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k)
