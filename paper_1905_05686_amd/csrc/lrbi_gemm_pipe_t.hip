@@ -38,7 +38,8 @@ struct SmemPipeT {
     static constexpr size_t mt_off = (size_t)PT_NS * PT_STAGE_BYTES;
     static constexpr size_t fz_off = mt_off + 2 * PT_MT_BYTES;
     static constexpr size_t fip_off = fz_off + PT_FZ_ROWS * PT_FZ_ROW_BYTES;
-    static constexpr size_t bytes = fip_off + 128 * PANEL_UNITS * 2 * 4; // I_p words [128 rows][4 units][2]; later [4][64][16 bytes]
+    static constexpr size_t sel_off = fip_off + 128 * PANEL_UNITS * 2 * 4; // (I_p words: 4 KB; later its columns as bits)
+    static constexpr size_t bytes = sel_off + PANEL_UNITS * 128 * 8;       // the ranks of every column, per unit
 };
 
 template <typename Tag, bool SPLIT>
@@ -55,8 +56,9 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
     extern __shared__ uint4 lrbi_dyn_smem[];
     unsigned char *smem = (unsigned char *)lrbi_dyn_smem;
     unsigned char *Mt = smem + S::mt_off;              // [2][128 columns of W][PT_MT_ROW]: mask bytes along the rows
-    uint32_t *Fz = (uint32_t *)(smem + S::fz_off);     // [64][16]: I_z rows under the workgroup's 128 columns, per unit
-    uint32_t *Fip = (uint32_t *)(smem + S::fip_off);   // [128][4][2] I_p words; then [4][64][4]: columns of I_p as bits
+    uint32_t *Fz = (uint32_t *)(smem + S::fz_off);     // [4 units][4 words][64 ranks]: I_z under the workgroup's 128 columns
+    uint32_t *Fip = (uint32_t *)(smem + S::fip_off);   // [4 units][2 words][128 rows] of I_p; then [4][64 ranks][4]: its columns as bits
+    uint2 *Sel = (uint2 *)(smem + S::sel_off);         // [4 units][128 columns]: the ranks of a column of I_z (unit's tile)
 
     int64_t bid = blockIdx.x;
     if (xcd_remap) {
@@ -168,21 +170,24 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
     };
     auto my_bytes = [&](u32x2 mk) -> uint32_t { return (kg ? mk.y : mk.x) >> (8 * lg); };
 
-    // ---- factor slices of one panel (512 rows of W = four units of 128 rows): global -> LDS.
+    // ---- factor slices of one panel (512 rows of W = four units of 128 rows): global -> LDS, word by word, in the
+    // order the gathers below want them: I_z as [unit][word of the 128 columns][rank] (a lane then reads four ranks of
+    // its word per 16-byte read), I_p as [unit][word][row].  Sixteen load instructions each, two per wavefront.
     // (cti, roff): tile row and row offset inside it of the next panel's first unit; a unit lies inside one tile
-    // (r % 128 == 0).  I_z: wavefronts 0 .. 3 fetch ranks 16 w .. + 15, lane = (rank, unit): the four words of that
-    // rank's row under the workgroup's 128 columns, from the unit's tile.  Ranks at or beyond k fetch rank 0 instead
-    // and are never looked at.  Units beyond the reduction range fetch the range's first unit: never used.
-    // I_p: one word per lane, image [row][unit][2]; with one word per row the second slot repeats the first.
+    // (r % 128 == 0).  Ranks at or beyond k fetch rank 0 instead and are masked out; units beyond the reduction range
+    // fetch the range's first unit and are never used; with one I_p word per row the second word repeats the first.
     int cti = (int)(ibeg / g.r), roff = (int)(ibeg - (ibeg / g.r) * g.r);
     int64_t crow = ibeg;
     const uint32_t zb_first = (uint32_t)(((((int64_t)cti * g.tile_cols + tj) * g.k) * (int64_t)g.izw + (coff >> 5)) * 4);
     const uint32_t pb_first = (uint32_t)(((((int64_t)cti * g.tile_cols + tj) * g.r + roff) * (int64_t)g.ipw) * 4);
-    const int fz_l = (wave & 3) * 16 + (lane >> 2);
-    const uint32_t fz_lane = (uint32_t)(((fz_l < g.k) ? fz_l : 0) * g.izw * 4);
-    const int fz_u = lane & 3;
+    const uint32_t fz_lane = (uint32_t)(((lane < g.k) ? lane : 0) * g.izw * 4);
+    int leaders = 1; // bit u: unit u of the panel whose factors were asked for last is the first one of its tile row
     auto load_factors = [&]() {
         uint32_t zb[PANEL_UNITS], pb[PANEL_UNITS];
+        leaders = 1;
+#pragma unroll
+        for (int u = 1; u < PANEL_UNITS; ++u)
+            if ((roff + 128 * u) % g.r == 0) leaders |= 1 << u;
 #pragma unroll
         for (int u = 0; u < PANEL_UNITS; ++u) {
             const bool ok = crow < iend;
@@ -196,17 +201,19 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
                 ++cti;
             }
         }
-        if (wave < 4) {
-            const uint32_t zsel = fz_u == 0 ? zb[0] : (fz_u == 1 ? zb[1] : (fz_u == 2 ? zb[2] : zb[3]));
-            load_to_lds16(lds0 + (uint32_t)S::fz_off + (uint32_t)wave * 1024u, Iz, zsel + fz_lane);
-        }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int idx = (wave * 2 + i) * 64 + lane;
-            const int row = idx >> 3, u = (idx >> 1) & 3, iw = (idx & 1) < g.ipw ? (idx & 1) : 0;
-            const uint32_t psel = u == 0 ? pb[0] : (u == 1 ? pb[1] : (u == 2 ? pb[2] : pb[3]));
-            load_to_lds4(lds0 + (uint32_t)S::fip_off + (uint32_t)(wave * 2 + i) * 256u, Ip,
-                         psel + (uint32_t)((row * g.ipw + iw) * 4));
+            const int q = wave * 2 + i; // uniform
+            {
+                const int u = q >> 2, w = q & 3;
+                const uint32_t zsel = u == 0 ? zb[0] : (u == 1 ? zb[1] : (u == 2 ? zb[2] : zb[3]));
+                load_to_lds4(lds0 + (uint32_t)S::fz_off + (uint32_t)q * 256u, Iz, zsel + fz_lane + (uint32_t)(w * 4));
+            }
+            {
+                const int u = q >> 2, iw = ((q >> 1) & 1) < g.ipw ? ((q >> 1) & 1) : 0, row = (q & 1) * 64 + lane;
+                const uint32_t psel = u == 0 ? pb[0] : (u == 1 ? pb[1] : (u == 2 ? pb[2] : pb[3]));
+                load_to_lds4(lds0 + (uint32_t)S::fip_off + (uint32_t)q * 256u, Ip, psel + (uint32_t)((row * g.ipw + iw) * 4));
+            }
         }
     };
     // Eq. 3 along the columns of W for one panel, in three steps with a workgroup barrier between them (the factor
@@ -214,21 +221,28 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
     //  1. lane (unit, rank l, 32-row chunk) gathers bit l of the chunk's 32 I_p words into one word: 32 rows of column
     //     l of I_p (a second word for rank l + 32 when k > 32);
     //  2. (nobody reads the I_p words any more) the gathered words are stored over them as [unit][rank][16 bytes];
-    //  3. lane (column j, unit): the ranks of column j are bit j of the I_z rows (gathered the same way, every lane
-    //     of a 32-column group reading the same words); the mask bits of the unit's 128 rows are the OR of those
-    //     ranks' bit strings.
+    //     in the same step, lane (unit, column j) gathers the ranks of column j, bit j of the I_z rows, for the units
+    //     that start a tile row (the units behind them share its I_z);
+    //  3. lane (column j, unit): the mask bits of the unit's 128 rows are the OR of the bit strings of the column's
+    //     ranks.
     // In the slab loop the three steps ride on the barriers of three consecutive iterations; only the first panel,
     // in the prologue, pays for barriers of its own.  Bits at or beyond k are zero in the packed factors.
     uint32_t tw0 = 0u, tw1 = 0u;
     auto panel_step1 = [&]() {
         const int u = tid >> 7, l = (tid >> 2) & 31, c = tid & 3;
-        const uint32_t *src = Fip + ((c * 32) * PANEL_UNITS + u) * 2; // row 32 c of the unit, word 0
+        const uint4 *src = (const uint4 *)(Fip + (u * 2) * 128 + c * 32); // rows 32 c .. + 31 of the unit, word 0
         uint32_t t0 = 0u, t1 = 0u;
 #pragma unroll
-        for (int i = 0; i < 32; ++i) t0 |= ((src[i * PANEL_UNITS * 2] >> l) & 1u) << i;
+        for (int i4 = 0; i4 < 8; ++i4) {
+            const uint4 v = src[i4];
+            t0 |= (((v.x >> l) & 1u) | (((v.y >> l) & 1u) << 1) | (((v.z >> l) & 1u) << 2) | (((v.w >> l) & 1u) << 3)) << (4 * i4);
+        }
         if (g.k > 32) {
 #pragma unroll
-            for (int i = 0; i < 32; ++i) t1 |= ((src[i * PANEL_UNITS * 2 + 1] >> l) & 1u) << i;
+            for (int i4 = 0; i4 < 8; ++i4) {
+                const uint4 v = src[32 + i4]; // word 1 of the same rows: 128 words further
+                t1 |= (((v.x >> l) & 1u) | (((v.y >> l) & 1u) << 1) | (((v.z >> l) & 1u) << 2) | (((v.w >> l) & 1u) << 3)) << (4 * i4);
+            }
         }
         tw0 = t0;
         tw1 = t1;
@@ -238,28 +252,39 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
         Fip[(u * FAST_MAX_K + l) * 4 + c] = tw0;
         if (g.k > 32) Fip[(u * FAST_MAX_K + 32 + l) * 4 + c] = tw1;
     };
-    auto panel_step3 = [&](int panel) {
-        const int col = tid >> 2, u = tid & 3;
-        const uint32_t *fz = Fz + 4 * u + (col >> 5);
+    auto panel_step3 = [&]() { // lane (unit, column); only the first unit of every tile row under the panel gathers
+        const int u = tid >> 7, col = tid & 127;
+        if (!((leaders >> u) & 1)) return; // uniform over the wavefront
+        const uint4 *fz = (const uint4 *)(Fz + (u * 4 + (col >> 5)) * 64); // this column's word of every rank
         const int sh = col & 31;
         uint32_t sel0 = 0u, sel1 = 0u; // the ranks of this column
-        for (int l0 = 0; l0 < g.k; l0 += 16) {
-            uint32_t part = 0u;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) { // rows at or beyond k are stand-ins: masked out below
-                const int l = (l0 + q < g.k) ? l0 + q : g.k - 1;
-                part |= ((fz[l * PANEL_WORDS] >> sh) & 1u) << q;
-            }
-            const int live = g.k - l0; // ranks of this round that exist
-            if (live < 16) part &= (1u << live) - 1u;
-            if (l0 < 32) sel0 |= part << l0;
-            else sel1 |= part << (l0 - 32);
+        for (int l4 = 0; l4 < 8; ++l4) {
+            const uint4 v = fz[l4];
+            sel0 |= (((v.x >> sh) & 1u) | (((v.y >> sh) & 1u) << 1) | (((v.z >> sh) & 1u) << 2) | (((v.w >> sh) & 1u) << 3)) << (4 * l4);
         }
+        if (g.k > 32) {
+#pragma unroll
+            for (int l4 = 0; l4 < 8; ++l4) {
+                const uint4 v = fz[8 + l4];
+                sel1 |= (((v.x >> sh) & 1u) | (((v.y >> sh) & 1u) << 1) | (((v.z >> sh) & 1u) << 2) | (((v.w >> sh) & 1u) << 3)) << (4 * l4);
+            }
+        }
+        // slots of ranks at or beyond k hold a stand-in (rank 0)
+        if (g.k < 32) sel0 &= (1u << g.k) - 1u;
+        if (g.k <= 32) sel1 = 0u;
+        else if (g.k < 64) sel1 &= (1u << (g.k - 32)) - 1u;
+        Sel[u * 128 + col] = make_uint2(sel0, sel1);
+    };
+    auto panel_step4 = [&](int panel) { // lane (column, unit): OR of the bit strings of the column's ranks
+        const int col = tid >> 2, u = tid & 3;
+        const int lead = 31 - __builtin_clz((uint32_t)(leaders & ((2 << u) - 1))); // the unit that gathered for u's tile row
+        const uint2 sel01 = Sel[lead * 128 + col];
         const uint4 *ipt = (const uint4 *)Fip + u * FAST_MAX_K;
         uint4 a = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
         for (int iw = 0; iw < 2; ++iw) {
-            uint32_t sel = iw ? sel1 : sel0;
+            uint32_t sel = iw ? sel01.y : sel01.x;
             while (sel) { // two ranks per round: their reads are in flight together
                 const int la = __builtin_ctz(sel) + 32 * iw;
                 sel &= sel - 1u;
@@ -310,8 +335,9 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
     panel_step1();
     __syncthreads();
     panel_step2();
+    panel_step3();
     __syncthreads();
-    panel_step3(0);
+    panel_step4(0);
     wait_loads<kProloguePieces - 4>(); // slab 0
     __syncthreads();
     uint32_t mcur = my_bytes(fetch_mask(0));
@@ -365,8 +391,10 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
                 // front of slab 1's barrier; the three steps follow the barriers of slabs 1, 2 and 3; first read at slab 7
                 if (np < npanels) {
                     if (ps == 1) panel_step1();
-                    else if (ps == 2) panel_step2();
-                    else if (ps == 3) panel_step3(np);
+                    else if (ps == 2) {
+                        panel_step2();
+                        panel_step3();
+                    } else if (ps == 3) panel_step4(np);
                 }
             }
         });
