@@ -106,6 +106,79 @@ struct StreamArgs {
     int ms_pitch;  // mask words per row in LDS (odd, at least 8 per slab)
 };
 
+
+// The mask of a workgroup's rows, first half: the tile row's packed I_z and the rows' I_p words into LDS.
+// Linear copies, spread evenly over the wavefronts (a wavefront's copies complete in order and only a few of
+// them overlap, so the wavefront with the most of them sets the time): I_z in 16-byte pieces when its slices
+// allow, else word by word; the I_p words of tile tj by wavefront tj % 8.
+__device__ __forceinline__ void stage_row_factors(const Geom &g, const StreamArgs &a, uint32_t *Fz, uint32_t *Fp, int ti,
+                                                  int il0, int rows_here, int wave, int lane)
+{
+    const uint32_t *zsrc = a.Iz + (int64_t)ti * g.tile_cols * g.k * (int64_t)g.izw;
+    if (a.fz_vec) {
+        const int pieces = a.fz_words >> 2;
+        for (int p0 = wave * 64; p0 < pieces; p0 += ST_THREADS) {
+            int p = p0 + lane;
+            if (p >= pieces) p = pieces - 1; // the copy instruction's slots past the end are part of the pad
+            load_to_lds16(lds_address(Fz + 4 * p0), zsrc, 16u * (uint32_t)p);
+        }
+    } else {
+        for (int w0 = wave * 64; w0 < a.fz_words; w0 += ST_THREADS) {
+            int w = w0 + lane;
+            if (w >= a.fz_words) w = a.fz_words - 1;
+            load_to_lds4(lds_address(Fz + w0), zsrc, 4u * (uint32_t)w);
+        }
+    }
+    // per tile, the I_p rows il0 .. il0 + rows_here - 1 (slots past them are filled with the last row, never used)
+    const int live = rows_here * g.ipw;
+    for (int tj = wave; tj < g.tile_cols; tj += ST_WAVES) {
+        const uint32_t *psrc = a.Ip + (((int64_t)ti * g.tile_cols + tj) * g.r + il0) * g.ipw;
+        for (int e0 = 0; e0 < a.fp_pitch; e0 += 64) {
+            int e = e0 + lane;
+            if (e >= live) e = live - 1;
+            load_to_lds4(lds_address(Fp + tj * a.fp_pitch + e0), psrc, 4u * (uint32_t)e);
+        }
+    }
+}
+
+// Second half: Eq. 3 from the factors in LDS, one work item per (tile, row, 32-bit word of the tile's I_z rows): the
+// item ORs the word of every I_z row that its I_p row selects and then ORs the result into the row's mask (cleared
+// by the caller) at the tile's bit position (two words when the tile does not start on a word boundary; neighbouring
+// tiles may share a word, hence LDS atomics).  No item looks at more than one tile, so tile edges need no special
+// cases.
+template <int BM>
+__device__ __forceinline__ void decode_row_masks(const Geom &g, const StreamArgs &a, const uint32_t *Fz,
+                                                 const uint32_t *Fp, uint32_t *Ms, int rows_here, int n, int tid)
+{
+    const uint32_t per_tile = (uint32_t)(BM * g.izw);
+    const uint32_t items = (uint32_t)g.tile_cols * per_tile;
+    for (uint32_t idx = tid; idx < items; idx += ST_THREADS) {
+        const uint32_t tj = idx / per_tile, rem = idx - tj * per_tile;
+        const uint32_t rl = rem / (uint32_t)g.izw, wz = rem - rl * (uint32_t)g.izw;
+        const int in_tile = (int)wz * 32;
+        const int col0 = (int)tj * g.c + in_tile;
+        if ((int)rl >= rows_here || in_tile >= g.c || col0 >= n) continue;
+        uint32_t v = 0u;
+        for (int iw = 0; iw < g.ipw; ++iw) {
+            uint32_t sel = Fp[tj * a.fp_pitch + rl * g.ipw + iw];
+            while (sel) {
+                const int l = __builtin_ctz(sel) + 32 * iw;
+                sel &= sel - 1u;
+                v |= Fz[(tj * g.k + l) * g.izw + wz];
+            }
+        }
+        // columns past the tile's width (pad bits of the packed rows) and past n (a cut-off last tile) stay out
+        const int lim = (g.c - in_tile < n - col0) ? g.c - in_tile : n - col0;
+        if (lim < 32) v &= (1u << lim) - 1u;
+        if (v == 0u) continue;
+        uint32_t *dst = Ms + rl * a.ms_pitch + (col0 >> 5);
+        const int sh = col0 & 31;
+        __hip_atomic_fetch_or(dst, v << sh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (sh && (v >> (32 - sh)))
+            __hip_atomic_fetch_or(dst + 1, v >> (32 - sh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+}
+
 template <typename Tag, int NS, int BM, int KS>
 __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamArgs a)
 {
@@ -162,69 +235,8 @@ __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamA
     };
 
     // ---- the mask of the workgroup's rows ----
-    // Linear copies, spread evenly over the wavefronts (a wavefront's copies complete in order and only a few of
-    // them overlap, so the wavefront with the most of them sets the time): I_z in 16-byte pieces when its slices
-    // allow, else word by word; the I_p words of tile tj by wavefront tj % 8.
-    auto stage_factors = [&]() {
-        const uint32_t *zsrc = a.Iz + (int64_t)ti * g.tile_cols * g.k * (int64_t)g.izw;
-        if (a.fz_vec) {
-            const int pieces = a.fz_words >> 2;
-            for (int p0 = wave * 64; p0 < pieces; p0 += ST_THREADS) {
-                int p = p0 + lane;
-                if (p >= pieces) p = pieces - 1; // the copy instruction's slots past the end are part of the pad
-                load_to_lds16(lds_address(Fz + 4 * p0), zsrc, 16u * (uint32_t)p);
-            }
-        } else {
-            for (int w0 = wave * 64; w0 < a.fz_words; w0 += ST_THREADS) {
-                int w = w0 + lane;
-                if (w >= a.fz_words) w = a.fz_words - 1;
-                load_to_lds4(lds_address(Fz + w0), zsrc, 4u * (uint32_t)w);
-            }
-        }
-        // per tile, the I_p rows il0 .. il0 + rows_here - 1 (slots past them are filled with the last row, never used)
-        const int live = rows_here * g.ipw;
-        for (int tj = wave; tj < g.tile_cols; tj += ST_WAVES) {
-            const uint32_t *psrc = a.Ip + (((int64_t)ti * g.tile_cols + tj) * g.r + il0) * g.ipw;
-            for (int e0 = 0; e0 < a.fp_pitch; e0 += 64) {
-                int e = e0 + lane;
-                if (e >= live) e = live - 1;
-                load_to_lds4(lds_address(Fp + tj * a.fp_pitch + e0), psrc, 4u * (uint32_t)e);
-            }
-        }
-    };
-    // Eq. 3 from the factors in LDS, one work item per (tile, row, 32-bit word of the tile's I_z rows): the item ORs
-    // the word of every I_z row that its I_p row selects and then ORs the result into the row's mask at the tile's
-    // bit position (two words when the tile does not start on a word boundary; neighbouring tiles may share a word,
-    // hence LDS atomics).  No item looks at more than one tile, so tile edges need no special cases.
-    auto decode_rows = [&]() {
-        const uint32_t per_tile = (uint32_t)(BM * g.izw);
-        const uint32_t items = (uint32_t)g.tile_cols * per_tile;
-        for (uint32_t idx = tid; idx < items; idx += ST_THREADS) {
-            const uint32_t tj = idx / per_tile, rem = idx - tj * per_tile;
-            const uint32_t rl = rem / (uint32_t)g.izw, wz = rem - rl * (uint32_t)g.izw;
-            const int in_tile = (int)wz * 32;
-            const int col0 = (int)tj * g.c + in_tile;
-            if ((int)rl >= rows_here || in_tile >= g.c || col0 >= n) continue;
-            uint32_t v = 0u;
-            for (int iw = 0; iw < g.ipw; ++iw) {
-                uint32_t sel = Fp[tj * a.fp_pitch + rl * g.ipw + iw];
-                while (sel) {
-                    const int l = __builtin_ctz(sel) + 32 * iw;
-                    sel &= sel - 1u;
-                    v |= Fz[(tj * g.k + l) * g.izw + wz];
-                }
-            }
-            // columns past the tile's width (pad bits of the packed rows) and past n (a cut-off last tile) stay out
-            const int lim = (g.c - in_tile < n - col0) ? g.c - in_tile : n - col0;
-            if (lim < 32) v &= (1u << lim) - 1u;
-            if (v == 0u) continue;
-            uint32_t *dst = Ms + rl * a.ms_pitch + (col0 >> 5);
-            const int sh = col0 & 31;
-            __hip_atomic_fetch_or(dst, v << sh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            if (sh && (v >> (32 - sh)))
-                __hip_atomic_fetch_or(dst + 1, v >> (32 - sh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
-    };
+    auto stage_factors = [&]() { stage_row_factors(g, a, Fz, Fp, ti, il0, rows_here, wave, lane); };
+    auto decode_rows = [&]() { decode_row_masks<BM>(g, a, Fz, Fp, Ms, rows_here, n, tid); };
 
     // ---- arithmetic ----
     const int row16 = lane & 15, kg = lane >> 4; // operand row / column, and which 8 of a step's 32 reduction indices
@@ -313,6 +325,102 @@ __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamA
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// One column (N = 1), rows of at most 8192 columns: W goes from global memory straight into registers
+// ---------------------------------------------------------------------------
+// A workgroup of eight wavefronts owns eight rows of one tile row, one row per wavefront.  Every wavefront asks for
+// its whole row at once (P loads of 1 KB, 16 bytes per lane), behind the copies of the factors and of x into LDS, so
+// the whole matrix is requested within the first microsecond and the mask of the rows is rebuilt (as above) while W
+// is on its way; no stage ring, no barrier per slab.  Then per row: select by mask byte, 2-element dot products in
+// fp32 against x from LDS, a butterfly sum over the lanes.
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_acc(F16Tag, uint32_t w, uint32_t x, float c)
+{
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), __builtin_bit_cast(f16x2, x), c, false);
+}
+__device__ __forceinline__ float dot2_acc(BF16Tag, uint32_t w, uint32_t x, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, x), c, false);
+}
+
+static constexpr int RV_ROWS = 8;      // rows per workgroup: one per wavefront
+static constexpr int RV_MAX_PIECES = 16; // 1 KB pieces of a row held in registers: rows of up to 8192 columns
+
+template <typename Tag, int P>
+__global__ __launch_bounds__(ST_THREADS) void rowvec_gemm_kernel(Geom g, StreamArgs a)
+{
+    static_assert(RV_ROWS == ST_WAVES && P <= RV_MAX_PIECES, "one row per wavefront");
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    unsigned char *smem = (unsigned char *)lrbi_dyn_smem;
+    unsigned char *Xs = smem;                               // x: P KB, column j at byte 2 j
+    uint32_t *Ms = (uint32_t *)(smem + P * 1024);           // [8][ms_pitch]: the rows' whole mask
+    uint32_t *Fz = Ms + RV_ROWS * a.ms_pitch;               // [tile_cols][k][izw]
+    uint32_t *Fp = Fz + a.fz_pad;                           // [tile_cols][fp_pitch]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ti = blockIdx.x / a.blocks_per_tile_row;
+    const int il0 = (blockIdx.x - ti * a.blocks_per_tile_row) * RV_ROWS;
+    const int64_t m0 = (int64_t)ti * g.r + il0;
+    int rows_here = RV_ROWS;
+    if (g.r - il0 < rows_here) rows_here = g.r - il0;
+    if (g.m - m0 < rows_here) rows_here = (int)(g.m - m0);
+    if (rows_here <= 0) return; // a tile row cut off by the end of the matrix: the whole workgroup leaves
+    const int n = (int)g.n;
+
+    // copies into LDS first: the loads of W below are then the youngest of the wavefront, and "at most P loads
+    // outstanding" means that every copy has landed
+    stage_row_factors(g, a, Fz, Fp, ti, il0, rows_here, wave, lane);
+    for (int i = wave; i < P; i += ST_WAVES) {
+        uint32_t piece = 64u * i + lane;
+        if (piece >= a.x_pieces) piece = a.x_pieces - 1u; // stays inside x; such columns are cleared below
+        load_to_lds16(lds_address(Xs + 1024 * i), a.X, piece * 16u);
+    }
+    // this wavefront's row (a wavefront past the last row repeats that row and stores nothing); columns past n - 8
+    // read the row's last piece instead: their mask bits are zero
+    const int my_row = wave < rows_here ? wave : rows_here - 1;
+    const char *wrow = (const char *)(a.W + (m0 + my_row) * a.ldw);
+    u32x4 w[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        int col = p * 512 + lane * 8;
+        if (col > n - 8) col = n - 8;
+        w[p] = *reinterpret_cast<const u32x4 *>(wrow + (size_t)col * 2);
+    }
+    for (int i = tid; i < RV_ROWS * a.ms_pitch; i += ST_THREADS) Ms[i] = 0u;
+    wait_loads<P>();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    decode_row_masks<RV_ROWS>(g, a, Fz, Fp, Ms, rows_here, n, tid);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    const unsigned char *mb = (const unsigned char *)(Ms + my_row * a.ms_pitch);
+    float acc = 0.f;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const u32x4 am = apply_mask8(w[p], mb[p * 64 + lane]);
+        u32x4 xv = *reinterpret_cast<const u32x4 *>(Xs + p * 1024 + lane * 16);
+        if (p * 512 + lane * 8 >= n) xv = u32x4{0u, 0u, 0u, 0u};
+        acc = dot2_acc(Tag{}, am.x, xv.x, acc);
+        acc = dot2_acc(Tag{}, am.y, xv.y, acc);
+        acc = dot2_acc(Tag{}, am.z, xv.z, acc);
+        acc = dot2_acc(Tag{}, am.w, xv.w, acc);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+    if (lane == 0 && wave < rows_here) {
+        const int64_t row = m0 + wave;
+        if (a.P) a.P[row * a.ldp] = acc;
+        if (a.Y) a.Y[row * a.ldy] = cvt_store(Tag{}, acc);
+    }
+}
+
 // The kernel serves: f16 / bf16, N = 1 or a multiple of 4 up to 32, X contiguous ([n][N] with ldx = N) and 16-byte
 // aligned, W rows 16-byte aligned, n a multiple of 8, a tile row's packed I_z small enough for LDS, and enough rows to
 // give every compute unit a workgroup or so.
@@ -321,6 +429,7 @@ struct StreamPlan {
     int bm, ks;   // rows per workgroup and columns per slab: (16, 256), or (8, 512) for a single column
     size_t lds;
     unsigned grid;
+    int rv_pieces; // above 0: the single-column kernel that holds a row in registers, with this many 1 KB pieces
     StreamArgs a; // the geometry-derived fields only
 };
 
@@ -346,6 +455,21 @@ static bool plan_stream(const Geom &g, int64_t N, int cus, StreamPlan &p)
     const int64_t grid = (int64_t)g.tile_rows * a.blocks_per_tile_row;
     if (grid > 0x7FFFFFFF || grid < cus / 2) return false;
     p.grid = (unsigned)grid;
+    p.rv_pieces = 0;
+    if (N == 1 && g.n <= RV_MAX_PIECES * 512) {
+        int pieces = 2;
+        while (pieces * 512 < g.n) pieces *= 2;
+        const int ms_pitch = pieces * 16 + 1;
+        const size_t lds = (size_t)pieces * 1024 +
+                           ((size_t)RV_ROWS * ms_pitch + a.fz_pad + (size_t)g.tile_cols * a.fp_pitch) * 4;
+        if (lds <= 64 * 1024) {
+            p.rv_pieces = pieces;
+            a.ms_pitch = ms_pitch;
+            p.ns = 0;
+            p.lds = lds;
+            return true;
+        }
+    }
     const size_t fixed = ((size_t)p.bm * a.ms_pitch + a.fz_pad + (size_t)g.tile_cols * a.fp_pitch) * 4;
     // two workgroups per compute unit when there are more workgroups than compute units, else the deepest ring;
     // a wavefront issues at most three copies per slab, so its 6-bit load counter never limits the depth
@@ -391,8 +515,23 @@ template <typename Tag, int BM, int KS> static int launch_stream_ns(const Geom &
     }
 }
 
+template <typename Tag, int P> static int launch_rowvec_t(const Geom &g, const StreamPlan &p, hipStream_t stream)
+{
+    auto kern = rowvec_gemm_kernel<Tag, P>;
+    LRBI_SET_MAX_LDS(kern, p.lds);
+    LRBI_LAUNCH(kern, dim3(p.grid), dim3(ST_THREADS), p.lds, stream, g, p.a);
+    return LRBI_OK;
+}
+
 template <typename Tag> static int launch_stream_shape(const Geom &g, const StreamPlan &p, hipStream_t stream)
 {
+    switch (p.rv_pieces) {
+    case 0: break;
+    case 2: return launch_rowvec_t<Tag, 2>(g, p, stream);
+    case 4: return launch_rowvec_t<Tag, 4>(g, p, stream);
+    case 8: return launch_rowvec_t<Tag, 8>(g, p, stream);
+    default: return launch_rowvec_t<Tag, 16>(g, p, stream);
+    }
     return (p.bm == 8) ? launch_stream_ns<Tag, 8, 512>(g, p, stream) : launch_stream_ns<Tag, 16, 256>(g, p, stream);
 }
 

@@ -109,6 +109,13 @@ STREAM = [
     _small(64, 520, 32, 130, 6, 0.25, 28, "f16"),
     _small(2048, 8, 512, 8, 2, 0.5, 1, "f16"),           # a single 16-byte piece per row
     _small(64, 96, 32, 32, 3, 0.3, 8, "bf16"),           # a tile row's I_z is no whole number of 16-byte pieces
+    # one column: a row travels in registers (rows of up to 8192 columns; 2, 4, 8 or 16 pieces of 1 KB)
+    _small(130, 4104, 65, 1368, 9, 0.1, 1, "bf16"),      # 16 pieces, the ninth holds 8 columns; tiles cut through words
+    _small(64, 4096, 32, 512, 32, 0.1, 1, "f16"),        # 8 full pieces
+    _small(72, 8192, 24, 1024, 16, 0.08, 1, "bf16"),     # 16 full pieces
+    _small(1152, 1024, 576, 512, 145, 0.02, 1, "f16"),   # 2 pieces, rank 145
+    _small(44, 1544, 22, 772, 7, 0.2, 1, "f16"),         # 4 pieces, the last one short; 6 of 8 rows in the last workgroup
+    _small(40, 8704, 20, 1088, 6, 0.15, 1, "bf16"),      # longer rows: back on the staged kernel, 17 slabs of 512
 ]
 
 
