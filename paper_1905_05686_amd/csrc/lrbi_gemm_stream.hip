@@ -20,6 +20,8 @@
 //     w (and w + 8); the eight partial accumulators are added through LDS at the end, in wavefront order.
 // X stays in its [k][N] order in LDS: for N = 1 an operand is 16 consecutive bytes of it, otherwise the transposing
 // LDS read delivers 8 consecutive k of one column per lane (needs N % 4 == 0 for its 8-byte alignment).
+#include <type_traits>
+
 #include "lrbi_internal.hpp"
 #include "lrbi_lds_dma.hpp"
 #include "lrbi_mfma_common.hpp"
@@ -104,6 +106,7 @@ struct StreamArgs {
     int fz_vec;    // the tile rows' slices of I_z are 16-byte aligned whole numbers of 16-byte pieces
     int fp_pitch;  // LDS words per tile for the I_p words of 16 rows: 16 * ipw rounded up to whole copy instructions
     int ms_pitch;  // mask words per row in LDS (odd, at least 8 per slab)
+    uint32_t izw_magic; // floor(2^32 / izw) + 1: an index below 2^16 times this, upper 32 bits, is the index / izw
 };
 
 
@@ -141,41 +144,55 @@ __device__ __forceinline__ void stage_row_factors(const Geom &g, const StreamArg
     }
 }
 
-// Second half: Eq. 3 from the factors in LDS, one work item per (tile, row, 32-bit word of the tile's I_z rows): the
-// item ORs the word of every I_z row that its I_p row selects and then ORs the result into the row's mask (cleared
-// by the caller) at the tile's bit position (two words when the tile does not start on a word boundary; neighbouring
-// tiles may share a word, hence LDS atomics).  No item looks at more than one tile, so tile edges need no special
-// cases.
+// Second half: Eq. 3 from the factors in LDS.  Wavefront w takes rows w, w + 8, ...; its lanes take the (tile, 32-bit
+// word of the tile's I_z rows) pairs of the row, 64 at a time.  An item ORs the word of every I_z row that its I_p row
+// selects and then ORs the result into the row's mask (cleared by the caller) at the tile's bit position (two words
+// when the tile does not start on a word boundary; neighbouring tiles may share a word, hence LDS atomics).  No item
+// looks at more than one tile, so tile edges need no special cases.  The tile of an item is its index divided by
+// izw: a multiplication by izw_magic = floor(2^32 / izw) + 1 (exact for the item counts that fit LDS; izw = 1 apart).
 template <int BM>
 __device__ __forceinline__ void decode_row_masks(const Geom &g, const StreamArgs &a, const uint32_t *Fz,
-                                                 const uint32_t *Fp, uint32_t *Ms, int rows_here, int n, int tid)
+                                                 const uint32_t *Fp, uint32_t *Ms, int rows_here, int n, int wave,
+                                                 int lane)
 {
-    const uint32_t per_tile = (uint32_t)(BM * g.izw);
-    const uint32_t items = (uint32_t)g.tile_cols * per_tile;
-    for (uint32_t idx = tid; idx < items; idx += ST_THREADS) {
-        const uint32_t tj = idx / per_tile, rem = idx - tj * per_tile;
-        const uint32_t rl = rem / (uint32_t)g.izw, wz = rem - rl * (uint32_t)g.izw;
-        const int in_tile = (int)wz * 32;
-        const int col0 = (int)tj * g.c + in_tile;
-        if ((int)rl >= rows_here || in_tile >= g.c || col0 >= n) continue;
-        uint32_t v = 0u;
-        for (int iw = 0; iw < g.ipw; ++iw) {
-            uint32_t sel = Fp[tj * a.fp_pitch + rl * g.ipw + iw];
-            while (sel) {
-                const int l = __builtin_ctz(sel) + 32 * iw;
-                sel &= sel - 1u;
-                v |= Fz[(tj * g.k + l) * g.izw + wz];
+    const uint32_t items = (uint32_t)g.tile_cols * (uint32_t)g.izw;
+    for (int rl = wave; rl < BM && rl < rows_here; rl += ST_WAVES) {
+        for (uint32_t j = lane; j < items; j += 64) {
+            const uint32_t tj = (g.izw == 1) ? j : __umulhi(j, a.izw_magic);
+            const uint32_t wz = j - tj * (uint32_t)g.izw;
+            const int in_tile = (int)wz * 32;
+            const int col0 = (int)tj * g.c + in_tile;
+            if (in_tile >= g.c || col0 >= n) continue;
+            uint32_t v = 0u;
+            const uint32_t *zcol = Fz + (size_t)tj * g.k * g.izw + wz; // this word of the tile's I_z rows
+            for (int iw = 0; iw < g.ipw; ++iw) {
+                uint32_t sel = Fp[tj * a.fp_pitch + rl * g.ipw + iw];
+                // four selected rows per round, their reads independent of one another; when fewer are left the
+                // last one is read again (an OR with the same word changes nothing)
+                while (sel) {
+                    const int l0 = __builtin_ctz(sel);
+                    sel &= sel - 1u;
+                    const int l1 = sel ? __builtin_ctz(sel) : l0;
+                    sel &= sel - 1u;
+                    const int l2 = sel ? __builtin_ctz(sel) : l1;
+                    sel &= sel - 1u;
+                    const int l3 = sel ? __builtin_ctz(sel) : l2;
+                    sel &= sel - 1u;
+                    const uint32_t z0 = zcol[(32 * iw + l0) * g.izw], z1 = zcol[(32 * iw + l1) * g.izw];
+                    const uint32_t z2 = zcol[(32 * iw + l2) * g.izw], z3 = zcol[(32 * iw + l3) * g.izw];
+                    v |= (z0 | z1) | (z2 | z3);
+                }
             }
+            // columns past the tile's width (pad bits of the packed rows) and past n (a cut-off last tile) stay out
+            const int lim = (g.c - in_tile < n - col0) ? g.c - in_tile : n - col0;
+            if (lim < 32) v &= (1u << lim) - 1u;
+            if (v == 0u) continue;
+            uint32_t *dst = Ms + rl * a.ms_pitch + (col0 >> 5);
+            const int sh = col0 & 31;
+            __hip_atomic_fetch_or(dst, v << sh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (sh && (v >> (32 - sh)))
+                __hip_atomic_fetch_or(dst + 1, v >> (32 - sh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
-        // columns past the tile's width (pad bits of the packed rows) and past n (a cut-off last tile) stay out
-        const int lim = (g.c - in_tile < n - col0) ? g.c - in_tile : n - col0;
-        if (lim < 32) v &= (1u << lim) - 1u;
-        if (v == 0u) continue;
-        uint32_t *dst = Ms + rl * a.ms_pitch + (col0 >> 5);
-        const int sh = col0 & 31;
-        __hip_atomic_fetch_or(dst, v << sh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (sh && (v >> (32 - sh)))
-            __hip_atomic_fetch_or(dst + 1, v >> (32 - sh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 }
 
@@ -236,7 +253,7 @@ __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamA
 
     // ---- the mask of the workgroup's rows ----
     auto stage_factors = [&]() { stage_row_factors(g, a, Fz, Fp, ti, il0, rows_here, wave, lane); };
-    auto decode_rows = [&]() { decode_row_masks<BM>(g, a, Fz, Fp, Ms, rows_here, n, tid); };
+    auto decode_rows = [&]() { decode_row_masks<BM>(g, a, Fz, Fp, Ms, rows_here, n, wave, lane); };
 
     // ---- arithmetic ----
     const int row16 = lane & 15, kg = lane >> 4; // operand row / column, and which 8 of a step's 32 reduction indices
@@ -345,6 +362,25 @@ __device__ __forceinline__ float dot2_acc(BF16Tag, uint32_t w, uint32_t x, float
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, x), c, false);
 }
 
+// Sum over the 64 lanes, valid in lane 63: butterflies inside the groups of four, mirrored halves and rows of 16 (after
+// which every lane of a row holds the row's sum), then row 0's sum into row 1 and row 2's into row 3, then row 1's
+// into rows 2 and 3.  Cross-lane operands of the vector ALU, no LDS traffic; the order of the additions is fixed.
+__device__ __forceinline__ float wave_sum_to_last_lane(float v)
+{
+    auto from = [](float x, auto ctrl, auto rows) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value,
+                                                                     decltype(rows)::value, 0xF, false));
+    };
+    using std::integral_constant;
+    v += from(v, integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{});  // quad_perm [1,0,3,2]
+    v += from(v, integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{});  // quad_perm [2,3,0,1]
+    v += from(v, integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{}); // row_half_mirror
+    v += from(v, integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{}); // row_mirror
+    v += from(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{}); // row_bcast15 into rows 1 and 3
+    v += from(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{}); // row_bcast31 into rows 2 and 3
+    return v;
+}
+
 static constexpr int RV_ROWS = 8;      // rows per workgroup: one per wavefront
 static constexpr int RV_MAX_PIECES = 16; // 1 KB pieces of a row held in registers: rows of up to 8192 columns
 
@@ -383,38 +419,43 @@ __global__ __launch_bounds__(ST_THREADS) void rowvec_gemm_kernel(Geom g, StreamA
     // read the row's last piece instead: their mask bits are zero
     const int my_row = wave < rows_here ? wave : rows_here - 1;
     const char *wrow = (const char *)(a.W + (m0 + my_row) * a.ldw);
+    // The first half of the row is asked for now, the second half once the mask is there: a wavefront cannot issue
+    // further loads while the memory pipeline is full, and it must get to the mask rebuild while W streams in.
+    constexpr int H = P / 2;
     u32x4 w[P];
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
+    auto load_piece = [&](int p) {
         int col = p * 512 + lane * 8;
         if (col > n - 8) col = n - 8;
-        w[p] = *reinterpret_cast<const u32x4 *>(wrow + (size_t)col * 2);
-    }
+        return *reinterpret_cast<const u32x4 *>(wrow + (size_t)col * 2);
+    };
+#pragma unroll
+    for (int p = 0; p < H; ++p) w[p] = load_piece(p);
     for (int i = tid; i < RV_ROWS * a.ms_pitch; i += ST_THREADS) Ms[i] = 0u;
-    wait_loads<P>();
+    wait_loads<H>();
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    decode_row_masks<RV_ROWS>(g, a, Fz, Fp, Ms, rows_here, n, tid);
+    decode_row_masks<RV_ROWS>(g, a, Fz, Fp, Ms, rows_here, n, wave, lane);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+#pragma unroll
+    for (int p = H; p < P; ++p) w[p] = load_piece(p);
 
     const unsigned char *mb = (const unsigned char *)(Ms + my_row * a.ms_pitch);
-    float acc = 0.f;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f; // four chains, added in a fixed order
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const u32x4 am = apply_mask8(w[p], mb[p * 64 + lane]);
         u32x4 xv = *reinterpret_cast<const u32x4 *>(Xs + p * 1024 + lane * 16);
         if (p * 512 + lane * 8 >= n) xv = u32x4{0u, 0u, 0u, 0u};
-        acc = dot2_acc(Tag{}, am.x, xv.x, acc);
-        acc = dot2_acc(Tag{}, am.y, xv.y, acc);
-        acc = dot2_acc(Tag{}, am.z, xv.z, acc);
-        acc = dot2_acc(Tag{}, am.w, xv.w, acc);
+        a0 = dot2_acc(Tag{}, am.x, xv.x, a0);
+        a1 = dot2_acc(Tag{}, am.y, xv.y, a1);
+        a2 = dot2_acc(Tag{}, am.z, xv.z, a2);
+        a3 = dot2_acc(Tag{}, am.w, xv.w, a3);
     }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
-    if (lane == 0 && wave < rows_here) {
+    const float acc = wave_sum_to_last_lane((a0 + a1) + (a2 + a3));
+    if (lane == 63 && wave < rows_here) {
         const int64_t row = m0 + wave;
         if (a.P) a.P[row * a.ldp] = acc;
         if (a.Y) a.Y[row * a.ldy] = cvt_store(Tag{}, acc);
@@ -448,6 +489,7 @@ static bool plan_stream(const Geom &g, int64_t N, int cus, StreamPlan &p)
     const int64_t fz_words = (int64_t)g.tile_cols * g.k * g.izw;
     if (fz_words * 4 > ST_FZ_MAX_BYTES) return false;
     a.fz_words = (int)fz_words;
+    a.izw_magic = (g.izw > 1) ? (uint32_t)((((uint64_t)1 << 32) / (uint64_t)g.izw) + 1u) : 0u;
     a.fz_pad = (a.fz_words + 255) / 256 * 256; // whole copy instructions of either width
     a.fp_pitch = (ST_FP_ROWS * g.ipw + 63) / 64 * 64;
     const int nslabs = (int)((g.n + p.ks - 1) / p.ks);
