@@ -72,6 +72,8 @@ EDGE = [
     (_small(130, 4104, 65, 1368, 9, 0.1, 3, "f16"), 0),
     (_small(128, 192, 64, 64, 8, 0.2, 128, "bf16"), 0),      # one 128x128 tile, 3 slabs
     (_small(300, 2400, 300, 300, 8, 0.12, 20, "f16"), 0),    # unaligned tiles, scalar X path, split
+    (_small(3000, 600, 300, 300, 8, 0.12, 20, "f16"), 0),    # the row-streaming kernel by itself: 190 workgroups, the last of a tile row with 12 rows
+    (_small(2100, 512, 300, 128, 6, 0.15, 8, "bf16"), 0),    # the same, bf16, 7 tile rows of 19 workgroups
     (_small(384, 1024, 128, 256, 16, 0.1, 72, "f16"), 0),    # 128x64 tile variant (N in 33..64 -> padded)
     (_small(384, 1024, 128, 256, 16, 0.1, 40, "bf16"), 0),
     (_small(200, 1000, 100, 500, 40, 0.05, 136, "bf16"), 0), # rank above 32, ragged m and N
