@@ -73,8 +73,9 @@ typedef struct lrbi_desc {
 #define LRBI_FLAG_PATH_AUTO   0x00000000u
 #define LRBI_FLAG_PATH_VALU   0x00000001u /* bandwidth-bound vector-ALU kernel    */
 #define LRBI_FLAG_PATH_MFMA   0x00000002u /* matrix-core kernel (f16 / bf16 only) */
-#define LRBI_FLAG_PATH_STREAM 0x00000003u /* row-streaming matrix-core kernel: f16 / bf16, N = 1 or a multiple of 4 up to
-                                             32, X contiguous (ldx = N) and 16-byte aligned, W rows 16-byte aligned */
+#define LRBI_FLAG_PATH_STREAM 0x00000003u /* row-streaming kernels (W read once, any tile shape): f16 / bf16, N = 1 or a
+                                             multiple of 4 up to 32, X contiguous (ldx = N) and 16-byte aligned, W rows
+                                             16-byte aligned */
 /* desc.flags bits 8..15: split of the n (reduction) range over workgroups for the
  * MFMA path, 0 = chosen by the library.  Values > 1 need a workspace. */
 #define LRBI_FLAG_SPLITK_SHIFT 8

@@ -20,6 +20,9 @@
 //     w (and w + 8); the eight partial accumulators are added through LDS at the end, in wavefront order.
 // X stays in its [k][N] order in LDS: for N = 1 an operand is 16 consecutive bytes of it, otherwise the transposing
 // LDS read delivers 8 consecutive k of one column per lane (needs N % 4 == 0 for its 8-byte alignment).
+//
+// A single column over rows of at most 8192 columns takes the second kernel of this file instead (a row of W goes
+// straight into the registers of its wavefront); the mask of the rows is rebuilt the same way in both.
 #include <type_traits>
 
 #include "lrbi_internal.hpp"
