@@ -570,6 +570,22 @@ def main():
                 del buf
             except Exception as e:
                 ceilings["fill_1GiB_GBs"] = {"error": repr(e)}
+            try:  # a plain read: the framework's own sum over 1 GiB of fp32, three buffers in turn
+                bufs = [torch.ones(1 << 28, dtype=torch.float32, device=dev) for _ in range(3)]
+                for t in bufs:
+                    t.sum()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()  # eager launches (a library reduction is not captured into a graph here): 0.25 ms each
+                for _ in range(3):
+                    for t in bufs:
+                        t.sum()
+                e1.record()
+                torch.cuda.synchronize()
+                ceilings["sum_1GiB_GBs"] = round((1 << 30) / (e0.elapsed_time(e1) / 9 * 1e-3) / 1e9, 1)
+                del bufs
+            except Exception as e:
+                ceilings["sum_1GiB_GBs"] = {"error": repr(e)}
             for name in ("C2", "C3b", "C5"):
                 try:
                     c = workloads.CONFIGS[name]
