@@ -61,10 +61,17 @@ __device__ __forceinline__ uint32_t slab_mask_word(const Geom &g, const uint32_t
     uint32_t acc = 0u;
     for (int iw = 0; iw < g.ipw; ++iw) {
         uint32_t sel = ip[iw];
-        while (sel) {
-            const int l = __builtin_ctz(sel) + 32 * iw;
+        const uint32_t *zr = iz + (int64_t)(32 * iw) * g.izw;
+        while (sel) { // four ranks per round, their loads in flight together (fewer left: the last one again)
+            const int l0 = __builtin_ctz(sel);
             sel &= sel - 1u;
-            acc |= iz[(int64_t)l * g.izw];
+            const int l1 = sel ? __builtin_ctz(sel) : l0;
+            sel &= sel - 1u;
+            const int l2 = sel ? __builtin_ctz(sel) : l1;
+            sel &= sel - 1u;
+            const int l3 = sel ? __builtin_ctz(sel) : l2;
+            sel &= sel - 1u;
+            acc |= (zr[(int64_t)l0 * g.izw] | zr[(int64_t)l1 * g.izw]) | (zr[(int64_t)l2 * g.izw] | zr[(int64_t)l3 * g.izw]);
         }
     }
     return acc;
