@@ -215,9 +215,9 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_kernel(
         decode_slab(0, 0);
         __syncthreads();
         stage_slab(0);
-        if (nslabs > 1) {
+        if (nslabs > 1) { // the mask words first: their dependent loads are waited for at once, and a wavefront's
+            decode_slab(1, 1); // loads complete in order, so operand loads issued ahead of them would be drained
             load_slab(1);
-            decode_slab(1, 1);
         }
         __syncthreads();
     }
@@ -248,8 +248,8 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_kernel(
         }
         if (s + 1 < nslabs) stage_slab(buf ^ 1);
         if (s + 2 < nslabs) {
-            load_slab(s + 2);
             decode_slab(s + 2, buf);
+            load_slab(s + 2);
         }
         __syncthreads();
     }
