@@ -270,6 +270,24 @@ FUSED = [
 ]
 
 
+@pytest.mark.parametrize("N", [1, 8, 128])
+def test_fp16_subnormal_weights_are_not_flushed(N):
+    """Weights below fp16's smallest normal number (2^-14) times inputs of 2^10: exact in fp32, and far above zero in
+    the sum; a path that flushes subnormal operands (the 2-element dot products of the single-column kernel, the
+    matrix cores of the others) would return zeros."""
+    cfg = _small(128, 1024, 128, 256, 8, 0.3, N, "f16")
+    rng = np.random.default_rng(11)
+    data = workloads.make(cfg)
+    data["W"] = (rng.integers(1, 64, (cfg.m, cfg.n)).astype(np.float32) * np.float32(2.0 ** -24)).astype(np.float16)
+    data["X"] = np.full((cfg.n, cfg.N), 1024.0, dtype=np.float16)
+    ref, M = _oracle(cfg, data)
+    assert np.abs(ref).max() > 1e-3 and M.sum() > 0
+    Y = to_float64(_run(cfg, data))
+    # every product k * 2^-14 and every partial sum is exact in fp32; only the final rounding to fp16 is left
+    exp = workloads.to_float64(workloads.to_storage(ref, "f16"), "f16")
+    assert np.array_equal(Y, exp)
+
+
 @pytest.mark.parametrize("idx", range(len(FUSED)))
 def test_decode_and_gemm_equals_the_two_calls(idx):
     cfg = FUSED[idx]
