@@ -403,8 +403,9 @@ def main():
             except Exception as e:
                 others[key] = {"error": repr(e)}
         # the LSTM configuration as a sequence: 2 layers x 35 fused steps (gate product + cell equations, h written
-        # straight into the next inputs), one graph replay; against the same sequence with separate product,
-        # reduction and (torch) gate kernels
+        # straight into the next inputs), one graph replay.  With two input buffers per layer in turn, h never goes
+        # into the buffer the step reads and a step is one kernel; with one buffer per layer it is two launches.
+        # Against the same sequence with separate product, reduction and (torch) gate kernels
         if wanted is None or "lstm_sequence_C4" in wanted:
             try:
                 Ld = workloads.make_lstm()
@@ -418,7 +419,18 @@ def main():
                 xh = [torch.zeros((2 * Hh, Bb), dtype=TD[c.dtype], device=dev) for _ in range(layers_)]
                 cs = [torch.zeros((Hh, Bb), dtype=torch.float32, device=dev) for _ in range(layers_)]
 
+                xh2 = [[torch.zeros((2 * Hh, Bb), dtype=TD[c.dtype], device=dev) for _ in range(2)] for _ in range(layers_)]
+
                 def fused_sequence():
+                    for t in range(steps_):
+                        cur, nx = t % 2, (t + 1) % 2
+                        xh2[0][cur][:Hh].copy_(xs_[t])
+                        for l in range(layers_):
+                            up = xh2[l + 1][cur][:Hh] if l + 1 < layers_ else None
+                            lrbi.lstm_step(de, Wd[l], fac[l][0], fac[l][1], xh2[l][cur], cs[l], xh2[l][nx][Hh:], up,
+                                           workspace=lws)
+
+                def two_launch_sequence():
                     for t in range(steps_):
                         xh[0][:Hh].copy_(xs_[t])
                         for l in range(layers_):
@@ -441,14 +453,16 @@ def main():
                                 xh[l + 1][:Hh].copy_(hcur)
 
                 ms_f, _ = event_times([fused_sequence], 3, 1)
+                ms_2, _ = event_times([two_launch_sequence], 3, 1)
                 ms_u, _ = event_times([unfused_sequence], 3, 1)
                 others["lstm_sequence_C4"] = {
                     "workload": "LSTM, %d layers x %d steps, hidden %d, batch %d, gate matrix %dx%d %s, tiles %dx%d rank %d"
                                 % (layers_, steps_, Hh, Bb, c.m, c.n, c.dtype, c.r, c.c, c.k),
                     "fused_sequence_ms": round(ms_f, 4), "fused_us_per_step": round(ms_f * 1e3 / (steps_ * layers_), 2),
+                    "two_launch_sequence_ms": round(ms_2, 4), "two_launch_us_per_step": round(ms_2 * 1e3 / (steps_ * layers_), 2),
                     "unfused_sequence_ms": round(ms_u, 4),
                     "dense_equiv_tflops_fused": round(2.0 * c.m * c.n * Bb * steps_ * layers_ / (ms_f * 1e-3) / 1e12, 2)}
-                del Wd, xs_, lws, xh, cs
+                del Wd, xs_, lws, xh, xh2, cs
             except Exception as e:
                 others["lstm_sequence_C4"] = {"error": repr(e)}
         # backward pass through the masking layer: dX = (W o I_a)^T dY and dW = (dY X^T) o I_a

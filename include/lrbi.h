@@ -386,7 +386,11 @@ int lrbi_masked_grad(const lrbi_desc *desc, lrbi_dtype dtype, const void *dDY, i
  *   ldh1 / ldh2 >= B; they may point into the buffer dXH points into (the product has finished
  *   reading it when they are written).  dWorkspace: required, 16-byte aligned, at least
  *   lrbi_lstm_step_workspace_bytes bytes (LRBI_ERR_WORKSPACE otherwise).  m % 4 != 0 is
- *   LRBI_ERR_SHAPE.  Two kernel launches on `stream`.
+ *   LRBI_ERR_SHAPE.  Two kernel launches on `stream`; a single one (product and cell equations
+ *   in one kernel, nothing through the workspace, same results bit for bit) when neither dH1
+ *   nor dH2 overlaps the n x B input, B is a multiple of 4 up to 32, H and the tile height r are
+ *   multiples of 4 and the shape is one the row-streaming product kernel serves: a caller that
+ *   alternates between two input buffers per layer gets that form.
  */
 int lrbi_lstm_step_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t B, uint64_t *bytes);
 int lrbi_lstm_step(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,

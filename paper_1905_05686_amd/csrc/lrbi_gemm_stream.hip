@@ -465,6 +465,244 @@ __global__ __launch_bounds__(ST_THREADS) void rowvec_gemm_kernel(Geom g, StreamA
     }
 }
 
+// ---------------------------------------------------------------------------
+// LSTM step in one kernel: gate product and cell equations
+// ---------------------------------------------------------------------------
+// The ring kernel above with another choice of rows: a workgroup owns four hidden units j0 .. j0 + 3 and, of W's four
+// row blocks [i; f; g; o] of H rows each, the rows of exactly these units (operand row 4 gate + unit: W row
+// gate * H + j0 + unit), so that after the sum over the wavefronts it holds all four pre-activations of its units and
+// applies the cell equations itself (the same arithmetic as lstm_cell_kernel): no plane of pre-activations, no second
+// launch.  The four groups of rows lie in four tile rows: each one's packed I_z is copied into LDS (four copies of
+// what the ring kernel stages), the rows' I_p words are gathered with one address per lane, and the rows' mask is
+// rebuilt as above.  Needs H % 4 == 0 and r % 4 == 0 (the four rows of a gate then lie in one tile), and h outputs
+// that do not alias the input: other workgroups still read it.
+struct LstmFuse {
+    int64_t H;
+    float *C;
+    int64_t ldc;
+    uint16_t *H1;
+    int64_t ldh1;
+    uint16_t *H2;
+    int64_t ldh2;
+    int fp_words; // I_p words per tile column in LDS: 16 rows x ipw
+    int fp_instr; // copy instructions for all of them
+};
+
+__device__ __forceinline__ float lstm_sigm(float z) { return 1.f / (1.f + expf(-z)); }
+
+template <typename Tag, int NS>
+__global__ __launch_bounds__(ST_THREADS) void stream_lstm_kernel(Geom g, StreamArgs a, LstmFuse f)
+{
+    constexpr int BM = 16, KS = 256;
+    constexpr int ROWS_PER_PIECE = 2;
+    constexpr int STEPS = KS / 32;
+    extern __shared__ uint4 lrbi_dyn_smem[];
+    unsigned char *smem = (unsigned char *)lrbi_dyn_smem;
+    unsigned char *Wst = smem;                                  // [NS][ST_WSTAGE]
+    unsigned char *Xst = smem + NS * ST_WSTAGE;                  // [NS][x_stage]
+    uint32_t *Ms = (uint32_t *)(Xst + (size_t)NS * a.x_stage);   // [16][ms_pitch]: the rows' whole mask
+    uint32_t *Fz = Ms + BM * a.ms_pitch;                         // [4 gates][fz_pad]: [tile_cols][k][izw] each
+    uint32_t *Fp = Fz + 4 * a.fz_pad;                            // [tile_cols][16 rows][ipw]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t j0 = (int64_t)blockIdx.x * 4;
+    const int units_here = (int)((f.H - j0 < 4) ? f.H - j0 : 4); // (H % 4 == 0: always 4; kept for safety)
+    const int n = (int)g.n;
+    const int N = a.N;
+    const int nslabs = (n + KS - 1) / KS;
+
+    // operand row rr = 4 gate + unit -> row of W, its tile row and its row inside the tile
+    auto w_row = [&](int rr) -> int64_t {
+        const int gate = rr >> 2;
+        int unit = rr & 3;
+        if (unit >= units_here) unit = units_here - 1; // repeats a row; its results are dropped
+        return (int64_t)gate * f.H + j0 + unit;
+    };
+
+    // ---- this wavefront's share of a slab's copies: piece `wave` of the W slab = operand rows 2 wave (lanes 0-31)
+    // and 2 wave + 1 (lanes 32-63), 512 bytes each; columns past n - 8 are clamped (they meet zero mask bits)
+    const uint32_t my_wrow_off = (uint32_t)(w_row(wave * ROWS_PER_PIECE + (lane >> 5)) * a.ldw * 2); // below 2^32: host
+    const int my_col = 8 * (lane & 31);
+    const int my_x_instr = (a.x_instr > wave ? 1 : 0) + (a.x_instr > wave + ST_WAVES ? 1 : 0);
+    const int my_per_slab = 1 + my_x_instr;
+    auto copy_slab = [&](int slab) {
+        const int stage = slab % NS;
+        const int k0 = slab * KS;
+        int col = k0 + my_col;
+        if (col > n - 8) col = n - 8;
+        load_to_lds16(lds_address(Wst + stage * ST_WSTAGE + wave * ST_WPIECE), a.W, my_wrow_off + (uint32_t)col * 2u);
+        const uint32_t x_lds = lds_address(Xst + (size_t)stage * a.x_stage);
+        const uint32_t first = (uint32_t)(((int64_t)k0 * N * 2) >> 4);
+        for (int i = wave; i < a.x_instr; i += ST_WAVES) {
+            uint32_t piece = first + 64u * i + lane;
+            if (piece >= a.x_pieces) piece = a.x_pieces - 1u;
+            load_to_lds16(x_lds + 1024u * i, a.X, piece * 16u);
+        }
+    };
+
+    // ---- factor copies: per gate the packed I_z of its tile row (as the ring kernel's, spread over the wavefronts),
+    // then the I_p words: entry e = (tile column, operand row, word), one per lane and copy instruction
+    auto stage_factors = [&]() {
+        for (int gate = 0; gate < 4; ++gate) {
+            const int ti = (int)(w_row(4 * gate) / g.r);
+            const uint32_t *zsrc = a.Iz + (int64_t)ti * g.tile_cols * g.k * (int64_t)g.izw;
+            uint32_t *dst = Fz + gate * a.fz_pad;
+            if (a.fz_vec) {
+                const int pieces = a.fz_words >> 2;
+                for (int p0 = wave * 64; p0 < pieces; p0 += ST_THREADS) {
+                    int p = p0 + lane;
+                    if (p >= pieces) p = pieces - 1;
+                    load_to_lds16(lds_address(dst + 4 * p0), zsrc, 16u * (uint32_t)p);
+                }
+            } else {
+                for (int w0 = wave * 64; w0 < a.fz_words; w0 += ST_THREADS) {
+                    int w = w0 + lane;
+                    if (w >= a.fz_words) w = a.fz_words - 1;
+                    load_to_lds4(lds_address(dst + w0), zsrc, 4u * (uint32_t)w);
+                }
+            }
+        }
+        const int entries = g.tile_cols * f.fp_words;
+        for (int i = wave; i < f.fp_instr; i += ST_WAVES) {
+            int e = i * 64 + lane;
+            if (e >= entries) e = entries - 1;
+            const int tj = e / f.fp_words, rem = e - tj * f.fp_words;
+            const int rr = rem / g.ipw, iw = rem - rr * g.ipw;
+            const int64_t row = w_row(rr);
+            const int ti = (int)(row / g.r);
+            const int il = (int)(row - (int64_t)ti * g.r);
+            const int64_t word = ((((int64_t)ti * g.tile_cols + tj) * g.r) + il) * g.ipw + iw; // below 2^30: host
+            load_to_lds4(lds_address(Fp + i * 64), a.Ip, (uint32_t)word * 4u);
+        }
+    };
+    const int my_factor_instr_max = 0; // (the factor copies are older than every slab copy: waited for by count)
+    (void)my_factor_instr_max;
+    // Eq. 3 from the factors in LDS: wavefront w takes operand rows w and w + 8, its lanes the (tile, word) pairs
+    auto decode_rows = [&]() {
+        const uint32_t items = (uint32_t)g.tile_cols * (uint32_t)g.izw;
+        for (int rl = wave; rl < BM; rl += ST_WAVES) {
+            if ((rl & 3) >= units_here) continue;
+            const uint32_t *fz = Fz + (rl >> 2) * a.fz_pad;
+            for (uint32_t j = lane; j < items; j += 64) {
+                const uint32_t tj = (g.izw == 1) ? j : __umulhi(j, a.izw_magic);
+                const uint32_t wz = j - tj * (uint32_t)g.izw;
+                const int in_tile = (int)wz * 32;
+                const int col0 = (int)tj * g.c + in_tile;
+                if (in_tile >= g.c || col0 >= n) continue;
+                uint32_t v = 0u;
+                const uint32_t *zcol = fz + (size_t)tj * g.k * g.izw + wz;
+                for (int iw = 0; iw < g.ipw; ++iw) {
+                    uint32_t sel = Fp[tj * f.fp_words + rl * g.ipw + iw];
+                    while (sel) {
+                        const int l0 = __builtin_ctz(sel);
+                        sel &= sel - 1u;
+                        const int l1 = sel ? __builtin_ctz(sel) : l0;
+                        sel &= sel - 1u;
+                        const int l2 = sel ? __builtin_ctz(sel) : l1;
+                        sel &= sel - 1u;
+                        const int l3 = sel ? __builtin_ctz(sel) : l2;
+                        sel &= sel - 1u;
+                        const uint32_t z0 = zcol[(32 * iw + l0) * g.izw], z1 = zcol[(32 * iw + l1) * g.izw];
+                        const uint32_t z2 = zcol[(32 * iw + l2) * g.izw], z3 = zcol[(32 * iw + l3) * g.izw];
+                        v |= (z0 | z1) | (z2 | z3);
+                    }
+                }
+                const int lim = (g.c - in_tile < n - col0) ? g.c - in_tile : n - col0;
+                if (lim < 32) v &= (1u << lim) - 1u;
+                if (v == 0u) continue;
+                uint32_t *dst = Ms + rl * a.ms_pitch + (col0 >> 5);
+                const int sh = col0 & 31;
+                __hip_atomic_fetch_or(dst, v << sh, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (sh && (v >> (32 - sh)))
+                    __hip_atomic_fetch_or(dst + 1, v >> (32 - sh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+    };
+
+    // ---- arithmetic: as the ring kernel's
+    const int row16 = lane & 15, kg = lane >> 4;
+    f32x4 acc[2];
+    acc[0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int nblocks = (N > 16) ? 2 : 1;
+    auto multiply_slab = [&](int slab) {
+        const int stage = slab % NS;
+        const unsigned char *ws = Wst + stage * ST_WSTAGE + (row16 / ROWS_PER_PIECE) * ST_WPIECE +
+                                  (row16 % ROWS_PER_PIECE) * (KS * 2);
+        const unsigned char *xs = Xst + (size_t)stage * a.x_stage;
+        const unsigned char *mb = (const unsigned char *)(Ms + row16 * a.ms_pitch + slab * STEPS);
+        const int step = wave;
+        const int kk = step * 32 + 8 * kg;
+        const u32x4 wf = *reinterpret_cast<const u32x4 *>(ws + kk * 2);
+        const u32x4 am = apply_mask8(wf, mb[step * 4 + kg]);
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            if (cb >= nblocks) break;
+            const unsigned char *p = xs + ((size_t)(kk + (row16 >> 2)) * N + cb * 16 + 4 * (row16 & 3)) * 2;
+            const u32x2 lo = lds_read_tr16_v((const uint16_t *)p);
+            const u32x2 hi = lds_read_tr16_v((const uint16_t *)(p + (size_t)4 * N * 2));
+            const u32x4 xf = {lo.x, lo.y, hi.x, hi.y};
+            acc[cb] = mfma_16x16x32(Tag{}, am, xf, acc[cb]);
+        }
+    };
+
+#define LRBI_BARRIER()                                      \
+    do {                                                    \
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  \
+        __builtin_amdgcn_s_barrier();                       \
+        asm volatile("" ::: "memory");                      \
+    } while (0)
+
+    stage_factors();
+    constexpr int EARLY = NS - 1 < 2 ? NS - 1 : 2;
+    for (int s = 0; s < EARLY; ++s) copy_slab(s);
+    for (int i = tid; i < BM * a.ms_pitch; i += ST_THREADS) Ms[i] = 0u;
+    wait_loads_at_most(EARLY * my_per_slab);
+    LRBI_BARRIER();
+    for (int s = EARLY; s < NS - 1; ++s) copy_slab(s);
+    decode_rows();
+    for (int s = 0; s < nslabs; ++s) {
+        wait_loads_at_most((NS - 2) * my_per_slab);
+        LRBI_BARRIER();
+        copy_slab(s + NS - 1);
+        multiply_slab(s);
+    }
+    wait_loads<0>();
+    LRBI_BARRIER();
+
+    // wavefronts' partial accumulators -> LDS; lane holds operand rows 4 kg + v, column row16 of each 16 x 16 block
+    float *red = (float *)smem; // [8][2][16][16]
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[((wave * 2 + cb) * 16 + 4 * kg + v) * 16 + row16] = acc[cb][v];
+    LRBI_BARRIER();
+#undef LRBI_BARRIER
+    // one lane per (unit, batch column): the four pre-activations (sums over the wavefronts, in wavefront order),
+    // then c = sigm(z_f) c + sigm(z_i) tanh(z_g), h = sigm(z_o) tanh(c)
+    for (int e = tid; e < units_here * N; e += ST_THREADS) {
+        const int unit = e / N, b = e - unit * N;
+        const int cb = b >> 4, cc = b & 15;
+        float z[4];
+#pragma unroll
+        for (int gate = 0; gate < 4; ++gate) {
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < ST_WAVES; ++w) v += red[((w * 2 + cb) * 16 + 4 * gate + unit) * 16 + cc];
+            z[gate] = v;
+        }
+        const int64_t j = j0 + unit;
+        const float c = lstm_sigm(z[1]) * f.C[j * f.ldc + b] + lstm_sigm(z[0]) * tanhf(z[2]);
+        const float h = lstm_sigm(z[3]) * tanhf(c);
+        f.C[j * f.ldc + b] = c;
+        const uint16_t hs = cvt_store(Tag{}, h);
+        f.H1[j * f.ldh1 + b] = hs;
+        if (f.H2) f.H2[j * f.ldh2 + b] = hs;
+    }
+}
+
 // The kernel serves: f16 / bf16, N = 1 or a multiple of 4 up to 32, X contiguous ([n][N] with ldx = N) and 16-byte
 // aligned, W rows 16-byte aligned, n a multiple of 8, a tile row's packed I_z small enough for LDS, and enough rows to
 // give every compute unit a workgroup or so.
@@ -601,6 +839,75 @@ int launch_stream_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw
     a.fz_vec = ((((uintptr_t)dIz) & 15) == 0 && (a.fz_words & 3) == 0) ? 1 : 0;
     if (dt == LRBI_F16) return launch_stream_shape<F16Tag>(g, p, stream);
     if (dt == LRBI_BF16) return launch_stream_shape<BF16Tag>(g, p, stream);
+    return LRBI_ERR_DTYPE;
+}
+
+// The fused LSTM step serves what the ring kernel serves at 4 to 32 columns (the caller has checked stream_ok()), when
+// in addition H = m / 4 and the tile height are multiples of 4, offsets fit 32 bits and LDS holds four tile rows' I_z.
+// Returns LRBI_ERR_SHAPE otherwise: the caller then runs the product and the cell kernel one after the other.
+template <typename Tag, int NS>
+static int launch_stream_lstm_t(const Geom &g, const StreamPlan &p, const LstmFuse &f, hipStream_t stream)
+{
+    auto kern = stream_lstm_kernel<Tag, NS>;
+    LRBI_SET_MAX_LDS(kern, p.lds);
+    LRBI_LAUNCH(kern, dim3(p.grid), dim3(ST_THREADS), p.lds, stream, g, p.a, f);
+    return LRBI_OK;
+}
+
+int launch_stream_lstm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
+                       const uint32_t *dIz, const void *dXH, int64_t B, float *dC, int64_t ldc, void *dH1, int64_t ldh1,
+                       void *dH2, int64_t ldh2, int cus, hipStream_t stream)
+{
+    if (B < 4 || B > 32 || B % 4 != 0) return LRBI_ERR_SHAPE;
+    const int64_t H = g.m / 4;
+    if (g.m % 4 != 0 || H % 4 != 0 || g.r % 4 != 0) return LRBI_ERR_SHAPE;
+    if ((uint64_t)g.m * (uint64_t)ldw * 2u >= ((uint64_t)1 << 32)) return LRBI_ERR_SHAPE;
+    const int64_t tiles = (int64_t)g.tile_rows * g.tile_cols;
+    if (tiles * g.r * g.ipw >= ((int64_t)1 << 30)) return LRBI_ERR_SHAPE;
+    StreamPlan p;
+    if (!plan_stream(g, B, cus, p)) return LRBI_ERR_SHAPE;
+    StreamArgs &a = p.a;
+    LstmFuse f;
+    f.H = H;
+    f.C = dC;
+    f.ldc = ldc;
+    f.H1 = (uint16_t *)dH1;
+    f.ldh1 = ldh1;
+    f.H2 = (uint16_t *)dH2;
+    f.ldh2 = ldh2;
+    f.fp_words = 16 * g.ipw;
+    f.fp_instr = (g.tile_cols * f.fp_words + 63) / 64;
+    const size_t fixed = ((size_t)16 * a.ms_pitch + (size_t)4 * a.fz_pad + (size_t)f.fp_instr * 64) * 4;
+    int ns = 0;
+    for (int cand : {6, 4, 3}) {
+        if ((size_t)cand * (ST_WSTAGE + a.x_stage) + fixed <= 80 * 1024) {
+            ns = cand;
+            break;
+        }
+    }
+    if (ns == 0) return LRBI_ERR_SHAPE;
+    p.lds = (size_t)ns * (ST_WSTAGE + a.x_stage) + fixed;
+    p.grid = (unsigned)(H / 4);
+    a.W = (const uint16_t *)dW;
+    a.ldw = ldw;
+    a.Ip = dIp;
+    a.Iz = dIz;
+    a.X = (const uint16_t *)dXH;
+    a.N = (int)B;
+    a.Y = nullptr;
+    a.ldy = 0;
+    a.P = nullptr;
+    a.ldp = 0;
+    a.fz_vec = ((((uintptr_t)dIz) & 15) == 0 && (a.fz_words & 3) == 0) ? 1 : 0;
+#define LRBI_LSTM_NS(TAG)                                                     \
+    switch (ns) {                                                             \
+    case 6: return launch_stream_lstm_t<TAG, 6>(g, p, f, stream);             \
+    case 4: return launch_stream_lstm_t<TAG, 4>(g, p, f, stream);             \
+    default: return launch_stream_lstm_t<TAG, 3>(g, p, f, stream);            \
+    }
+    if (dt == LRBI_F16) { LRBI_LSTM_NS(F16Tag) }
+    if (dt == LRBI_BF16) { LRBI_LSTM_NS(BF16Tag) }
+#undef LRBI_LSTM_NS
     return LRBI_ERR_DTYPE;
 }
 

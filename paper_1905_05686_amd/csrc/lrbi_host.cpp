@@ -614,6 +614,21 @@ extern "C" int lrbi_lstm_step(const lrbi_desc *desc, lrbi_dtype dtype, const voi
         // narrow batches: the row-streaming kernel leaves the fp32 pre-activations as a single plane
         const int cus = compute_units_of((hipStream_t)stream);
         if (stream_ok(g, dtype, dW, ldw, dXH, ldxh, B, cus)) {
+            // One kernel (product and cell equations) when h does not go into the buffer the product reads: there
+            // other workgroups would still be reading what the first ones overwrite.
+            const char *x0 = (const char *)dXH, *x1 = x0 + ((desc->n - 1) * ldxh + B) * 2;
+            const int64_t Hh = desc->m / 4;
+            auto overlaps_input = [&](const void *p, int64_t ld) {
+                if (!p) return false;
+                const char *h0 = (const char *)p, *h1 = h0 + ((Hh - 1) * ld + B) * 2;
+                return h0 < x1 && x0 < h1;
+            };
+            if (B > 1 && !overlaps_input(dH1, ldh1) && !overlaps_input(dH2, ldh2)) {
+                const int rcf = launch_stream_lstm(g, dtype, dW, ldw, (const uint32_t *)dIp_packed,
+                                                   (const uint32_t *)dIz_packed, dXH, B, dC, ldc, dH1, ldh1, dH2, ldh2, cus,
+                                                   (hipStream_t)stream);
+                if (rcf != LRBI_ERR_SHAPE) return rcf; // done, or a launch error; LRBI_ERR_SHAPE: not served, go on
+            }
             const int64_t ldp = (B + 3) / 4 * 4;
             const int rc1 = launch_stream_gemm(g, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
                                                dXH, B, nullptr, 0, (float *)dWorkspace, ldp, cus, (hipStream_t)stream);

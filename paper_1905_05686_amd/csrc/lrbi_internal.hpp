@@ -111,6 +111,9 @@ bool mfma_gemm_emits_mask(const Geom &g, const MfmaPlan &plan, const void *dW, i
 
 // row-streaming kernel for narrow batches (lrbi_gemm_stream.hip)
 bool stream_ok(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const void *dX, int64_t ldx, int64_t N, int cus);
+int launch_stream_lstm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
+                       const uint32_t *dIz, const void *dXH, int64_t B, float *dC, int64_t ldc, void *dH1, int64_t ldh1,
+                       void *dH2, int64_t ldh2, int cus, hipStream_t stream);
 int launch_stream_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
                        const uint32_t *dIz, const void *dX, int64_t N, void *dY, int64_t ldy, float *dP, int64_t ldp,
                        int cus, hipStream_t stream);

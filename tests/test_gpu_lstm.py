@@ -121,6 +121,54 @@ def test_fused_lstm_step_against_the_oracle():
         assert eh <= 1e-2 and ec <= 1e-2
 
 
+def test_lstm_step_single_kernel_form():
+    """When h does not go into the buffer the step reads, product and cell equations run as one kernel (a workgroup
+    owns the four gate rows of its hidden units).  Same bits as the two-launch form (forced here by letting the second
+    h output alias the input), and the free-running 2 x 35 sequence with alternating input buffers against the oracle."""
+    L = workloads.make_lstm()
+    cfg = L["cfg"]
+    H, B, steps, layers = L["hidden"], L["batch"], L["steps"], L["layers"]
+    desc = desc_of(cfg)
+    dW = [to_device(w, cfg.dtype) for w in L["W"]]
+    fac = [device_factors(desc, L["Ip01"][l], L["Iz01"][l]) for l in range(layers)]
+    ws = torch.empty(lrbi.lstm_step_workspace_bytes(desc, lrbi.F16, B), dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(21)
+    xh_host = (rng.standard_normal((2 * H, B)) * 0.5).astype(np.float16)
+    c_prev = rng.standard_normal((H, B)).astype(np.float32)
+    outs = []
+    for alias in (False, True):
+        xh = torch.from_numpy(xh_host.copy()).cuda()
+        C = torch.from_numpy(c_prev.copy()).cuda()
+        h1 = torch.full((H, B), 7.0, dtype=torch.float16, device="cuda")
+        h2 = xh[:H] if alias else None
+        print("lstm single-kernel form, alias", alias, flush=True)
+        lrbi.lstm_step(desc, dW[0], fac[0][0], fac[0][1], xh, C, h1, h2, workspace=ws)
+        torch.cuda.synchronize()
+        outs.append((C.clone(), h1.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+    Ws64 = [workloads.to_float64(w, cfg.dtype) for w in L["W"]]
+    Ms = [orc.decode_mask(L["Ip01"][l], L["Iz01"][l], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k) for l in range(layers)]
+    ref = lstm_oracle.lstm_sequence(Ws64, Ms, workloads.to_float64(L["x"], cfg.dtype), round_input=_round_f16,
+                                    threads=ORACLE_THREADS)
+    xs = to_device(L["x"], cfg.dtype)
+    xh = [[torch.zeros((2 * H, B), dtype=torch.float16, device="cuda") for _ in range(2)] for _ in range(layers)]
+    c = [torch.zeros((H, B), dtype=torch.float32, device="cuda") for _ in range(layers)]
+    print("lstm single-kernel form, free-running", flush=True)
+    for t in range(steps):
+        cur, nxt = t % 2, (t + 1) % 2
+        xh[0][cur][:H].copy_(xs[t])
+        for l in range(layers):
+            up = xh[l + 1][cur][:H] if l + 1 < layers else None
+            lrbi.lstm_step(desc, dW[l], fac[l][0], fac[l][1], xh[l][cur], c[l], xh[l][nxt][H:], up, workspace=ws)
+    torch.cuda.synchronize()
+    for l in range(layers):
+        eh = orc.rel_err(to_float64(xh[l][steps % 2][H:]), ref["h"][l])
+        ec = orc.rel_err(to_float64(c[l]), ref["c"][l])
+        print("single-kernel free-running layer %d: h err %.3e, c err %.3e" % (l, eh, ec), flush=True)
+        assert eh <= 1e-2 and ec <= 1e-2
+
+
 @pytest.mark.parametrize("H,n,r,c,k,B,dtype", [
     (64, 128, 64, 64, 4, 20, "f16"),       # one slice: a single plane in the workspace
     (75, 152, 100, 76, 8, 3, "bf16"),      # tiles that fit no tuned kernel, tiny batch, cut-off edge tiles
