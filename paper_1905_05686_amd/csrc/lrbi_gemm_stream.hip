@@ -577,8 +577,6 @@ __global__ __launch_bounds__(ST_THREADS) void stream_lstm_kernel(Geom g, StreamA
             load_to_lds4(lds_address(Fp + i * 64), a.Ip, (uint32_t)word * 4u);
         }
     };
-    const int my_factor_instr_max = 0; // (the factor copies are older than every slab copy: waited for by count)
-    (void)my_factor_instr_max;
     // Eq. 3 from the factors in LDS: wavefront w takes operand rows w and w + 8, its lanes the (tile, word) pairs
     auto decode_rows = [&]() {
         const uint32_t items = (uint32_t)g.tile_cols * (uint32_t)g.izw;
