@@ -174,6 +174,11 @@ def test_lstm_step_single_kernel_form():
     (75, 152, 100, 76, 8, 3, "bf16"),      # tiles that fit no tuned kernel, tiny batch, cut-off edge tiles
     (128, 512, 128, 128, 8, 36, "f16"),    # tuned product kernel, several slices
     (256, 1024, 256, 256, 16, 128, "bf16"),
+    # enough rows for the row-streaming kernels, h apart from the input: the step as one kernel
+    (512, 520, 256, 130, 6, 12, "bf16"),   # a short last slab, tiles cut through mask words, one block of columns
+    (512, 512, 128, 128, 8, 32, "f16"),    # both blocks of columns; a gate's rows start a tile
+    (516, 256, 172, 64, 5, 4, "f16"),      # tile height no multiple of 16: the units of a workgroup sit anywhere in a tile
+    (510, 256, 170, 64, 5, 8, "f16"),      # H and r no multiples of 4: two launches
 ])
 def test_fused_lstm_step_small_shapes(H, n, r, c, k, B, dtype):
     cfg = workloads.Config("t", 4 * H, n, r, c, k, 0.2, B, dtype, 0.1, 5)
