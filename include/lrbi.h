@@ -204,8 +204,11 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
  * lrbi_masked_gemm_workspace_bytes).  For f16 / bf16 layers whose tile shape lines up with the tile kernel
  * (c % 128 == 0, r % 128 == 0, k <= 64, no cut-off tiles, N > 64, X and W readable in 16-byte pieces) this is one
  * product launch (plus the split reduction when the plan splits): the kernel rebuilds every mask byte for its own
- * use and stores it on the way, so the stand-alone decode kernel and its launch drop out.  Every other case runs
- * lrbi_decode_mask and then lrbi_masked_gemm on `stream`.  Results are bit-identical to those two calls.
+ * use and stores it on the way, so the stand-alone decode kernel and its launch drop out.  The same holds for the
+ * narrow batches that the row-streaming kernels serve (f16 / bf16, N = 1 or a multiple of 4 up to 32, any tile
+ * shape): a workgroup rebuilds the whole mask of its rows before its first product and stores it from there.
+ * Every other case runs lrbi_decode_mask and then lrbi_masked_gemm on `stream`.  Results are bit-identical to those
+ * two calls.
  * Errors: those of the two entry points.
  */
 int lrbi_decode_and_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,

@@ -109,6 +109,9 @@ struct StreamArgs {
     int fz_vec;    // the tile rows' slices of I_z are 16-byte aligned whole numbers of 16-byte pieces
     int fp_pitch;  // LDS words per tile for the I_p words of 16 rows: 16 * ipw rounded up to whole copy instructions
     int ms_pitch;  // mask words per row in LDS (odd, at least 8 per slab)
+    uint32_t *mask_out;   // not null: the rows' mask also goes to global memory, in the stand-alone decode's layout
+    int64_t mask_pitch32; // 32-bit words per row of that mask
+    int mask_words;       // words per row that the decode writes: whole 16-byte pieces up to column n
     uint32_t izw_magic; // floor(2^32 / izw) + 1: an index below 2^16 times this, upper 32 bits, is the index / izw
 };
 
@@ -196,6 +199,17 @@ __device__ __forceinline__ void decode_row_masks(const Geom &g, const StreamArgs
             if (sh && (v >> (32 - sh)))
                 __hip_atomic_fetch_or(dst + 1, v >> (32 - sh), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
+    }
+}
+
+// The rows' mask as the stand-alone decode leaves it in global memory (one bit per weight, pad bits zero): the
+// workgroup has just rebuilt exactly these words in LDS.  Call behind the barrier that publishes them.
+__device__ __forceinline__ void store_row_masks(const StreamArgs &a, const uint32_t *Ms, int64_t m0, int rows_here, int tid)
+{
+    if (!a.mask_out) return;
+    for (int i = tid; i < rows_here * a.mask_words; i += ST_THREADS) {
+        const int row = i / a.mask_words, w = i - row * a.mask_words;
+        a.mask_out[(m0 + row) * a.mask_pitch32 + w] = Ms[row * a.ms_pitch + w];
     }
 }
 
@@ -322,6 +336,7 @@ __global__ __launch_bounds__(ST_THREADS) void stream_gemm_kernel(Geom g, StreamA
         multiply_slab(s);
     }
     wait_loads<0>(); // nothing may still be landing when the stages are reused below
+    store_row_masks(a, Ms, m0, rows_here, tid); // (behind the loop: a store inside it would enter the counted waits)
     LRBI_BARRIER();
 
     // wavefronts' partial accumulators -> LDS; lane holds rows 4 kg + v, column row16 of each 16 x 16 block
@@ -444,6 +459,7 @@ __global__ __launch_bounds__(ST_THREADS) void rowvec_gemm_kernel(Geom g, StreamA
     asm volatile("" ::: "memory");
 #pragma unroll
     for (int p = H; p < P; ++p) w[p] = load_piece(p);
+    store_row_masks(a, Ms, m0, rows_here, tid);
 
     const unsigned char *mb = (const unsigned char *)(Ms + my_row * a.ms_pitch);
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f; // four chains, added in a fixed order
@@ -819,7 +835,7 @@ template <typename Tag> static int launch_stream_shape(const Geom &g, const Stre
 // dY (storage dtype) and / or dP (fp32) receive the product; the caller has checked stream_ok() with the same cus
 int launch_stream_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
                        const uint32_t *dIz, const void *dX, int64_t N, void *dY, int64_t ldy, float *dP, int64_t ldp,
-                       int cus, hipStream_t stream)
+                       int cus, hipStream_t stream, MaskOut mo)
 {
     StreamPlan p;
     if (!plan_stream(g, N, cus, p)) return LRBI_ERR_SHAPE;
@@ -835,6 +851,9 @@ int launch_stream_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw
     a.P = dP;
     a.ldp = ldp;
     a.fz_vec = ((((uintptr_t)dIz) & 15) == 0 && (a.fz_words & 3) == 0) ? 1 : 0;
+    a.mask_out = (uint32_t *)mo.ptr;
+    a.mask_pitch32 = mo.pitch16 * 4;
+    a.mask_words = (int)((g.n + 127) / 128 * 4);
     if (dt == LRBI_F16) return launch_stream_shape<F16Tag>(g, p, stream);
     if (dt == LRBI_BF16) return launch_stream_shape<BF16Tag>(g, p, stream);
     return LRBI_ERR_DTYPE;
@@ -897,6 +916,9 @@ int launch_stream_lstm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw
     a.P = nullptr;
     a.ldp = 0;
     a.fz_vec = ((((uintptr_t)dIz) & 15) == 0 && (a.fz_words & 3) == 0) ? 1 : 0;
+    a.mask_out = nullptr;
+    a.mask_pitch32 = 0;
+    a.mask_words = 0;
 #define LRBI_LSTM_NS(TAG)                                                     \
     switch (ns) {                                                             \
     case 6: return launch_stream_lstm_t<TAG, 6>(g, p, f, stream);             \

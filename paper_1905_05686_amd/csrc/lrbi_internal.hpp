@@ -116,7 +116,7 @@ int launch_stream_lstm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw
                        void *dH2, int64_t ldh2, int cus, hipStream_t stream);
 int launch_stream_gemm(const Geom &g, lrbi_dtype dt, const void *dW, int64_t ldw, const uint32_t *dIp,
                        const uint32_t *dIz, const void *dX, int64_t N, void *dY, int64_t ldy, float *dP, int64_t ldp,
-                       int cus, hipStream_t stream);
+                       int cus, hipStream_t stream, MaskOut mo = {nullptr, 0});
 
 // a 3 x 3 convolution with padding 1 read as a product (lrbi_gemm_pipe.hip): the activation is zero-padded,
 // [batch][H + 2][Wd + 2][cin] with channels fastest; reduction index = (kh * 3 + kw) * cin + ci

@@ -267,6 +267,12 @@ FUSED = [
     _small(130, 264, 65, 33, 5, 0.3, 70, "bf16"),        # general tile kernel
     _small(50, 120, 25, 60, 4, 0.2, 3, "f32"),
     workloads.CONFIGS["C2"],                             # the benchmark's workload at full size
+    # narrow batches with enough rows for the row-streaming kernels: they store the rows' mask from LDS
+    _small(3000, 600, 300, 300, 8, 0.12, 20, "f16"),     # ring kernel, tiles cut through mask words, last workgroups short
+    _small(2048, 1024, 256, 128, 8, 0.15, 1, "bf16"),    # single-column kernel
+    _small(1040, 4104, 65, 1368, 9, 0.1, 1, "bf16"),     # single-column kernel, n no multiple of 128: the last piece's pad bits
+    workloads.CONFIGS["C3a"],
+    workloads.CONFIGS["C4"],
 ]
 
 
