@@ -271,6 +271,7 @@ FUSED = [
     _small(3000, 600, 300, 300, 8, 0.12, 20, "f16"),     # ring kernel, tiles cut through mask words, last workgroups short
     _small(2048, 1024, 256, 128, 8, 0.15, 1, "bf16"),    # single-column kernel
     _small(1040, 4104, 65, 1368, 9, 0.1, 1, "bf16"),     # single-column kernel, n no multiple of 128: the last piece's pad bits
+    _small(1040, 8704, 520, 1088, 6, 0.15, 1, "bf16"),   # one column over rows longer than 8192: the ring kernel's 8-row form
     workloads.CONFIGS["C3a"],
     workloads.CONFIGS["C4"],
 ]
