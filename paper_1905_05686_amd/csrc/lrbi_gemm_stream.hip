@@ -561,23 +561,24 @@ __global__ __launch_bounds__(ST_THREADS) void stream_lstm_kernel(Geom g, StreamA
     // ---- factor copies: per gate the packed I_z of its tile row (as the ring kernel's, spread over the wavefronts),
     // then the I_p words: entry e = (tile column, operand row, word), one per lane and copy instruction
     auto stage_factors = [&]() {
-        for (int gate = 0; gate < 4; ++gate) {
+        // (the copy instructions of the four gates in one list, dealt round the wavefronts: the wavefront with the
+        // most copies sets the time)
+        const int per_instr = a.fz_vec ? 256 : 64; // words per copy instruction
+        const int instr_per_gate = (a.fz_words + per_instr - 1) / per_instr;
+        for (int q = wave; q < 4 * instr_per_gate; q += ST_WAVES) {
+            const int gate = q / instr_per_gate, chunk = q - gate * instr_per_gate;
             const int ti = (int)(w_row(4 * gate) / g.r);
             const uint32_t *zsrc = a.Iz + (int64_t)ti * g.tile_cols * g.k * (int64_t)g.izw;
-            uint32_t *dst = Fz + gate * a.fz_pad;
+            uint32_t *dst = Fz + gate * a.fz_pad + chunk * per_instr;
             if (a.fz_vec) {
                 const int pieces = a.fz_words >> 2;
-                for (int p0 = wave * 64; p0 < pieces; p0 += ST_THREADS) {
-                    int p = p0 + lane;
-                    if (p >= pieces) p = pieces - 1;
-                    load_to_lds16(lds_address(dst + 4 * p0), zsrc, 16u * (uint32_t)p);
-                }
+                int p = chunk * 64 + lane;
+                if (p >= pieces) p = pieces - 1;
+                load_to_lds16(lds_address(dst), zsrc, 16u * (uint32_t)p);
             } else {
-                for (int w0 = wave * 64; w0 < a.fz_words; w0 += ST_THREADS) {
-                    int w = w0 + lane;
-                    if (w >= a.fz_words) w = a.fz_words - 1;
-                    load_to_lds4(lds_address(dst + w0), zsrc, 4u * (uint32_t)w);
-                }
+                int w = chunk * 64 + lane;
+                if (w >= a.fz_words) w = a.fz_words - 1;
+                load_to_lds4(lds_address(dst), zsrc, 4u * (uint32_t)w);
             }
         }
         const int entries = g.tile_cols * f.fp_words;
