@@ -201,14 +201,14 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
 /*
  * Rows a1-a6 of the hot path in one call: the decoded mask (Eq. 3, layout and pitch rules of lrbi_decode_mask)
  * AND the fused masked product Y = (W o I_a) X (arguments of lrbi_masked_gemm, workspace as sized by
- * lrbi_masked_gemm_workspace_bytes).  For f16 / bf16 layers whose tile shape lines up with the tile kernel
- * (c % 128 == 0, r % 128 == 0, k <= 64, no cut-off tiles, N > 64, X and W readable in 16-byte pieces) this is one
- * product launch (plus the split reduction when the plan splits): the kernel rebuilds every mask byte for its own
- * use and stores it on the way, so the stand-alone decode kernel and its launch drop out.  The same holds for the
- * narrow batches that the row-streaming kernels serve (f16 / bf16, N = 1 or a multiple of 4 up to 32, any tile
- * shape): a workgroup rebuilds the whole mask of its rows before its first product and stores it from there.
- * Every other case runs lrbi_decode_mask and then lrbi_masked_gemm on `stream`.  Results are bit-identical to those
- * two calls.
+ * lrbi_masked_gemm_workspace_bytes).  For f16 / bf16 layers this is one product launch (plus the split reduction
+ * when the plan splits) on the kernels that rebuild the mask in a form they can store on the way, so that the
+ * stand-alone decode kernel and its launch drop out: the pipelined tile kernel (c % 128 == 0, r % 128 == 0, k <= 64,
+ * no cut-off tiles, N > 64, X and W readable in 16-byte pieces), the generic tile kernel (any tile shape and rank,
+ * cut-off tiles, N > 4, W readable in 16-byte pieces), and the row-streaming kernels for narrow batches (N = 1 or a
+ * multiple of 4 up to 32, any tile shape).  Every other case (fp32, the staged panel kernel at 33 to 64 columns on
+ * aligned tile shapes, unaligned W) runs lrbi_decode_mask and then lrbi_masked_gemm on `stream`.  Results are
+ * bit-identical to those two calls.
  * Errors: those of the two entry points.
  */
 int lrbi_decode_and_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, int64_t ldw,

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_kernel(
     Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
     const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ X, int64_t ldx, int N,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ P, int64_t ldp, int mblocks, int nblocks,
-    int64_t kper, int xcd_remap, int y_vec_ok)
+    int64_t kper, int xcd_remap, int y_vec_ok, uint32_t *__restrict__ mask_out, int64_t mask_pitch32)
 {
     static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -163,6 +163,7 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_kernel(
         }
     };
 
+    const int64_t mask_cols = (g.n + 127) / 128 * 128; // columns of a mask row up to the end of its last 16-byte piece
     auto decode_slab = [&](int slab, int buf) {
         const int k0 = kbeg + slab * BK;
         int tj = 0, wt = 0;
@@ -175,7 +176,22 @@ __global__ __launch_bounds__(kThreads) void mfma_gemm_kernel(
             const int idx = tid + kThreads * i;
             if (idx < BM * 2) {
                 const int row = idx >> 1, half = idx & 1;
-                Ms[buf * S::ms_words + idx] = slab_mask_word<ALIGNED>(g, Ip, Iz, m0 + row, k0, half, tj, wt);
+                const uint32_t word = slab_mask_word<ALIGNED>(g, Ip, Iz, m0 + row, k0, half, tj, wt);
+                Ms[buf * S::ms_words + idx] = word;
+                // The mask as a by-product (the stand-alone decode's layout: one bit per weight, whole 16-byte pieces
+                // per row, pad bits zero): every (row, word) is formed by exactly one workgroup of the first column
+                // block; the last slab of a row also clears what is left of the row's last 16-byte piece.
+                if (mask_out && ni == 0 && m0 + row < g.m) {
+                    const int col0 = k0 + 32 * half;
+                    uint32_t *mrow = mask_out + (m0 + row) * mask_pitch32;
+                    if (col0 < g.n) {
+                        const int64_t left = g.n - col0;
+                        mrow[col0 >> 5] = (left < 32) ? (word & ((1u << left) - 1u)) : word;
+                    } else if (col0 < mask_cols) {
+                        mrow[col0 >> 5] = 0u;
+                    }
+                    if (slab == nslabs - 1 && kend == g.n && col0 + 64 < mask_cols) mrow[(col0 + 64) >> 5] = 0u;
+                }
             }
         }
     };
@@ -801,8 +817,9 @@ static int launch_reduce(const Geom &g, const MfmaPlan &plan, int64_t N, void *d
 template <typename Tag, int BM, int BN, int WAVES_M, int WAVES_N, int RS /* 0: generic kernel */, int KGROUPS = 1>
 static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
                        const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
-                       void *dWorkspace, hipStream_t stream)
+                       void *dWorkspace, hipStream_t stream, MaskOut mo)
 {
+    if (RS > 0 && mo.ptr) return LRBI_ERR_SHAPE; // only the generic kernel leaves the mask
     const int64_t mblocks = (g.m + BM - 1) / BM;
     const int64_t nblocks = (N + BN - 1) / BN;
     const int64_t blocks = mblocks * nblocks * plan.splitk;
@@ -823,6 +840,15 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
                            (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp,      \
                            (int)mblocks, (int)nblocks, plan.kper, xcd_remap, y_vec_ok);                           \
     } while (0)
+#define LRBI_LAUNCH_GEN(KERN, SMEM)                                                                                    \
+    do {                                                                                                          \
+        auto kern = KERN;                                                                                         \
+        LRBI_SET_MAX_LDS(kern, (SMEM));                                                                           \
+        LRBI_LAUNCH(kern, grid, block, (SMEM), stream, g, (const uint16_t *)dW, ldw, dIp, dIz,             \
+                           (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp,      \
+                           (int)mblocks, (int)nblocks, plan.kper, xcd_remap, y_vec_ok, (uint32_t *)mo.ptr,        \
+                           mo.pitch16 * 4);                                                                       \
+    } while (0)
 
     if constexpr (RS > 0) {
         const size_t smem = SmemPanel<BM, BN>::bytes;
@@ -837,33 +863,34 @@ static int launch_tile(const Geom &g, const MfmaPlan &plan, const void *dW, int6
         const size_t smem = Smem<BM, BN>::bytes;
         if (aligned) {
             if (xvec) {
-                if (split) LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, true>), smem);
-                else LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, false>), smem);
+                if (split) LRBI_LAUNCH_GEN((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, true>), smem);
+                else LRBI_LAUNCH_GEN((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, true, false>), smem);
             } else {
-                if (split) LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, true>), smem);
-                else LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, false>), smem);
+                if (split) LRBI_LAUNCH_GEN((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, true>), smem);
+                else LRBI_LAUNCH_GEN((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, true, false, false>), smem);
             }
         } else {
             if (xvec) {
-                if (split) LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, true>), smem);
-                else LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, false>), smem);
+                if (split) LRBI_LAUNCH_GEN((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, true>), smem);
+                else LRBI_LAUNCH_GEN((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, true, false>), smem);
             } else {
-                if (split) LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, true>), smem);
-                else LRBI_LAUNCH_TILE((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, false>), smem);
+                if (split) LRBI_LAUNCH_GEN((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, true>), smem);
+                else LRBI_LAUNCH_GEN((mfma_gemm_kernel<Tag, BM, BN, WAVES_M, WAVES_N, false, false, false>), smem);
             }
         }
     }
 #undef LRBI_LAUNCH_TILE
+#undef LRBI_LAUNCH_GEN
 
     if (split && !plan.planes_only) return launch_reduce<Tag>(g, plan, N, dY, ldy, dWorkspace, stream);
     return LRBI_OK;
 }
 
-#define LRBI_TILE_ARGS g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream
+#define LRBI_TILE_ARGS g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream, mo
 template <typename Tag>
 static int launch_dtype(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
                         const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
-                        void *dWorkspace, hipStream_t stream)
+                        void *dWorkspace, hipStream_t stream, MaskOut mo)
 {
     int tile = plan.tile;
     // the panel kernel keeps per-lane element offsets in 32 bits
@@ -906,6 +933,7 @@ bool mfma_gemm_emits_mask(const Geom &g, const MfmaPlan &plan, const void *dW, i
                           const void *dX, int64_t ldx, int64_t N)
 {
     if (((uintptr_t)dW & 15) != 0 || ldw % 8 != 0 || g.n % 8 != 0) return false;
+    if (plan.tile >= 1 && plan.tile <= 3) return true; // the generic kernel: any shape
     return plan.tile >= kFirstPipeTile && pipe_ok(g, dIz, dX, ldw, ldx, N);
 }
 
@@ -929,11 +957,11 @@ int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan_in, lrbi_dtype dt, cons
         }
         plan.tile = 9; // same blocking on the staged panel kernel
     }
-    if (mo.ptr) return LRBI_ERR_SHAPE; // the caller asks mfma_gemm_emits_mask() first
+    if (mo.ptr && !(plan.tile >= 1 && plan.tile <= 3)) return LRBI_ERR_SHAPE; // the caller asks mfma_gemm_emits_mask() first
     if (dt == LRBI_F16)
-        return launch_dtype<F16Tag>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+        return launch_dtype<F16Tag>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream, mo);
     if (dt == LRBI_BF16)
-        return launch_dtype<BF16Tag>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream);
+        return launch_dtype<BF16Tag>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, stream, mo);
     return LRBI_ERR_DTYPE;
 }
 

@@ -294,9 +294,23 @@ extern "C" int lrbi_decode_and_gemm(const lrbi_desc *desc, lrbi_dtype dtype, con
     if (!aligned_to(dIp_packed, 4) || !aligned_to(dIz_packed, 8) || !aligned_to(dMask, 16)) return LRBI_ERR_ALIGN;
     if (!aligned_to(dW, (uintptr_t)es) || !aligned_to(dX, (uintptr_t)es) || !aligned_to(dY, (uintptr_t)es))
         return LRBI_ERR_ALIGN;
-    // One launch when the pipelined tile kernel serves the product: it rebuilds every mask byte anyway and stores
-    // it on the way.  Batches of up to 32 columns belong to the row-streaming kernels (below).
-    if (N > 32 && use_mfma(desc, dtype, N)) {
+    // Narrow batches on the row-streaming kernels (tried first, as in lrbi_masked_gemm): a workgroup rebuilds the
+    // whole mask of its rows in LDS before its first product and stores it from there.
+    {
+        const uint32_t path = desc->flags & LRBI_FLAG_PATH_MASK;
+        if (path == LRBI_FLAG_PATH_AUTO || path == LRBI_FLAG_PATH_STREAM) {
+            const Geom g = make_geom(desc);
+            const int cus = (path == LRBI_FLAG_PATH_STREAM) ? 0 : compute_units_of((hipStream_t)stream);
+            if (stream_ok(g, dtype, dW, ldw, dX, ldx, N, cus))
+                return launch_stream_gemm(g, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
+                                          dX, N, dY, ldy, nullptr, 0, cus, (hipStream_t)stream,
+                                          MaskOut{dMask, mask_pitch_bytes / 16});
+            if (path == LRBI_FLAG_PATH_STREAM) return (dtype == LRBI_F32) ? LRBI_ERR_DTYPE : LRBI_ERR_ALIGN;
+        }
+    }
+    // One launch when the pipelined or the generic tile kernel serves the product: they rebuild every mask word for
+    // their own use and store it on the way (the workgroups of the first block of batch columns do).
+    if (use_mfma(desc, dtype, N) && aligned_to(dW, 16) && ldw % 8 == 0 && desc->n % 8 == 0) {
         const Geom g = make_geom(desc);
         MfmaPlan plan = plan_mfma(g, desc->flags, N);
         if (plan.splitk > 1) {
@@ -310,19 +324,6 @@ extern "C" int lrbi_decode_and_gemm(const lrbi_desc *desc, lrbi_dtype dtype, con
             return launch_mfma_gemm(g, plan, dtype, dW, ldw, (const uint32_t *)dIp_packed,
                                     (const uint32_t *)dIz_packed, dX, ldx, N, dY, ldy, dWorkspace, (hipStream_t)stream,
                                     MaskOut{dMask, mask_pitch_bytes / 16});
-    }
-    // Narrow batches on the row-streaming kernels: a workgroup rebuilds the whole mask of its rows in LDS before its
-    // first product and stores it from there.
-    {
-        const uint32_t path = desc->flags & LRBI_FLAG_PATH_MASK;
-        if (path == LRBI_FLAG_PATH_AUTO || path == LRBI_FLAG_PATH_STREAM) {
-            const Geom g = make_geom(desc);
-            const int cus = (path == LRBI_FLAG_PATH_STREAM) ? 0 : compute_units_of((hipStream_t)stream);
-            if (stream_ok(g, dtype, dW, ldw, dX, ldx, N, cus))
-                return launch_stream_gemm(g, dtype, dW, ldw, (const uint32_t *)dIp_packed, (const uint32_t *)dIz_packed,
-                                          dX, N, dY, ldy, nullptr, 0, cus, (hipStream_t)stream,
-                                          MaskOut{dMask, mask_pitch_bytes / 16});
-        }
     }
     // every other shape: the two entry points one after the other on the same stream
     const int rc1 = lrbi_decode_mask(desc, dIp_packed, dIz_packed, dMask, mask_pitch_bytes, stream);

@@ -263,8 +263,11 @@ FUSED = [
     _small(256, 1152, 128, 128, 8, 0.2, 128, "f16"),     # the tile kernel leaves the mask: one column block, unsplit
     _small(256, 1024, 256, 256, 16, 0.1, 256, "bf16"),   # two column blocks: only the first one stores the mask
     _small(128, 9216, 128, 256, 16, 0.08, 128, "f16"),   # split over n: every slice stores its own units, last panel short
-    _small(300, 2400, 300, 300, 8, 0.12, 20, "f16"),     # no fused kernel for this shape: the two entry points in a row
-    _small(130, 264, 65, 33, 5, 0.3, 70, "bf16"),        # general tile kernel
+    _small(300, 2400, 300, 300, 8, 0.12, 20, "f16"),     # generic tile kernel, 32-column blocks, tiles cut through mask words
+    _small(130, 264, 65, 33, 5, 0.3, 70, "bf16"),        # generic tile kernel, tiles narrower than two mask words
+    _small(260, 520, 128, 128, 8, 0.2, 96, "f16"),       # generic kernel on cut-off aligned tiles: 8 bits of the last piece live
+    _small(1152, 1024, 576, 512, 145, 0.02, 64, "f16"),  # rank 145
+    _small(256, 1088, 128, 64, 8, 0.2, 200, "bf16"),     # two blocks of columns, n a multiple of 64 but not of 128
     _small(50, 120, 25, 60, 4, 0.2, 3, "f32"),
     workloads.CONFIGS["C2"],                             # the benchmark's workload at full size
     # narrow batches with enough rows for the row-streaming kernels: they store the rows' mask from LDS
