@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, lstm_sequence_C4, nmf_C2, nmf_C3, "
+                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, paper_fc5_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, lstm_sequence_C4, nmf_C2, nmf_C3, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -296,11 +296,15 @@ def main():
         general = {
             "general_resnet_tiles": workloads.Config("general_resnet_tiles", 2304, 2048, 576, 512, 145, 0.02, 128, "bf16", 0.02),
             "general_edge_tiles": workloads.Config("general_edge_tiles", 4100, 9224, 256, 256, 16, 0.08, 128, "f16", 0.01),
+            # C2's layer in the tiling the paper itself uses for it (Table 2, note 2: 16 x 8 blocks of 576 x 512, here
+            # with the 9216 inputs along the columns, so tiles of 512 x 576; rank 32; p for a mask density of 0.09)
+            "paper_fc5_tiles": workloads.Config("paper_fc5_tiles", 4096, 9216, 512, 576, 32, 0.054, 128, "f16", 0.01),
         }
         # the C3 tile shape on a product large enough that the prologue and the last partial wave of workgroups do not
         # count: the matrix-core kernel's steady state
         steady = {"steady_state_C3_tiles": workloads.Config("steady_state_C3_tiles", 16384, 16384, 512, 512, 32, 0.06, 4096, "bf16", 0.01)}
-        for name in ("C3a", "C3b", "C4", "C5", "C1", "general_resnet_tiles", "general_edge_tiles", "steady_state_C3_tiles"):
+        for name in ("C3a", "C3b", "C4", "C5", "C1", "general_resnet_tiles", "general_edge_tiles", "paper_fc5_tiles",
+                     "steady_state_C3_tiles"):
             if wanted is not None and name not in wanted:
                 continue
             try:
@@ -329,8 +333,12 @@ def main():
                 if name in general:
                     gmask = torch.empty((c.m, ((c.n + 127) // 128) * 16), dtype=torch.uint8, device=dev)
                     ms_dec, _ = event_times([lambda: lrbi.decode_mask(de, ip_, iz_, out=gmask)], 20, 3)
+                    dfns = [(lambda Wi=Wi: lrbi.decode_and_gemm(de, Wi, ip_, iz_, X_, out=Y_, mask=gmask, workspace=w_))
+                            for Wi in Wl]
+                    ms_both, _ = event_times(dfns, 6 * len(dfns), len(dfns))
                     extra = {"shape": "W %dx%d, tiles %dx%d, rank %d" % (c.m, c.n, c.r, c.c, c.k),
-                             "decode_ms": round(ms_dec, 5), "decode_gbit_s": round(c.m * c.n / (ms_dec * 1e-3) / 1e9, 1)}
+                             "decode_ms": round(ms_dec, 5), "decode_gbit_s": round(c.m * c.n / (ms_dec * 1e-3) / 1e9, 1),
+                             "decode_and_gemm_ms_cold": round(ms_both, 5)}
                     del gmask
                 others[name] = {"N": c.N, "dtype": c.dtype, "avg_launch_ms_cold": round(ms, 5), **extra,
                                 "avg_launch_ms_warm": round(ms_warm, 5),

@@ -759,10 +759,13 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
 {
     MfmaPlan p;
     int tile = (int)((flags & LRBI_FLAG_TILE_MASK) >> LRBI_FLAG_TILE_SHIFT);
-    if (tile >= 1 && tile <= kNumTiles && kTiles[tile].panel && !panel_ok(g, kTiles[tile].bm)) tile = 0;
+    if (tile >= 1 && tile <= kNumTiles && kTiles[tile].panel && !panel_ok(g, kTiles[tile].bm) &&
+        !(tile >= kFirstPipeTile && pipe_shape_ok(g)))
+        tile = 0;
     if (tile < 1 || tile > kNumTiles) {
         tile = (N > 64) ? 1 : (N > 32 ? 2 : 3);
         if (panel_ok(g, 128)) tile = (N > 64) ? 14 : (N > 32 ? 10 : 11); // 14: falls back to 9 when X is not 16-byte readable
+        else if (N > 64 && pipe_shape_ok(g)) tile = 14; // tile widths of 64 (2 j + 1): falls back to the generic kernel
     }
     p.tile = tile;
     p.bm = kTiles[tile].bm;
@@ -955,7 +958,7 @@ int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan_in, lrbi_dtype dt, cons
             }
             return LRBI_OK;
         }
-        plan.tile = 9; // same blocking on the staged panel kernel
+        plan.tile = panel_ok(g, 128) ? 9 : 1; // same blocking on the staged panel kernel, or on the generic one
     }
     if (mo.ptr && !(plan.tile >= 1 && plan.tile <= 3)) return LRBI_ERR_SHAPE; // the caller asks mfma_gemm_emits_mask() first
     if (dt == LRBI_F16)

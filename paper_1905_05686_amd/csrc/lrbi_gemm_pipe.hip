@@ -37,12 +37,13 @@ static constexpr int MT_BYTES = PIPE_BM * MT_ROW;    // one mask panel
 static constexpr int FZ_ROWS = FAST_MAX_K + 1;       // I_z rows under a panel; row 64 stays zero
 static constexpr int FZ_ROW_BYTES = PANEL_WORDS * 4; // 64
 
-template <int NS> struct SmemDma {
+template <int NS, bool HALF = false> struct SmemDma {
     static constexpr size_t mt_off = (size_t)NS * STAGE_BYTES;
     static constexpr size_t fz_off = mt_off + 2 * MT_BYTES;
     static constexpr size_t fip_off = fz_off + FZ_ROWS * FZ_ROW_BYTES;
-    static constexpr size_t bytes = fip_off + PIPE_BM * PANEL_UNITS * 2 * 4;
+    static constexpr size_t bytes = fip_off + PIPE_BM * PANEL_UNITS * (HALF ? 2 : 1) * 2 * 4;
 };
+static_assert(SmemDma<4, true>::bytes <= 160 * 1024, "LDS of a compute unit");
 
 
 // CONV: X is not a matrix in memory but a zero-padded activation [B][H + 2][Wd + 2][C] (channels fastest), and column
@@ -54,7 +55,10 @@ template <int NS> struct SmemDma {
 // decode (one bit per weight, rows of `mask_pitch16` 16-byte pieces): every (row, 128-column unit) of the mask is
 // formed by exactly one workgroup of the first column block, so the decode costs one 16-byte store per lane and
 // panel instead of a kernel of its own.
-template <typename Tag, int NS, bool SPREAD, bool SPLIT, bool CONV, bool EMIT = false>
+// HALF: tile widths that are an odd multiple of 64 (the paper's 576-column tiles, Table 2): a 128-column unit may
+// then lie across two tile columns, so the factor slices are gathered, and Eq. 3 is evaluated, per 64-column half
+// unit, each with the I_p word and the I_z words of its own tile.  Everything behind the mask bytes is the same.
+template <typename Tag, int NS, bool SPREAD, bool SPLIT, bool CONV, bool EMIT = false, bool HALF = false>
 __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
     Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
     const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ X, int64_t ldx, int N,
@@ -64,13 +68,15 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
     static_assert(NS == 4, "LDS stages (an even number: the W operand registers alternate with the slab's parity)");
     static_assert(!SPREAD || NS == 4, "loads spread over the iteration land one iteration later: four stages");
     constexpr int FN = PIPE_BN / 32; // 32-column blocks of the wave tile
-    using S = SmemDma<NS>;
+    static_assert(!(HALF && CONV), "half units: the plain product only");
+    using S = SmemDma<NS, HALF>;
 
     extern __shared__ uint4 lrbi_dyn_smem[];
     unsigned char *smem = (unsigned char *)lrbi_dyn_smem;
     unsigned char *Mt = smem + S::mt_off;                // [2][128][MT_ROW]  mask bytes of two panels
     uint32_t *Fz = (uint32_t *)(smem + S::fz_off);       // [65][16]          I_z rows under the panel being decoded
     uint32_t *Fip = (uint32_t *)(smem + S::fip_off);     // [128][4][2]       I_p words per row and 128-column unit
+                                                         // (HALF: [128][8][2], per 64-column half unit)
 
     int64_t bid = blockIdx.x;
     if (xcd_remap) {
@@ -240,6 +246,46 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
     const uint32_t fz_lane = (uint32_t)(((fz_l < g.k) ? fz_l : 0) * g.izw * 4);
     const int fz_u = lane & 3;
     auto load_factors = [&]() {
+        if constexpr (HALF) {
+            // per half unit (64 columns, two words of an I_z row): one word per lane.  I_z: instruction q of 16
+            // (two per wavefront) fills ranks 4 q .. + 3, lane = (rank, half unit, word); I_p: image
+            // [row][half unit][2], four instructions per wavefront.
+            constexpr int HU = 2 * PANEL_UNITS;
+            uint32_t zb[HU], pb[HU];
+#pragma unroll
+            for (int h = 0; h < HU; ++h) {
+                const bool ok = ccol < kend;
+                zb[h] = ok ? (uint32_t)((((trow + ctj) * g.k) * (int64_t)g.izw + (coff >> 5)) * 4) : zb_first;
+                pb[h] = ok ? (uint32_t)((((trow + ctj) * g.r + il0) * (int64_t)g.ipw) * 4) : pb_first;
+                ccol += 64;
+                coff += 64;
+                if (coff >= g.c) {
+                    coff = 0;
+                    ++ctj;
+                }
+            }
+            const int hu = (lane >> 1) & 7;
+            const uint32_t zlo = (hu & 2) ? ((hu & 1) ? zb[3] : zb[2]) : ((hu & 1) ? zb[1] : zb[0]);
+            const uint32_t zhi = (hu & 2) ? ((hu & 1) ? zb[7] : zb[6]) : ((hu & 1) ? zb[5] : zb[4]);
+            const uint32_t plo = (hu & 2) ? ((hu & 1) ? pb[3] : pb[2]) : ((hu & 1) ? pb[1] : pb[0]);
+            const uint32_t phi = (hu & 2) ? ((hu & 1) ? pb[7] : pb[6]) : ((hu & 1) ? pb[5] : pb[4]);
+            const uint32_t zsel = (hu & 4) ? zhi : zlo, psel = (hu & 4) ? phi : plo;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int q = wave * 2 + i;
+                const int rank = q * 4 + (lane >> 4);
+                load_to_lds4(lds0 + (uint32_t)S::fz_off + (uint32_t)q * 256u, Iz,
+                             zsel + (uint32_t)((((rank < g.k) ? rank : 0) * g.izw + (lane & 1)) * 4));
+            }
+            const int iw = (lane & 1) < g.ipw ? (lane & 1) : 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int q = wave * 4 + i;
+                const int row = q * 4 + (lane >> 4);
+                load_to_lds4(lds0 + (uint32_t)S::fip_off + (uint32_t)q * 256u, Ip, psel + (uint32_t)((row * g.ipw + iw) * 4));
+            }
+            return;
+        }
         uint32_t zb[PANEL_UNITS], pb[PANEL_UNITS]; // byte offsets of each unit's tile slices (uniform)
 #pragma unroll
         for (int u = 0; u < PANEL_UNITS; ++u) {
@@ -273,10 +319,35 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
     auto decode_panel = [&](int panel) {
         const int row = tid >> 2, u = tid & 3;
         unsigned char *out = Mt + (panel & 1) * MT_BYTES + row * MT_ROW + u * 16;
-        const uint32_t *fp = Fip + (row * PANEL_UNITS + u) * 2;
+        const uint32_t *fp = Fip + (row * PANEL_UNITS + u) * (HALF ? 4 : 2);
         const uint32_t *fz = Fz + 4 * u;
         uint4 a;
-        if (g.ipw == 1) { // ranks up to 32: one word
+        if constexpr (HALF) {
+            // the unit's two halves, each from the I_p word(s) and the two I_z words of its own tile
+            uint2 hv[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                unsigned long long sel = (unsigned long long)fp[2 * h];
+                if (g.ipw > 1) sel |= (unsigned long long)fp[2 * h + 1] << 32;
+                const uint32_t *fh = fz + 2 * h;
+                const int l0 = sel ? __builtin_ctzll(sel) : FAST_MAX_K;
+                sel &= sel - 1ull;
+                const int l1 = sel ? __builtin_ctzll(sel) : FAST_MAX_K;
+                sel &= sel - 1ull;
+                const uint2 z0 = *reinterpret_cast<const uint2 *>(fh + l0 * PANEL_WORDS);
+                const uint2 z1 = *reinterpret_cast<const uint2 *>(fh + l1 * PANEL_WORDS);
+                uint2 o = make_uint2(z0.x | z1.x, z0.y | z1.y);
+                while (sel) {
+                    const int le = __builtin_ctzll(sel);
+                    sel &= sel - 1ull;
+                    const uint2 ze = *reinterpret_cast<const uint2 *>(fh + le * PANEL_WORDS);
+                    o.x |= ze.x;
+                    o.y |= ze.y;
+                }
+                hv[h] = o;
+            }
+            a = make_uint4(hv[0].x, hv[0].y, hv[1].x, hv[1].y);
+        } else if (g.ipw == 1) { // ranks up to 32: one word
             uint32_t sel = fp[0];
             const int l0 = sel ? __builtin_ctz(sel) : FAST_MAX_K;
             sel &= sel - 1u;
@@ -502,11 +573,19 @@ __global__ __launch_bounds__(PIPE_THREADS) void mfma_gemm_pipe_kernel(
     }
 }
 
+// tile shapes the pipelined kernel's blocking lines up with: tile rows in blocks of 128, tile widths a multiple of
+// 128, or of 64 (gathered per half unit) when the row length is still a multiple of 128
+bool pipe_shape_ok(const Geom &g)
+{
+    if ((g.r % PIPE_BM) != 0 || g.k > FAST_MAX_K || g.ragged) return false;
+    return (g.c % 128) == 0 || ((g.c % 64) == 0 && (g.n % 128) == 0);
+}
+
 // true when the pipelined kernel serves this call: aligned tile shapes, X readable in 16-byte pieces, offsets
 // that fit the kernel's 32-bit per-lane byte offsets
 bool pipe_ok(const Geom &g, const void *dIz, const void *dX, int64_t ldw, int64_t ldx, int64_t N)
 {
-    if ((g.c % 128) != 0 || (g.r % PIPE_BM) != 0 || g.k > FAST_MAX_K || g.ragged) return false;
+    if (!pipe_shape_ok(g)) return false;
     if ((((uintptr_t)dX & 15) != 0) || (ldx % 8 != 0) || (N % 8 != 0) || N < 8) return false;
     if (((uintptr_t)dIz & 15) != 0) return false; // the I_z slices are fetched in 16-byte pieces
     if (ldw > (1 << 22) || ldx > (1 << 22)) return false;
@@ -516,7 +595,7 @@ bool pipe_ok(const Geom &g, const void *dIz, const void *dX, int64_t ldw, int64_
     return true;
 }
 
-template <typename Tag, int NS, bool SPREAD, bool CONV, bool EMIT = false>
+template <typename Tag, int NS, bool SPREAD, bool CONV, bool EMIT = false, bool HALF = false>
 static int launch_pipe_t(const Geom &g, const MfmaPlan &plan, const void *dW, int64_t ldw, const uint32_t *dIp,
                          const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY, int64_t ldy,
                          void *dWorkspace, const ConvGeom &cg, hipStream_t stream, MaskOut mo = {nullptr, 0})
@@ -529,9 +608,9 @@ static int launch_pipe_t(const Geom &g, const MfmaPlan &plan, const void *dW, in
     const int y_vec_ok = (((uintptr_t)dY & 7) == 0) && (ldy % 4 == 0);
     const int xcd_remap = (blocks % 8 == 0) ? 1 : 0;
     const int64_t ldp = (N + 3) / 4 * 4;
-    const size_t smem = SmemDma<NS>::bytes;
-    auto kern = split ? mfma_gemm_pipe_kernel<Tag, NS, SPREAD, true, CONV, EMIT>
-                      : mfma_gemm_pipe_kernel<Tag, NS, SPREAD, false, CONV, EMIT>;
+    const size_t smem = SmemDma<NS, HALF>::bytes;
+    auto kern = split ? mfma_gemm_pipe_kernel<Tag, NS, SPREAD, true, CONV, EMIT, HALF>
+                      : mfma_gemm_pipe_kernel<Tag, NS, SPREAD, false, CONV, EMIT, HALF>;
     LRBI_SET_MAX_LDS(kern, smem);
     LRBI_LAUNCH(kern, dim3((unsigned)blocks), dim3(PIPE_THREADS), smem, stream, g, (const uint16_t *)dW, ldw, dIp, dIz,
                 (const uint16_t *)dX, ldx, (int)N, (uint16_t *)dY, ldy, (float *)dWorkspace, ldp, (int)mblocks,
@@ -547,6 +626,17 @@ int launch_pipe_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, int var
                      int64_t ldy, void *dWorkspace, hipStream_t stream, MaskOut mo)
 {
     const ConvGeom none = {0, 0, 0};
+    if (g.c % 128 != 0) { // half units: one variant per dtype (loads spread over the iteration), with or without the mask
+#define LRBI_PIPE_ARGS g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace, none, stream, mo
+        if (dt == LRBI_F16)
+            return mo.ptr ? launch_pipe_t<F16Tag, 4, true, false, true, true>(LRBI_PIPE_ARGS)
+                          : launch_pipe_t<F16Tag, 4, true, false, false, true>(LRBI_PIPE_ARGS);
+        if (dt == LRBI_BF16)
+            return mo.ptr ? launch_pipe_t<BF16Tag, 4, true, false, true, true>(LRBI_PIPE_ARGS)
+                          : launch_pipe_t<BF16Tag, 4, true, false, false, true>(LRBI_PIPE_ARGS);
+#undef LRBI_PIPE_ARGS
+        return LRBI_ERR_DTYPE;
+    }
     if (mo.ptr) { // the mask as a by-product: one variant per dtype (loads spread over the iteration)
         if (dt == LRBI_F16)
             return launch_pipe_t<F16Tag, 4, true, false, true>(g, plan, dW, ldw, dIp, dIz, dX, ldx, N, dY, ldy, dWorkspace,

@@ -133,6 +133,7 @@ int launch_mfma_conv(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, const C
                      void *dWorkspace, hipStream_t stream);
 
 // software-pipelined tile kernel (lrbi_gemm_pipe.hip)
+bool pipe_shape_ok(const Geom &g);
 bool pipe_ok(const Geom &g, const void *dIz, const void *dX, int64_t ldw, int64_t ldx, int64_t N);
 int launch_pipe_gemm(const Geom &g, const MfmaPlan &plan, lrbi_dtype dt, int pf, const void *dW, int64_t ldw,
                      const uint32_t *dIp, const uint32_t *dIz, const void *dX, int64_t ldx, int64_t N, void *dY,

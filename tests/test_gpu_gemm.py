@@ -86,6 +86,14 @@ EDGE = [
     # tile shape and ranks of the paper's own experiments (Sec. 4: 576 x 512 tiles, rank 145; Table 1: rank 256)
     (_small(1152, 1024, 576, 512, 145, 0.02, 64, "f16"), 0),
     (_small(1152, 1024, 576, 512, 256, 0.015, 1, "bf16"), 0),
+    # tile widths that are an odd multiple of 64 on the pipelined tile kernel (Table 2's 576-column tiles): 128-column
+    # units of the mask that lie across two tile columns
+    (_small(256, 1152, 128, 576, 8, 0.2, 128, "f16"), 0),      # two tile columns, three panels, the last one short
+    (_small(256, 3456, 128, 576, 40, 0.05, 136, "bf16"), 0),   # two I_p words per row, two column blocks, ragged N
+    (_small(128, 9216, 128, 576, 32, 0.054, 128, "f16"), 0),   # split over n: slices begin inside tiles
+    (_small(256, 768, 256, 192, 16, 0.1, 72, "bf16"), 0),      # 192-column tiles
+    (_small(128, 512, 128, 64, 8, 0.2, 128, "f16"), 0),        # 64-column tiles: every unit has two tiles
+    (_small(256, 2304, 128, 576, 16, 0.1, 256, "bf16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_splitk(3)),
 ]
 
 
@@ -270,6 +278,12 @@ FUSED = [
     _small(256, 1088, 128, 64, 8, 0.2, 200, "bf16"),     # two blocks of columns, n a multiple of 64 but not of 128
     _small(50, 120, 25, 60, 4, 0.2, 3, "f32"),
     workloads.CONFIGS["C2"],                             # the benchmark's workload at full size
+    # the pipelined tile kernel on tile widths of 64 (2 j + 1): mask units gathered per 64-column half
+    _small(256, 1152, 128, 576, 8, 0.2, 128, "f16"),
+    _small(256, 3456, 128, 576, 40, 0.05, 136, "bf16"),
+    _small(128, 9216, 128, 576, 32, 0.054, 128, "f16"),
+    _small(128, 512, 128, 64, 8, 0.2, 128, "f16"),
+    workloads.Config("paper_fc5_tiles", 4096, 9216, 512, 576, 32, 0.054, 128, "f16", 0.01),  # Table 2's tiling of C2's layer
     # narrow batches with enough rows for the row-streaming kernels: they store the rows' mask from LDS
     _small(3000, 600, 300, 300, 8, 0.12, 20, "f16"),     # ring kernel, tiles cut through mask words, last workgroups short
     _small(2048, 1024, 256, 128, 8, 0.15, 1, "bf16"),    # single-column kernel
