@@ -27,6 +27,11 @@
 namespace lrbi {
 
 static constexpr int kDecodeThreads = 256;
+// masks too small for the streaming kernel: the span of an item is halved (down to 4 pieces = 64 bytes of a row)
+// until there are this many items.  Measured on 4096 x 9216 with 576-column tiles, rank 32 / 64: 18.3 / 18.9 us at the
+// widest span (288 items), 9.7 / 10.6 us with 512; 1024 and more cost the 300-column tiles of a 6000 x 3000 mask 3 us.
+static constexpr int kSmallMaskItems = 512;
+static constexpr int kSmallMaskMinShift = 2;
 static constexpr int kStreamThreads = 1024;
 static constexpr int kZTableBudgetBytes = 32 * 1024; // (k + 1) * span pieces * 16 bytes
 static constexpr int kIpBudgetBytes = 12 * 1024;     // tiles under the span * (rows + 1) * ipw * 4 bytes
@@ -747,25 +752,35 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
 
     // Column span per item: as wide as the Z table budget allows, at most 64 pieces (one
     // wavefront across).  Rows per band: as many as the I_p budget allows (one table build per
-    // band), cut down only when that leaves compute units without work.
+    // band), cut down only when that leaves compute units without work; when the shortest band still gives
+    // too few items (small masks), the span is halved as well, down to 64-byte row segments.
     p.span_chunks = kZTableBudgetBytes / (16 * (g.k + 1));
     if (p.span_chunks < 1) p.span_chunks = 1;
     if (p.span_chunks > 64) p.span_chunks = 64;
     p.zshift = 0;
     while ((2 << p.zshift) <= p.span_chunks) ++p.zshift;
     while (p.zshift > 0 && (1 << (p.zshift - 1)) >= p.chunks) --p.zshift; // no wider than the row needs
-    p.span_chunks = 1 << p.zshift;
-    p.spans = (p.chunks + p.span_chunks - 1) / p.span_chunks;
-    p.tx_log2 = p.zshift;
-    p.span_tiles = (int)(((int64_t)p.span_chunks * 128 + g.c - 1) / g.c) + 1;
-    p.rows_per_band = g.r;
-    const int cap_rows = kIpBudgetBytes / (4 * g.ipw * p.span_tiles) - 1;
-    if (p.rows_per_band > cap_rows) p.rows_per_band = cap_rows;
-    if (p.rows_per_band < 1) return launch_generic(); // not even one row of I_p words fits next to the table
-    const int min_rows = (2 * g.k > 32) ? 2 * g.k : 32;
-    while (p.rows_per_band > min_rows &&
-           (int64_t)p.spans * g.tile_rows * ((g.r + p.rows_per_band - 1) / p.rows_per_band) < 2048)
-        p.rows_per_band = (p.rows_per_band + 1) / 2;
+    bool widest = true, streaming = false;
+    for (;; --p.zshift, widest = false) {
+        p.span_chunks = 1 << p.zshift;
+        p.spans = (p.chunks + p.span_chunks - 1) / p.span_chunks;
+        p.tx_log2 = p.zshift;
+        p.span_tiles = (int)(((int64_t)p.span_chunks * 128 + g.c - 1) / g.c) + 1;
+        p.rows_per_band = g.r;
+        const int cap_rows = kIpBudgetBytes / (4 * g.ipw * p.span_tiles) - 1;
+        if (p.rows_per_band > cap_rows) p.rows_per_band = cap_rows;
+        if (p.rows_per_band < 1) {
+            if (p.zshift > kSmallMaskMinShift) continue;
+            return launch_generic(); // not even one row of I_p words fits next to the table
+        }
+        const int min_rows = (2 * g.k > 32) ? 2 * g.k : 32;
+        while (p.rows_per_band > min_rows &&
+               (int64_t)p.spans * g.tile_rows * ((g.r + p.rows_per_band - 1) / p.rows_per_band) < 2048)
+            p.rows_per_band = (p.rows_per_band + 1) / 2;
+        const int64_t items = (int64_t)p.spans * g.tile_rows * ((g.r + p.rows_per_band - 1) / p.rows_per_band);
+        if (widest && items >= 4 * (int64_t)cus) streaming = true; // streaming pays off once every compute unit gets several items
+        if (streaming || p.zshift <= kSmallMaskMinShift || items >= kSmallMaskItems) break;
+    }
     p.bands_per_tile_row = (g.r + p.rows_per_band - 1) / p.rows_per_band;
     p.items = (int64_t)p.spans * g.tile_rows * p.bands_per_tile_row;
     if (p.items > 0x7FFFFFFF) return LRBI_ERR_SHAPE;
@@ -774,8 +789,7 @@ int launch_decode(const Geom &g, uint32_t flags, const uint32_t *dIp, const uint
     const size_t ip_bytes = ((size_t)p.span_tiles * (p.rows_per_band + 1) * g.ipw * 4 + 15) / 16 * 16;
     const bool aligned = (g.c % 128) == 0;
 
-    // streaming pays off once every compute unit gets several items
-    if (p.items >= 4 * (int64_t)cus) {
+    if (streaming) {
         const size_t lds = 2 * (z_bytes + ip_bytes);
         auto kern = aligned ? decode_stream_kernel<true> : decode_stream_kernel<false>;
         LRBI_SET_MAX_LDS(kern, lds);
