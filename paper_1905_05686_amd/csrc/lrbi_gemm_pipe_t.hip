@@ -34,15 +34,21 @@ static constexpr int PT_MT_BYTES = PT_BJ * PT_MT_ROW;
 static constexpr int PT_FZ_ROWS = FAST_MAX_K;
 static constexpr int PT_FZ_ROW_BYTES = PANEL_WORDS * 4;   // 64: four units x four words
 
-struct SmemPipeT {
+// HALF (tile widths that are an odd multiple of 64, e.g. the 576-column tiles of Table 2): the workgroup's 128
+// columns may lie in two tile columns, so the I_p words are kept per 64-column half (8 KB instead of 4 KB) and the
+// ranks of every column, 4 KB, take the place of the I_z slices once those have been read (one more barrier).
+template <bool HALF = false> struct SmemPipeT {
     static constexpr size_t mt_off = (size_t)PT_NS * PT_STAGE_BYTES;
     static constexpr size_t fz_off = mt_off + 2 * PT_MT_BYTES;
     static constexpr size_t fip_off = fz_off + PT_FZ_ROWS * PT_FZ_ROW_BYTES;
-    static constexpr size_t sel_off = fip_off + 128 * PANEL_UNITS * 2 * 4; // (I_p words: 4 KB; later its columns as bits)
-    static constexpr size_t bytes = sel_off + PANEL_UNITS * 128 * 8;       // the ranks of every column, per unit
+    static constexpr size_t sel_off = HALF ? fz_off : fip_off + 128 * PANEL_UNITS * 2 * 4; // (I_p words: 4 KB; later its columns as bits)
+    static constexpr size_t bytes = HALF ? fip_off + 128 * PANEL_UNITS * 2 * 2 * 4
+                                         : sel_off + PANEL_UNITS * 128 * 8; // the ranks of every column, per unit
 };
+static_assert(SmemPipeT<true>::bytes <= 160 * 1024 && SmemPipeT<false>::bytes <= 160 * 1024, "LDS of a compute unit");
+static_assert(PT_FZ_ROWS * PT_FZ_ROW_BYTES == PANEL_UNITS * 128 * 8, "the ranks of the columns fit where the I_z slices were");
 
-template <typename Tag, bool SPLIT>
+template <typename Tag, bool SPLIT, bool HALF = false>
 __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
     Geom g, const uint16_t *__restrict__ W, int64_t ldw, const uint32_t *__restrict__ Ip,
     const uint32_t *__restrict__ Iz, const uint16_t *__restrict__ DY, int64_t lddy, int N,
@@ -51,7 +57,7 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
 {
     constexpr int NS = PT_NS;
     constexpr int FN = PT_BQ / 32;
-    using S = SmemPipeT;
+    using S = SmemPipeT<HALF>;
 
     extern __shared__ uint4 lrbi_dyn_smem[];
     unsigned char *smem = (unsigned char *)lrbi_dyn_smem;
@@ -77,6 +83,8 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
     const int npanels = (nslabs + PANEL_SLABS - 1) / PANEL_SLABS;
     const int tj = j0 / g.c;                       // the workgroup's columns lie inside one tile column (c % 128 == 0)
     const int coff = j0 - tj * g.c;
+    const int tjb = (j0 + 64) / g.c;               // HALF: tile column and offset of the upper 64 columns
+    const int coffb = j0 + 64 - tjb * g.c;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -188,6 +196,44 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
 #pragma unroll
         for (int u = 1; u < PANEL_UNITS; ++u)
             if ((roff + 128 * u) % g.r == 0) leaders |= 1 << u;
+        if constexpr (HALF) {
+            // the same images with the upper two words of a column's I_z row and a second set of I_p words taken from
+            // the upper half's tile: I_z 16 instructions as below, I_p [unit][half][word][row]: 32, four per wavefront
+            uint32_t zc[PANEL_UNITS], pc[PANEL_UNITS];
+#pragma unroll
+            for (int u = 0; u < PANEL_UNITS; ++u) {
+                const bool ok = crow < iend;
+                const int64_t ta = (int64_t)cti * g.tile_cols + tj, tb = (int64_t)cti * g.tile_cols + tjb;
+                zb[u] = ok ? (uint32_t)(((ta * g.k) * (int64_t)g.izw + (coff >> 5)) * 4) : zb_first;
+                pb[u] = ok ? (uint32_t)(((ta * g.r + roff) * (int64_t)g.ipw) * 4) : pb_first;
+                zc[u] = ok ? (uint32_t)(((tb * g.k) * (int64_t)g.izw + (coffb >> 5)) * 4) : zb_first;
+                pc[u] = ok ? (uint32_t)(((tb * g.r + roff) * (int64_t)g.ipw) * 4) : pb_first;
+                crow += 128;
+                roff += 128;
+                if (roff >= g.r) {
+                    roff = 0;
+                    ++cti;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int q = wave * 2 + i; // uniform
+                const int u = q >> 2, w = q & 3;
+                const uint32_t za = u == 0 ? zb[0] : (u == 1 ? zb[1] : (u == 2 ? zb[2] : zb[3]));
+                const uint32_t zu = u == 0 ? zc[0] : (u == 1 ? zc[1] : (u == 2 ? zc[2] : zc[3]));
+                load_to_lds4(lds0 + (uint32_t)S::fz_off + (uint32_t)q * 256u, Iz,
+                             ((w & 2) ? zu : za) + fz_lane + (uint32_t)((w & 1) * 4));
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int q = wave * 4 + i; // uniform
+                const int u = q >> 3, h = (q >> 2) & 1, iw = ((q >> 1) & 1) < g.ipw ? ((q >> 1) & 1) : 0, row = (q & 1) * 64 + lane;
+                const uint32_t pa = u == 0 ? pb[0] : (u == 1 ? pb[1] : (u == 2 ? pb[2] : pb[3]));
+                const uint32_t pu = u == 0 ? pc[0] : (u == 1 ? pc[1] : (u == 2 ? pc[2] : pc[3]));
+                load_to_lds4(lds0 + (uint32_t)S::fip_off + (uint32_t)q * 256u, Ip, (h ? pu : pa) + (uint32_t)((row * g.ipw + iw) * 4));
+            }
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < PANEL_UNITS; ++u) {
             const bool ok = crow < iend;
@@ -227,9 +273,36 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
     //     ranks.
     // In the slab loop the three steps ride on the barriers of three consecutive iterations; only the first panel,
     // in the prologue, pays for barriers of its own.  Bits at or beyond k are zero in the packed factors.
-    uint32_t tw0 = 0u, tw1 = 0u;
+    uint32_t tw0 = 0u, tw1 = 0u, tw2 = 0u, tw3 = 0u, csel0 = 0u, csel1 = 0u;
     auto panel_step1 = [&]() {
         const int u = tid >> 7, l = (tid >> 2) & 31, c = tid & 3;
+        if constexpr (HALF) { // both halves' I_p words: [unit][half][word][row]
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint4 *src = (const uint4 *)(Fip + ((u * 2 + h) * 2) * 128 + c * 32);
+                uint32_t t0 = 0u, t1 = 0u;
+#pragma unroll
+                for (int i4 = 0; i4 < 8; ++i4) {
+                    const uint4 v = src[i4];
+                    t0 |= (((v.x >> l) & 1u) | (((v.y >> l) & 1u) << 1) | (((v.z >> l) & 1u) << 2) | (((v.w >> l) & 1u) << 3)) << (4 * i4);
+                }
+                if (g.k > 32) {
+#pragma unroll
+                    for (int i4 = 0; i4 < 8; ++i4) {
+                        const uint4 v = src[32 + i4];
+                        t1 |= (((v.x >> l) & 1u) | (((v.y >> l) & 1u) << 1) | (((v.z >> l) & 1u) << 2) | (((v.w >> l) & 1u) << 3)) << (4 * i4);
+                    }
+                }
+                if (h == 0) {
+                    tw0 = t0;
+                    tw1 = t1;
+                } else {
+                    tw2 = t0;
+                    tw3 = t1;
+                }
+            }
+            return;
+        }
         const uint4 *src = (const uint4 *)(Fip + (u * 2) * 128 + c * 32); // rows 32 c .. + 31 of the unit, word 0
         uint32_t t0 = 0u, t1 = 0u;
 #pragma unroll
@@ -249,6 +322,15 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
     };
     auto panel_step2 = [&]() {
         const int u = tid >> 7, l = (tid >> 2) & 31, c = tid & 3;
+        if constexpr (HALF) { // [unit][half][rank][16 bytes]
+            Fip[((u * 2) * FAST_MAX_K + l) * 4 + c] = tw0;
+            Fip[((u * 2 + 1) * FAST_MAX_K + l) * 4 + c] = tw2;
+            if (g.k > 32) {
+                Fip[((u * 2) * FAST_MAX_K + 32 + l) * 4 + c] = tw1;
+                Fip[((u * 2 + 1) * FAST_MAX_K + 32 + l) * 4 + c] = tw3;
+            }
+            return;
+        }
         Fip[(u * FAST_MAX_K + l) * 4 + c] = tw0;
         if (g.k > 32) Fip[(u * FAST_MAX_K + 32 + l) * 4 + c] = tw1;
     };
@@ -274,13 +356,23 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
         if (g.k < 32) sel0 &= (1u << g.k) - 1u;
         if (g.k <= 32) sel1 = 0u;
         else if (g.k < 64) sel1 &= (1u << (g.k - 32)) - 1u;
-        Sel[u * 128 + col] = make_uint2(sel0, sel1);
+        if constexpr (HALF) { // kept in registers: the words go where the I_z slices are, behind the next barrier
+            csel0 = sel0;
+            csel1 = sel1;
+        } else {
+            Sel[u * 128 + col] = make_uint2(sel0, sel1);
+        }
+    };
+    auto panel_step3b = [&]() { // HALF only
+        const int u = tid >> 7, col = tid & 127;
+        if (!((leaders >> u) & 1)) return;
+        Sel[u * 128 + col] = make_uint2(csel0, csel1);
     };
     auto panel_step4 = [&](int panel) { // lane (column, unit): OR of the bit strings of the column's ranks
         const int col = tid >> 2, u = tid & 3;
         const int lead = 31 - __builtin_clz((uint32_t)(leaders & ((2 << u) - 1))); // the unit that gathered for u's tile row
         const uint2 sel01 = Sel[lead * 128 + col];
-        const uint4 *ipt = (const uint4 *)Fip + u * FAST_MAX_K;
+        const uint4 *ipt = (const uint4 *)Fip + (HALF ? u * 2 + (col >> 6) : u) * FAST_MAX_K;
         uint4 a = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
         for (int iw = 0; iw < 2; ++iw) {
@@ -337,6 +429,10 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
     panel_step2();
     panel_step3();
     __syncthreads();
+    if constexpr (HALF) {
+        panel_step3b();
+        __syncthreads();
+    }
     panel_step4(0);
     wait_loads<kProloguePieces - 4>(); // slab 0
     __syncthreads();
@@ -394,7 +490,10 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
                     else if (ps == 2) {
                         panel_step2();
                         panel_step3();
-                    } else if (ps == 3) panel_step4(np);
+                    } else if (ps == 3) {
+                        if constexpr (HALF) panel_step3b();
+                        else panel_step4(np);
+                    } else if (HALF && ps == 4) panel_step4(np); // (written behind slab 4's barrier, first read at slab 7)
                 }
             }
         });
@@ -474,7 +573,8 @@ __global__ __launch_bounds__(PT_THREADS) void mfma_gemm_pipe_t_kernel(
 // batch wide enough for its 128-column blocks to pay, offsets that fit the kernel's 32-bit per-lane byte offsets
 bool pipe_t_ok(const Geom &g, const void *dW, int64_t ldw, const void *dIz, const void *dDY, int64_t lddy, int64_t N)
 {
-    if ((g.c % 128) != 0 || (g.r % 128) != 0 || g.k > FAST_MAX_K || g.ragged) return false;
+    if ((g.r % 128) != 0 || g.k > FAST_MAX_K || g.ragged) return false;
+    if ((g.c % 128) != 0 && ((g.c % 64) != 0 || (g.n % 128) != 0)) return false; // 64 (2 j + 1): gathered per half
     if ((((uintptr_t)dDY & 15) != 0) || (lddy % 8 != 0) || (N % 8 != 0) || N <= 64) return false;
     if ((((uintptr_t)dW & 15) != 0) || (ldw % 8 != 0)) return false;
     if (((uintptr_t)dIz & 15) != 0) return false;
@@ -510,8 +610,10 @@ static int launch_pipe_t_dtype(const Geom &g, int slices, int64_t iper, const vo
     const int y_vec_ok = (((uintptr_t)dDX & 7) == 0) && (lddx % 4 == 0);
     const int xcd_remap = (blocks % 8 == 0) ? 1 : 0;
     const int64_t ldp = (N + 3) / 4 * 4;
-    const size_t smem = SmemPipeT::bytes;
-    auto kern = slices > 1 ? mfma_gemm_pipe_t_kernel<Tag, true> : mfma_gemm_pipe_t_kernel<Tag, false>;
+    const bool half = (g.c % 128) != 0;
+    const size_t smem = half ? SmemPipeT<true>::bytes : SmemPipeT<false>::bytes;
+    auto kern = slices > 1 ? (half ? mfma_gemm_pipe_t_kernel<Tag, true, true> : mfma_gemm_pipe_t_kernel<Tag, true>)
+                           : (half ? mfma_gemm_pipe_t_kernel<Tag, false, true> : mfma_gemm_pipe_t_kernel<Tag, false>);
     LRBI_SET_MAX_LDS(kern, smem);
     LRBI_LAUNCH(kern, dim3((unsigned)blocks), dim3(PT_THREADS), smem, stream, g, (const uint16_t *)dW, ldw, dIp, dIz,
                 (const uint16_t *)dDY, lddy, (int)N, (uint16_t *)dDX, lddx, (float *)dWorkspace, ldp, (int)jblocks,

@@ -90,6 +90,13 @@ EDGE = [
     (_small(1024, 128, 128, 128, 64, 0.03, 72, "f16"), 0),      # rank 64: two I_p words per row, a batch block of 72
     (_small(768, 256, 384, 128, 40, 0.05, 80, "bf16"), 8),      # rank 40, three units per tile row, padded leading dimensions
     (_small(2048, 256, 512, 256, 5, 0.3, 256, "f16"), 0),       # rank 5 (a short round of ranks), four panels
+    # the same kernel on tile widths that are an odd multiple of 64 (Table 2's 576-column tiles): workgroups whose 128
+    # columns lie in two tile columns
+    (_small(512, 1152, 128, 576, 8, 0.2, 128, "f16"), 0),       # nine workgroups, the fifth across the two tile columns
+    (_small(1536, 1152, 512, 576, 40, 0.05, 136, "bf16"), 0),   # two I_p words, three panels, slices, a short batch block
+    (_small(1024, 384, 256, 192, 16, 0.1, 72, "f16"), 8),       # 192-column tiles, padded leading dimensions
+    (_small(640, 256, 128, 64, 8, 0.2, 128, "bf16"), 0),        # 64-column tiles: every workgroup has two tile columns
+    (_small(2048, 1152, 512, 576, 64, 0.04, 256, "f16"), 0),    # rank 64, four panels
 ]
 
 
