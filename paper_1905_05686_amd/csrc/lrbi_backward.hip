@@ -571,16 +571,27 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
     // parked factors any more.  Other shapes: word by word from global memory (a chain of dependent loads).
     static_assert(S::ms_words == 2 * kBwdThreads && FAST_MAX_K * 4 <= kBwdThreads && BI * 2 <= kBwdThreads,
                   "factor slices fit the mask array, one load per lane and factor");
-    const bool lined_up = (g.c % BJ) == 0 && (g.r % BI) == 0 && g.k <= FAST_MAX_K && !g.ragged;
+    // Tile widths that are an odd multiple of 64 (the 576-column tiles of Table 2), ranks up to 32: the block's upper
+    // 64 columns may lie in the next tile column; words 2 and 3 of the I_z rows and a second set of I_p words (behind
+    // the first one: one word per row) then come from that tile.
+    const bool half = (g.c % BJ) != 0 && (g.c % 64) == 0 && g.k <= 32;
+    const bool lined_up = ((g.c % BJ) == 0 || half) && (g.r % BI) == 0 && g.k <= FAST_MAX_K && !g.ragged;
     if (lined_up) {
         const int ti = (int)(i0 / g.r), tj = j0 / g.c;
         const int il0 = (int)(i0 - (int64_t)ti * g.r), coff = j0 - tj * g.c;
         const int64_t t = (int64_t)ti * g.tile_cols + tj;
+        const int jb = (j0 + 64 < n) ? j0 + 64 : j0; // (a block whose upper half is past the matrix: stand-in, never stored)
+        const int tjb = jb / g.c, coffb = jb - tjb * g.c;
+        const int64_t tb = (int64_t)ti * g.tile_cols + tjb;
+        const int w = tid & 3;
         uint32_t fzv = 0u, fpv = 0u;
-        if (tid < g.k * 4) fzv = Iz[(t * g.k + (tid >> 2)) * g.izw + (coff >> 5) + (tid & 3)];
+        if (tid < g.k * 4)
+            fzv = (half && w >= 2) ? Iz[(tb * g.k + (tid >> 2)) * g.izw + (coffb >> 5) + (w - 2)]
+                                   : Iz[(t * g.k + (tid >> 2)) * g.izw + (coff >> 5) + w];
         if (tid < BI * g.ipw) fpv = Ip[(t * g.r + il0) * g.ipw + tid];
+        else if (half) fpv = Ip[(tb * g.r + il0) + (tid - BI)];
         Ms[tid] = fzv;               // [k][4]
-        Ms[kBwdThreads + tid] = fpv; // [128][ipw]
+        Ms[kBwdThreads + tid] = fpv; // [128][ipw]; half: [2][128]
     }
     // this lane's two mask words
     auto mask_word = [&](int c) -> uint32_t {
@@ -588,8 +599,9 @@ __global__ __launch_bounds__(kBwdThreads) void mfma_grad_kernel(Geom g, const ui
         uint32_t word = 0u;
         if (lined_up) {
             const int row = idx >> 2, w = idx & 3;
+            const int pbase = kBwdThreads + ((half && w >= 2) ? BI : 0);
             for (int iw = 0; iw < g.ipw; ++iw) {
-                uint32_t sel = Ms[kBwdThreads + row * g.ipw + iw];
+                uint32_t sel = Ms[pbase + row * g.ipw + iw];
                 while (sel) {
                     const int l = __builtin_ctz(sel) + 32 * iw;
                     sel &= sel - 1u;

@@ -97,6 +97,8 @@ EDGE = [
     (_small(1024, 384, 256, 192, 16, 0.1, 72, "f16"), 8),       # 192-column tiles, padded leading dimensions
     (_small(640, 256, 128, 64, 8, 0.2, 128, "bf16"), 0),        # 64-column tiles: every workgroup has two tile columns
     (_small(2048, 1152, 512, 576, 64, 0.04, 256, "f16"), 0),    # rank 64, four panels
+    (_small(256, 960, 128, 192, 8, 0.2, 24, "f16"), 0),         # gradient: the last column block's upper half is past the matrix
+    (_small(1024, 1152, 512, 576, 32, 0.054, 64, "bf16"), 0),   # gradient: rank 32 on 576-column tiles
 ]
 
 
