@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, paper_fc5_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_search_C2, backward_C2, backward_C3b, backward_paper_fc5_tiles, lstm_sequence_C4, nmf_C2, nmf_C3, "
+                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, paper_fc5_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_eval_paper_fc5_tiles, alg1_search_C2, backward_C2, backward_C3b, backward_paper_fc5_tiles, lstm_sequence_C4, nmf_C2, nmf_C3, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -384,12 +384,12 @@ def main():
             except Exception as e:
                 others["conv_C5"] = {"error": repr(e)}
         # one candidate of Algorithm 1 per launch (threshold, decode on chip, ones and cost per tile)
-        for name in ("C2", "C3a"):
-            key = "alg1_eval_" + name[:2]
+        for name in ("C2", "C3a", "paper_fc5_tiles"):
+            key = "alg1_eval_" + (name[:2] if name in workloads.CONFIGS else name)
             if wanted is not None and key not in wanted:
                 continue
             try:
-                c = workloads.CONFIGS[name]
+                c = workloads.CONFIGS.get(name) or general[name]
                 d = workloads.make(c, want_x=False)
                 f = workloads.make_real_factors(c)
                 de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)

@@ -267,19 +267,19 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
     const int p_shift = 31 - __builtin_clz(P);
     const T *wtile = W + ((int64_t)ti * g.r + row_lo) * ldw + col0;
     constexpr int U = 4;
-    // Usual tile widths (a power of two of whole 32-column words per row, rows 16-byte aligned): a lane keeps its word
+    // Usual tile widths (whole 32-column words per row, rows 16-byte aligned): a lane keeps its word
     // column and walks down the rows.  Per row it requests the word's pieces of W (no test in front of a load: every
     // row it visits is inside the band), rebuilds the mask word ONCE for all of them, and its offsets, its word of
     // the I_z rows and its addresses' increment are constants: no index arithmetic in the loop.
     constexpr int PW = 32 / VEC; // 16-byte pieces per mask word
     const int words = ct >> 5;
-    const bool w_pow2 = words > 0 && (words & (words - 1)) == 0;
-    const bool walk = (ct % 32 == 0) && w_pow2 && words <= kEvalThreads && w_vec_ok && (col0 % VEC == 0);
+    const bool walk = (ct % 32 == 0) && words > 0 && words <= kEvalThreads && w_vec_ok && (col0 % VEC == 0);
     if (walk) {
-        const int w_shift = 31 - __builtin_clz(words);
-        const int wc = tid & (words - 1);
-        const int r0 = tid >> w_shift;
-        const int rstep = kEvalThreads >> w_shift;
+        // (one division per lane, outside the loop; when the words do not divide the workgroup, e.g. the 18 words of a
+        // 576-column tile, the lanes past the last whole row sit out)
+        const int wc = tid % words;
+        const int rstep = kEvalThreads / words;
+        const int r0 = (tid / words < rstep) ? tid / words : nrows;
         const uint32_t *izc = iz + wc;
         const T *wp = wtile + (int64_t)r0 * ldw + 32 * wc;
         const int64_t wstride = (int64_t)rstep * ldw;

@@ -87,6 +87,9 @@ EDGE = [
     (_small(600, 300, 300, 300, 8, 0.12, "f16"), 0),    # two tiles of 300 rows: 9 bands of 34 rows, ragged last band
     (_small(512, 512, 512, 512, 32, 0.06, "bf16"), 0),  # one tile, 16 bands
     (_small(1152, 1024, 576, 512, 145, 0.02, "f16"), 0), # the paper's 576 x 512 tiles at rank 145 (Sec. 4)
+    (_small(1024, 1152, 512, 576, 32, 0.054, "f16"), 0), # 576-column tiles: 18 words per row, lanes past 14 whole rows sit out
+    (_small(192, 288, 96, 96, 6, 0.2, "bf16"), 0),       # three words per row
+    (_small(256, 320, 128, 160, 8, 0.2, "f32"), 0),      # five words per row, four pieces per word
 ]
 
 
