@@ -75,7 +75,9 @@ typedef struct lrbi_desc {
 #define LRBI_FLAG_PATH_MFMA   0x00000002u /* matrix-core kernel (f16 / bf16 only) */
 #define LRBI_FLAG_PATH_STREAM 0x00000003u /* row-streaming kernels (W read once, any tile shape): f16 / bf16, N = 1 or a
                                              multiple of 4 up to 32, X contiguous (ldx = N) and 16-byte aligned, W rows
-                                             16-byte aligned */
+                                             16-byte aligned.  Chosen by the library for such calls when the matrix has
+                                             rows for half the compute units, or when its rows are short (64 KB of W per
+                                             16 rows on tile shapes the panel kernels take, 256 KB on others) */
 /* desc.flags bits 8..15: split of the n (reduction) range over workgroups for the
  * MFMA path, 0 = chosen by the library.  Values > 1 need a workspace. */
 #define LRBI_FLAG_SPLITK_SHIFT 8

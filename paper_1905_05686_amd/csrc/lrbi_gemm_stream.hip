@@ -37,6 +37,9 @@ static constexpr int ST_W_INSTR = 8;              // 1 KB copy instructions per 
 static constexpr int ST_WPIECE = 1024 + 16;       // LDS bytes per such piece (16 bytes of skew against bank conflicts)
 static constexpr int ST_WSTAGE = ST_W_INSTR * ST_WPIECE;
 static constexpr int ST_FP_ROWS = 16;             // I_p rows per tile held in LDS
+// bytes of W per workgroup up to which a grid of fewer workgroups than half the compute units is still served: tile
+// shapes that the panel kernels take, and every other shape (the generic tile kernel)
+static constexpr int ST_LONE_ROWS_BYTES_PANEL = 64 * 1024, ST_LONE_ROWS_BYTES = 256 * 1024;
 static constexpr int ST_FZ_MAX_BYTES = 40 * 1024; // packed I_z of one tile row that the kernel is willing to hold in LDS
 static constexpr int ST_X_PAD = 64;               // the transposing read of the last k rows may run this far past the slab
 
@@ -751,7 +754,13 @@ static bool plan_stream(const Geom &g, int64_t N, int cus, StreamPlan &p)
     const int nslabs = (int)((g.n + p.ks - 1) / p.ks);
     a.ms_pitch = nslabs * (p.ks / 32) + 1;
     const int64_t grid = (int64_t)g.tile_rows * a.blocks_per_tile_row;
-    if (grid > 0x7FFFFFFF || grid < cus / 2) return false;
+    // Few workgroups (small m) each walk a whole row length alone, at the latency of their own ring: worth it while a
+    // workgroup's rows are short (measured, 800 x 400 at rank 145 and 20 columns: 6.9 us against 29 + 4 us on the
+    // tile kernel with its split reduction; 256 x 2304 at 4 columns: 8.8 against 19.7 us; against the panel kernels
+    // on their tile shapes it breaks even at 128 KB per workgroup: 128 x 4096 at 8 columns 11.0 against 10.4 us)
+    if (grid > 0x7FFFFFFF) return false;
+    const bool panel_shape = (g.c % 128) == 0 && (g.r % 128) == 0 && g.k <= FAST_MAX_K && !g.ragged;
+    if (grid < cus / 2 && (int64_t)p.bm * g.n * 2 > (panel_shape ? ST_LONE_ROWS_BYTES_PANEL : ST_LONE_ROWS_BYTES)) return false;
     p.grid = (unsigned)grid;
     p.rv_pieces = 0;
     if (N == 1 && g.n <= RV_MAX_PIECES * 512) {

@@ -68,10 +68,10 @@ EDGE = [
     (_small(96, 200, 48, 100, 4, 0.2, 1, "f32"), 0),
     (_small(96, 200, 48, 100, 4, 0.2, 7, "f32"), 0),
     (_small(33, 77, 3, 7, 3, 0.3, 2, "f32"), 0),             # nothing aligned: scalar loads everywhere
-    (_small(130, 4104, 65, 1368, 9, 0.1, 1, "bf16"), 0),     # n spans three 2048-column segments
+    (_small(130, 4104, 65, 1368, 9, 0.1, 1, "bf16"), lrbi.FLAG_PATH_VALU),  # n spans three 2048-column segments
     (_small(130, 4104, 65, 1368, 9, 0.1, 3, "f16"), 0),
     (_small(128, 192, 64, 64, 8, 0.2, 128, "bf16"), 0),      # one 128x128 tile, 3 slabs
-    (_small(300, 2400, 300, 300, 8, 0.12, 20, "f16"), 0),    # unaligned tiles, scalar X path, split
+    (_small(300, 2400, 300, 300, 8, 0.12, 20, "f16"), lrbi.FLAG_PATH_MFMA),  # unaligned tiles, scalar X path, split
     (_small(3000, 600, 300, 300, 8, 0.12, 20, "f16"), 0),    # the row-streaming kernel by itself: 190 workgroups, the last of a tile row with 12 rows
     (_small(2100, 512, 300, 128, 6, 0.15, 8, "bf16"), 0),    # the same, bf16, 7 tile rows of 19 workgroups
     (_small(384, 1024, 128, 256, 16, 0.1, 72, "f16"), 0),    # 128x64 tile variant (N in 33..64 -> padded)
@@ -86,6 +86,10 @@ EDGE = [
     # tile shape and ranks of the paper's own experiments (Sec. 4: 576 x 512 tiles, rank 145; Table 1: rank 256)
     (_small(1152, 1024, 576, 512, 145, 0.02, 64, "f16"), 0),
     (_small(1152, 1024, 576, 512, 256, 0.015, 1, "bf16"), 0),
+    # few rows, short rows: the row-streaming kernels on a grid far smaller than the chip (automatic choice)
+    (_small(800, 400, 800, 400, 145, 0.05, 20, "f16"), 0),   # one untiled LSTM layer of 200 units at rank 145 (Table 2's LSTM row)
+    (_small(128, 1024, 128, 256, 16, 0.1, 8, "f16"), 0),     # eight workgroups
+    (_small(64, 4096, 64, 256, 16, 0.1, 1, "bf16"), 0),      # eight workgroups of the single-column kernel
     # tile widths that are an odd multiple of 64 on the pipelined tile kernel (Table 2's 576-column tiles): 128-column
     # units of the mask that lie across two tile columns
     (_small(256, 1152, 128, 576, 8, 0.2, 128, "f16"), 0),      # two tile columns, three panels, the last one short
@@ -183,7 +187,7 @@ def test_without_workspace_falls_back_to_unsplit_kernel():
     data = workloads.make(cfg)
     assert lrbi.masked_gemm_workspace_bytes(desc_of(cfg), lrbi.F16, cfg.N) > 0
     ref, _ = _oracle(cfg, data)
-    _assert_close(_run(cfg, data, use_workspace=False), ref, cfg.dtype, "no-ws")
+    _assert_close(_run(cfg, data, flags=lrbi.FLAG_PATH_MFMA, use_workspace=False), ref, cfg.dtype, "no-ws")
     with pytest.raises(lrbi.LrbiError) as e:
         _run(cfg, data, flags=lrbi.FLAG_PATH_MFMA | lrbi.flag_splitk(2), use_workspace=False)
     assert e.value.status == -8
@@ -271,7 +275,8 @@ FUSED = [
     _small(256, 1152, 128, 128, 8, 0.2, 128, "f16"),     # the tile kernel leaves the mask: one column block, unsplit
     _small(256, 1024, 256, 256, 16, 0.1, 256, "bf16"),   # two column blocks: only the first one stores the mask
     _small(128, 9216, 128, 256, 16, 0.08, 128, "f16"),   # split over n: every slice stores its own units, last panel short
-    _small(300, 2400, 300, 300, 8, 0.12, 20, "f16"),     # generic tile kernel, 32-column blocks, tiles cut through mask words
+    (_small(300, 2400, 300, 300, 8, 0.12, 20, "f16"), lrbi.FLAG_PATH_MFMA),  # generic tile kernel, 32-column blocks, tiles cut through mask words
+    _small(800, 400, 800, 400, 145, 0.05, 20, "f16"),    # few, short rows: the ring kernel on 50 workgroups
     _small(130, 264, 65, 33, 5, 0.3, 70, "bf16"),        # generic tile kernel, tiles narrower than two mask words
     _small(260, 520, 128, 128, 8, 0.2, 96, "f16"),       # generic kernel on cut-off aligned tiles: 8 bits of the last piece live
     _small(1152, 1024, 576, 512, 145, 0.02, 64, "f16"),  # rank 145
@@ -314,10 +319,10 @@ def test_fp16_subnormal_weights_are_not_flushed(N):
 
 @pytest.mark.parametrize("idx", range(len(FUSED)))
 def test_decode_and_gemm_equals_the_two_calls(idx):
-    cfg = FUSED[idx]
-    print("decode_and_gemm", idx, cfg, flush=True)
+    cfg, flags = FUSED[idx] if isinstance(FUSED[idx], tuple) else (FUSED[idx], 0)
+    print("decode_and_gemm", idx, cfg, hex(flags), flush=True)
     data = workloads.make(cfg)
-    desc = desc_of(cfg)
+    desc = desc_of(cfg, flags)
     dIp, dIz = device_factors(desc, data["Ip01"], data["Iz01"])
     W, X = to_device(data["W"], cfg.dtype), to_device(data["X"], cfg.dtype)
     ws = workspace_for(desc, DT_CODE[cfg.dtype], cfg.N)

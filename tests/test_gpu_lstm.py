@@ -169,21 +169,23 @@ def test_lstm_step_single_kernel_form():
         assert eh <= 1e-2 and ec <= 1e-2
 
 
-@pytest.mark.parametrize("H,n,r,c,k,B,dtype", [
-    (64, 128, 64, 64, 4, 20, "f16"),       # one slice: a single plane in the workspace
-    (75, 152, 100, 76, 8, 3, "bf16"),      # tiles that fit no tuned kernel, tiny batch, cut-off edge tiles
-    (128, 512, 128, 128, 8, 36, "f16"),    # tuned product kernel, several slices
-    (256, 1024, 256, 256, 16, 128, "bf16"),
+@pytest.mark.parametrize("H,n,r,c,k,B,dtype,flags", [
+    (64, 128, 64, 64, 4, 20, "f16", lrbi.FLAG_PATH_MFMA),  # tile kernel, one slice: a single plane in the workspace
+    (64, 128, 64, 64, 4, 20, "f16", 0),       # the same as one kernel on 16 workgroups
+    (200, 400, 800, 400, 145, 20, "f16", 0),  # 200 units, untiled, rank 145 (Table 2's LSTM row): one kernel, 50 workgroups
+    (75, 152, 100, 76, 8, 3, "bf16", 0),      # tiles that fit no tuned kernel, tiny batch, cut-off edge tiles
+    (128, 512, 128, 128, 8, 36, "f16", 0),    # tuned product kernel, several slices
+    (256, 1024, 256, 256, 16, 128, "bf16", 0),
     # enough rows for the row-streaming kernels, h apart from the input: the step as one kernel
-    (512, 520, 256, 130, 6, 12, "bf16"),   # a short last slab, tiles cut through mask words, one block of columns
-    (512, 512, 128, 128, 8, 32, "f16"),    # both blocks of columns; a gate's rows start a tile
-    (516, 256, 172, 64, 5, 4, "f16"),      # tile height no multiple of 16: the units of a workgroup sit anywhere in a tile
-    (510, 256, 170, 64, 5, 8, "f16"),      # H and r no multiples of 4: two launches
+    (512, 520, 256, 130, 6, 12, "bf16", 0),   # a short last slab, tiles cut through mask words, one block of columns
+    (512, 512, 128, 128, 8, 32, "f16", 0),    # both blocks of columns; a gate's rows start a tile
+    (516, 256, 172, 64, 5, 4, "f16", 0),      # tile height no multiple of 16: the units of a workgroup sit anywhere in a tile
+    (510, 256, 170, 64, 5, 8, "f16", 0),      # H and r no multiples of 4: two launches
 ])
-def test_fused_lstm_step_small_shapes(H, n, r, c, k, B, dtype):
-    cfg = workloads.Config("t", 4 * H, n, r, c, k, 0.2, B, dtype, 0.1, 5)
+def test_fused_lstm_step_small_shapes(H, n, r, c, k, B, dtype, flags):
+    cfg = workloads.Config("t", 4 * H, n, r, c, k, 0.2 if k < 64 else 0.05, B, dtype, 0.1, 5)
     data = workloads.make(cfg)
-    desc = desc_of(cfg)
+    desc = desc_of(cfg, flags)
     dIp, dIz = device_factors(desc, data["Ip01"], data["Iz01"])
     rng = np.random.default_rng(9)
     c_prev = rng.standard_normal((H, B)).astype(np.float32)
