@@ -765,7 +765,10 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
     if (tile < 1 || tile > kNumTiles) {
         tile = (N > 64) ? 1 : (N > 32 ? 2 : 3);
         if (panel_ok(g, 128)) tile = (N > 64) ? 14 : (N > 32 ? 10 : 11); // 14: falls back to 9 when X is not 16-byte readable
-        else if (N > 64 && pipe_shape_ok(g)) tile = 14; // tile widths of 64 (2 j + 1): falls back to the generic kernel
+        // tile widths of 64 (2 j + 1): no panel kernel, so the pipelined kernel also takes 33 to 64 columns (half of its
+        // column block idle, but W is streamed at the same rate: 4096 x 9216 in 512 x 576 tiles, N = 64, 25 us against
+        // 40 us on the generic kernel); falls back to the generic kernel when X is not 16-byte readable
+        else if (N > 32 && pipe_shape_ok(g)) tile = 14;
     }
     p.tile = tile;
     p.bm = kTiles[tile].bm;

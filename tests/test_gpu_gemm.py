@@ -97,6 +97,8 @@ EDGE = [
     (_small(128, 9216, 128, 576, 32, 0.054, 128, "f16"), 0),   # split over n: slices begin inside tiles
     (_small(256, 768, 256, 192, 16, 0.1, 72, "bf16"), 0),      # 192-column tiles
     (_small(128, 512, 128, 64, 8, 0.2, 128, "f16"), 0),        # 64-column tiles: every unit has two tiles
+    (_small(256, 1152, 128, 576, 8, 0.2, 64, "f16"), 0),       # 33 to 64 columns on these widths: the same kernel, half a block
+    (_small(256, 1152, 128, 576, 8, 0.2, 40, "bf16"), 0),
     (_small(256, 2304, 128, 576, 16, 0.1, 256, "bf16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_splitk(3)),
 ]
 
@@ -288,6 +290,7 @@ FUSED = [
     _small(256, 3456, 128, 576, 40, 0.05, 136, "bf16"),
     _small(128, 9216, 128, 576, 32, 0.054, 128, "f16"),
     _small(128, 512, 128, 64, 8, 0.2, 128, "f16"),
+    _small(256, 1152, 128, 576, 8, 0.2, 40, "bf16"),
     workloads.Config("paper_fc5_tiles", 4096, 9216, 512, 576, 32, 0.054, 128, "f16", 0.01),  # Table 2's tiling of C2's layer
     # narrow batches with enough rows for the row-streaming kernels: they store the rows' mask from LDS
     _small(3000, 600, 300, 300, 8, 0.12, 20, "f16"),     # ring kernel, tiles cut through mask words, last workgroups short
