@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, paper_fc5_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_eval_paper_fc5_tiles, alg1_search_C2, backward_C2, backward_C3b, backward_paper_fc5_tiles, lstm_sequence_C4, nmf_C2, nmf_C3, "
+                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, paper_fc5_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_eval_paper_fc5_tiles, alg1_search_C2, backward_C2, backward_C3b, backward_paper_fc5_tiles, lstm_sequence_C4, lstm_sequence_paper_rank145, nmf_C2, nmf_C3, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -414,9 +414,14 @@ def main():
         # straight into the next inputs), one graph replay.  With two input buffers per layer in turn, h never goes
         # into the buffer the step reads and a step is one kernel; with one buffer per layer it is two launches.
         # Against the same sequence with separate product, reduction and (torch) gate kernels
-        if wanted is None or "lstm_sequence_C4" in wanted:
+        # (and the layer Table 2's LSTM row implies: rank 145 at a compression of 1.82 means an untiled 800 x 400 gate
+        # matrix, 200 hidden units)
+        for lkey, lkw in (("lstm_sequence_C4", {}),
+                          ("lstm_sequence_paper_rank145", {"hidden": 200, "r": 800, "c": 400, "k": 145, "p": 0.05})):
+            if wanted is not None and lkey not in wanted:
+                continue
             try:
-                Ld = workloads.make_lstm()
+                Ld = workloads.make_lstm(**lkw)
                 c = Ld["cfg"]
                 Hh, Bb, steps_, layers_ = Ld["hidden"], Ld["batch"], Ld["steps"], Ld["layers"]
                 de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
@@ -463,7 +468,7 @@ def main():
                 ms_f, _ = event_times([fused_sequence], 3, 1)
                 ms_2, _ = event_times([two_launch_sequence], 3, 1)
                 ms_u, _ = event_times([unfused_sequence], 3, 1)
-                others["lstm_sequence_C4"] = {
+                others[lkey] = {
                     "workload": "LSTM, %d layers x %d steps, hidden %d, batch %d, gate matrix %dx%d %s, tiles %dx%d rank %d"
                                 % (layers_, steps_, Hh, Bb, c.m, c.n, c.dtype, c.r, c.c, c.k),
                     "fused_sequence_ms": round(ms_f, 4), "fused_us_per_step": round(ms_f * 1e3 / (steps_ * layers_), 2),
@@ -472,7 +477,7 @@ def main():
                     "dense_equiv_tflops_fused": round(2.0 * c.m * c.n * Bb * steps_ * layers_ / (ms_f * 1e-3) / 1e12, 2)}
                 del Wd, xs_, lws, xh, xh2, cs
             except Exception as e:
-                others["lstm_sequence_C4"] = {"error": repr(e)}
+                others[lkey] = {"error": repr(e)}
         # backward pass through the masking layer: dX = (W o I_a)^T dY and dW = (dY X^T) o I_a
         for name in ("C2", "C3b", "paper_fc5_tiles"):
             key = "backward_" + name

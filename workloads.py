@@ -157,11 +157,14 @@ def make_factors_only(cfg: Config) -> dict:
 
 
 def make_lstm(seed: int = 0, steps: int = LSTM_STEPS, layers: int = LSTM_LAYERS,
-              hidden: int = LSTM_HIDDEN, batch: int = 20) -> dict:
+              hidden: int = LSTM_HIDDEN, batch: int = 20, r: int = 0, c: int = 0, k: int = 0, p: float = 0.0) -> dict:
     """C4: per layer a (4*hidden) x (2*hidden) fp16 gate matrix with 300x300
-    tiles of rank 8, plus the input sequence x_t [hidden, batch] for every step."""
+    tiles of rank 8 (or tiles r x c of rank k, factor density p), plus the input
+    sequence x_t [hidden, batch] for every step."""
     base = CONFIGS["C4"]
     cfg = replace(base, m=4 * hidden, n=2 * hidden, N=batch, seed=seed)
+    if r and c and k and p:
+        cfg = replace(cfg, r=r, c=c, k=k, p=p)
     rng = np.random.default_rng(seed)
     Ws, Ips, Izs = [], [], []
     for _ in range(layers):
