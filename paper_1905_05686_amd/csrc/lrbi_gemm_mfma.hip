@@ -769,6 +769,16 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
         // column block idle, but W is streamed at the same rate: 4096 x 9216 in 512 x 576 tiles, N = 64, 25 us against
         // 40 us on the generic kernel); falls back to the generic kernel when X is not 16-byte readable
         else if (N > 32 && pipe_shape_ok(g)) tile = 14;
+        else if (tile == 1) {
+            // few rows, many columns (a small convolution layer as a product): narrower column blocks that fill the
+            // chip by themselves instead of a split with its round trip of partial planes (64 x 576, N = 16384:
+            // 19.4 us against 18.7 + 4.2 us)
+            const int64_t mb = (g.m + 127) / 128;
+            if (mb * ((N + 127) / 128) < 192) {
+                if (mb * ((N + 63) / 64) >= 192) tile = 2;
+                else if (mb * ((N + 31) / 32) >= 192) tile = 3;
+            }
+        }
     }
     p.tile = tile;
     p.bm = kTiles[tile].bm;

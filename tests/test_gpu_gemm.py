@@ -86,6 +86,8 @@ EDGE = [
     # tile shape and ranks of the paper's own experiments (Sec. 4: 576 x 512 tiles, rank 145; Table 1: rank 256)
     (_small(1152, 1024, 576, 512, 145, 0.02, 64, "f16"), 0),
     (_small(1152, 1024, 576, 512, 256, 0.015, 1, "bf16"), 0),
+    (_small(64, 576, 64, 576, 8, 0.2, 12416, "bf16"), 0),    # few rows, many columns: 64-column blocks, unsplit
+    (_small(48, 288, 16, 96, 4, 0.3, 3080, "f16"), 0),       # ... 32-column blocks
     # few rows, short rows: the row-streaming kernels on a grid far smaller than the chip (automatic choice)
     (_small(800, 400, 800, 400, 145, 0.05, 20, "f16"), 0),   # one untiled LSTM layer of 200 units at rank 145 (Table 2's LSTM row)
     (_small(128, 1024, 128, 256, 16, 0.1, 8, "f16"), 0),     # eight workgroups
