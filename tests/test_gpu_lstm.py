@@ -200,3 +200,37 @@ def test_fused_lstm_step_small_shapes(H, n, r, c, k, B, dtype, flags):
     c_ref = sg(z[H:2 * H]) * c_prev.astype(np.float64) + sg(z[0:H]) * np.tanh(z[2 * H:3 * H])
     h_ref = sg(z[3 * H:]) * np.tanh(c_ref)
     assert orc.rel_err(to_float64(C), c_ref) <= 1e-2 and orc.rel_err(to_float64(h1), h_ref) <= 1e-2
+
+
+def test_lstm_sequence_on_the_rank_145_layer():
+    """The layer that Table 2's LSTM row implies (200 hidden units: an untiled 800 x 400 gate matrix at rank 145), 2
+    layers x 35 steps through lrbi_lstm_step with alternating input buffers, free-running, against the oracle; the
+    product runs on the row-streaming kernel with far fewer workgroups than compute units."""
+    L = workloads.make_lstm(hidden=200, r=800, c=400, k=145, p=0.05)
+    cfg = L["cfg"]
+    H, B, steps, layers = L["hidden"], L["batch"], L["steps"], L["layers"]
+    assert (cfg.m, cfg.n, cfg.r, cfg.c, cfg.k) == (800, 400, 800, 400, 145)
+    Ws64 = [workloads.to_float64(w, cfg.dtype) for w in L["W"]]
+    Ms = [orc.decode_mask(L["Ip01"][l], L["Iz01"][l], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k) for l in range(layers)]
+    assert 0.2 < Ms[0].mean() < 0.5
+    ref = lstm_oracle.lstm_sequence(Ws64, Ms, workloads.to_float64(L["x"], cfg.dtype), round_input=_round_f16,
+                                    threads=ORACLE_THREADS)
+    desc = desc_of(cfg)
+    dW = [to_device(w, cfg.dtype) for w in L["W"]]
+    fac = [device_factors(desc, L["Ip01"][l], L["Iz01"][l]) for l in range(layers)]
+    ws = torch.empty(max(16, lrbi.lstm_step_workspace_bytes(desc, lrbi.F16, B)), dtype=torch.uint8, device="cuda")
+    xs = to_device(L["x"], cfg.dtype)
+    xh = [[torch.zeros((2 * H, B), dtype=torch.float16, device="cuda") for _ in range(2)] for _ in range(layers)]
+    c = [torch.zeros((H, B), dtype=torch.float32, device="cuda") for _ in range(layers)]
+    for t in range(steps):
+        cur, nxt = t % 2, (t + 1) % 2
+        xh[0][cur][:H].copy_(xs[t])
+        for l in range(layers):
+            up = xh[l + 1][cur][:H] if l + 1 < layers else None
+            lrbi.lstm_step(desc, dW[l], fac[l][0], fac[l][1], xh[l][cur], c[l], xh[l][nxt][H:], up, workspace=ws)
+    torch.cuda.synchronize()
+    for l in range(layers):
+        eh = orc.rel_err(to_float64(xh[l][steps % 2][H:]), ref["h"][l])
+        ec = orc.rel_err(to_float64(c[l]), ref["c"][l])
+        print("rank-145 layer %d: h err %.3e, c err %.3e" % (l, eh, ec), flush=True)
+        assert eh <= 1e-2 and ec <= 1e-2
