@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, paper_fc5_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_eval_paper_fc5_tiles, alg1_search_C2, backward_C2, backward_C3b, backward_paper_fc5_tiles, lstm_sequence_C4, lstm_sequence_paper_rank145, nmf_C2, nmf_C3, "
+                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, paper_fc5_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_eval_C4, alg1_eval_paper_fc5_tiles, alg1_search_C2, backward_C2, backward_C3b, backward_paper_fc5_tiles, lstm_sequence_C4, lstm_sequence_paper_rank145, nmf_C2, nmf_C3, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -384,7 +384,7 @@ def main():
             except Exception as e:
                 others["conv_C5"] = {"error": repr(e)}
         # one candidate of Algorithm 1 per launch (threshold, decode on chip, ones and cost per tile)
-        for name in ("C2", "C3a", "paper_fc5_tiles"):
+        for name in ("C2", "C3a", "C4", "paper_fc5_tiles"):
             key = "alg1_eval_" + (name[:2] if name in workloads.CONFIGS else name)
             if wanted is not None and key not in wanted:
                 continue
@@ -402,8 +402,8 @@ def main():
                        for Wi in Wl]
                 ms, _ = event_times(fns, 6 * len(fns), len(fns))
                 byts = c.m * c.n * 2 + c.tiles * c.k * (c.r + c.c) * 4 + c.tiles * 16
-                others[key] = {"workload": "%s: W %dx%d %s, U(0,1) factors thresholded at 1 - p, cost threshold 1.645 sigma"
-                                           % (name[:2], c.m, c.n, c.dtype),
+                others[key] = {"workload": "%s: W %dx%d %s, tiles %dx%d rank %d, U(0,1) factors thresholded at 1 - p, cost threshold 1.645 sigma"
+                                           % (key[10:], c.m, c.n, c.dtype, c.r, c.c, c.k),
                                "avg_launch_ms_cold": round(ms, 5), "GBs": round(byts / (ms * 1e-3) / 1e9, 1),
                                "hbm_frac": round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                                "candidates_per_s": round(1.0 / (ms * 1e-3), 1)}

@@ -340,10 +340,16 @@ __global__ __launch_bounds__(kEvalThreads) void threshold_eval_kernel(Geom g, co
                 const int j = (id - i * P) * VEC;
                 const T *wrow = wtile + (int64_t)i * ldw;
                 const int nvalid = (ct - j < VEC) ? ct - j : VEC;
-                const bool vec = w_vec_ok && (nvalid == VEC) && (((col0 + j) % VEC) == 0);
+                const int mis = (int)((col0 + j) % VEC);
+                const bool vec = w_vec_ok && (nvalid == VEC) && mis == 0;
                 if (vec) {
                     const uint4 v = *reinterpret_cast<const uint4 *>(wrow + j);
                     w4[u][0] = v.x; w4[u][1] = v.y; w4[u][2] = v.z; w4[u][3] = v.w;
+                } else if (w_vec_ok && (nvalid == VEC) && 2 * mis == VEC) {
+                    // tiles that start half a piece off (300-column tiles: every other tile column): two 8-byte loads
+                    const uint2 v0 = *reinterpret_cast<const uint2 *>(wrow + j);
+                    const uint2 v1 = *reinterpret_cast<const uint2 *>(wrow + j + VEC / 2);
+                    w4[u][0] = v0.x; w4[u][1] = v0.y; w4[u][2] = v1.x; w4[u][3] = v1.y;
                 } else if (sizeof(T) == 4) {
                     const uint32_t *wr = reinterpret_cast<const uint32_t *>(wrow);
 #pragma unroll
