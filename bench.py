@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the per-configuration extras")
     ap.add_argument("--extras", default="all",
                     help="comma-separated subset of the extras to run (decode_scaled_C2, decode_scaled_C3, C3a, C3b, "
-                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, paper_fc5_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_eval_C4, alg1_eval_paper_fc5_tiles, alg1_search_C2, backward_C2, backward_C3b, backward_paper_fc5_tiles, lstm_sequence_C4, lstm_sequence_paper_rank145, nmf_C2, nmf_C3, "
+                         "C4, C5, conv_C5, C1, general_resnet_tiles, general_edge_tiles, paper_fc5_tiles, steady_state_C3_tiles, alg1_eval_C2, alg1_eval_C3, alg1_eval_C4, alg1_eval_paper_fc5_tiles, alg1_search_C2, backward_C2, backward_C3b, backward_paper_fc5_tiles, lstm_sequence_C4, lstm_sequence_paper_rank145, nmf_C2, nmf_C3, nmf_C4, nmf_paper_fc5_tiles, "
                          "ceilings); used to profile one workload at a time")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -512,12 +512,12 @@ def main():
             except Exception as e:
                 others[key] = {"error": repr(e)}
         # non-negative factorisation of |W| per tile (Algorithm 1's first step): multiplicative updates on C2 and C3
-        for name in ("C2", "C3a"):
-            key = "nmf_" + name[:2]
+        for name in ("C2", "C3a", "C4", "paper_fc5_tiles"):
+            key = "nmf_" + (name[:2] if name in workloads.CONFIGS else name)
             if wanted is not None and key not in wanted:
                 continue
             try:
-                c = workloads.CONFIGS[name]
+                c = workloads.CONFIGS.get(name) or general[name]
                 d = workloads.make(c, want_x=False)
                 de = lrbi.Desc(c.m, c.n, c.r, c.c, c.k)
                 W_ = to_dev(d["W"], c.dtype)
@@ -540,7 +540,7 @@ def main():
                 ms = float(sorted(ts)[1])
                 fl = iters_ * 4.0 * c.m * c.n * c.k  # two products with the magnitude matrix per iteration
                 others[key] = {"workload": "%s: |W| %dx%d %s, tiles %dx%d, rank %d, %d multiplicative updates"
-                                           % (name[:2], c.m, c.n, c.dtype, c.r, c.c, c.k, iters_),
+                                           % (key[4:], c.m, c.n, c.dtype, c.r, c.c, c.k, iters_),
                                "ms": round(ms, 4), "us_per_iteration": round(ms * 1e3 / iters_, 2),
                                "tflops_fp32": round(fl / (ms * 1e-3) / 1e12, 2),
                                "alu_frac_of_157_tflops": round(fl / (ms * 1e-3) / 1e12 / 157.3, 4)}
