@@ -414,10 +414,10 @@ def main():
         # straight into the next inputs), one graph replay.  With two input buffers per layer in turn, h never goes
         # into the buffer the step reads and a step is one kernel; with one buffer per layer it is two launches.
         # Against the same sequence with separate product, reduction and (torch) gate kernels
-        # (and the layer Table 2's LSTM row implies: rank 145 at a compression of 1.82 means an untiled 800 x 400 gate
-        # matrix, 200 hidden units)
+        # (and on a layer of the size Sec. 4 names for its LSTM, 300 units: a 1200 x 600 gate matrix, untiled, at
+        # Table 2's rank 145)
         for lkey, lkw in (("lstm_sequence_C4", {}),
-                          ("lstm_sequence_paper_rank145", {"hidden": 200, "r": 800, "c": 400, "k": 145, "p": 0.05})):
+                          ("lstm_sequence_paper_rank145", {"hidden": 300, "r": 1200, "c": 600, "k": 145, "p": 0.05})):
             if wanted is not None and lkey not in wanted:
                 continue
             try:

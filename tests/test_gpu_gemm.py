@@ -89,7 +89,8 @@ EDGE = [
     (_small(64, 576, 64, 576, 8, 0.2, 12416, "bf16"), 0),    # few rows, many columns: 64-column blocks, unsplit
     (_small(48, 288, 16, 96, 4, 0.3, 3080, "f16"), 0),       # ... 32-column blocks
     # few rows, short rows: the row-streaming kernels on a grid far smaller than the chip (automatic choice)
-    (_small(800, 400, 800, 400, 145, 0.05, 20, "f16"), 0),   # one untiled LSTM layer of 200 units at rank 145 (Table 2's LSTM row)
+    (_small(1200, 600, 1200, 600, 145, 0.05, 20, "f16"), 0), # the gate matrix of an LSTM layer of size 300 (Sec. 4), untiled, at Table 2's rank 145
+    (_small(800, 400, 800, 400, 145, 0.05, 20, "f16"), 0),   # 50 workgroups
     (_small(128, 1024, 128, 256, 16, 0.1, 8, "f16"), 0),     # eight workgroups
     (_small(64, 4096, 64, 256, 16, 0.1, 1, "bf16"), 0),      # eight workgroups of the single-column kernel
     # tile widths that are an odd multiple of 64 on the pipelined tile kernel (Table 2's 576-column tiles): 128-column
@@ -280,7 +281,7 @@ FUSED = [
     _small(256, 1024, 256, 256, 16, 0.1, 256, "bf16"),   # two column blocks: only the first one stores the mask
     _small(128, 9216, 128, 256, 16, 0.08, 128, "f16"),   # split over n: every slice stores its own units, last panel short
     (_small(300, 2400, 300, 300, 8, 0.12, 20, "f16"), lrbi.FLAG_PATH_MFMA),  # generic tile kernel, 32-column blocks, tiles cut through mask words
-    _small(800, 400, 800, 400, 145, 0.05, 20, "f16"),    # few, short rows: the ring kernel on 50 workgroups
+    _small(1200, 600, 1200, 600, 145, 0.05, 20, "f16"),  # few, short rows (an LSTM layer of size 300 at rank 145): the ring kernel on 75 workgroups
     _small(130, 264, 65, 33, 5, 0.3, 70, "bf16"),        # generic tile kernel, tiles narrower than two mask words
     _small(260, 520, 128, 128, 8, 0.2, 96, "f16"),       # generic kernel on cut-off aligned tiles: 8 bits of the last piece live
     _small(1152, 1024, 576, 512, 145, 0.02, 64, "f16"),  # rank 145

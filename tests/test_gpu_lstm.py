@@ -172,7 +172,7 @@ def test_lstm_step_single_kernel_form():
 @pytest.mark.parametrize("H,n,r,c,k,B,dtype,flags", [
     (64, 128, 64, 64, 4, 20, "f16", lrbi.FLAG_PATH_MFMA),  # tile kernel, one slice: a single plane in the workspace
     (64, 128, 64, 64, 4, 20, "f16", 0),       # the same as one kernel on 16 workgroups
-    (200, 400, 800, 400, 145, 20, "f16", 0),  # 200 units, untiled, rank 145 (Table 2's LSTM row): one kernel, 50 workgroups
+    (300, 600, 1200, 600, 145, 20, "f16", 0),  # a layer of size 300 (Sec. 4), untiled, rank 145 (Table 2): 75 workgroups
     (75, 152, 100, 76, 8, 3, "bf16", 0),      # tiles that fit no tuned kernel, tiny batch, cut-off edge tiles
     (128, 512, 128, 128, 8, 36, "f16", 0),    # tuned product kernel, several slices
     (256, 1024, 256, 256, 16, 128, "bf16", 0),
@@ -203,13 +203,13 @@ def test_fused_lstm_step_small_shapes(H, n, r, c, k, B, dtype, flags):
 
 
 def test_lstm_sequence_on_the_rank_145_layer():
-    """The layer that Table 2's LSTM row implies (200 hidden units: an untiled 800 x 400 gate matrix at rank 145), 2
-    layers x 35 steps through lrbi_lstm_step with alternating input buffers, free-running, against the oracle; the
+    """An LSTM layer of the size Sec. 4 names (300 units: a 1200 x 600 gate matrix; untiled here, the paper does not say)
+    at Table 2's rank 145, 2 layers x 35 steps through lrbi_lstm_step with alternating input buffers, free-running, against the oracle; the
     product runs on the row-streaming kernel with far fewer workgroups than compute units."""
-    L = workloads.make_lstm(hidden=200, r=800, c=400, k=145, p=0.05)
+    L = workloads.make_lstm(hidden=300, r=1200, c=600, k=145, p=0.05)
     cfg = L["cfg"]
     H, B, steps, layers = L["hidden"], L["batch"], L["steps"], L["layers"]
-    assert (cfg.m, cfg.n, cfg.r, cfg.c, cfg.k) == (800, 400, 800, 400, 145)
+    assert (cfg.m, cfg.n, cfg.r, cfg.c, cfg.k) == (1200, 600, 1200, 600, 145)
     Ws64 = [workloads.to_float64(w, cfg.dtype) for w in L["W"]]
     Ms = [orc.decode_mask(L["Ip01"][l], L["Iz01"][l], cfg.m, cfg.n, cfg.r, cfg.c, cfg.k) for l in range(layers)]
     assert 0.2 < Ms[0].mean() < 0.5
