@@ -77,7 +77,9 @@ typedef struct lrbi_desc {
                                              multiple of 4 up to 32, X contiguous (ldx = N) and 16-byte aligned, W rows
                                              16-byte aligned.  Chosen by the library for such calls when the matrix has
                                              rows for half the compute units, or when its rows are short (64 KB of W per
-                                             16 rows on tile shapes the panel kernels take, 256 KB on others) */
+                                             16 rows on tile shapes the panel kernels take, 256 KB on others); not for
+                                             N = 16, 24, 32 on those tile shapes when rows are long (above 128 KB per 16
+                                             rows) and there is at most one workgroup per compute unit */
 /* desc.flags bits 8..15: split of the n (reduction) range over workgroups for the
  * MFMA path, 0 = chosen by the library.  Values > 1 need a workspace. */
 #define LRBI_FLAG_SPLITK_SHIFT 8

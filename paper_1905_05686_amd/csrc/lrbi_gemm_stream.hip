@@ -761,6 +761,11 @@ static bool plan_stream(const Geom &g, int64_t N, int cus, StreamPlan &p)
     if (grid > 0x7FFFFFFF) return false;
     const bool panel_shape = (g.c % 128) == 0 && (g.r % 128) == 0 && g.k <= FAST_MAX_K && !g.ragged;
     if (grid < cus / 2 && (int64_t)p.bm * g.n * 2 > (panel_shape ? ST_LONE_ROWS_BYTES_PANEL : ST_LONE_ROWS_BYTES)) return false;
+    // At most one workgroup per compute unit walking long rows, on a tile shape and batch that the panel kernels take
+    // with 16-byte X loads: their split over n keeps more loads in flight (HBM-cold W, N = 32: 2048 x 9216 18.6 against
+    // 25.8 us, 4096 x 9216 24.1 against 27.6 us; 4096 x 4096, 128 KB per workgroup: 15.2 against 14.1 us, left here)
+    if (panel_shape && N >= 16 && N % 8 == 0 && grid <= cus && (int64_t)p.bm * g.n * 2 > 2 * ST_LONE_ROWS_BYTES_PANEL)
+        return false;
     p.grid = (unsigned)grid;
     p.rv_pieces = 0;
     if (N == 1 && g.n <= RV_MAX_PIECES * 512) {
