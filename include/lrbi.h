@@ -208,10 +208,10 @@ int lrbi_masked_gemm(const lrbi_desc *desc, lrbi_dtype dtype, const void *dW, in
  * lrbi_masked_gemm_workspace_bytes).  For f16 / bf16 layers this is one product launch (plus the split reduction
  * when the plan splits) on the kernels that rebuild the mask in a form they can store on the way, so that the
  * stand-alone decode kernel and its launch drop out: the pipelined tile kernel (c % 128 == 0, or c % 64 == 0 with
- * n % 128 == 0 (then N > 32 is enough); r % 128 == 0, k <= 64, no cut-off tiles, N > 64, X and W readable in 16-byte pieces), the generic tile kernel (any tile shape and rank,
- * cut-off tiles, N > 4, W readable in 16-byte pieces), and the row-streaming kernels for narrow batches (N = 1 or a
- * multiple of 4 up to 32, any tile shape).  Every other case (fp32, the staged panel kernel at 33 to 64 columns on
- * aligned tile shapes, unaligned W) runs lrbi_decode_mask and then lrbi_masked_gemm on `stream`.  Results are
+ * n % 128 == 0; r % 128 == 0, k <= 64, no cut-off tiles, N > 32, X and W readable in 16-byte pieces), the generic
+ * tile kernel (any tile shape and rank, cut-off tiles, N > 4, W readable in 16-byte pieces), and the row-streaming
+ * kernels for narrow batches (N = 1 or a multiple of 4 up to 32, any tile shape).  Every other case (fp32, the
+ * staged panel kernels, unaligned W) runs lrbi_decode_mask and then lrbi_masked_gemm on `stream`.  Results are
  * bit-identical to those two calls.
  * Errors: those of the two entry points.
  */

@@ -764,7 +764,9 @@ MfmaPlan plan_mfma(const Geom &g, uint32_t flags, int64_t N)
         tile = 0;
     if (tile < 1 || tile > kNumTiles) {
         tile = (N > 64) ? 1 : (N > 32 ? 2 : 3);
-        if (panel_ok(g, 128)) tile = (N > 64) ? 14 : (N > 32 ? 10 : 11); // 14: falls back to 9 when X is not 16-byte readable
+        // 14 (the pipelined kernel, also at 33 to 64 columns: HBM-cold 4096 x 9216 at N = 64 25.0 against 26.9 us on
+        // the 128 x 64 panel kernel) falls back to 9 / 10 when X is not 16-byte readable
+        if (panel_ok(g, 128)) tile = (N > 32) ? 14 : 11;
         // tile widths of 64 (2 j + 1): no panel kernel, so the pipelined kernel also takes 33 to 64 columns (half of its
         // column block idle, but W is streamed at the same rate: 4096 x 9216 in 512 x 576 tiles, N = 64, 25 us against
         // 40 us on the generic kernel); falls back to the generic kernel when X is not 16-byte readable
@@ -971,7 +973,7 @@ int launch_mfma_gemm(const Geom &g, const MfmaPlan &plan_in, lrbi_dtype dt, cons
             }
             return LRBI_OK;
         }
-        plan.tile = panel_ok(g, 128) ? 9 : 1; // same blocking on the staged panel kernel, or on the generic one
+        plan.tile = panel_ok(g, 128) ? (N > 64 ? 9 : 10) : 1; // the staged panel kernels, or the generic one
     }
     if (mo.ptr && !(plan.tile >= 1 && plan.tile <= 3)) return LRBI_ERR_SHAPE; // the caller asks mfma_gemm_emits_mask() first
     if (dt == LRBI_F16)

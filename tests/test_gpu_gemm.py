@@ -76,6 +76,8 @@ EDGE = [
     (_small(2100, 512, 300, 128, 6, 0.15, 8, "bf16"), 0),    # the same, bf16, 7 tile rows of 19 workgroups
     (_small(384, 1024, 128, 256, 16, 0.1, 72, "f16"), 0),    # 128x64 tile variant (N in 33..64 -> padded)
     (_small(384, 1024, 128, 256, 16, 0.1, 40, "bf16"), 0),
+    (_small(384, 1024, 128, 256, 16, 0.1, 48, "bf16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_tile(10)),  # the 128 x 64 panel kernel by flag
+    (_small(384, 1024, 128, 256, 16, 0.1, 44, "f16"), 0),    # N no multiple of 8: the 128 x 64 panel kernel by itself
     (_small(200, 1000, 100, 500, 40, 0.05, 136, "bf16"), 0), # rank above 32, ragged m and N
     (_small(256, 2048, 128, 512, 32, 0.06, 256, "bf16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_splitk(4)),
     (_small(256, 2048, 128, 512, 32, 0.06, 256, "f16"), lrbi.FLAG_PATH_MFMA | lrbi.flag_splitk(1)),
