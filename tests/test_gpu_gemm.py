@@ -281,6 +281,7 @@ def test_full_size_sampled_rows_in_bench_configuration():
 FUSED = [
     _small(256, 1152, 128, 128, 8, 0.2, 128, "f16"),     # the tile kernel leaves the mask: one column block, unsplit
     _small(256, 1024, 256, 256, 16, 0.1, 256, "bf16"),   # two column blocks: only the first one stores the mask
+    _small(256, 1024, 256, 256, 16, 0.1, 48, "bf16"),    # 33 to 64 columns: the same kernel, part of its column block idle
     _small(128, 9216, 128, 256, 16, 0.08, 128, "f16"),   # split over n: every slice stores its own units, last panel short
     (_small(300, 2400, 300, 300, 8, 0.12, 20, "f16"), lrbi.FLAG_PATH_MFMA),  # generic tile kernel, 32-column blocks, tiles cut through mask words
     _small(1200, 600, 1200, 600, 145, 0.05, 20, "f16"),  # few, short rows (an LSTM layer of size 300 at rank 145): the ring kernel on 75 workgroups
