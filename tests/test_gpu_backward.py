@@ -84,12 +84,13 @@ EDGE = [
     (_small(1024, 384, 256, 384, 16, 0.1, 40, "f16"), 0),       # workgroups at three offsets inside a tile column
     (_small(512, 128, 128, 128, 64, 0.03, 8, "f16"), 0),        # smallest tile rows of the tuned mask path, rank 64
     (_small(2048, 512, 512, 512, 32, 0.06, 4, "bf16"), 0),      # batch of 4: vector-ALU kernels at a large shape
-    # the pipelined transposed kernel (aligned tiles, batch above 64 columns)
+    # the pipelined transposed kernel (aligned tiles, batch above 32 columns)
     (_small(256, 256, 128, 128, 8, 0.2, 128, "f16"), 0),        # one panel of four slabs, one 128-row unit per tile row
     (_small(1536, 384, 256, 384, 16, 0.1, 136, "bf16"), 0),     # three panels, three slices, a short second batch block
     (_small(1024, 128, 128, 128, 64, 0.03, 72, "f16"), 0),      # rank 64: two I_p words per row, a batch block of 72
     (_small(768, 256, 384, 128, 40, 0.05, 80, "bf16"), 8),      # rank 40, three units per tile row, padded leading dimensions
     (_small(2048, 256, 512, 256, 5, 0.3, 256, "f16"), 0),       # rank 5 (a short round of ranks), four panels
+    (_small(1024, 256, 256, 128, 16, 0.1, 48, "bf16"), 0),      # 33 to 64 batch columns: part of the batch block idle
     # the same kernel on tile widths that are an odd multiple of 64 (Table 2's 576-column tiles): workgroups whose 128
     # columns lie in two tile columns
     (_small(512, 1152, 128, 576, 8, 0.2, 128, "f16"), 0),       # nine workgroups, the fifth across the two tile columns
