@@ -770,7 +770,9 @@ __global__ __launch_bounds__(64) void valu_grad_kernel(Geom g, const T *__restri
 BwdPlan plan_gemm_t(const Geom &g, lrbi_dtype dt, int64_t N, bool aligned)
 {
     BwdPlan p;
-    p.mfma = (dt != LRBI_F32) && aligned && N > 4;
+    // (also the narrowest batches: the vector-ALU kernel walks the m rows one by one per lane, with a chain of dependent
+    // factor loads per row: 3.9 ms on a 4096 x 9216 matrix at one column, where the tile kernel takes 26 us)
+    p.mfma = (dt != LRBI_F32) && aligned && N >= 1;
     p.bq = (N > 32) ? 128 : 32;
     p.slices = 1;
     p.iper = g.m;

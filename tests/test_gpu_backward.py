@@ -83,7 +83,9 @@ EDGE = [
     (_small(768, 256, 384, 128, 40, 0.05, 16, "bf16"), 0),      # slices that start inside a tile, two I_p words
     (_small(1024, 384, 256, 384, 16, 0.1, 40, "f16"), 0),       # workgroups at three offsets inside a tile column
     (_small(512, 128, 128, 128, 64, 0.03, 8, "f16"), 0),        # smallest tile rows of the tuned mask path, rank 64
-    (_small(2048, 512, 512, 512, 32, 0.06, 4, "bf16"), 0),      # batch of 4: vector-ALU kernels at a large shape
+    (_small(2048, 512, 512, 512, 32, 0.06, 4, "bf16"), 0),      # batch of 4: the tile kernel's 32-column form, mostly idle
+    (_small(1024, 640, 256, 128, 16, 0.1, 1, "f16"), 0),        # one column
+    (_small(300, 1096, 128, 256, 8, 0.15, 3, "bf16"), 0),       # three columns, edge tiles
     # the pipelined transposed kernel (aligned tiles, batch above 32 columns)
     (_small(256, 256, 128, 128, 8, 0.2, 128, "f16"), 0),        # one panel of four slabs, one 128-row unit per tile row
     (_small(1536, 384, 256, 384, 16, 0.1, 136, "bf16"), 0),     # three panels, three slices, a short second batch block
