@@ -353,8 +353,8 @@ int lrbi_search_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
  *   dW: m x n row-major, ldw >= n.  dDY: m x N row-major, lddy >= N.  dDX: n x N row-major,
  *   lddx >= N; overwritten.  All of `dtype`; fp32 accumulation in a fixed order (identical bits
  *   from call to call), rounded to nearest-even on store.  Pointers aligned to the element size;
- *   f16 / bf16 with 16-byte aligned W, ldw % 8 == 0, n % 8 == 0 and N > 4 run on the matrix
- *   cores, everything else on a plain vector-ALU kernel with the same results.
+ *   f16 / bf16 with 16-byte aligned W, ldw % 8 == 0 and n % 8 == 0 run on the matrix cores at
+ *   any N, everything else on a plain (and for large m slow) vector-ALU kernel with the same results.
  *   dWorkspace / workspace_bytes: optional scratch (16-byte aligned) of at least
  *   lrbi_masked_gemm_t_workspace_bytes bytes: partial sums when the reduction over m is split
  *   across workgroups; with NULL or too few bytes it is not split (slower for small n * N).
@@ -363,8 +363,8 @@ int lrbi_search_workspace_bytes(const lrbi_desc *desc, uint64_t *bytes);
  * lrbi_masked_grad: dW = (dY X^T) o I_a, m x n, the gradient with respect to W: entry (i, j) is
  *   sum_q dY[i, q] X[j, q] where I_a keeps the weight and exactly 0 where it prunes it.
  *   dDY: m x N, lddy >= N.  dX: n x N, ldx >= N.  dDW: m x n, lddw >= n; overwritten (every
- *   entry is written).  Same dtype, accumulation and rounding rules as above; f16 / bf16 with
- *   N >= 8 run on the matrix cores (16-byte aligned dY, X with lddy, ldx, N multiples of 8, and
+ *   entry is written).  Same dtype, accumulation and rounding rules as above; f16 / bf16 run on
+ *   the matrix cores at any N (16-byte aligned dY, X with lddy, ldx, N multiples of 8, and
  *   16-byte aligned dW rows, take the vector paths inside it).  One kernel launch on `stream`.
  */
 int lrbi_masked_gemm_t_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t N,
