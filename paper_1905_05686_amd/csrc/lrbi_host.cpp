@@ -204,7 +204,10 @@ static bool use_mfma(const lrbi_desc *desc, lrbi_dtype dt, int64_t N)
     if (dt == LRBI_F32) return false;
     if (path == LRBI_FLAG_PATH_MFMA) return true;
     if (path == LRBI_FLAG_PATH_VALU) return false;
-    return N > 4; // below that the product is a bandwidth-bound matrix-vector sweep
+    // below five columns the product is a bandwidth-bound matrix-vector sweep; the row-streaming kernels take one and
+    // four columns ahead of this choice, and for two or three columns of a large matrix the tile kernel's split over n
+    // beats the sweep (HBM-cold 4096 x 9216: 34 against 83-95 us; 6000 x 3000 in 300 x 300 tiles: 26.5 against 37.3 us)
+    return N > 4 || (N >= 2 && (int64_t)desc->m * desc->n >= ((int64_t)1 << 23)); // (level at 2048 x 2048, the sweep ahead at 1024 x 1024)
 }
 
 extern "C" int lrbi_masked_gemm_workspace_bytes(const lrbi_desc *desc, lrbi_dtype dtype, int64_t N,

@@ -90,6 +90,7 @@ EDGE = [
     (_small(1152, 1024, 576, 512, 256, 0.015, 1, "bf16"), 0),
     (_small(64, 576, 64, 576, 8, 0.2, 12416, "bf16"), 0),    # few rows, many columns: 64-column blocks, unsplit
     (_small(48, 288, 16, 96, 4, 0.3, 3080, "f16"), 0),       # ... 32-column blocks
+    (_small(4096, 2304, 256, 256, 16, 0.08, 3, "bf16"), 0),  # three columns of a large matrix: the tile kernel, mostly idle
     # few rows, short rows: the row-streaming kernels on a grid far smaller than the chip (automatic choice)
     (_small(1200, 600, 1200, 600, 145, 0.05, 20, "f16"), 0), # the gate matrix of an LSTM layer of size 300 (Sec. 4), untiled, at Table 2's rank 145
     (_small(800, 400, 800, 400, 145, 0.05, 20, "f16"), 0),   # 50 workgroups
